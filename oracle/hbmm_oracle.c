@@ -1,0 +1,220 @@
+/*
+ * CPU oracle for the Hadamard Binary Matrix Multiply (HBMM) of HadaNets.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the GPU
+ * library is checked against.  It shares no code, header, table or helper with the HIP
+ * path, and nothing on the product path may call it: only the tests, the smoke check and
+ * the benchmark's cpu_baseline leg load it.
+ *
+ * Everything is written out from the paper's definitions, in double precision, with
+ * no blocking, fusion or reordering.  OpenMP only spreads independent output rows over
+ * cores; the arithmetic that produces any single output is sequential and in the order
+ * the definition states.
+ *
+ * Notation (paper section 3 and section 4.2):
+ *   x        full-precision operand, `rows` x K, row-major, K contiguous (section 4,
+ *            "row-major order", "row-wise binarization").
+ *   beta     segment length ("binarization aggression"), segments are consecutive runs
+ *            of beta elements along K inside one row.
+ *   delta    scale of a segment = mean of |x| over the segment (Eq. 1 / Eq. 3; the sums
+ *            there are read as beta terms, r = 0 .. beta-1, to agree with the 1/beta
+ *            factor and with "mean of the absolute value of segments" in section 3).
+ *   x~       delta (Hadamard product) Sign(x)  (Eq. 2 / Eq. 4), Sign(0) = +1.
+ *   O        Eq. 7: sum over segments of W_f,j * A_f,j * (signed agreement count).  Eq. 7
+ *            prints popcount(xnor(.)), the number p of agreeing signs; the +-1 inner
+ *            product it stands for is 2p - n = n - 2*popcount(xor), n the segment length.
+ *
+ * Readings taken where the paper is silent (all listed in the design document):
+ *   - a last segment shorter than beta is averaged over its own length;
+ *   - bit k of a row is bit (k mod 32) of 32-bit word (k div 32), -1 -> 0, +1 -> 1
+ *     (the 6-element example of section 4 fixes the value mapping, not the endianness);
+ *   - bits past K inside the last word, and pad words, are 0;
+ *   - the stored scale is fp32 (sum in double, divide, round once);
+ *   - beta = 1 means "not binarised": x~ = x (with -0.0 -> +0.0).
+ *
+ * Parity pins: every function below is pinned by tests/test_oracle_pins.py (brute
+ * force on tiny inputs, closed forms, the paper's packing example, special cases that
+ * reduce to a plain matrix product or to XNOR-Net per-row scaling).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+static int sgn_ge0(float v) { return (v >= 0.0f) ? 1 : 0; } /* -0.0 -> 1, NaN -> 0 */
+
+/* Eq. 1 / Eq. 3: delta[r, j] = mean_{k in segment j} |x[r, k]|, stored as fp32.
+ * s is rows x lds, ceil(K/beta) valid entries per row. */
+void oracle_block_scales(const float *x, int64_t rows, int64_t K, int64_t ldx, int64_t beta,
+                         float *s, int64_t lds)
+{
+    int64_t nb = (K + beta - 1) / beta;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t j = 0; j < nb; ++j) {
+            int64_t k0 = j * beta;
+            int64_t k1 = k0 + beta < K ? k0 + beta : K;
+            double acc = 0.0;
+            for (int64_t k = k0; k < k1; ++k)
+                acc += fabs((double)x[r * ldx + k]);
+            s[r * lds + j] = (float)(acc / (double)(k1 - k0));
+        }
+    }
+}
+
+/* Sign + bit-pack (section 4: the row "-1 1 1 -1 -1 1" is stored as 011001).
+ * bits is rows x ldw uint32; every word of the row, pad words included, is written. */
+void oracle_sign_pack(const float *x, int64_t rows, int64_t K, int64_t ldx,
+                      uint32_t *bits, int64_t ldw)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t w = 0; w < ldw; ++w)
+            bits[r * ldw + w] = 0u;
+        for (int64_t k = 0; k < K; ++k)
+            if (sgn_ge0(x[r * ldx + k]))
+                bits[r * ldw + (k >> 5)] |= (uint32_t)1 << (k & 31);
+    }
+}
+
+/* Eq. 2 / Eq. 4: xt[r, k] = delta[r, k div beta] * Sign(x[r, k]) in double (xt is rows x K,
+ * dense).  beta == 1 keeps the operand itself (section 3.1: beta = 1 is the unquantised
+ * setting), which is also what |x| * Sign(x) gives. */
+void oracle_materialize(const float *x, int64_t rows, int64_t K, int64_t ldx, int64_t beta,
+                        const float *s, int64_t lds, double *xt)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t k = 0; k < K; ++k) {
+            float v = x[r * ldx + k];
+            if (beta == 1)
+                xt[r * K + k] = (v == 0.0f) ? 0.0 : (double)v;
+            else
+                xt[r * K + k] = sgn_ge0(v) ? (double)s[r * lds + k / beta]
+                                           : -(double)s[r * lds + k / beta];
+        }
+    }
+}
+
+/* Plain definition of the product HBMM reaches: C[m, n] = sum_k At[m, k] * Bt[n, k],
+ * both operands dense double, K contiguous, k ascending. */
+void oracle_dense_f64_gemm(const double *At, const double *Bt, int64_t M, int64_t N, int64_t K,
+                           double *C)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            double acc = 0.0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += At[m * K + k] * Bt[n * K + k];
+            C[m * N + n] = acc;
+        }
+    }
+}
+
+/* popcount of (a xor b) restricted to bit range [k0, k1) of two packed rows. */
+static int64_t hamming_range(const uint32_t *a, const uint32_t *b, int64_t k0, int64_t k1)
+{
+    int64_t h = 0;
+    for (int64_t w = k0 >> 5; w <= (k1 - 1) >> 5; ++w) {
+        int64_t lo = w << 5;
+        uint32_t x = a[w] ^ b[w];
+        if (k0 > lo)
+            x &= ~(uint32_t)0 << (k0 - lo);
+        if (k1 < lo + 32)
+            x &= ~(uint32_t)0 >> (lo + 32 - k1);
+        h += __builtin_popcount(x);
+    }
+    return h;
+}
+
+/* Eq. 7 on packed operands: the K axis is cut wherever a segment of either operand ends
+ * (section 4.2: with different beta the finer one sets the granularity); on every piece
+ * d = n - 2 * popcount(a xor b) is the exact +-1 inner product and contributes
+ * sA * sB * d.  C and T are M x N doubles; T (may be NULL) receives the sum of the
+ * absolute values of the contributions, the scale of fp32 accumulation error. */
+void oracle_popcount_gemm(const uint32_t *a_bits, int64_t ldw_a, const float *a_s, int64_t lds_a,
+                          int64_t beta_a, const uint32_t *b_bits, int64_t ldw_b, const float *b_s,
+                          int64_t lds_b, int64_t beta_w, int64_t M, int64_t N, int64_t K,
+                          double *C, double *T)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            double acc = 0.0, tacc = 0.0;
+            int64_t k0 = 0;
+            while (k0 < K) {
+                int64_t ea = (k0 / beta_a + 1) * beta_a;
+                int64_t ew = (k0 / beta_w + 1) * beta_w;
+                int64_t k1 = ea < ew ? ea : ew;
+                if (k1 > K)
+                    k1 = K;
+                int64_t h = hamming_range(a_bits + m * ldw_a, b_bits + n * ldw_b, k0, k1);
+                int64_t d = (k1 - k0) - 2 * h;
+                double term = (double)a_s[m * lds_a + k0 / beta_a] *
+                              (double)b_s[n * lds_b + k0 / beta_w] * (double)d;
+                acc += term;
+                tacc += fabs(term);
+                k0 = k1;
+            }
+            C[m * N + n] = acc;
+            if (T)
+                T[m * N + n] = tacc;
+        }
+    }
+}
+
+/* Whole-row +-1 inner product: D[m, n] = K - 2 * hamming(a_row, b_row). */
+void oracle_int_dot(const uint32_t *a_bits, int64_t ldw_a, const uint32_t *b_bits, int64_t ldw_b,
+                    int64_t M, int64_t N, int64_t K, int32_t *D)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n)
+            D[m * N + n] = (int32_t)(K - 2 * hamming_range(a_bits + m * ldw_a, b_bits + n * ldw_b, 0, K));
+}
+
+/* Binary-weight form (beta_a = 1, the paper's HBWN): activations stay full precision,
+ *   C[m, n] = sum_j sB[n, j] * sum_{k in segment j} A[m, k] * (+-1)_B[n, k].
+ * T (may be NULL) receives sum_k |A[m, k]| * sB[n, k div beta_w]. */
+void oracle_binary_weight_gemm(const float *A, int64_t lda, const uint32_t *b_bits, int64_t ldw_b,
+                               const float *b_s, int64_t lds_b, int64_t beta_w, int64_t M, int64_t N,
+                               int64_t K, double *C, double *T)
+{
+    int64_t nb = (K + beta_w - 1) / beta_w;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            double acc = 0.0, tacc = 0.0;
+            for (int64_t j = 0; j < nb; ++j) {
+                int64_t k0 = j * beta_w;
+                int64_t k1 = k0 + beta_w < K ? k0 + beta_w : K;
+                double seg = 0.0, aseg = 0.0;
+                for (int64_t k = k0; k < k1; ++k) {
+                    double a = (double)A[m * lda + k];
+                    int bit = (b_bits[n * ldw_b + (k >> 5)] >> (k & 31)) & 1u;
+                    seg += bit ? a : -a;
+                    aseg += fabs(a);
+                }
+                acc += (double)b_s[n * lds_b + j] * seg;
+                tacc += (double)b_s[n * lds_b + j] * aseg;
+            }
+            C[m * N + n] = acc;
+            if (T)
+                T[m * N + n] = tacc;
+        }
+    }
+}
