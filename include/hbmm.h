@@ -1,0 +1,124 @@
+/*
+ * libhbmm -- Hadamard Binary Matrix Multiply (HBMM) of HadaNets for AMD MI355X (gfx950).
+ *
+ * Plain C ABI.  Conventions shared by every entry point:
+ *
+ *  - Every buffer is a DEVICE pointer owned by the caller.  The library never allocates,
+ *    frees or synchronises: each call validates its arguments on the host, enqueues its
+ *    kernels on `stream` (a hipStream_t passed as void*, NULL = the default stream) and
+ *    returns.  There is no global state; calls on different streams may overlap as long as
+ *    their output buffers do not.
+ *  - Return value: HBMM_OK, or a negative HBMM_E* code.  Nothing is thrown or aborted; on an
+ *    error no kernel has been launched and no output has been touched.
+ *  - Matrices are row-major (paper, section 4: tensors are stored row-major and binarised
+ *    row-wise).  Leading dimensions (`ld*`) are in elements of the pointed-to type.
+ *  - Pointers must be 16-byte aligned.  `ldw*` must be a multiple of 4 words.
+ *
+ * Operand convention (paper, section 3.1.1 and section 4.2).  A is the activation operand,
+ * M x K.  B is the weight operand in the paper's reshaped form W^f = Reshape(W, (filters, -1)):
+ * N x K, so that both operands have K contiguous and the product is C = A~ . B~^T, M x N.
+ * A~ = delta_a (.) Sign(A) and B~ = delta_w (.) Sign(B) (Eq. 2, Eq. 4), where delta is the mean
+ * of |x| over consecutive segments of beta elements along K inside one row (Eq. 1, Eq. 3).
+ *
+ * Packed form of an operand with `rows` rows:
+ *   bits    rows x ldw uint32.  Element k of a row is bit (k mod 32) of word (k div 32);
+ *           bit 1 <=> x >= 0 (Sign = +1; Sign(0) = +1, -0.0 counts as 0, NaN gives bit 0),
+ *           bit 0 <=> Sign = -1 (section 4: the row -1 1 1 -1 -1 1 packs to 011001).
+ *           Words [0, hbmm_packed_ld_words(K)) of every row are written; bits at k >= K
+ *           inside them are 0.  Words past that (if ldw is larger) are not touched.
+ *   scales  rows x lds fp32, entry j of a row = mean |x| over k in [j*beta, (j+1)*beta);
+ *           hbmm_num_blocks(K, beta) entries per row are written ("the full precision vector
+ *           can be compressed beta times", section 4.2).
+ */
+#ifndef HBMM_H
+#define HBMM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HBMM_OK 0
+#define HBMM_EINVAL (-1)       /* null pointer, bad shape, misaligned pointer, ld too small */
+#define HBMM_EUNSUPPORTED (-2) /* beta / K / algo / dtype outside the supported set */
+#define HBMM_ELAUNCH (-3)      /* HIP reported an error when the kernel was enqueued */
+
+/* Human-readable text for a return code (static storage, never NULL). */
+const char *hbmm_strerror(int code);
+
+/* ceil(K / beta): scale entries per row (Eq. 7 sums over this many segments). 0 if K < 0 or beta < 1. */
+int64_t hbmm_num_blocks(int64_t K, int32_t beta);
+
+/* 32-bit words per packed row: ceil(K / 32) rounded up to a multiple of 4 (16-byte rows). */
+int64_t hbmm_packed_ld_words(int64_t K);
+
+/*
+ * Hadamard binarisation of one operand: block scales (Eq. 1 / Eq. 3), Sign (Eq. 2 / Eq. 4) and
+ * bit-packing (section 4), in one pass over x.
+ *
+ *   x       fp32 source.  layout 0: rows x K, element (r, k) at x[r*ldx + k]   (ldx >= K).
+ *                         layout 1: K x rows, element (r, k) at x[k*ldx + r]   (ldx >= rows);
+ *                         this is a right-hand operand written the usual K x N way; the result
+ *                         is identical to packing its transpose.
+ *   beta    segment length; supported: 32, 64, 128, 256 with K a multiple of beta.
+ *   bits    out, rows x ldw (ldw >= hbmm_packed_ld_words(K), multiple of 4).
+ *   scales  out, rows x lds (lds >= hbmm_num_blocks(K, beta)).
+ *
+ * rows == 0 or K == 0 is a valid no-op.  The fp32 scale is a pairwise fp32 sum for layout 0
+ * (relative error <= (log2(beta) + 1) * 2^-24) and a double-precision sequential sum rounded
+ * once for layout 1.
+ */
+int hbmm_quantize_pack(const float *x, int64_t rows, int64_t K, int64_t ldx, int32_t layout,
+                       int32_t beta, uint32_t *bits, int64_t ldw, float *scales, int64_t lds,
+                       void *stream);
+
+/*
+ * HBMM proper (Eq. 7, with popcount(xnor) read as the signed agreement count):
+ *
+ *   C[m, n] = sum over segments g of  sA[m, g*G / beta_a] * sB[n, g*G / beta_w] * d[m, n, g],
+ *   d[m, n, g] = G - 2 * popcount(a_bits[m, g] xor b_bits[n, g])     (the +-1 inner product)
+ *
+ * with G = min(beta_a, beta_w) (section 4.2: the finer segmentation sets the granularity).
+ * Integer work is exact; the scaled terms are accumulated in fp32 in ascending g.
+ *
+ *   a_bits, a_scales  packed A (M rows), from hbmm_quantize_pack with beta_a.
+ *   b_bits, b_scales  packed B (N rows), from hbmm_quantize_pack with beta_w.
+ *   beta_a, beta_w    each in {32, 64, 128, 256}, K a multiple of both.
+ *                     beta_a == 1 selects the binary-weight form (the paper's HBWN): a_bits must
+ *                     be NULL, a_scales points at the raw fp32 A (M x K, leading dimension lds_a)
+ *                     and C[m, n] = sum_j sB[n, j] * sum_{k in j} A[m, k] * Sign(B)[n, k].
+ *   C                 out, M x N fp32, leading dimension ldc >= N.
+ *   algo              0: XNOR + popcount on the vector ALU (the method's kernel).
+ *                     1: the same d[m, n, g] from int8 +-1 matrix-core (MFMA) products, kept as a
+ *                        comparison point; same epilogue, same result up to fp32 rounding order.
+ *
+ * M == 0 or N == 0 is a valid no-op; K == 0 writes zeros.
+ */
+int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int64_t lds_a,
+              int32_t beta_a, const uint32_t *b_bits, const float *b_scales, int64_t ldw_b,
+              int64_t lds_b, int32_t beta_w, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
+              int32_t algo, void *stream);
+
+/*
+ * Unscaled whole-row +-1 inner products, for exact parity checks of the contraction:
+ *   D[m, n] = K - 2 * popcount(a_row xor b_row),  int32, M x N, leading dimension ldd >= N.
+ * Uses the same inner loop as hbmm_gemm(algo 0).  K need not be a multiple of 32 (pad bits are 0
+ * in both operands and cancel).
+ */
+int hbmm_gemm_int(const uint32_t *a_bits, int64_t ldw_a, const uint32_t *b_bits, int64_t ldw_b,
+                  int64_t M, int64_t N, int64_t K, int32_t *D, int64_t ldd, void *stream);
+
+/*
+ * Dense comparison product on unquantised operands (the role the paper's "classical matrix
+ * multiply" plays in section 4.2):  C = A . B^T, A M x K, B N x K, both K contiguous.
+ *   dtype 0: fp32 operands.  dtype 1: bf16 operands (raw uint16 bit patterns).
+ * fp32 accumulation and fp32 C in both cases.  K must be a multiple of 32.
+ */
+int hbmm_dense_ref_gemm(const void *A, int64_t lda, const void *B, int64_t ldb, int32_t dtype,
+                        int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HBMM_H */

@@ -1,0 +1,209 @@
+// C-ABI layer of libhbmm: argument validation and dispatch.  See include/hbmm.h for the contract.
+// Nothing here allocates, frees or synchronises; every path either returns an error before any
+// launch or enqueues its kernels on the caller's stream.
+#include "../../include/hbmm.h"
+#include "kernels.h"
+
+namespace {
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+int log2_exact(int v)
+{
+    int s = 0;
+    while ((1 << s) < v) ++s;
+    return s;
+}
+
+bool supported_beta(int beta) { return beta == 32 || beta == 64 || beta == 128 || beta == 256; }
+
+int from_hip(hipError_t e)
+{
+    if (e == hipSuccess) return HBMM_OK;
+    return e == hipErrorNotSupported ? HBMM_EUNSUPPORTED : HBMM_ELAUNCH;
+}
+
+// Zero an M x N block of 4-byte elements (K == 0 products).  A kernel rather than a memset so that
+// the call can be captured into a HIP graph like every other launch of this library.
+__global__ void zero_block_kernel(uint32_t *dst, int64_t ld, int64_t M, int64_t N)
+{
+    const int64_t total = M * N;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x)
+        dst[(i / N) * ld + i % N] = 0u;
+}
+hipError_t zero_block(void *dst, int64_t ld, int64_t M, int64_t N, hipStream_t s)
+{
+    const int64_t total = M * N;
+    const unsigned blocks = (unsigned)((total + 255) / 256 > 4096 ? 4096 : (total + 255) / 256);
+    zero_block_kernel<<<dim3(blocks), dim3(256), 0, s>>>(static_cast<uint32_t *>(dst), ld, M, N);
+    return hipGetLastError();
+}
+
+constexpr int64_t kMaxDim = (int64_t)1 << 30;   // rows, K: index arithmetic stays inside 32/64 bits
+constexpr int64_t kMaxPackK = (int64_t)1 << 26; // pack grid: K / 1024 must fit gridDim.y
+
+}  // namespace
+
+extern "C" {
+
+const char *hbmm_strerror(int code)
+{
+    switch (code) {
+    case HBMM_OK: return "ok";
+    case HBMM_EINVAL: return "invalid argument (null or misaligned pointer, bad shape or leading dimension)";
+    case HBMM_EUNSUPPORTED: return "unsupported beta, K, algo or dtype";
+    case HBMM_ELAUNCH: return "HIP error at kernel launch";
+    }
+    return "unknown hbmm error code";
+}
+
+int64_t hbmm_num_blocks(int64_t K, int32_t beta)
+{
+    if (K < 0 || beta < 1) return 0;
+    return (K + beta - 1) / beta;
+}
+
+int64_t hbmm_packed_ld_words(int64_t K)
+{
+    if (K < 0) return 0;
+    return hbmm::packed_words(K);
+}
+
+int hbmm_quantize_pack(const float *x, int64_t rows, int64_t K, int64_t ldx, int32_t layout,
+                       int32_t beta, uint32_t *bits, int64_t ldw, float *scales, int64_t lds,
+                       void *stream)
+{
+    if (rows < 0 || K < 0 || rows > kMaxDim || K > kMaxPackK) return HBMM_EINVAL;
+    if (layout != 0 && layout != 1) return HBMM_EINVAL;
+    if (beta < 1) return HBMM_EINVAL;
+    if (!supported_beta(beta)) return HBMM_EUNSUPPORTED;
+    if (K % beta != 0) return HBMM_EUNSUPPORTED;
+    if (rows == 0 || K == 0) return HBMM_OK;
+    if (!x || !bits || !scales) return HBMM_EINVAL;
+    if (!aligned16(x) || !aligned16(bits) || !aligned16(scales)) return HBMM_EINVAL;
+    if (ldx < (layout == 0 ? K : rows)) return HBMM_EINVAL;
+    if (ldw < hbmm::packed_words(K) || ldw % 4 != 0) return HBMM_EINVAL;
+    if (lds < K / beta) return HBMM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (layout == 0) return from_hip(hbmm::launch_pack_rows(x, rows, K, ldx, beta, bits, ldw, scales, lds, s));
+    return from_hip(hbmm::launch_pack_cols(x, rows, K, ldx, beta, bits, ldw, scales, lds, s));
+}
+
+static int check_packed(const uint32_t *bits, int64_t rows, int64_t K, int64_t ldw)
+{
+    if (!bits || !aligned16(bits)) return HBMM_EINVAL;
+    if (ldw < hbmm::packed_words(K) || ldw % 4 != 0) return HBMM_EINVAL;
+    if (rows * ldw >= ((int64_t)1 << 29)) return HBMM_EINVAL;   // byte offsets of rows fit 32 bits
+    return HBMM_OK;
+}
+
+// Pick which operand is held per lane (tile 256) and which is broadcast (tile 128): the one that
+// wastes fewer padded outputs; B per lane is preferred because then a wave stores along a row of C.
+static bool b_is_lane_side(int64_t M, int64_t N)
+{
+    auto up = [](int64_t v, int64_t t) { return (v + t - 1) / t * t; };
+    const double cost_b = (double)up(N, 256) * (double)up(M, 128);
+    const double cost_a = (double)up(M, 256) * (double)up(N, 128) * 1.05;
+    return cost_b <= cost_a;
+}
+
+int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int64_t lds_a,
+              int32_t beta_a, const uint32_t *b_bits, const float *b_scales, int64_t ldw_b,
+              int64_t lds_b, int32_t beta_w, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
+              int32_t algo, void *stream)
+{
+    if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim) return HBMM_EINVAL;
+    if (beta_a < 1 || beta_w < 1) return HBMM_EINVAL;
+    if (algo != 0 && algo != 1) return HBMM_EUNSUPPORTED;
+    if (!supported_beta(beta_w) || (beta_a != 1 && !supported_beta(beta_a))) return HBMM_EUNSUPPORTED;
+    if (K % beta_w != 0 || K % beta_a != 0) return HBMM_EUNSUPPORTED;
+    if (beta_a == 1 && algo != 0) return HBMM_EUNSUPPORTED;
+    if (M == 0 || N == 0) return HBMM_OK;
+    if (!C || !aligned16(C) || ldc < N) return HBMM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (K == 0) return from_hip(zero_block(C, ldc, M, N, s));
+
+    if (!b_scales || !aligned16(b_scales) || lds_b < K / beta_w) return HBMM_EINVAL;
+    if (int rc = check_packed(b_bits, N, K, ldw_b)) return rc;
+
+    if (beta_a == 1) {
+        if (a_bits != nullptr) return HBMM_EINVAL;
+        if (!a_scales || !aligned16(a_scales) || lds_a < K) return HBMM_EINVAL;
+        return from_hip(hbmm::launch_binary_weight_gemm(a_scales, lds_a, b_bits, b_scales, ldw_b, lds_b,
+                                                        beta_w, M, N, K, C, ldc, s));
+    }
+
+    if (!a_scales || !aligned16(a_scales) || lds_a < K / beta_a) return HBMM_EINVAL;
+    if (int rc = check_packed(a_bits, M, K, ldw_a)) return rc;
+
+    if (algo == 1)
+        return from_hip(hbmm::launch_mfma_i8_gemm(a_bits, a_scales, ldw_a, lds_a, beta_a, b_bits, b_scales,
+                                                  ldw_b, lds_b, beta_w, M, N, K, C, ldc, s));
+
+    const int G = beta_a < beta_w ? beta_a : beta_w;
+    hbmm::PopcountGemmArgs g{};
+    const bool b_lane = b_is_lane_side(M, N);
+    if (b_lane) {
+        g.p_bits = b_bits; g.p_scales = b_scales; g.ldw_p = (int32_t)ldw_b; g.lds_p = (int32_t)lds_b;
+        g.P = (int32_t)N; g.shift_p = log2_exact(beta_w / G);
+        g.q_bits = a_bits; g.q_scales = a_scales; g.ldw_q = (int32_t)ldw_a; g.lds_q = (int32_t)lds_a;
+        g.Q = (int32_t)M; g.shift_q = log2_exact(beta_a / G);
+        g.ld_out_p = 1; g.ld_out_q = ldc;
+    } else {
+        g.p_bits = a_bits; g.p_scales = a_scales; g.ldw_p = (int32_t)ldw_a; g.lds_p = (int32_t)lds_a;
+        g.P = (int32_t)M; g.shift_p = log2_exact(beta_a / G);
+        g.q_bits = b_bits; g.q_scales = b_scales; g.ldw_q = (int32_t)ldw_b; g.lds_q = (int32_t)lds_b;
+        g.Q = (int32_t)N; g.shift_q = log2_exact(beta_w / G);
+        g.ld_out_p = ldc; g.ld_out_q = 1;
+    }
+    if (lds_a >= ((int64_t)1 << 31) || lds_b >= ((int64_t)1 << 31)) return HBMM_EINVAL;
+    g.out = C;
+    g.kwords = (int32_t)hbmm::packed_words(K);
+    g.ngran = (int32_t)(K / G);
+    g.K = (int32_t)K;
+    return from_hip(hbmm::launch_popcount_gemm(g, G, 0, s));
+}
+
+int hbmm_gemm_int(const uint32_t *a_bits, int64_t ldw_a, const uint32_t *b_bits, int64_t ldw_b,
+                  int64_t M, int64_t N, int64_t K, int32_t *D, int64_t ldd, void *stream)
+{
+    if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim) return HBMM_EINVAL;
+    if (M == 0 || N == 0) return HBMM_OK;
+    if (!D || !aligned16(D) || ldd < N) return HBMM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (K == 0) return from_hip(zero_block(D, ldd, M, N, s));
+    if (int rc = check_packed(a_bits, M, K, ldw_a)) return rc;
+    if (int rc = check_packed(b_bits, N, K, ldw_b)) return rc;
+
+    hbmm::PopcountGemmArgs g{};
+    if (b_is_lane_side(M, N)) {
+        g.p_bits = b_bits; g.ldw_p = (int32_t)ldw_b; g.P = (int32_t)N;
+        g.q_bits = a_bits; g.ldw_q = (int32_t)ldw_a; g.Q = (int32_t)M;
+        g.ld_out_p = 1; g.ld_out_q = ldd;
+    } else {
+        g.p_bits = a_bits; g.ldw_p = (int32_t)ldw_a; g.P = (int32_t)M;
+        g.q_bits = b_bits; g.ldw_q = (int32_t)ldw_b; g.Q = (int32_t)N;
+        g.ld_out_p = ldd; g.ld_out_q = 1;
+    }
+    g.out = D;
+    g.kwords = (int32_t)hbmm::packed_words(K);
+    g.K = (int32_t)K;
+    return from_hip(hbmm::launch_popcount_gemm(g, 64, 1, s));
+}
+
+int hbmm_dense_ref_gemm(const void *A, int64_t lda, const void *B, int64_t ldb, int32_t dtype,
+                        int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, void *stream)
+{
+    if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim) return HBMM_EINVAL;
+    if (dtype != 0 && dtype != 1) return HBMM_EUNSUPPORTED;
+    if (K % 32 != 0) return HBMM_EUNSUPPORTED;
+    if (M == 0 || N == 0) return HBMM_OK;
+    if (!C || !aligned16(C) || ldc < N) return HBMM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (K == 0) return from_hip(zero_block(C, ldc, M, N, s));
+    if (!A || !B || !aligned16(A) || !aligned16(B) || lda < K || ldb < K) return HBMM_EINVAL;
+    if (lda % 8 != 0 || ldb % 8 != 0) return HBMM_EINVAL;   // 16-byte row starts for either dtype
+    return from_hip(hbmm::launch_dense_ref(A, lda, B, ldb, dtype, M, N, K, C, ldc, s));
+}
+
+}  // extern "C"

@@ -1,0 +1,376 @@
+// XNOR + popcount HBMM (HadaNets Eq. 7) on the gfx950 vector ALU, with the fp32 block-scale
+// epilogue fused in.
+//
+// For one output and one segment g of G = min(beta_p, beta_q) bits,
+//     d = sum_k (+-1)(+-1) = G - 2 * popcount(p_word xor q_word)
+// (Eq. 7 prints popcount(xnor(.)), the count of agreeing signs; d is the signed count it stands
+// for), and the output accumulates  sP * sQ * d  in fp32, in ascending g.
+//
+// Mapping to the machine.  The cost is two VALU instructions per 32 binary multiply-adds
+// (v_xor_b32 + the accumulating v_bcnt_u32_b32), so the kernel is organised to issue nothing
+// else in the inner loop:
+//   * "P" operand rows live one-per-lane: a wave owns 64 * kTP rows of P and reads their packed
+//     words from an LDS tile (padded so that 8-byte reads are bank-conflict free).
+//   * "Q" operand rows are wave-uniform: each wave owns kTQ rows of Q and fetches their words
+//     with scalar loads into SGPRs, which v_xor_b32 takes as a free operand.  No VGPR, LDS or
+//     vector-memory traffic is spent on Q bits.
+//   * each lane keeps kTP x kTQ integer accumulators and as many fp32 results.
+//   * the popcount accumulator of a segment is seeded with -G/2 (first v_bcnt of the segment takes
+//     the seed instead of the old value, so no reset instruction exists); then d = -2 * acc and the
+//     factor -2 is folded into the P scale.  Epilogue per accumulator per segment: cvt, mul, fma.
+//   * K is walked in chunks of kCK words; the next chunk's P words and both operands' scales are
+//     fetched from global memory while the current chunk is being reduced, then parked in the
+//     other LDS buffer (one barrier per chunk).
+// Either of A / B can be P or Q: the host picks the role by output strides.
+#include "kernels.h"
+
+namespace hbmm {
+namespace {
+
+constexpr int kTP = 4;                 // P rows per lane
+constexpr int kTQ = 16;                // Q rows per wave
+constexpr int kWaves = 8;
+constexpr int kThreads = 64 * kWaves;  // 512
+constexpr int kTileP = 64 * kTP;       // 256 P rows per workgroup
+constexpr int kTileQ = kTQ * kWaves;   // 128 Q rows per workgroup
+constexpr int kCK = 16;                // 32-bit words of K per chunk (512 bits)
+constexpr int kStep = 2;               // words per inner step (one 8-byte LDS read, one s_load_dwordx2)
+constexpr int kBitsStride = kCK + 2;   // LDS row stride in words: 2 * odd => conflict-free b64 reads
+constexpr int kScaleStrideP = 17;      // odd => conflict-free b32 reads
+constexpr int kMaxScalesPerChunk = 16; // 512 bits / beta 32
+
+typedef const uint32_t __attribute__((address_space(4))) *const_u32_ptr;
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef const u32x2 __attribute__((address_space(4))) *const_u32x2_ptr;
+
+// popcount(x) + acc in one instruction.  Written as asm so that the optimiser cannot re-associate
+// chains of these into separate popcounts plus three-operand adds.
+__device__ __forceinline__ int bcnt_acc(uint32_t x, int acc)
+{
+    int d;
+    asm("v_bcnt_u32_b32 %0, %1, %2" : "=v"(d) : "v"(x), "v"(acc));
+    return d;
+}
+__device__ __forceinline__ int bcnt_seed(uint32_t x, int seed)
+{
+    int d;
+    asm("v_bcnt_u32_b32 %0, %1, %2" : "=v"(d) : "v"(x), "s"(seed));
+    return d;
+}
+
+template <int G, bool INTEGER>
+__global__ __launch_bounds__(kThreads) void popcount_gemm_kernel(const PopcountGemmArgs a)
+{
+    constexpr int kWordsPerGran = G / 32;                       // 1, 2, 4, 8
+    constexpr int kGranPerChunk = kCK / kWordsPerGran;          // 16, 8, 4, 2
+    constexpr int kSteps = kCK / kStep;                         // 8
+    constexpr int kSeed = INTEGER ? 0 : -(G / 2);
+
+    __shared__ __attribute__((aligned(16))) uint32_t s_bits[2][kTileP * kBitsStride];
+    __shared__ __attribute__((aligned(16))) float s_ps[INTEGER ? 1 : 2][INTEGER ? 1 : kTileP * kScaleStrideP];
+    __shared__ __attribute__((aligned(16))) float s_qs[INTEGER ? 1 : 2][INTEGER ? 1 : kMaxScalesPerChunk * kTileQ];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tile_p = blockIdx.x % a.tiles_p;
+    const int tile_q = blockIdx.x / a.tiles_p;
+    const int p0 = tile_p * kTileP;
+    const int q0_wg = tile_q * kTileQ;
+    const int q0 = q0_wg + wave * kTQ;
+
+    const int nchunks = (a.kwords + kCK - 1) / kCK;
+    // scale entries per chunk for each operand: 512 / beta = kGranPerChunk >> shift
+    const int nsp = INTEGER ? 0 : (kGranPerChunk >> a.shift_p);
+    const int nsq = INTEGER ? 0 : (kGranPerChunk >> a.shift_q);
+    const int nblk_p = INTEGER ? 0 : (a.ngran >> a.shift_p);
+    const int nblk_q = INTEGER ? 0 : (a.ngran >> a.shift_q);
+
+    // ---- staging registers for the next chunk
+    constexpr int kBitPieces = kTileP * (kCK / 4) / kThreads;             // 2 x 16 bytes per thread
+    constexpr int kPsPerThread = kTileP * kGranPerChunk / kThreads;       // <= 8
+    constexpr int kQsPerThread = (kTileQ * kGranPerChunk + kThreads - 1) / kThreads;  // <= 4
+    uint4 st_bits[kBitPieces];
+    float st_ps[INTEGER ? 1 : kPsPerThread];
+    float st_qs[INTEGER ? 1 : kQsPerThread];
+
+    auto fetch = [&](int chunk) {
+#pragma unroll
+        for (int r = 0; r < kBitPieces; ++r) {
+            const int id = tid + r * kThreads;
+            const int row = p0 + id / (kCK / 4);
+            const int w = chunk * kCK + (id % (kCK / 4)) * 4;
+            st_bits[r] = make_uint4(0, 0, 0, 0);
+            if (row < a.P && w < a.kwords)
+                st_bits[r] = *reinterpret_cast<const uint4 *>(a.p_bits + (int64_t)row * a.ldw_p + w);
+        }
+        if constexpr (!INTEGER) {
+#pragma unroll
+            for (int r = 0; r < kPsPerThread; ++r) {
+                const int id = tid + r * kThreads;
+                const int row = p0 + id / kGranPerChunk;
+                const int e = id % kGranPerChunk;
+                const int blk = chunk * nsp + e;
+                st_ps[r] = 0.f;
+                if (e < nsp && row < a.P && blk < nblk_p) st_ps[r] = a.p_scales[(int64_t)row * a.lds_p + blk];
+            }
+#pragma unroll
+            for (int r = 0; r < kQsPerThread; ++r) {
+                const int id = tid + r * kThreads;
+                const int row = q0_wg + id / kGranPerChunk;
+                const int e = id % kGranPerChunk;
+                const int blk = chunk * nsq + e;
+                st_qs[r] = 0.f;
+                if (id < kTileQ * kGranPerChunk && e < nsq && row < a.Q && blk < nblk_q)
+                    st_qs[r] = a.q_scales[(int64_t)row * a.lds_q + blk];
+            }
+        }
+    };
+    auto park = [&](int buf) {
+#pragma unroll
+        for (int r = 0; r < kBitPieces; ++r) {
+            const int id = tid + r * kThreads;
+            const int row = id / (kCK / 4);
+            const int w = (id % (kCK / 4)) * 4;
+            uint32_t *dst = &s_bits[buf][row * kBitsStride + w];
+            // rows start at an 8-byte boundary only (stride 18 words): two 8-byte stores
+            *reinterpret_cast<uint2 *>(dst) = make_uint2(st_bits[r].x, st_bits[r].y);
+            *reinterpret_cast<uint2 *>(dst + 2) = make_uint2(st_bits[r].z, st_bits[r].w);
+        }
+        if constexpr (!INTEGER) {
+#pragma unroll
+            for (int r = 0; r < kPsPerThread; ++r) {
+                const int id = tid + r * kThreads;
+                s_ps[buf][(id / kGranPerChunk) * kScaleStrideP + id % kGranPerChunk] = st_ps[r];
+            }
+#pragma unroll
+            for (int r = 0; r < kQsPerThread; ++r) {
+                const int id = tid + r * kThreads;
+                if (id < kTileQ * kGranPerChunk)
+                    s_qs[buf][(id % kGranPerChunk) * kTileQ + id / kGranPerChunk] = st_qs[r];
+            }
+        }
+    };
+
+    // ---- accumulators
+    int acc[kTP][kTQ];
+    float res[INTEGER ? 1 : kTP][INTEGER ? 1 : kTQ];
+#pragma unroll
+    for (int i = 0; i < kTP; ++i)
+#pragma unroll
+        for (int q = 0; q < kTQ; ++q) {
+            acc[i][q] = kSeed;
+            if (!INTEGER) res[i][q] = 0.f;
+        }
+
+    // scalar-side row offsets in bytes (rows past Q re-read row Q-1; their results are never stored)
+    typedef const char __attribute__((address_space(4))) *const_byte_ptr;
+    const const_byte_ptr qbase = (const_byte_ptr)a.q_bits;
+    uint32_t qoff[kTQ];
+#pragma unroll
+    for (int q = 0; q < kTQ; ++q) qoff[q] = (uint32_t)(min(q0 + q, a.Q - 1) * a.ldw_q) * 4u;
+
+    fetch(0);
+    park(0);
+    __syncthreads();
+
+    // Scales of segment g_local of the chunk in `buf`: sp = -2 * sP (folds d = -2 * acc), sq = sQ.
+    auto load_scales = [&](float (&sp)[kTP], float (&sq)[kTQ], int buf, int g_local) {
+#pragma unroll
+        for (int i = 0; i < kTP; ++i)
+            sp[i] = s_ps[buf][(lane + 64 * i) * kScaleStrideP + (g_local >> a.shift_p)];
+        const float4 *sq4 =
+            reinterpret_cast<const float4 *>(&s_qs[buf][(g_local >> a.shift_q) * kTileQ + wave * kTQ]);
+#pragma unroll
+        for (int v = 0; v < kTQ / 4; ++v) {
+            const float4 t = sq4[v];
+            sq[4 * v + 0] = t.x;
+            sq[4 * v + 1] = t.y;
+            sq[4 * v + 2] = t.z;
+            sq[4 * v + 3] = t.w;
+        }
+    };
+    // Epilogue of one segment: res += (acc * -2 sP) * sQ  (acc = hamming - G/2, so -2 acc = d).
+    auto epilogue = [&](const float (&sp)[kTP], const float (&sq)[kTQ]) {
+#pragma unroll
+        for (int i = 0; i < kTP; ++i) {
+            const float sp2 = -2.0f * sp[i];
+#pragma unroll
+            for (int q = 0; q < kTQ; ++q)
+                res[i][q] = __builtin_fmaf((float)acc[i][q] * sp2, sq[q], res[i][q]);
+        }
+        // Pin the results here: without a use at this point the optimiser sinks the whole epilogue
+        // to the end of the chunk and keeps every segment's accumulators alive until then.
+#pragma unroll
+        for (int i = 0; i < kTP; ++i)
+#pragma unroll
+            for (int q = 0; q < kTQ; ++q) asm volatile("" : "+v"(res[i][q]));
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    // Scalar loads of Q words.  `a.step_words` is kStep at run time; passing it as an argument keeps
+    // the compiler from fusing the loads of consecutive steps into wider ones, which would need more
+    // scalar registers than exist.
+    auto load_q = [&](u32x2 (&qw)[kTQ], int step_index, int wbase) {
+        const const_byte_ptr base = qbase + (int64_t)(wbase + step_index * a.step_words) * 4;
+#pragma unroll
+        for (int q = 0; q < kTQ; ++q) qw[q] = *(const_u32x2_ptr)(base + (uint64_t)qoff[q]);
+    };
+    auto load_p = [&](u32x2 (&pw)[kTP], int buf, int s) {
+        const uint32_t *lbits = &s_bits[buf][lane * kBitsStride + s * kStep];
+#pragma unroll
+        for (int i = 0; i < kTP; ++i) pw[i] = *reinterpret_cast<const u32x2 *>(lbits + i * 64 * kBitsStride);
+    };
+    // One word of one half of the Q rows: 32 x (v_xor_b32 + v_bcnt_u32_b32).
+    auto reduce_half = [&](const uint32_t (&pwv)[kTP], const uint32_t (&qwv)[kTQ], int half, bool first) {
+#pragma unroll
+        for (int q = half * (kTQ / 2); q < (half + 1) * (kTQ / 2); ++q)
+#pragma unroll
+            for (int i = 0; i < kTP; ++i)
+                acc[i][q] = first ? bcnt_seed(pwv[i] ^ qwv[q], kSeed) : bcnt_acc(pwv[i] ^ qwv[q], acc[i][q]);
+    };
+
+    // Chunks whose 16 words all lie inside K: branch-free and fully unrolled.  Per step the first
+    // half of the Q rows is reduced (its first instruction absorbs the wait for this step's
+    // operands), then the next step's operands are requested, then the second half is reduced
+    // while those requests are in flight.
+    const int nfull = INTEGER ? a.kwords / kCK : (a.ngran * kWordsPerGran) / kCK;
+    int chunk = 0;
+    for (; chunk < nfull; ++chunk) {
+        const int buf = chunk & 1;
+        fetch(chunk + 1);   // past the last chunk every guard fails and zeros are staged
+        const int wbase = chunk * kCK;
+
+        u32x2 pw[2][kTP];
+        u32x2 qw[2][kTQ];
+        float sp[kTP], sq[kTQ];
+        load_p(pw[0], buf, 0);
+        load_q(qw[0], 0, wbase);
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s) {
+            const int cur = s & 1;
+            const bool first0 = !INTEGER && ((s * kStep) % kWordsPerGran == 0);
+            const bool first1 = !INTEGER && ((s * kStep + 1) % kWordsPerGran == 0);
+            const bool last0 = !INTEGER && ((s * kStep + 1) % kWordsPerGran == 0);
+            const bool last1 = !INTEGER && ((s * kStep + 2) % kWordsPerGran == 0);
+            uint32_t px[kTP], py[kTP], qx[kTQ], qy[kTQ];
+#pragma unroll
+            for (int i = 0; i < kTP; ++i) { px[i] = pw[cur][i].x; py[i] = pw[cur][i].y; }
+#pragma unroll
+            for (int q = 0; q < kTQ; ++q) { qx[q] = qw[cur][q].x; qy[q] = qw[cur][q].y; }
+
+            if (last0) {
+                // one-word segments: both words end a segment; no room to hide the scale reads
+                reduce_half(px, qx, 0, first0);
+                reduce_half(px, qx, 1, first0);
+                load_scales(sp, sq, buf, (s * kStep) / kWordsPerGran);
+                epilogue(sp, sq);
+                reduce_half(py, qy, 0, first1);
+                __builtin_amdgcn_sched_barrier(0);
+                if (s + 1 < kSteps) {
+                    load_p(pw[cur ^ 1], buf, s + 1);
+                    load_q(qw[cur ^ 1], s + 1, wbase);
+                }
+                load_scales(sp, sq, buf, (s * kStep + 1) / kWordsPerGran);
+                __builtin_amdgcn_sched_barrier(0);
+                reduce_half(py, qy, 1, first1);
+                epilogue(sp, sq);
+            } else {
+                reduce_half(px, qx, 0, first0);
+                reduce_half(py, qy, 0, first1);
+                __builtin_amdgcn_sched_barrier(0);
+                if (s + 1 < kSteps) {
+                    load_p(pw[cur ^ 1], buf, s + 1);
+                    load_q(qw[cur ^ 1], s + 1, wbase);
+                }
+                if (last1) load_scales(sp, sq, buf, (s * kStep + 1) / kWordsPerGran);
+                __builtin_amdgcn_sched_barrier(0);
+                reduce_half(px, qx, 1, first0);
+                reduce_half(py, qy, 1, first1);
+                if (last1) epilogue(sp, sq);
+            }
+        }
+        park(buf ^ 1);
+        __syncthreads();
+    }
+    // Ragged last chunk (at most one): word-at-a-time loop with explicit accumulator resets.
+    if (!INTEGER && chunk < nchunks) {
+#pragma unroll
+        for (int i = 0; i < kTP; ++i)
+#pragma unroll
+            for (int q = 0; q < kTQ; ++q) acc[i][q] = kSeed;
+    }
+    for (; chunk < nchunks; ++chunk) {
+        const int buf = chunk & 1;
+        const int wbase = chunk * kCK;
+        for (int w = 0; w < kCK && wbase + w < a.kwords; ++w) {
+            uint32_t pw1[kTP];
+#pragma unroll
+            for (int i = 0; i < kTP; ++i) pw1[i] = s_bits[buf][(lane + 64 * i) * kBitsStride + w];
+#pragma unroll
+            for (int q = 0; q < kTQ; ++q) {
+                const uint32_t qw1 = *(const_u32_ptr)(qbase + (uint64_t)qoff[q] + (int64_t)(wbase + w) * 4);
+#pragma unroll
+                for (int i = 0; i < kTP; ++i) acc[i][q] += __builtin_popcount(pw1[i] ^ qw1);
+            }
+            if (!INTEGER && (w + 1) % kWordsPerGran == 0) {
+                const int g_local = w / kWordsPerGran;
+                if (chunk * kGranPerChunk + g_local < a.ngran) {
+                    float sp[kTP], sq[kTQ];
+                    load_scales(sp, sq, buf, g_local);
+                    epilogue(sp, sq);
+                }
+#pragma unroll
+                for (int i = 0; i < kTP; ++i)
+#pragma unroll
+                    for (int q = 0; q < kTQ; ++q) acc[i][q] = kSeed;
+            }
+        }
+    }
+
+    // ---- store
+#pragma unroll
+    for (int i = 0; i < kTP; ++i) {
+        const int p = p0 + lane + 64 * i;
+        if (p >= a.P) continue;
+#pragma unroll
+        for (int q = 0; q < kTQ; ++q) {
+            const int qq = q0 + q;
+            if (qq >= a.Q) continue;
+            const int64_t off = (int64_t)p * a.ld_out_p + (int64_t)qq * a.ld_out_q;
+            if (INTEGER)
+                reinterpret_cast<int32_t *>(a.out)[off] = a.K - 2 * acc[i][q];
+            else
+                reinterpret_cast<float *>(a.out)[off] = res[i][q];
+        }
+    }
+}
+
+template <int G, bool INTEGER>
+hipError_t launch(const PopcountGemmArgs &a, hipStream_t s)
+{
+    const int64_t tiles_q = (a.Q + kTileQ - 1) / kTileQ;
+    const int64_t nblocks = (int64_t)a.tiles_p * tiles_q;
+    if (nblocks <= 0) return hipSuccess;
+    if (nblocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    popcount_gemm_kernel<G, INTEGER><<<dim3((unsigned)nblocks), dim3(kThreads), 0, s>>>(a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_popcount_gemm(const PopcountGemmArgs &args, int G, int integer, hipStream_t s)
+{
+    PopcountGemmArgs a = args;
+    a.tiles_p = (a.P + kTileP - 1) / kTileP;
+    a.step_words = kStep;
+    if (integer) return launch<64, true>(a, s);
+    switch (G) {
+    case 32: return launch<32, false>(a, s);
+    case 64: return launch<64, false>(a, s);
+    case 128: return launch<128, false>(a, s);
+    case 256: return launch<256, false>(a, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace hbmm

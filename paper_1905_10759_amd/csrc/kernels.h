@@ -1,0 +1,62 @@
+// Internal launch interface between the C-ABI layer (api.hip) and the kernel files.
+// Every launcher validates nothing: shapes, alignment and supported sets are checked by the
+// caller in api.hip before any of these is reached.  Each returns the hipError_t of its launch.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hbmm {
+
+// Words written per packed row: ceil(K/32) rounded up to a multiple of 4.
+inline int64_t packed_words(int64_t K) { return ((K + 31) / 32 + 3) / 4 * 4; }
+
+// ---- pack.hip ---------------------------------------------------------------------------------
+hipError_t launch_pack_rows(const float *x, int64_t rows, int64_t K, int64_t ldx, int beta,
+                            uint32_t *bits, int64_t ldw, float *scales, int64_t lds, hipStream_t s);
+hipError_t launch_pack_cols(const float *x, int64_t rows, int64_t K, int64_t ldx, int beta,
+                            uint32_t *bits, int64_t ldw, float *scales, int64_t lds, hipStream_t s);
+
+// ---- gemm_popcount.hip ------------------------------------------------------------------------
+// One operand ("P") is held per lane, the other ("Q") is broadcast through scalar registers.
+// out[p * ld_out_p + q * ld_out_q] receives the result for P-row p and Q-row q, so either of
+// A / B can play either role.
+struct PopcountGemmArgs {
+    const uint32_t *p_bits;
+    const float *p_scales;
+    const uint32_t *q_bits;
+    const float *q_scales;
+    void *out;           // float* (scaled) or int32_t* (integer mode)
+    int64_t ld_out_p;
+    int64_t ld_out_q;
+    int32_t P, Q;        // rows of each operand
+    int32_t ldw_p, ldw_q;
+    int32_t lds_p, lds_q;
+    int32_t kwords;      // words per row that are read: packed_words(K)
+    int32_t ngran;       // K / G   (scaled mode)
+    int32_t shift_p;     // log2(beta_p / G)
+    int32_t shift_q;     // log2(beta_q / G)
+    int32_t K;           // bits (integer mode: D = K - 2 * hamming)
+    int32_t tiles_p;     // ceil(P / tile)
+    int32_t step_words;  // always 2; a run-time value on purpose (see load_q in the kernel)
+};
+// G = min(beta_p, beta_q) in {32, 64, 128, 256}; integer != 0 selects the unscaled whole-row mode.
+hipError_t launch_popcount_gemm(const PopcountGemmArgs &a, int G, int integer, hipStream_t s);
+
+// ---- gemm_binary_weight.hip -------------------------------------------------------------------
+hipError_t launch_binary_weight_gemm(const float *A, int64_t lda, const uint32_t *b_bits,
+                                     const float *b_scales, int64_t ldw_b, int64_t lds_b, int beta_w,
+                                     int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
+                                     hipStream_t s);
+
+// ---- gemm_mfma_i8.hip -------------------------------------------------------------------------
+hipError_t launch_mfma_i8_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a,
+                               int64_t lds_a, int beta_a, const uint32_t *b_bits,
+                               const float *b_scales, int64_t ldw_b, int64_t lds_b, int beta_w,
+                               int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, hipStream_t s);
+
+// ---- dense_ref.hip ----------------------------------------------------------------------------
+hipError_t launch_dense_ref(const void *A, int64_t lda, const void *B, int64_t ldb, int dtype,
+                            int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, hipStream_t s);
+
+}  // namespace hbmm

@@ -1,0 +1,182 @@
+// Hadamard binarisation of one operand in a single pass: block scales (HadaNets Eq. 1 / Eq. 3),
+// Sign (Eq. 2 / Eq. 4) and bit-packing (section 4), for gfx950.
+//
+// The pass is bound by HBM reads: 4 bytes in per element against 1/8 + 4/beta bytes out.
+//
+// pack_rows_kernel (source rows x K, K contiguous):
+//   A wave covers 256 consecutive K elements of one row with one 16-byte load per lane, and keeps
+//   kUnroll such loads in flight.  Lane l holds elements 4l .. 4l+3, i.e. one nibble of the packed
+//   word; the eight nibbles of a 32-bit word sit in eight consecutive lanes and are OR-ed together
+//   with three DPP steps, so no ballot-reordering is needed.  |x| is summed as
+//   (|x0|+|x1|)+(|x2|+|x3|) in the lane and then pairwise over the beta/4 lanes of the segment.
+//
+// pack_cols_kernel (source K x rows, rows contiguous): a lane owns one output row and walks K, so
+//   every load is a coalesced 256-byte wave access; the word is built with shifts and the scale
+//   is a sequential double-precision sum rounded once.
+#include "kernels.h"
+
+namespace hbmm {
+namespace {
+
+constexpr int kUnroll = 4;          // 16-byte loads in flight per lane
+constexpr int kChunk = 256;         // K elements per wave per load
+constexpr int kWavesPerBlock = 4;
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+constexpr int kQuadSwap1 = 0xB1;    // quad_perm [1,0,3,2]
+constexpr int kQuadSwap2 = 0x4E;    // quad_perm [2,3,0,1]
+constexpr int kHalfMirror = 0x141;  // lane i <-> 7-i inside each group of 8
+constexpr int kRowMirror = 0x140;   // lane i <-> 15-i inside each group of 16
+
+// Sum over `LANES` consecutive lanes (a power of two, aligned); every lane gets the result.
+template <int LANES>
+__device__ __forceinline__ float segment_sum(float v)
+{
+    if (LANES >= 2) v += dpp_f32<kQuadSwap1>(v);
+    if (LANES >= 4) v += dpp_f32<kQuadSwap2>(v);
+    if (LANES >= 8) v += dpp_f32<kHalfMirror>(v);
+    if (LANES >= 16) v += dpp_f32<kRowMirror>(v);
+    if (LANES >= 32) v += __shfl_xor(v, 16);
+    if (LANES >= 64) v += __shfl_xor(v, 32);
+    return v;
+}
+
+template <int BETA, bool VEC>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void pack_rows_kernel(
+    const float *__restrict__ x, int64_t rows, int K, int64_t ldx, uint32_t *__restrict__ bits,
+    int64_t ldw, float *__restrict__ scales, int64_t lds, int words_valid)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const int kbase = blockIdx.y * (kUnroll * kChunk) + 4 * lane;
+    const float *xr = x + row * ldx;
+
+    float4 v[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        const int k = kbase + u * kChunk;
+        v[u] = make_float4(-1.f, -1.f, -1.f, -1.f);   // sign bit 0; excluded from sums by `k < K` below
+        if (k < K) {
+            if (VEC) {
+                v[u] = *reinterpret_cast<const float4 *>(xr + k);
+            } else {
+                v[u].x = xr[k];
+                v[u].y = xr[k + 1];
+                v[u].z = xr[k + 2];
+                v[u].w = xr[k + 3];
+            }
+        }
+    }
+
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        const int k = kbase + u * kChunk;
+        const bool live = k < K;
+        // --- signs -> nibble -> 32-bit word over 8 lanes
+        uint32_t nib = (v[u].x >= 0.f ? 1u : 0u) | (v[u].y >= 0.f ? 2u : 0u) |
+                       (v[u].z >= 0.f ? 4u : 0u) | (v[u].w >= 0.f ? 8u : 0u);
+        uint32_t w = nib << (4 * (lane & 7));
+        w |= dpp_u32<kQuadSwap1>(w);
+        w |= dpp_u32<kQuadSwap2>(w);
+        w |= dpp_u32<kHalfMirror>(w);
+        const int widx = k >> 5;
+        if ((lane & 7) == 0 && widx < words_valid) bits[row * ldw + widx] = w;
+        // --- mean |x| over the beta-segment
+        float p = live ? (fabsf(v[u].x) + fabsf(v[u].y)) + (fabsf(v[u].z) + fabsf(v[u].w)) : 0.f;
+        p = segment_sum<BETA / 4>(p);
+        if ((lane & (BETA / 4 - 1)) == 0 && live) scales[row * lds + k / BETA] = p * (1.0f / BETA);
+    }
+}
+
+template <int BETA>
+__global__ __launch_bounds__(256) void pack_cols_kernel(
+    const float *__restrict__ x, int64_t rows, int K, int64_t ldx, uint32_t *__restrict__ bits,
+    int64_t ldw, float *__restrict__ scales, int64_t lds, int words_valid)
+{
+    constexpr int kSpan = 256;   // K elements per thread: a whole number of segments for every beta
+    const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (r >= rows) return;
+    const int k0 = blockIdx.y * kSpan;
+    const int k1 = min(K, k0 + kSpan);
+    double acc = 0.0;
+    for (int kw = k0; kw < k1; kw += 32) {
+        uint32_t w = 0;
+#pragma unroll 8
+        for (int b = 0; b < 32; ++b) {
+            const float v = x[(int64_t)(kw + b) * ldx + r];
+            w |= (v >= 0.f ? 1u : 0u) << b;
+            acc += fabs((double)v);
+        }
+        bits[r * ldw + (kw >> 5)] = w;
+        if (((kw + 32) & (BETA - 1)) == 0) {
+            scales[r * lds + kw / BETA] = (float)(acc / (double)BETA);
+            acc = 0.0;
+        }
+    }
+    if (k1 == K)
+        for (int w = K >> 5; w < words_valid; ++w) bits[r * ldw + w] = 0u;
+}
+
+template <int BETA>
+hipError_t pack_rows_beta(const float *x, int64_t rows, int64_t K, int64_t ldx, uint32_t *bits,
+                          int64_t ldw, float *scales, int64_t lds, hipStream_t s)
+{
+    dim3 grid((unsigned)((rows + kWavesPerBlock - 1) / kWavesPerBlock),
+              (unsigned)((K + kUnroll * kChunk - 1) / (kUnroll * kChunk)));
+    dim3 block(64 * kWavesPerBlock);
+    const int wv = (int)packed_words(K);
+    const bool vec = (ldx % 4 == 0) && ((reinterpret_cast<uintptr_t>(x) & 15) == 0);
+    if (vec)
+        pack_rows_kernel<BETA, true><<<grid, block, 0, s>>>(x, rows, (int)K, ldx, bits, ldw, scales, lds, wv);
+    else
+        pack_rows_kernel<BETA, false><<<grid, block, 0, s>>>(x, rows, (int)K, ldx, bits, ldw, scales, lds, wv);
+    return hipGetLastError();
+}
+
+template <int BETA>
+hipError_t pack_cols_beta(const float *x, int64_t rows, int64_t K, int64_t ldx, uint32_t *bits,
+                          int64_t ldw, float *scales, int64_t lds, hipStream_t s)
+{
+    dim3 grid((unsigned)((rows + 255) / 256), (unsigned)((K + 255) / 256));
+    pack_cols_kernel<BETA><<<grid, dim3(256), 0, s>>>(x, rows, (int)K, ldx, bits, ldw, scales, lds,
+                                                      (int)packed_words(K));
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_pack_rows(const float *x, int64_t rows, int64_t K, int64_t ldx, int beta,
+                            uint32_t *bits, int64_t ldw, float *scales, int64_t lds, hipStream_t s)
+{
+    switch (beta) {
+    case 32: return pack_rows_beta<32>(x, rows, K, ldx, bits, ldw, scales, lds, s);
+    case 64: return pack_rows_beta<64>(x, rows, K, ldx, bits, ldw, scales, lds, s);
+    case 128: return pack_rows_beta<128>(x, rows, K, ldx, bits, ldw, scales, lds, s);
+    case 256: return pack_rows_beta<256>(x, rows, K, ldx, bits, ldw, scales, lds, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_pack_cols(const float *x, int64_t rows, int64_t K, int64_t ldx, int beta,
+                            uint32_t *bits, int64_t ldw, float *scales, int64_t lds, hipStream_t s)
+{
+    switch (beta) {
+    case 32: return pack_cols_beta<32>(x, rows, K, ldx, bits, ldw, scales, lds, s);
+    case 64: return pack_cols_beta<64>(x, rows, K, ldx, bits, ldw, scales, lds, s);
+    case 128: return pack_cols_beta<128>(x, rows, K, ldx, bits, ldw, scales, lds, s);
+    case 256: return pack_cols_beta<256>(x, rows, K, ldx, bits, ldw, scales, lds, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace hbmm

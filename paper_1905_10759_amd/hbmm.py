@@ -1,0 +1,161 @@
+"""Thin binding over ``libhbmm.so``: argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; this module allocates outputs with
+torch (device memory and streams are the only things torch is used for), forwards raw device
+pointers and the current HIP stream, and raises on a non-zero return code.  There is no CPU
+fallback: if the library is missing or fails to load, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from pathlib import Path
+
+import torch
+
+_HERE = Path(__file__).resolve().parent
+LIB_PATH = _HERE / "libhbmm.so"
+
+OK, EINVAL, EUNSUPPORTED, ELAUNCH = 0, -1, -2, -3
+ALGO_POPCOUNT, ALGO_MFMA_I8 = 0, 1
+
+EXPORTS = (
+    "hbmm_strerror", "hbmm_num_blocks", "hbmm_packed_ld_words", "hbmm_quantize_pack", "hbmm_gemm",
+    "hbmm_gemm_int", "hbmm_dense_ref_gemm",
+)
+
+
+class HbmmError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} (code {code})")
+
+
+def _load() -> C.CDLL:
+    if not LIB_PATH.exists():
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_1905_10759_amd.build` "
+            "(or __graft_entry__.build()); there is no fallback path")
+    lib = C.CDLL(str(LIB_PATH))
+    i64, i32, p = C.c_int64, C.c_int32, C.c_void_p
+    lib.hbmm_strerror.restype = C.c_char_p
+    lib.hbmm_strerror.argtypes = [C.c_int]
+    lib.hbmm_num_blocks.restype = i64
+    lib.hbmm_num_blocks.argtypes = [i64, i32]
+    lib.hbmm_packed_ld_words.restype = i64
+    lib.hbmm_packed_ld_words.argtypes = [i64]
+    lib.hbmm_quantize_pack.restype = C.c_int
+    lib.hbmm_quantize_pack.argtypes = [p, i64, i64, i64, i32, i32, p, i64, p, i64, p]
+    lib.hbmm_gemm.restype = C.c_int
+    lib.hbmm_gemm.argtypes = [p, p, i64, i64, i32, p, p, i64, i64, i32, i64, i64, i64, p, i64, i32, p]
+    lib.hbmm_gemm_int.restype = C.c_int
+    lib.hbmm_gemm_int.argtypes = [p, i64, p, i64, i64, i64, i64, p, i64, p]
+    lib.hbmm_dense_ref_gemm.restype = C.c_int
+    lib.hbmm_dense_ref_gemm.argtypes = [p, i64, p, i64, i32, i64, i64, i64, p, i64, p]
+    return lib
+
+
+lib = _load()
+
+
+def strerror(code: int) -> str:
+    return lib.hbmm_strerror(int(code)).decode()
+
+
+def num_blocks(K: int, beta: int) -> int:
+    return int(lib.hbmm_num_blocks(K, beta))
+
+
+def packed_ld_words(K: int) -> int:
+    return int(lib.hbmm_packed_ld_words(K))
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != OK:
+        raise HbmmError(rc, where)
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> None:
+    if not t.is_cuda or t.dtype != dtype:
+        raise TypeError(f"{name}: expected a {dtype} device tensor")
+
+
+def quantize_pack(x: torch.Tensor, beta: int, layout: int = 0, bits: torch.Tensor | None = None,
+                  scales: torch.Tensor | None = None):
+    """hbmm_quantize_pack.  x: fp32 device matrix; layout 0 = rows x K, layout 1 = K x rows.
+    Returns (bits int32[rows, ldw] holding the uint32 words, scales fp32[rows, nb])."""
+    _dev(x, torch.float32, "x")
+    if x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be a 2-D matrix with unit inner stride")
+    rows, K = (x.shape[0], x.shape[1]) if layout == 0 else (x.shape[1], x.shape[0])
+    ldx = x.stride(0) if x.shape[0] > 1 else x.shape[1]
+    ldw, nb = packed_ld_words(K), num_blocks(K, beta)
+    if bits is None:
+        bits = torch.empty((rows, ldw), dtype=torch.int32, device=x.device)
+    if scales is None:
+        scales = torch.empty((rows, nb), dtype=torch.float32, device=x.device)
+    _dev(bits, torch.int32, "bits")
+    _dev(scales, torch.float32, "scales")
+    rc = lib.hbmm_quantize_pack(x.data_ptr(), rows, K, ldx, layout, beta, bits.data_ptr(),
+                                bits.stride(0) if rows > 1 else bits.shape[1], scales.data_ptr(),
+                                scales.stride(0) if rows > 1 else max(scales.shape[1], 1), _stream())
+    _check(rc, "hbmm_quantize_pack")
+    return bits, scales
+
+
+def gemm(a_bits, a_scales, beta_a: int, b_bits, b_scales, beta_w: int, K: int, algo: int = ALGO_POPCOUNT,
+         out: torch.Tensor | None = None) -> torch.Tensor:
+    """hbmm_gemm.  For beta_a == 1 pass a_bits=None and a_scales = the raw fp32 A (M x K)."""
+    _dev(b_bits, torch.int32, "b_bits")
+    _dev(b_scales, torch.float32, "b_scales")
+    _dev(a_scales, torch.float32, "a_scales")
+    M, N = a_scales.shape[0], b_bits.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=b_bits.device)
+    _dev(out, torch.float32, "out")
+    a_ptr, ldw_a = (0, 0)
+    if a_bits is not None:
+        _dev(a_bits, torch.int32, "a_bits")
+        a_ptr, ldw_a = a_bits.data_ptr(), a_bits.stride(0) if M > 1 else a_bits.shape[1]
+    rc = lib.hbmm_gemm(a_ptr, a_scales.data_ptr(), ldw_a,
+                       a_scales.stride(0) if M > 1 else max(a_scales.shape[1], 1), beta_a,
+                       b_bits.data_ptr(), b_scales.data_ptr(),
+                       b_bits.stride(0) if N > 1 else b_bits.shape[1],
+                       b_scales.stride(0) if N > 1 else max(b_scales.shape[1], 1), beta_w,
+                       M, N, K, out.data_ptr(), out.stride(0) if M > 1 else max(N, 1), algo, _stream())
+    _check(rc, "hbmm_gemm")
+    return out
+
+
+def gemm_int(a_bits, b_bits, K: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    """hbmm_gemm_int: D[m, n] = K - 2 * hamming(a_row, b_row), int32."""
+    _dev(a_bits, torch.int32, "a_bits")
+    _dev(b_bits, torch.int32, "b_bits")
+    M, N = a_bits.shape[0], b_bits.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=a_bits.device)
+    _dev(out, torch.int32, "out")
+    rc = lib.hbmm_gemm_int(a_bits.data_ptr(), a_bits.stride(0) if M > 1 else a_bits.shape[1],
+                           b_bits.data_ptr(), b_bits.stride(0) if N > 1 else b_bits.shape[1],
+                           M, N, K, out.data_ptr(), out.stride(0) if M > 1 else max(N, 1), _stream())
+    _check(rc, "hbmm_gemm_int")
+    return out
+
+
+def dense_ref_gemm(A: torch.Tensor, B: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """hbmm_dense_ref_gemm: C = A . B^T, A M x K, B N x K, fp32 or bf16 operands, fp32 result."""
+    if A.dtype != B.dtype or A.dtype not in (torch.float32, torch.bfloat16):
+        raise TypeError("A and B must both be fp32 or both bf16")
+    _dev(A, A.dtype, "A")
+    _dev(B, A.dtype, "B")
+    (M, K), N = A.shape, B.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=A.device)
+    rc = lib.hbmm_dense_ref_gemm(A.data_ptr(), A.stride(0) if M > 1 else K, B.data_ptr(),
+                                 B.stride(0) if N > 1 else K, 0 if A.dtype == torch.float32 else 1,
+                                 M, N, K, out.data_ptr(), out.stride(0) if M > 1 else max(N, 1), _stream())
+    _check(rc, "hbmm_dense_ref_gemm")
+    return out

@@ -1,0 +1,110 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+its size helpers agree with the layout contract, and argument validation rejects bad calls
+before anything is launched (so these run without a GPU)."""
+from __future__ import annotations
+
+import ctypes as C
+import re
+from pathlib import Path
+
+import pytest
+
+ROOT = Path(__file__).resolve().parent.parent
+LIB = ROOT / "paper_1905_10759_amd" / "libhbmm.so"
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not LIB.exists():
+        from paper_1905_10759_amd import build
+        build.build()
+    return C.CDLL(str(LIB))
+
+
+def declared_symbols():
+    text = (ROOT / "include" / "hbmm.h").read_text()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hbmm_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = declared_symbols()
+    assert {"hbmm_quantize_pack", "hbmm_gemm", "hbmm_dense_ref_gemm", "hbmm_gemm_int"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_binding_lists_same_symbols():
+    src = (ROOT / "paper_1905_10759_amd" / "hbmm.py").read_text()
+    for name in declared_symbols():
+        assert f'"{name}"' in src, name
+
+
+def test_size_helpers(lib):
+    lib.hbmm_num_blocks.restype = C.c_int64
+    lib.hbmm_num_blocks.argtypes = [C.c_int64, C.c_int32]
+    lib.hbmm_packed_ld_words.restype = C.c_int64
+    lib.hbmm_packed_ld_words.argtypes = [C.c_int64]
+    assert lib.hbmm_num_blocks(512, 32) == 16
+    assert lib.hbmm_num_blocks(513, 32) == 17
+    assert lib.hbmm_num_blocks(10, 0) == 0
+    assert [lib.hbmm_packed_ld_words(k) for k in (0, 1, 32, 33, 128, 129, 576, 8192)] == [0, 4, 4, 4, 4, 8, 20, 256]
+
+
+def test_strerror(lib):
+    lib.hbmm_strerror.restype = C.c_char_p
+    assert lib.hbmm_strerror(0) == b"ok"
+    for code in (-1, -2, -3, 7):
+        assert len(lib.hbmm_strerror(code)) > 3
+
+
+def test_validation_rejects_before_launch(lib):
+    i64, i32, p = C.c_int64, C.c_int32, C.c_void_p
+    qp = lib.hbmm_quantize_pack
+    qp.argtypes = [p, i64, i64, i64, i32, i32, p, i64, p, i64, p]
+    fake = 0x1000  # 16-byte aligned, never dereferenced: every call below fails validation first
+    assert qp(None, 4, 64, 64, 0, 32, fake, 4, fake, 2, None) == -1          # null x
+    assert qp(fake, 4, 64, 64, 0, 48, fake, 4, fake, 2, None) == -2          # beta not supported
+    assert qp(fake, 4, 96, 96, 0, 64, fake, 4, fake, 2, None) == -2          # K not a multiple of beta
+    assert qp(fake, 4, 64, 32, 0, 32, fake, 4, fake, 2, None) == -1          # ldx < K
+    assert qp(fake, 4, 64, 64, 0, 32, fake, 2, fake, 2, None) == -1          # ldw too small
+    assert qp(fake, 4, 64, 64, 0, 32, fake, 6, fake, 2, None) == -1          # ldw not a multiple of 4
+    assert qp(fake, 4, 64, 64, 0, 32, fake, 4, fake, 1, None) == -1          # lds too small
+    assert qp(fake + 4, 4, 64, 64, 0, 32, fake, 4, fake, 2, None) == -1      # misaligned
+    assert qp(fake, 4, 64, 64, 2, 32, fake, 4, fake, 2, None) == -1          # bad layout
+    assert qp(fake, -1, 64, 64, 0, 32, fake, 4, fake, 2, None) == -1
+    assert qp(None, 0, 64, 64, 0, 32, None, 4, None, 2, None) == 0           # empty is a no-op
+
+    g = lib.hbmm_gemm
+    g.argtypes = [p, p, i64, i64, i32, p, p, i64, i64, i32, i64, i64, i64, p, i64, i32, p]
+    ok = dict(a=fake, sa=fake, ldwa=4, ldsa=2, ba=32, b=fake, sb=fake, ldwb=4, ldsb=2, bw=32, M=8, N=8, K=64,
+              C=fake, ldc=8, algo=0)
+
+    def call(**kw):
+        a = {**ok, **kw}
+        return g(a["a"], a["sa"], a["ldwa"], a["ldsa"], a["ba"], a["b"], a["sb"], a["ldwb"], a["ldsb"], a["bw"],
+                 a["M"], a["N"], a["K"], a["C"], a["ldc"], a["algo"], None)
+
+    assert call(C=None) == -1
+    assert call(ldc=4) == -1
+    assert call(ba=16) == -2
+    assert call(bw=512) == -2
+    assert call(algo=5) == -2
+    assert call(K=96, ba=64, bw=32) == -2
+    assert call(a=None) == -1
+    assert call(ba=1, a=fake, ldsa=64) == -1      # beta_a = 1 takes raw A through a_scales, a_bits must be NULL
+    assert call(ba=1, a=None, ldsa=8) == -1       # lds_a is then the leading dimension of A (>= K)
+    assert call(ldwa=2) == -1
+    assert call(M=0) == 0 and call(N=0) == 0
+
+    gi = lib.hbmm_gemm_int
+    gi.argtypes = [p, i64, p, i64, i64, i64, i64, p, i64, p]
+    assert gi(None, 4, fake, 4, 8, 8, 64, fake, 8, None) == -1
+    assert gi(fake, 4, fake, 4, 8, 8, 64, fake, 4, None) == -1
+    assert gi(fake, 4, fake, 4, 0, 8, 64, fake, 8, None) == 0
+
+    d = lib.hbmm_dense_ref_gemm
+    d.argtypes = [p, i64, p, i64, i32, i64, i64, i64, p, i64, p]
+    assert d(fake, 64, fake, 64, 3, 8, 8, 64, fake, 8, None) == -2
+    assert d(None, 64, fake, 64, 0, 8, 8, 64, fake, 8, None) == -1
+    assert d(fake, 32, fake, 64, 0, 8, 8, 64, fake, 8, None) == -1

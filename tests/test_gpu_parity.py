@@ -1,0 +1,174 @@
+"""GPU parity: every entry point of libhbmm against the CPU oracle, element by element, on the
+same seeded inputs.  Packed words and integer sums must be bit-exact; scales and fp32 outputs
+within the documented tolerances."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1905_10759_amd import synth
+
+from gpu_common import assert_close_to_oracle, dev, words
+
+pytestmark = pytest.mark.gpu
+
+hbmm = None
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _load():
+    global hbmm
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    from paper_1905_10759_amd import hbmm as mod
+    hbmm = mod
+    yield
+    torch.cuda.synchronize()
+
+
+def scale_tol(beta: int) -> float:
+    # pairwise fp32 sum of beta magnitudes: log2(beta) roundings, plus the oracle's own final rounding
+    return (np.log2(beta) + 1) * 2.0 ** -24
+
+
+# ------------------------------------------------------------------------------ quantize_pack
+@pytest.mark.parametrize("beta", [32, 64, 128, 256])
+@pytest.mark.parametrize("rows,K", [(1, 256), (5, 768), (67, 1280), (130, 4608), (3, 256 * 9)])
+def test_pack_rows(beta, rows, K):
+    x = synth.normal(100 + beta + rows, (rows, K))
+    x[0, :4] = [0.0, -0.0, 1e-38, -1e-38]
+    bits, scales = hbmm.quantize_pack(dev(x), beta)
+    torch.cuda.synchronize()
+    assert np.array_equal(words(bits), oracle.sign_pack(x))
+    ref = oracle.block_scales(x, beta)
+    got = scales.cpu().numpy()
+    assert got.shape == ref.shape
+    assert np.all(np.abs(got - ref) <= scale_tol(beta) * ref)
+
+
+def test_pack_rows_ragged_k_and_strided_source():
+    """K = 576 (two and a quarter wave chunks), source with a padded leading dimension, and a
+    source whose rows are not 16-byte aligned (scalar-load variant)."""
+    K, beta = 576, 64
+    x = synth.relu_normal(7, (37, K))
+    wide = torch.zeros((37, K + 24), dtype=torch.float32, device="cuda")
+    wide[:, :K] = dev(x)
+    for src in (wide[:, :K], ):
+        bits, scales = hbmm.quantize_pack(src, beta)
+        assert np.array_equal(words(bits), oracle.sign_pack(x))
+        ref = oracle.block_scales(x, beta)
+        assert np.all(np.abs(scales.cpu().numpy() - ref) <= scale_tol(beta) * ref + 1e-30)
+    odd = torch.zeros((37, K + 3), dtype=torch.float32, device="cuda")
+    odd[:, :K] = dev(x)
+    bits, scales = hbmm.quantize_pack(odd[:, :K], beta)
+    assert np.array_equal(words(bits), oracle.sign_pack(x))
+    assert (words(bits)[:, K // 32:] == 0).all()
+
+
+@pytest.mark.parametrize("beta", [32, 64, 128, 256])
+def test_pack_cols(beta):
+    K, rows = 1024, 333
+    xkn = synth.normal(200 + beta, (K, rows))
+    bits, scales = hbmm.quantize_pack(dev(xkn), beta, layout=1)
+    xt = oracle.as_rows_by_k(xkn, 1)
+    assert np.array_equal(words(bits), oracle.sign_pack(xt))
+    # double-precision sequential sum in the same order as the oracle: identical fp32 scales
+    assert np.array_equal(scales.cpu().numpy(), oracle.block_scales(xt, beta))
+
+
+def test_pack_all_zero_and_negative():
+    x = np.zeros((4, 256), dtype=np.float32)
+    x[1] = -1.0
+    x[2] = -0.0
+    bits, scales = hbmm.quantize_pack(dev(x), 128)
+    w = words(bits)
+    assert (w[0, :8] == 0xFFFFFFFF).all() and (w[1] == 0).all() and (w[2, :8] == 0xFFFFFFFF).all()
+    assert np.array_equal(scales.cpu().numpy(), np.array([[0, 0], [1, 1], [0, 0], [0, 0]], dtype=np.float32))
+
+
+# ---------------------------------------------------------------------------------- gemm_int
+@pytest.mark.parametrize("M,N,K", [(64, 64, 512), (1, 1, 32), (300, 130, 1000), (257, 129, 544), (40, 600, 4608),
+                                   (513, 17, 96)])
+def test_gemm_int_bit_exact(M, N, K):
+    A, B = synth.normal(300 + M, (M, K)), synth.normal(301 + N, (N, K))
+    a, b = oracle.sign_pack(A), oracle.sign_pack(B)
+    D = hbmm.gemm_int(dev(a.view(np.int32)), dev(b.view(np.int32)), K)
+    assert np.array_equal(D.cpu().numpy(), oracle.int_dot(a, b, K))
+
+
+# -------------------------------------------------------------------------------------- gemm
+def run_gemm_case(A, B, beta_a, beta_w, algo=0):
+    """GEMM parity with the SAME packed words and fp32 scales on both sides (oracle-made), so that
+    only the contraction and its epilogue are under test."""
+    M, K = A.shape
+    a_bits, b_bits = oracle.sign_pack(A), oracle.sign_pack(B)
+    a_s, b_s = oracle.block_scales(A, beta_a), oracle.block_scales(B, beta_w)
+    ref, T = oracle.popcount_gemm(a_bits, a_s, beta_a, b_bits, b_s, beta_w, K, want_T=True)
+    got = hbmm.gemm(dev(a_bits.view(np.int32)), dev(a_s), beta_a, dev(b_bits.view(np.int32)), dev(b_s), beta_w, K,
+                    algo=algo)
+    return assert_close_to_oracle(got.cpu().numpy(), ref, T, f"gemm {A.shape}x{B.shape} b=({beta_a},{beta_w})")
+
+
+@pytest.mark.parametrize("beta", [32, 64, 128, 256])
+@pytest.mark.parametrize("M,N,K", [(64, 64, 512), (300, 200, 1024), (129, 257, 1536), (5, 3, 256), (260, 140, 4608)])
+def test_gemm_equal_beta(beta, M, N, K):
+    run_gemm_case(synth.normal(400 + M, (M, K)), synth.uniform_pm1(401 + N, (N, K)), beta, beta)
+
+
+@pytest.mark.parametrize("beta_a,beta_w", [(32, 64), (64, 32), (32, 256), (256, 32), (128, 64), (64, 256)])
+def test_gemm_mixed_beta(beta_a, beta_w):
+    run_gemm_case(synth.relu_normal(500, (150, 1280)), synth.normal(501, (270, 1280), std=0.04), beta_a, beta_w)
+
+
+def test_gemm_against_dense_f64_path_end_to_end():
+    """Whole hot path on the GPU (pack A, pack B, gemm) against the dense double-precision oracle
+    that materialises delta (.) Sign(.) and multiplies.  GPU-made scales differ from the oracle's
+    by a few ulp, which the same tolerance absorbs."""
+    M, N, K, beta = 200, 136, 2048, 64
+    A, B = synth.normal(600, (M, K)), synth.normal(601, (N, K))
+    ab, as_ = hbmm.quantize_pack(dev(A), beta)
+    bb, bs = hbmm.quantize_pack(dev(B), beta)
+    got = hbmm.gemm(ab, as_, beta, bb, bs, beta, K).cpu().numpy()
+    ref = oracle.hbmm_dense(A, B, beta, beta)
+    _, T = oracle.hbmm_popcount(A, B, beta, beta, want_T=True)
+    assert_close_to_oracle(got, ref, T, "end to end")
+
+
+def test_gemm_whole_row_scale_is_xnor_net():
+    """beta = K = 256 for both operands: C = sA[m] sB[n] D[m, n]."""
+    K = 256
+    A, B = synth.normal(610, (70, K)), synth.normal(611, (90, K))
+    ab, as_ = hbmm.quantize_pack(dev(A), K)
+    bb, bs = hbmm.quantize_pack(dev(B), K)
+    C = hbmm.gemm(ab, as_, K, bb, bs, K, K).cpu().numpy().astype(np.float64)
+    D = hbmm.gemm_int(ab, bb, K).cpu().numpy().astype(np.float64)
+    want = as_.cpu().numpy().astype(np.float64) * bs.cpu().numpy().astype(np.float64).T * D
+    assert np.allclose(C, want, rtol=3e-7, atol=0)
+
+
+@pytest.mark.parametrize("beta_w", [32, 64, 128, 256])
+@pytest.mark.parametrize("M,N,K", [(64, 64, 512), (100, 70, 1280), (33, 130, 4608)])
+def test_gemm_binary_weight(beta_w, M, N, K):
+    """beta_a = 1: fp32 activations against packed weights."""
+    A, B = synth.relu_normal(700 + M, (M, K)), synth.normal(701 + N, (N, K), std=float(np.sqrt(2.0 / K)))
+    b_bits, b_s = oracle.sign_pack(B), oracle.block_scales(B, beta_w)
+    ref, T = oracle.binary_weight_gemm(A, b_bits, b_s, beta_w, want_T=True)
+    got = hbmm.gemm(None, dev(A), 1, dev(b_bits.view(np.int32)), dev(b_s), beta_w, K)
+    assert_close_to_oracle(got.cpu().numpy(), ref, T, "binary weight")
+
+
+def test_gemm_empty_and_zero_k():
+    e = torch.empty((0, 4), dtype=torch.int32, device="cuda")
+    s = torch.empty((0, 1), dtype=torch.float32, device="cuda")
+    b = torch.zeros((8, 4), dtype=torch.int32, device="cuda")
+    sb = torch.ones((8, 1), dtype=torch.float32, device="cuda")
+    assert hbmm.gemm(e, s, 32, b, sb, 32, 32).shape == (0, 8)
+    assert hbmm.gemm_int(e, b, 32).shape == (0, 8)
+
+
+def test_unsupported_is_reported_not_faked():
+    x = torch.zeros((4, 96), dtype=torch.float32, device="cuda")
+    with pytest.raises(hbmm.HbmmError) as ei:
+        hbmm.quantize_pack(x, 48)
+    assert ei.value.code == hbmm.EUNSUPPORTED
