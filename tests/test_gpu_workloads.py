@@ -1,0 +1,82 @@
+"""The five benchmark workloads (and the binary-weight variant of the third) at FULL size, in the
+launch configuration bench.py times: packed words and integer dots are checked bit-exactly in
+full against the oracle's integer path; fp32 outputs in full against the oracle's integer path
+and, on sampled rows, against its dense double-precision path."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1905_10759_amd import synth
+
+from gpu_common import assert_close_to_oracle, dev, words
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hbmm():
+    assert torch.cuda.is_available()
+    from paper_1905_10759_amd import hbmm as mod
+    return mod
+
+
+def scale_tol(beta):
+    return (np.log2(beta) + 1) * 2.0 ** -24
+
+
+@pytest.mark.parametrize("name", ["tiny", "c2x", "c5x", "sq4k", "sq8k"])
+def test_workload_full_size(hbmm, name):
+    w = synth.WORKLOADS[name]
+    A, Bsrc = w.make_a(), w.make_b()
+    B = oracle.as_rows_by_k(Bsrc, w.b_layout)
+    print(f"[{name}] inputs ready", flush=True)
+
+    a_bits, a_s = hbmm.quantize_pack(dev(A), w.beta_a)
+    b_bits, b_s = hbmm.quantize_pack(dev(Bsrc), w.beta_w, layout=w.b_layout)
+    torch.cuda.synchronize()
+
+    # --- pack: words bit-exact, scales to the fp32 pairwise-sum bound
+    ra, rb = oracle.sign_pack(A), oracle.sign_pack(B)
+    assert np.array_equal(words(a_bits), ra)
+    assert np.array_equal(words(b_bits), rb)
+    sa, sb = oracle.block_scales(A, w.beta_a), oracle.block_scales(B, w.beta_w)
+    assert np.all(np.abs(a_s.cpu().numpy() - sa) <= scale_tol(w.beta_a) * sa + 1e-30)
+    assert np.all(np.abs(b_s.cpu().numpy() - sb) <= scale_tol(w.beta_w) * sb + 1e-30)
+    print(f"[{name}] pack ok", flush=True)
+
+    # --- integer contraction, every output
+    D = hbmm.gemm_int(a_bits, b_bits, w.K).cpu().numpy()
+    assert np.array_equal(D, oracle.int_dot(ra, rb, w.K))
+    del D
+    print(f"[{name}] int dots ok", flush=True)
+
+    # --- scaled outputs, every output, same scales on both sides
+    ref, T = oracle.popcount_gemm(ra, sa, w.beta_a, rb, sb, w.beta_w, w.K, want_T=True)
+    got = hbmm.gemm(a_bits, dev(sa), w.beta_a, b_bits, dev(sb), w.beta_w, w.K).cpu().numpy()
+    worst = assert_close_to_oracle(got, ref, T, name)
+    print(f"[{name}] gemm ok, worst err/(1e-5 T) = {worst:.3f}", flush=True)
+
+    # --- whole path with the GPU's own scales against the dense f64 definition, sampled rows
+    got2 = hbmm.gemm(a_bits, a_s, w.beta_a, b_bits, b_s, w.beta_w, w.K).cpu().numpy()
+    rows = np.unique(np.linspace(0, w.M - 1, 24).astype(np.int64))
+    dense = oracle.dense_f64_gemm(oracle.materialize(A[rows], w.beta_a), oracle.materialize(B, w.beta_w))
+    assert_close_to_oracle(got2[rows], dense, T[rows], name + " (dense f64, sampled rows)")
+
+
+def test_workload_binary_weight_full_size(hbmm):
+    w = synth.WORKLOADS["c5xw"]
+    A, B = w.make_a(), w.make_b()
+    b_bits, b_s = hbmm.quantize_pack(dev(B), w.beta_w)
+    rb, sb = oracle.sign_pack(B), oracle.block_scales(B, w.beta_w)
+    assert np.array_equal(words(b_bits), rb)
+    got = hbmm.gemm(None, dev(A), 1, b_bits, dev(sb), w.beta_w, w.K).cpu().numpy()
+    print("[c5xw] gpu done", flush=True)
+    ref, T = oracle.binary_weight_gemm(A, rb, sb, w.beta_w, want_T=True)
+    worst = assert_close_to_oracle(got, ref, T, "c5xw")
+    print(f"[c5xw] ok, worst err/(1e-5 T) = {worst:.3f}", flush=True)
+    rows = np.unique(np.linspace(0, w.M - 1, 16).astype(np.int64))
+    dense = oracle.dense_f64_gemm(oracle.materialize(A[rows], 1), oracle.materialize(B, w.beta_w, sb))
+    assert_close_to_oracle(got[rows], dense, T[rows], "c5xw (dense f64, sampled rows)")
