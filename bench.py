@@ -39,7 +39,21 @@ def parse():
     ap.add_argument("--workload", default="sq8k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip comparison kernels and the other configs")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 256 MiB device copy per step (known-size reference for HBM counters)")
     return ap.parse_args()
+
+
+def profiled_traffic(kernel_file: str):
+    """HBM bytes per launch measured with rocprofv3 counters for the headline workload (a committed
+    summary under profiles/; bench.py cannot collect counters itself).  None if absent."""
+    try:
+        for line in (ROOT / "profiles" / kernel_file).read_text().splitlines():
+            if line.startswith("TRAFFIC_BYTES_PER_LAUNCH="):
+                return float(line.split("=", 1)[1])
+    except OSError:
+        pass
+    return None
 
 
 def pack_bytes(rows: int, K: int, beta: int) -> float:
@@ -65,13 +79,13 @@ def cpu_baseline(w, A, B):
     import oracle
 
     threads = oracle.num_threads()
-    rows_i = min(w.M, 1024)
+    rows_i = w.M
     t0 = time.perf_counter()
     a_bits, a_s = oracle.sign_pack(A[:rows_i]), oracle.block_scales(A[:rows_i], w.beta_a)
     b_bits, b_s = oracle.sign_pack(B), oracle.block_scales(B, w.beta_w)
     oracle.popcount_gemm(a_bits, a_s, w.beta_a, b_bits, b_s, w.beta_w, w.K)
     t_int = time.perf_counter() - t0
-    rows_d = min(w.M, 32)
+    rows_d = min(w.M, 3072)
     t0 = time.perf_counter()
     oracle.dense_f64_gemm(oracle.materialize(A[:rows_d], w.beta_a), oracle.materialize(B, w.beta_w))
     t_dense = time.perf_counter() - t0
@@ -80,9 +94,9 @@ def cpu_baseline(w, A, B):
         "unit": "GOPS",
         "cores": threads,
         "kind": "oracle",
-        "sample": f"integer path (pack A rows + pack all of B + Eq.7 popcount): first {rows_i} of {w.M} rows of A "
-                  f"x all {w.N} rows of B, {t_int:.2f} s; dense f64 path on first {rows_d} rows: "
-                  f"{2.0 * rows_d * w.N * w.K / t_dense / 1e9:.2f} GOPS in {t_dense:.2f} s (B side not amortised)",
+        "sample": f"integer path (scales + sign-pack of both operands + Eq.7 popcount product), all {rows_i} rows of A "
+                  f"x all {w.N} rows of B: {t_int:.2f} s; dense f64 path (materialise + naive product) on the first "
+                  f"{rows_d} rows of A x all of B: {2.0 * rows_d * w.N * w.K / t_dense / 1e9:.2f} GOPS in {t_dense:.2f} s",
         "dense_f64_gops": 2.0 * rows_d * w.N * w.K / t_dense / 1e9,
         "cpu_model": _cpu_model(),
     }
@@ -127,6 +141,11 @@ def main():
     C = torch.empty((w.M, w.N), dtype=torch.float32, device="cuda")
     binary_act = w.beta_a != 1
 
+    cal_src = cal_dst = None
+    if args.copy_calibration:
+        cal_src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")   # 256 MiB
+        cal_dst = torch.empty_like(cal_src)
+
     marks = []   # (pack_a0, pack_a1/pack_b0, pack_b1/gemm0, gemm1) per timed step
 
     def step(record=False):
@@ -147,6 +166,8 @@ def main():
         if record:
             e[3].record()
             marks.append(e)
+        if cal_src is not None:
+            cal_dst.copy_(cal_src)
 
     for _ in range(args.warmup):
         step()
@@ -196,7 +217,8 @@ def main():
             "peak": POPCOUNT_PEAK_TOPS,
             "unit": "TOP/s",
             "frac": ops / (t_gemm * 1e-3) / 1e12 / POPCOUNT_PEAK_TOPS,
-            "traffic": None,
+            "traffic": profiled_traffic("popcount_gemm_kernel_sq8k.txt") if w.name == "sq8k" else None,
+            "traffic_unit": "bytes per launch (FETCH_SIZE + WRITE_SIZE, calibrated; algorithmic 287.3e6)",
         }
     else:
         fma_peak = VALU_LANE_OPS * 2 / 1e12
@@ -205,11 +227,26 @@ def main():
             "achieved": ops / (t_gemm * 1e-3) / 1e12, "peak": fma_peak, "unit": "TFLOP/s",
             "frac": ops / (t_gemm * 1e-3) / 1e12 / fma_peak, "traffic": None,
         }
-    if binary_act:
-        gbs_a = pack_bytes(w.M, w.K, w.beta_a) / (t_pack_a * 1e-3) / 1e9
+    if binary_act and w.b_layout == 0:
+        # Pack timed on its own: launches queued back to back (A, B, A, B, ...: 2 x 268 MB of source at
+        # the headline size, more than the 256 MB last-level cache) between one pair of events, so the
+        # figure is kernel time and not launch latency.
+        n_pack = 2 * max(10, args.steps)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(n_pack // 2):
+            hbmm.quantize_pack(A, w.beta_a, 0, a_bits, a_s)
+            hbmm.quantize_pack(B, w.beta_w, 0, b_bits, b_s)
+        e1.record()
+        torch.cuda.synchronize()
+        t_pack = e0.elapsed_time(e1) / n_pack
+        gbs = 0.5 * (pack_bytes(w.M, w.K, w.beta_a) + pack_bytes(w.N, w.K, w.beta_w)) / (t_pack * 1e-3) / 1e9
         out["roofline_pack"] = {
-            "kernel": "pack_rows_kernel (hbmm_quantize_pack, A operand)", "bound": "hbm",
-            "achieved": gbs_a, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs_a / HBM_PEAK_GBS, "traffic": None,
+            "kernel": "pack_rows_kernel (hbmm_quantize_pack)", "bound": "hbm", "achieved": gbs,
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+            "traffic": profiled_traffic("pack_rows_kernel_sq8k.txt") if w.name == "sq8k" else None,
+            "ms_per_launch": t_pack, "launches": n_pack,
         }
 
     if not args.no_extras:

@@ -4,8 +4,9 @@
 // The pass is bound by HBM reads: 4 bytes in per element against 1/8 + 4/beta bytes out.
 //
 // pack_rows_kernel (source rows x K, K contiguous):
-//   A wave covers 256 consecutive K elements of one row with one 16-byte load per lane, and keeps
-//   kUnroll such loads in flight.  Lane l holds elements 4l .. 4l+3, i.e. one nibble of the packed
+//   A wave covers 256 consecutive K elements of one row with one 16-byte load per lane, keeps
+//   kUnroll such loads in flight (4 KB contiguous per wave) and consecutive waves sweep memory
+//   linearly.  Lane l holds elements 4l .. 4l+3, i.e. one nibble of the packed
 //   word; the eight nibbles of a 32-bit word sit in eight consecutive lanes and are OR-ed together
 //   with three DPP steps, so no ballot-reordering is needed.  |x| is summed as
 //   (|x0|+|x1|)+(|x2|+|x3|) in the lane and then pairwise over the beta/4 lanes of the segment.
@@ -50,25 +51,41 @@ __device__ __forceinline__ float segment_sum(float v)
     return v;
 }
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint32_t pick4(const uint32_t (&v)[4], int i)
+{
+    return i == 0 ? v[0] : i == 1 ? v[1] : i == 2 ? v[2] : v[3];
+}
+__device__ __forceinline__ float pick4(const float (&v)[4], int i)
+{
+    return i == 0 ? v[0] : i == 1 ? v[1] : i == 2 ? v[2] : v[3];
+}
+
+// One wave = one "slot": kUnroll consecutive 256-element chunks (4 KB) of one row.  Slots are
+// numbered row-major, so consecutive waves and workgroups sweep the source linearly.
 template <int BETA, bool VEC>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void pack_rows_kernel(
-    const float *__restrict__ x, int64_t rows, int K, int64_t ldx, uint32_t *__restrict__ bits,
-    int64_t ldw, float *__restrict__ scales, int64_t lds, int words_valid)
+    const float *__restrict__ x, uint32_t total_slots, uint32_t slots_per_row, int K, int64_t ldx,
+    uint32_t *__restrict__ bits, int64_t ldw, float *__restrict__ scales, int64_t lds, int words_valid)
 {
+    constexpr int kSegLanes = BETA / 4;          // lanes per segment: 8 .. 64
     const int lane = threadIdx.x & 63;
-    const int64_t row = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
-    if (row >= rows) return;
-    const int kbase = blockIdx.y * (kUnroll * kChunk) + 4 * lane;
-    const float *xr = x + row * ldx;
+    const uint32_t slot = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+    if (slot >= total_slots) return;
+    const uint32_t row = slot / slots_per_row;
+    const int g = (int)(slot - row * slots_per_row);
+    const int kbase = g * (kUnroll * kChunk) + 4 * lane;
+    const float *xr = x + (int64_t)row * ldx;
 
-    float4 v[kUnroll];
+    f32x4 v[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
         const int k = kbase + u * kChunk;
-        v[u] = make_float4(-1.f, -1.f, -1.f, -1.f);   // sign bit 0; excluded from sums by `k < K` below
+        v[u] = f32x4{-1.f, -1.f, -1.f, -1.f};   // sign bit 0; kept out of the sums by `live` below
         if (k < K) {
             if (VEC) {
-                v[u] = *reinterpret_cast<const float4 *>(xr + k);
+                v[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(xr + k));
             } else {
                 v[u].x = xr[k];
                 v[u].y = xr[k + 1];
@@ -78,23 +95,36 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void pack_rows_kernel(
         }
     }
 
+    uint32_t w[kUnroll];
+    float p[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
-        const int k = kbase + u * kChunk;
-        const bool live = k < K;
-        // --- signs -> nibble -> 32-bit word over 8 lanes
-        uint32_t nib = (v[u].x >= 0.f ? 1u : 0u) | (v[u].y >= 0.f ? 2u : 0u) |
-                       (v[u].z >= 0.f ? 4u : 0u) | (v[u].w >= 0.f ? 8u : 0u);
-        uint32_t w = nib << (4 * (lane & 7));
-        w |= dpp_u32<kQuadSwap1>(w);
-        w |= dpp_u32<kQuadSwap2>(w);
-        w |= dpp_u32<kHalfMirror>(w);
-        const int widx = k >> 5;
-        if ((lane & 7) == 0 && widx < words_valid) bits[row * ldw + widx] = w;
-        // --- mean |x| over the beta-segment
-        float p = live ? (fabsf(v[u].x) + fabsf(v[u].y)) + (fabsf(v[u].z) + fabsf(v[u].w)) : 0.f;
-        p = segment_sum<BETA / 4>(p);
-        if ((lane & (BETA / 4 - 1)) == 0 && live) scales[row * lds + k / BETA] = p * (1.0f / BETA);
+        const bool live = kbase + u * kChunk < K;
+        // signs -> nibble -> 32-bit word, OR-ed over the 8 lanes that hold it
+        const uint32_t nib = (v[u].x >= 0.f ? 1u : 0u) | (v[u].y >= 0.f ? 2u : 0u) |
+                             (v[u].z >= 0.f ? 4u : 0u) | (v[u].w >= 0.f ? 8u : 0u);
+        uint32_t t = nib << (4 * (lane & 7));
+        t |= dpp_u32<kQuadSwap1>(t);
+        t |= dpp_u32<kQuadSwap2>(t);
+        t |= dpp_u32<kHalfMirror>(t);
+        w[u] = t;
+        // sum of |x| over the beta-segment, every lane of the segment gets it
+        const float a = live ? (fabsf(v[u].x) + fabsf(v[u].y)) + (fabsf(v[u].z) + fabsf(v[u].w)) : 0.f;
+        p[u] = segment_sum<kSegLanes>(a);
+    }
+
+    // Stores.  After the reductions every lane of a group holds the group's value for all kUnroll
+    // chunks; lane j (< kUnroll) of each group stores chunk j's value, so the wave writes its 32
+    // words (128 bytes) with one instruction, and its 4 * 256 / beta scales with another.
+    {
+        const int j = lane & 7, grp = lane >> 3;
+        const int widx = g * (kUnroll * kChunk / 32) + j * (kChunk / 32) + grp;
+        if (j < kUnroll && widx < words_valid) bits[(int64_t)row * ldw + widx] = pick4(w, j);
+    }
+    {
+        const int j = lane & (kSegLanes - 1), e = lane / kSegLanes;
+        const int k = g * (kUnroll * kChunk) + j * kChunk + e * BETA;
+        if (j < kUnroll && k < K) scales[(int64_t)row * lds + k / BETA] = pick4(p, j) * (1.0f / BETA);
     }
 }
 
@@ -131,15 +161,19 @@ template <int BETA>
 hipError_t pack_rows_beta(const float *x, int64_t rows, int64_t K, int64_t ldx, uint32_t *bits,
                           int64_t ldw, float *scales, int64_t lds, hipStream_t s)
 {
-    dim3 grid((unsigned)((rows + kWavesPerBlock - 1) / kWavesPerBlock),
-              (unsigned)((K + kUnroll * kChunk - 1) / (kUnroll * kChunk)));
+    const int64_t slots_per_row = (K + kUnroll * kChunk - 1) / (kUnroll * kChunk);
+    const int64_t total = rows * slots_per_row;
+    if (total >= ((int64_t)1 << 32)) return hipErrorInvalidConfiguration;
+    dim3 grid((unsigned)((total + kWavesPerBlock - 1) / kWavesPerBlock));
     dim3 block(64 * kWavesPerBlock);
     const int wv = (int)packed_words(K);
     const bool vec = (ldx % 4 == 0) && ((reinterpret_cast<uintptr_t>(x) & 15) == 0);
     if (vec)
-        pack_rows_kernel<BETA, true><<<grid, block, 0, s>>>(x, rows, (int)K, ldx, bits, ldw, scales, lds, wv);
+        pack_rows_kernel<BETA, true><<<grid, block, 0, s>>>(x, (uint32_t)total, (uint32_t)slots_per_row, (int)K, ldx,
+                                                             bits, ldw, scales, lds, wv);
     else
-        pack_rows_kernel<BETA, false><<<grid, block, 0, s>>>(x, rows, (int)K, ldx, bits, ldw, scales, lds, wv);
+        pack_rows_kernel<BETA, false><<<grid, block, 0, s>>>(x, (uint32_t)total, (uint32_t)slots_per_row, (int)K, ldx,
+                                                              bits, ldw, scales, lds, wv);
     return hipGetLastError();
 }
 
