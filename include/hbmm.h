@@ -113,7 +113,8 @@ int hbmm_gemm_int(const uint32_t *a_bits, int64_t ldw_a, const uint32_t *b_bits,
  * Dense comparison product on unquantised operands (the role the paper's "classical matrix
  * multiply" plays in section 4.2):  C = A . B^T, A M x K, B N x K, both K contiguous.
  *   dtype 0: fp32 operands.  dtype 1: bf16 operands (raw uint16 bit patterns).
- * fp32 accumulation and fp32 C in both cases.  K must be a multiple of 32.
+ * fp32 accumulation and fp32 C in both cases.  K must be a multiple of 32 (fp32) or 64 (bf16); lda and
+ * ldb must be multiples of 8 elements.
  */
 int hbmm_dense_ref_gemm(const void *A, int64_t lda, const void *B, int64_t ldb, int32_t dtype,
                         int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, void *stream);

@@ -172,3 +172,20 @@ def test_unsupported_is_reported_not_faked():
     with pytest.raises(hbmm.HbmmError) as ei:
         hbmm.quantize_pack(x, 48)
     assert ei.value.code == hbmm.EUNSUPPORTED
+
+
+# -------------------------------------------------------------------------- dense comparison
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("M,N,K", [(128, 128, 64), (200, 130, 256), (64, 300, 1024), (257, 129, 4608)])
+def test_dense_ref_gemm(dtype, M, N, K):
+    """C = A . B^T on unquantised operands against a double-precision library product of the same
+    (already rounded) operands; fp32 accumulation, so the error is taken relative to sum |a||b|."""
+    A, B = synth.normal(800 + M, (M, K)), synth.normal(801 + N, (N, K))
+    dA, dB = dev(A), dev(B)
+    if dtype == "bf16":
+        dA, dB = dA.to(torch.bfloat16), dB.to(torch.bfloat16)
+        A, B = dA.float().cpu().numpy(), dB.float().cpu().numpy()
+    got = hbmm.dense_ref_gemm(dA, dB).cpu().numpy()
+    ref = A.astype(np.float64) @ B.astype(np.float64).T
+    T = np.abs(A.astype(np.float64)) @ np.abs(B.astype(np.float64)).T
+    assert_close_to_oracle(got, ref, T, f"dense {dtype}")
