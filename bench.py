@@ -221,11 +221,13 @@ def main():
             "traffic_unit": "bytes per launch (FETCH_SIZE + WRITE_SIZE, calibrated; algorithmic 287.3e6)",
         }
     else:
-        fma_peak = VALU_LANE_OPS * 2 / 1e12
+        # beta_a = 1 runs on the matrix cores: each fp32 activation is split into three bf16 pieces, so
+        # the kernel issues 3 x 2MNK bf16 flops per launch.
+        mfma_flops = 3.0 * ops
         out["roofline"] = {
-            "kernel": "binary_weight_gemm_kernel (hbmm_gemm beta_a=1)", "bound": "alu",
-            "achieved": ops / (t_gemm * 1e-3) / 1e12, "peak": fma_peak, "unit": "TFLOP/s",
-            "frac": ops / (t_gemm * 1e-3) / 1e12 / fma_peak, "traffic": None,
+            "kernel": "binary_weight_mfma_kernel (hbmm_gemm beta_a=1)", "bound": "mfma",
+            "achieved": mfma_flops / (t_gemm * 1e-3) / 1e12, "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": mfma_flops / (t_gemm * 1e-3) / 1e12 / BF16_PEAK_TFLOPS, "traffic": None,
         }
     if binary_act and w.b_layout == 0:
         # Pack timed on its own: launches queued back to back (A, B, A, B, ...: 2 x 268 MB of source at

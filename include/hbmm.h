@@ -86,7 +86,8 @@ int hbmm_quantize_pack(const float *x, int64_t rows, int64_t K, int64_t ldx, int
  *   b_bits, b_scales  packed B (N rows), from hbmm_quantize_pack with beta_w.
  *   beta_a, beta_w    each in {32, 64, 128, 256}, K a multiple of both.
  *                     beta_a == 1 selects the binary-weight form (the paper's HBWN): a_bits must
- *                     be NULL, a_scales points at the raw fp32 A (M x K, leading dimension lds_a)
+ *                     be NULL, a_scales points at the raw fp32 A (M x K, leading dimension lds_a, a
+ *                     multiple of 4)
  *                     and C[m, n] = sum_j sB[n, j] * sum_{k in j} A[m, k] * Sign(B)[n, k].
  *   C                 out, M x N fp32, leading dimension ldc >= N.
  *   algo              0: XNOR + popcount on the vector ALU (the method's kernel).

@@ -121,6 +121,20 @@ def test_gemm_mixed_beta(beta_a, beta_w):
     run_gemm_case(synth.relu_normal(500, (150, 1280)), synth.normal(501, (270, 1280), std=0.04), beta_a, beta_w)
 
 
+@pytest.mark.parametrize("beta", [32, 64, 128, 256])
+@pytest.mark.parametrize("M,N,K", [(64, 64, 512), (300, 200, 1024), (129, 257, 1536), (5, 3, 256), (260, 140, 4608)])
+def test_gemm_mfma_i8_equal_beta(beta, M, N, K):
+    """The int8 matrix-core comparison variant must give the same product."""
+    run_gemm_case(synth.normal(400 + M, (M, K)), synth.uniform_pm1(401 + N, (N, K)), beta, beta, algo=1)
+
+
+@pytest.mark.parametrize("beta_a,beta_w,K", [(32, 64, 1280), (256, 32, 1280), (128, 64, 1280), (64, 256, 1280),
+                                             (32, 32, 1248), (64, 64, 576), (32, 96 // 3, 96)])
+def test_gemm_mfma_i8_mixed_and_ragged(beta_a, beta_w, K):
+    """Mixed segment lengths, and K whose word count is not a multiple of the 4-word stage."""
+    run_gemm_case(synth.normal(510, (150, K)), synth.normal(511, (270, K), std=0.04), beta_a, beta_w, algo=1)
+
+
 def test_gemm_against_dense_f64_path_end_to_end():
     """Whole hot path on the GPU (pack A, pack B, gemm) against the dense double-precision oracle
     that materialises delta (.) Sign(.) and multiplies.  GPU-made scales differ from the oracle's
