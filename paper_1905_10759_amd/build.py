@@ -38,6 +38,10 @@ def build(force: bool = True) -> Path:
     with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as pool:
         objs = list(pool.map(_compile, srcs))
     subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *map(str, objs), "-o", str(LIB)], check=True)
+    from . import check_isa
+    if check_isa.compile_and_check(verbose=False):
+        LIB.unlink()
+        raise RuntimeError("check_isa: an in-flight scalar-load register is touched before its wait; library removed")
     return LIB
 
 

@@ -13,14 +13,18 @@
 //     words from an LDS tile (padded so that 8-byte reads are bank-conflict free).
 //   * "Q" operand rows are wave-uniform: each wave owns kTQ rows of Q and fetches their words
 //     with scalar loads into SGPRs, which v_xor_b32 takes as a free operand.  No VGPR, LDS or
-//     vector-memory traffic is spent on Q bits.
+//     vector-memory traffic is spent on Q bits.  The scalar loads are written as inline asm (row
+//     offset in the instruction's SGPR-offset field, no per-load address arithmetic) and are
+//     waited for explicitly; check_isa.py verifies on the compiled ISA that nothing touches their
+//     destination registers before that wait.
 //   * each lane keeps kTP x kTQ integer accumulators and as many fp32 results.
 //   * the popcount accumulator of a segment is seeded with -G/2 (first v_bcnt of the segment takes
 //     the seed instead of the old value, so no reset instruction exists); then d = -2 * acc and the
 //     factor -2 is folded into the P scale.  Epilogue per accumulator per segment: cvt, mul, fma.
 //   * K is walked in chunks of kCK words; the next chunk's P words and both operands' scales are
 //     fetched from global memory while the current chunk is being reduced, then parked in the
-//     other LDS buffer (one barrier per chunk).
+//     other LDS buffer (one barrier per chunk).  A workgroup is 4 waves (tile 256 x 64) and two
+//     workgroups share a CU, so one group's barrier and LDS refill overlap the other's arithmetic.
 // Either of A / B can be P or Q: the host picks the role by output strides.
 #include "kernels.h"
 
@@ -29,15 +33,19 @@ namespace {
 
 constexpr int kTP = 4;                 // P rows per lane
 constexpr int kTQ = 16;                // Q rows per wave
-constexpr int kWaves = 8;
+#ifndef HBMM_GEMM_ASM_SMEM
+#define HBMM_GEMM_ASM_SMEM 1
+#endif
+#ifndef HBMM_GEMM_WAVES
+#define HBMM_GEMM_WAVES 4
+#endif
+constexpr int kWaves = HBMM_GEMM_WAVES;
 constexpr int kThreads = 64 * kWaves;  // 512
 constexpr int kTileP = 64 * kTP;       // 256 P rows per workgroup
 constexpr int kTileQ = kTQ * kWaves;   // 128 Q rows per workgroup
 constexpr int kCK = 16;                // 32-bit words of K per chunk (512 bits)
 constexpr int kStep = 2;               // words per inner step (one 8-byte LDS read, one s_load_dwordx2)
 constexpr int kBitsStride = kCK + 2;   // LDS row stride in words: 2 * odd => conflict-free b64 reads
-constexpr int kScaleStrideP = 17;      // odd => conflict-free b32 reads
-constexpr int kMaxScalesPerChunk = 16; // 512 bits / beta 32
 
 typedef const uint32_t __attribute__((address_space(4))) *const_u32_ptr;
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -59,7 +67,7 @@ __device__ __forceinline__ int bcnt_seed(uint32_t x, int seed)
 }
 
 template <int G, bool INTEGER>
-__global__ __launch_bounds__(kThreads) void popcount_gemm_kernel(const PopcountGemmArgs a)
+__global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel(const PopcountGemmArgs a)
 {
     constexpr int kWordsPerGran = G / 32;                       // 1, 2, 4, 8
     constexpr int kGranPerChunk = kCK / kWordsPerGran;          // 16, 8, 4, 2
@@ -67,8 +75,9 @@ __global__ __launch_bounds__(kThreads) void popcount_gemm_kernel(const PopcountG
     constexpr int kSeed = INTEGER ? 0 : -(G / 2);
 
     __shared__ __attribute__((aligned(16))) uint32_t s_bits[2][kTileP * kBitsStride];
+    constexpr int kScaleStrideP = kGranPerChunk + 1;   // odd => conflict-free b32 reads
     __shared__ __attribute__((aligned(16))) float s_ps[INTEGER ? 1 : 2][INTEGER ? 1 : kTileP * kScaleStrideP];
-    __shared__ __attribute__((aligned(16))) float s_qs[INTEGER ? 1 : 2][INTEGER ? 1 : kMaxScalesPerChunk * kTileQ];
+    __shared__ __attribute__((aligned(16))) float s_qs[INTEGER ? 1 : 2][INTEGER ? 1 : kGranPerChunk * kTileQ];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -207,6 +216,25 @@ __global__ __launch_bounds__(kThreads) void popcount_gemm_kernel(const PopcountG
             for (int q = 0; q < kTQ; ++q) asm volatile("" : "+v"(res[i][q]));
         __builtin_amdgcn_sched_barrier(0);
     };
+#if HBMM_GEMM_ASM_SMEM
+    // Scalar loads of Q words, written as asm so that the row offset can ride in the instruction's
+    // SGPR-offset field (no address arithmetic per load).  The compiler does not count these loads,
+    // so wait_q() must run before their results are read: it waits for every outstanding scalar /
+    // LDS access and ties the 16 results to itself so that no use can be scheduled above it.
+    auto load_q = [&](u32x2 (&qw)[kTQ], int step_index, int wbase) {
+        const uint64_t base = (uint64_t)qbase + (uint64_t)(wbase + step_index * kStep) * 4u;
+#pragma unroll
+        for (int q = 0; q < kTQ; ++q)
+            asm volatile("s_load_dwordx2 %0, %1, %2" : "=s"(qw[q]) : "s"(base), "s"(qoff[q]));
+    };
+    auto wait_q = [&](u32x2 (&qw)[kTQ]) {
+        static_assert(kTQ == 16, "operand list below is written out for 16 rows");
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+s"(qw[0]), "+s"(qw[1]), "+s"(qw[2]), "+s"(qw[3]), "+s"(qw[4]), "+s"(qw[5]), "+s"(qw[6]),
+                       "+s"(qw[7]), "+s"(qw[8]), "+s"(qw[9]), "+s"(qw[10]), "+s"(qw[11]), "+s"(qw[12]),
+                       "+s"(qw[13]), "+s"(qw[14]), "+s"(qw[15]));
+    };
+#else
     // Scalar loads of Q words.  `a.step_words` is kStep at run time; passing it as an argument keeps
     // the compiler from fusing the loads of consecutive steps into wider ones, which would need more
     // scalar registers than exist.
@@ -215,6 +243,8 @@ __global__ __launch_bounds__(kThreads) void popcount_gemm_kernel(const PopcountG
 #pragma unroll
         for (int q = 0; q < kTQ; ++q) qw[q] = *(const_u32x2_ptr)(base + (uint64_t)qoff[q]);
     };
+    auto wait_q = [&](u32x2 (&)[kTQ]) {};
+#endif
     auto load_p = [&](u32x2 (&pw)[kTP], int buf, int s) {
         const uint32_t *lbits = &s_bits[buf][lane * kBitsStride + s * kStep];
 #pragma unroll
@@ -253,6 +283,7 @@ __global__ __launch_bounds__(kThreads) void popcount_gemm_kernel(const PopcountG
             const bool last0 = !INTEGER && ((s * kStep + 1) % kWordsPerGran == 0);
             const bool last1 = !INTEGER && ((s * kStep + 2) % kWordsPerGran == 0);
             uint32_t px[kTP], py[kTP], qx[kTQ], qy[kTQ];
+            wait_q(qw[cur]);
 #pragma unroll
             for (int i = 0; i < kTP; ++i) { px[i] = pw[cur][i].x; py[i] = pw[cur][i].y; }
 #pragma unroll

@@ -108,3 +108,28 @@ def test_validation_rejects_before_launch(lib):
     assert d(fake, 64, fake, 64, 3, 8, 8, 64, fake, 8, None) == -2
     assert d(None, 64, fake, 64, 0, 8, 8, 64, fake, 8, None) == -1
     assert d(fake, 32, fake, 64, 0, 8, 8, 64, fake, 8, None) == -1
+
+
+def test_compiled_gemm_keeps_inflight_scalar_registers_untouched():
+    """The popcount GEMM waits for its asm-issued scalar loads by hand; the compiled ISA must not touch
+    their destination registers before that wait (checked on freshly compiled gfx950 assembly)."""
+    from paper_1905_10759_amd import check_isa
+    assert check_isa.compile_and_check(verbose=False) == 0
+
+
+def test_isa_checker_detects_a_planted_early_use(tmp_path):
+    """The checker itself: a use of an in-flight register before the wait must be reported."""
+    from paper_1905_10759_amd import check_isa
+    good = """
+\t;;#ASMSTART
+\ts_load_dwordx2 s[4:5], s[0:1], s2
+\t;;#ASMEND
+\tv_xor_b32_e32 v1, s8, v2
+\ts_waitcnt lgkmcnt(0)
+\tv_xor_b32_e32 v1, s4, v2
+"""
+    bad = good.replace("v_xor_b32_e32 v1, s8, v2", "v_xor_b32_e32 v1, s5, v2")
+    (tmp_path / "good.s").write_text(good)
+    (tmp_path / "bad.s").write_text(bad)
+    assert check_isa.check(str(tmp_path / "good.s"), verbose=False) == 0
+    assert check_isa.check(str(tmp_path / "bad.s"), verbose=False) == 1
