@@ -17,6 +17,8 @@
 //     consecutive rows land on distinct banks);
 //   * B: one packed word per weight row per stage goes through LDS as is; each lane expands its own
 //     byte (8 signs) into a bf16x8 fragment with three ALU instructions per pair of elements.
+// Global loads run three stages ahead of the multiply (three rotating register sets): a stage is
+// only 16 KB per workgroup, and HBM latency is several stages long.
 // Tiles that share rows of A are given consecutive slots on the same XCD so that the second read
 // of an A tile comes from that XCD's L2.
 #include "kernels.h"
@@ -67,22 +69,29 @@ __global__ __launch_bounds__(kThreadsW) void binary_weight_mfma_kernel(
     const int wm = wave >> 2, wn = wave & 3;
     const int nstages = K / kStageK;
 
-    // ---- staging: 2 x (4 fp32 of A) per thread, one word of B for the first 256 threads
-    float4 stA[2];
-    uint32_t stB = 0;
-    auto fetch = [&](int stage) {
+    // ---- staging: 2 x (4 fp32 of A) per thread, one word of B for the first 256 threads.  Three
+    // register sets rotate so that three stages of global loads are in flight: one stage is only
+    // 16 KB per workgroup, far less than what the HBM latency needs to be covered.
+    struct Staged {
+        float4 a[2];
+        uint32_t b;
+    };
+    // Every load is unconditional (row and stage indices are clamped instead of guarded): a guarded
+    // load would make the number of outstanding loads unknown at compile time and force a full
+    // wait before every park.  Rows past M / N only feed outputs that are never stored, and the
+    // stages past the end are parked but never multiplied.
+    const float *a_src[2];
 #pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            const int id = tid + r * kThreadsW;
-            const int row = id >> 3, c = id & 7;
-            stA[r] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (m0 + row < M)
-                stA[r] = *reinterpret_cast<const float4 *>(A + (int64_t)(m0 + row) * lda + stage * kStageK + c * 4);
-        }
-        if (tid < kBNw) {
-            stB = 0;
-            if (n0 + tid < N) stB = b_bits[(int64_t)(n0 + tid) * ldw_b + stage];
-        }
+    for (int r = 0; r < 2; ++r) {
+        const int id = tid + r * kThreadsW;
+        a_src[r] = A + (int64_t)min(m0 + (id >> 3), M - 1) * lda + (id & 7) * 4;
+    }
+    const uint32_t *b_src = b_bits + (int64_t)min(n0 + (tid & (kBNw - 1)), N - 1) * ldw_b;
+    auto fetch = [&](Staged &st, int stage) {
+        const int sg = min(stage, nstages - 1);
+#pragma unroll
+        for (int r = 0; r < 2; ++r) st.a[r] = *reinterpret_cast<const float4 *>(a_src[r] + sg * kStageK);
+        st.b = b_src[sg];
     };
     auto split_pair = [](float a, float b, uint32_t &hi, uint32_t &mid, uint32_t &lo) {
         const uint32_t ua = __builtin_bit_cast(uint32_t, a), ub = __builtin_bit_cast(uint32_t, b);
@@ -95,20 +104,20 @@ __global__ __launch_bounds__(kThreadsW) void binary_weight_mfma_kernel(
         mid = (ma >> 16) | mb;
         lo = (__builtin_bit_cast(uint32_t, la) >> 16) | (__builtin_bit_cast(uint32_t, lb) & 0xffff0000u);
     };
-    auto park = [&](int buf) {
+    auto park = [&](const Staged &st, int buf) {
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
             const int id = tid + r * kThreadsW;
             const int row = id >> 3, c = id & 7;
             uint2 hi, mid, lo;
-            split_pair(stA[r].x, stA[r].y, hi.x, mid.x, lo.x);
-            split_pair(stA[r].z, stA[r].w, hi.y, mid.y, lo.y);
+            split_pair(st.a[r].x, st.a[r].y, hi.x, mid.x, lo.x);
+            split_pair(st.a[r].z, st.a[r].w, hi.y, mid.y, lo.y);
             unsigned char *dst = &sA[buf][row * kRowBytes + c * 8];
             *reinterpret_cast<uint2 *>(dst) = hi;
             *reinterpret_cast<uint2 *>(dst + kPieceBytes) = mid;
             *reinterpret_cast<uint2 *>(dst + 2 * kPieceBytes) = lo;
         }
-        if (tid < kBNw) sB[buf][tid] = stB;
+        if (tid < kBNw) sB[buf][tid] = st.b;
     };
 
     f32x16 acc[2][2], res[2][2];
@@ -132,13 +141,12 @@ __global__ __launch_bounds__(kThreadsW) void binary_weight_mfma_kernel(
         srow[tb] = b_scales + (int64_t)min(col, N - 1) * lds_b;
     }
 
-    fetch(0);
-    park(0);
-    __syncthreads();
     float sc[2] = {0.f, 0.f};
-    for (int stage = 0; stage < nstages; ++stage) {
+    // One K stage: multiply the tile parked in LDS buffer (stage mod 2), request stage + 3 into
+    // `incoming`, and park `ready` (stage + 1, requested three stages ago) in the other buffer.
+    auto run_stage = [&](int stage, const Staged &ready, Staged &incoming) {
         const int buf = stage & 1;
-        if (stage + 1 < nstages) fetch(stage + 1);
+        fetch(incoming, stage + 3);
         const bool seg_first = stage % stages_per_seg == 0;
         const bool seg_last = (stage + 1) % stages_per_seg == 0;
         if (seg_first) {
@@ -178,8 +186,20 @@ __global__ __launch_bounds__(kThreadsW) void binary_weight_mfma_kernel(
                         acc[ta][tb][v] = 0.f;
                     }
         }
-        if (stage + 1 < nstages) park(buf ^ 1);
+        park(ready, buf ^ 1);   // past the last stage this parks zeros that nobody reads
         __syncthreads();
+    };
+
+    Staged s0, s1, s2;
+    fetch(s0, 0);
+    park(s0, 0);
+    fetch(s0, 1);
+    fetch(s1, 2);
+    __syncthreads();
+    for (int stage = 0; stage < nstages; stage += 3) {
+        run_stage(stage, s0, s2);
+        if (stage + 1 < nstages) run_stage(stage + 1, s1, s0);
+        if (stage + 2 < nstages) run_stage(stage + 2, s2, s1);
     }
 
 #pragma unroll

@@ -36,6 +36,9 @@ constexpr int kTQ = 16;                // Q rows per wave
 #ifndef HBMM_GEMM_ASM_SMEM
 #define HBMM_GEMM_ASM_SMEM 1
 #endif
+#ifndef HBMM_GEMM_Q_PREFETCH
+#define HBMM_GEMM_Q_PREFETCH 1
+#endif
 #ifndef HBMM_GEMM_WAVES
 #define HBMM_GEMM_WAVES 4
 #endif
@@ -44,6 +47,8 @@ constexpr int kThreads = 64 * kWaves;  // 512
 constexpr int kTileP = 64 * kTP;       // 256 P rows per workgroup
 constexpr int kTileQ = kTQ * kWaves;   // 128 Q rows per workgroup
 constexpr int kCK = 16;                // 32-bit words of K per chunk (512 bits)
+constexpr int kNumXcd = 8;
+constexpr int kSuperTiles = 64;          // tiles per super-tile (two workgroups per CU x 32 CUs of an XCD)
 constexpr int kStep = 2;               // words per inner step (one 8-byte LDS read, one s_load_dwordx2)
 constexpr int kBitsStride = kCK + 2;   // LDS row stride in words: 2 * odd => conflict-free b64 reads
 
@@ -82,8 +87,25 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int tile_p = blockIdx.x % a.tiles_p;
-    const int tile_q = blockIdx.x / a.tiles_p;
+    // Workgroup -> tile.  Workgroups are dealt to the 8 XCDs round-robin and every XCD has its own
+    // L2, so tiles are grouped into super-tiles of sup_p x sup_q = 64 tiles whose workgroups all land
+    // on one XCD at about the same time: a P tile is then fetched into that L2 once for sup_q
+    // workgroups and a Q tile once for sup_p of them.
+    // Small grids (sup_p == 0) are mapped plainly.
+    int tile_p, tile_q;
+    if (a.sup_p == 0) {
+        tile_p = blockIdx.x % a.tiles_p;
+        tile_q = blockIdx.x / a.tiles_p;
+    } else {
+        const int xcd = blockIdx.x % kNumXcd;
+        const int in_xcd = blockIdx.x / kNumXcd;
+        const int super = (in_xcd / kSuperTiles) * kNumXcd + xcd;
+        if (super >= a.n_super) return;
+        const int r_in_super = in_xcd % kSuperTiles;
+        tile_p = (super % a.n_super_p) * a.sup_p + r_in_super % a.sup_p;
+        tile_q = (super / a.n_super_p) * (kSuperTiles / a.sup_p) + r_in_super / a.sup_p;
+        if (tile_p >= a.tiles_p || tile_q >= a.tiles_q) return;
+    }
     const int p0 = tile_p * kTileP;
     const int q0_wg = tile_q * kTileQ;
     const int q0 = q0_wg + wave * kTQ;
@@ -103,7 +125,18 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
     float st_ps[INTEGER ? 1 : kPsPerThread];
     float st_qs[INTEGER ? 1 : kQsPerThread];
 
+    uint32_t st_qline = 0;
     auto fetch = [&](int chunk) {
+#if HBMM_GEMM_Q_PREFETCH
+        // Touch the 64-byte line of this wave's Q rows that the scalar loads of `chunk` will read,
+        // one chunk ahead, through the vector path (its counter is separate from the scalar one), so
+        // that those scalar loads find the line in L2.
+        if (lane < kTQ) {
+            const int row = min(q0 + lane, a.Q - 1);
+            const int w = min(chunk * kCK, a.kwords - 4);
+            st_qline = a.q_bits[(int64_t)row * a.ldw_q + w];
+        }
+#endif
 #pragma unroll
         for (int r = 0; r < kBitPieces; ++r) {
             const int id = tid + r * kThreads;
@@ -136,6 +169,9 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
         }
     };
     auto park = [&](int buf) {
+#if HBMM_GEMM_Q_PREFETCH
+        asm volatile("" ::"v"(st_qline));   // keeps the touch load alive; its value is not used
+#endif
 #pragma unroll
         for (int r = 0; r < kBitPieces; ++r) {
             const int id = tid + r * kThreads;
@@ -287,7 +323,10 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
 #pragma unroll
             for (int i = 0; i < kTP; ++i) { px[i] = pw[cur][i].x; py[i] = pw[cur][i].y; }
 #pragma unroll
-            for (int q = 0; q < kTQ; ++q) { qx[q] = qw[cur][q].x; qy[q] = qw[cur][q].y; }
+            for (int q = 0; q < kTQ; ++q) {
+                qx[q] = qw[cur][q].x;
+                qy[q] = qw[cur][q].y;
+            }
 
             if (last0) {
                 // one-word segments: both words end a segment; no room to hide the scale reads
@@ -379,9 +418,9 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
 template <int G, bool INTEGER>
 hipError_t launch(const PopcountGemmArgs &a, hipStream_t s)
 {
-    const int64_t tiles_q = (a.Q + kTileQ - 1) / kTileQ;
-    const int64_t nblocks = (int64_t)a.tiles_p * tiles_q;
+    int64_t nblocks = (int64_t)a.tiles_p * a.tiles_q;
     if (nblocks <= 0) return hipSuccess;
+    if (a.sup_p != 0) nblocks = (int64_t)((a.n_super + kNumXcd - 1) / kNumXcd) * kNumXcd * kSuperTiles;
     if (nblocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     popcount_gemm_kernel<G, INTEGER><<<dim3((unsigned)nblocks), dim3(kThreads), 0, s>>>(a);
     return hipGetLastError();
@@ -393,6 +432,16 @@ hipError_t launch_popcount_gemm(const PopcountGemmArgs &args, int G, int integer
 {
     PopcountGemmArgs a = args;
     a.tiles_p = (a.P + kTileP - 1) / kTileP;
+    a.tiles_q = (a.Q + kTileQ - 1) / kTileQ;
+    // super-tile shape: sup_p x (64 / sup_p); a P tile is 4x the rows of a Q tile, so 4 x 16 balances
+    // the two footprints; narrower when P has fewer tiles
+    a.sup_p = a.tiles_p >= 4 ? 4 : (a.tiles_p >= 2 ? 2 : 1);
+    if ((int64_t)a.tiles_p * a.tiles_q <= 2 * kNumXcd * kSuperTiles) a.sup_p = 0;   // at most two rounds: plain map
+    if (a.sup_p != 0) {
+        a.n_super_p = (a.tiles_p + a.sup_p - 1) / a.sup_p;
+        const int sup_q = kSuperTiles / a.sup_p;
+        a.n_super = a.n_super_p * ((a.tiles_q + sup_q - 1) / sup_q);
+    }
     a.step_words = kStep;
     if (integer) return launch<64, true>(a, s);
     switch (G) {
