@@ -61,7 +61,7 @@ int64_t hbmm_packed_ld_words(int64_t K);
  *                         layout 1: K x rows, element (r, k) at x[k*ldx + r]   (ldx >= rows);
  *                         this is a right-hand operand written the usual K x N way; the result
  *                         is identical to packing its transpose.
- *   beta    segment length; supported: 32, 64, 128, 256 with K a multiple of beta.
+ *   beta    segment length; supported: the powers of two 2 .. 256, with K a multiple of beta and of 32.
  *   bits    out, rows x ldw (ldw >= hbmm_packed_ld_words(K), multiple of 4).
  *   scales  out, rows x lds (lds >= hbmm_num_blocks(K, beta)).
  *

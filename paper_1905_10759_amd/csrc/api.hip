@@ -16,6 +16,7 @@ int log2_exact(int v)
 }
 
 bool supported_beta(int beta) { return beta == 32 || beta == 64 || beta == 128 || beta == 256; }
+bool supported_pack_beta(int beta) { return beta >= 2 && beta <= 256 && (beta & (beta - 1)) == 0; }
 
 int from_hip(hipError_t e)
 {
@@ -76,8 +77,8 @@ int hbmm_quantize_pack(const float *x, int64_t rows, int64_t K, int64_t ldx, int
     if (rows < 0 || K < 0 || rows > kMaxDim || K > kMaxPackK) return HBMM_EINVAL;
     if (layout != 0 && layout != 1) return HBMM_EINVAL;
     if (beta < 1) return HBMM_EINVAL;
-    if (!supported_beta(beta)) return HBMM_EUNSUPPORTED;
-    if (K % beta != 0) return HBMM_EUNSUPPORTED;
+    if (!supported_pack_beta(beta)) return HBMM_EUNSUPPORTED;
+    if (K % beta != 0 || K % 32 != 0) return HBMM_EUNSUPPORTED;
     if (rows == 0 || K == 0) return HBMM_OK;
     if (!x || !bits || !scales) return HBMM_EINVAL;
     if (!aligned16(x) || !aligned16(bits) || !aligned16(scales)) return HBMM_EINVAL;

@@ -69,7 +69,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void pack_rows_kernel(
     const float *__restrict__ x, uint32_t total_slots, uint32_t slots_per_row, int K, int64_t ldx,
     uint32_t *__restrict__ bits, int64_t ldw, float *__restrict__ scales, int64_t lds, int words_valid)
 {
-    constexpr int kSegLanes = BETA / 4;          // lanes per segment: 8 .. 64
+    constexpr int kSegLanes = BETA >= 4 ? BETA / 4 : 1;   // lanes per segment (beta 2: two segments per lane)
     const int lane = threadIdx.x & 63;
     const uint32_t slot = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
     if (slot >= total_slots) return;
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void pack_rows_kernel(
     }
 
     uint32_t w[kUnroll];
-    float p[kUnroll];
+    float p[kUnroll], p2[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
         const bool live = kbase + u * kChunk < K;
@@ -109,22 +109,44 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void pack_rows_kernel(
         t |= dpp_u32<kHalfMirror>(t);
         w[u] = t;
         // sum of |x| over the beta-segment, every lane of the segment gets it
-        const float a = live ? (fabsf(v[u].x) + fabsf(v[u].y)) + (fabsf(v[u].z) + fabsf(v[u].w)) : 0.f;
-        p[u] = segment_sum<kSegLanes>(a);
+        const float lo = live ? fabsf(v[u].x) + fabsf(v[u].y) : 0.f;
+        const float hi = live ? fabsf(v[u].z) + fabsf(v[u].w) : 0.f;
+        if (BETA == 2) {
+            p[u] = lo;
+            p2[u] = hi;
+        } else {
+            p[u] = segment_sum<kSegLanes>(lo + hi);
+            p2[u] = 0.f;
+        }
     }
 
     // Stores.  After the reductions every lane of a group holds the group's value for all kUnroll
     // chunks; lane j (< kUnroll) of each group stores chunk j's value, so the wave writes its 32
-    // words (128 bytes) with one instruction, and its 4 * 256 / beta scales with another.
+    // words (128 bytes) with one instruction.
     {
         const int j = lane & 7, grp = lane >> 3;
         const int widx = g * (kUnroll * kChunk / 32) + j * (kChunk / 32) + grp;
         if (j < kUnroll && widx < words_valid) bits[(int64_t)row * ldw + widx] = pick4(w, j);
     }
-    {
+    float *srow = scales + (int64_t)row * lds;
+    if (BETA >= 16) {
+        // same trick for the scales: 4 * 256 / beta values with one instruction
         const int j = lane & (kSegLanes - 1), e = lane / kSegLanes;
         const int k = g * (kUnroll * kChunk) + j * kChunk + e * BETA;
-        if (j < kUnroll && k < K) scales[(int64_t)row * lds + k / BETA] = pick4(p, j) * (1.0f / BETA);
+        if (j < kUnroll && k < K) srow[k / BETA] = pick4(p, j) * (1.0f / BETA);
+    } else {
+        // short segments: at least one scale per two lanes, stored chunk by chunk
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int k = kbase + u * kChunk;
+            if (k >= K) continue;
+            if (BETA == 2) {
+                srow[k / 2] = p[u] * 0.5f;
+                srow[k / 2 + 1] = p2[u] * 0.5f;
+            } else if ((lane & (kSegLanes - 1)) == 0) {
+                srow[k / BETA] = p[u] * (1.0f / BETA);
+            }
+        }
     }
 }
 
@@ -146,9 +168,13 @@ __global__ __launch_bounds__(256) void pack_cols_kernel(
             const float v = x[(int64_t)(kw + b) * ldx + r];
             w |= (v >= 0.f ? 1u : 0u) << b;
             acc += fabs((double)v);
+            if (BETA < 32 && ((b + 1) & (BETA - 1)) == 0) {
+                scales[r * lds + (kw + b) / BETA] = (float)(acc / (double)BETA);
+                acc = 0.0;
+            }
         }
         bits[r * ldw + (kw >> 5)] = w;
-        if (((kw + 32) & (BETA - 1)) == 0) {
+        if (BETA >= 32 && ((kw + 32) & (BETA - 1)) == 0) {
             scales[r * lds + kw / BETA] = (float)(acc / (double)BETA);
             acc = 0.0;
         }
@@ -193,6 +219,10 @@ hipError_t launch_pack_rows(const float *x, int64_t rows, int64_t K, int64_t ldx
                             uint32_t *bits, int64_t ldw, float *scales, int64_t lds, hipStream_t s)
 {
     switch (beta) {
+    case 2: return pack_rows_beta<2>(x, rows, K, ldx, bits, ldw, scales, lds, s);
+    case 4: return pack_rows_beta<4>(x, rows, K, ldx, bits, ldw, scales, lds, s);
+    case 8: return pack_rows_beta<8>(x, rows, K, ldx, bits, ldw, scales, lds, s);
+    case 16: return pack_rows_beta<16>(x, rows, K, ldx, bits, ldw, scales, lds, s);
     case 32: return pack_rows_beta<32>(x, rows, K, ldx, bits, ldw, scales, lds, s);
     case 64: return pack_rows_beta<64>(x, rows, K, ldx, bits, ldw, scales, lds, s);
     case 128: return pack_rows_beta<128>(x, rows, K, ldx, bits, ldw, scales, lds, s);
@@ -205,6 +235,10 @@ hipError_t launch_pack_cols(const float *x, int64_t rows, int64_t K, int64_t ldx
                             uint32_t *bits, int64_t ldw, float *scales, int64_t lds, hipStream_t s)
 {
     switch (beta) {
+    case 2: return pack_cols_beta<2>(x, rows, K, ldx, bits, ldw, scales, lds, s);
+    case 4: return pack_cols_beta<4>(x, rows, K, ldx, bits, ldw, scales, lds, s);
+    case 8: return pack_cols_beta<8>(x, rows, K, ldx, bits, ldw, scales, lds, s);
+    case 16: return pack_cols_beta<16>(x, rows, K, ldx, bits, ldw, scales, lds, s);
     case 32: return pack_cols_beta<32>(x, rows, K, ldx, bits, ldw, scales, lds, s);
     case 64: return pack_cols_beta<64>(x, rows, K, ldx, bits, ldw, scales, lds, s);
     case 128: return pack_cols_beta<128>(x, rows, K, ldx, bits, ldw, scales, lds, s);

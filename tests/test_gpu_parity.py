@@ -33,7 +33,7 @@ def scale_tol(beta: int) -> float:
 
 
 # ------------------------------------------------------------------------------ quantize_pack
-@pytest.mark.parametrize("beta", [32, 64, 128, 256])
+@pytest.mark.parametrize("beta", [2, 4, 8, 16, 32, 64, 128, 256])
 @pytest.mark.parametrize("rows,K", [(1, 256), (5, 768), (67, 1280), (130, 4608), (3, 256 * 9)])
 def test_pack_rows(beta, rows, K):
     x = synth.normal(100 + beta + rows, (rows, K))
@@ -45,6 +45,22 @@ def test_pack_rows(beta, rows, K):
     got = scales.cpu().numpy()
     assert got.shape == ref.shape
     assert np.all(np.abs(got - ref) <= scale_tol(beta) * ref)
+
+
+@pytest.mark.parametrize("beta", [2, 4, 8, 16])
+def test_pack_rows_short_segments_ragged(beta):
+    """Short segments with K = 96 + 32 j (not a multiple of the 256-element wave chunk) and an odd
+    scale leading dimension."""
+    for K in (96, 160, 1056):
+        x = synth.normal(150 + beta + K, (9, K))
+        nb = K // beta
+        scales = torch.full((9, nb + 3), -7.0, dtype=torch.float32, device="cuda")
+        bits, _ = hbmm.quantize_pack(dev(x), beta, 0, None, scales[:, :nb])
+        assert np.array_equal(words(bits), oracle.sign_pack(x))
+        ref = oracle.block_scales(x, beta)
+        got = scales.cpu().numpy()
+        assert np.all(np.abs(got[:, :nb] - ref) <= scale_tol(beta) * ref)
+        assert (got[:, nb:] == -7.0).all()
 
 
 def test_pack_rows_ragged_k_and_strided_source():
@@ -66,7 +82,7 @@ def test_pack_rows_ragged_k_and_strided_source():
     assert (words(bits)[:, K // 32:] == 0).all()
 
 
-@pytest.mark.parametrize("beta", [32, 64, 128, 256])
+@pytest.mark.parametrize("beta", [2, 4, 8, 16, 32, 64, 128, 256])
 def test_pack_cols(beta):
     K, rows = 1024, 333
     xkn = synth.normal(200 + beta, (K, rows))
