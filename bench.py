@@ -209,7 +209,8 @@ def main():
         "wall_ms_per_step": wall_ms / args.steps,
         "kernel_ms": {"pack_a": t_pack_a, "pack_b": t_pack_b, "gemm": t_gemm},
     }
-    if binary_act:
+    word_sized = w.beta_a >= 32 and w.beta_w >= 32
+    if word_sized:
         out["roofline"] = {
             "kernel": "popcount_gemm_kernel (hbmm_gemm algo 0)",
             "bound": "alu",
@@ -221,11 +222,11 @@ def main():
             "traffic_unit": "bytes per launch (FETCH_SIZE + WRITE_SIZE, calibrated; algorithmic 287.3e6)",
         }
     else:
-        # beta_a = 1 runs on the matrix cores: each fp32 activation is split into three bf16 pieces, so
-        # the kernel issues 3 x 2MNK bf16 flops per launch.
+        # beta = 1 or a segment shorter than 32 runs on the matrix cores: the dense side is split into
+        # three bf16 pieces, so the kernel issues 3 x 2MNK bf16 flops per launch.
         mfma_flops = 3.0 * ops
         out["roofline"] = {
-            "kernel": "binary_weight_mfma_kernel (hbmm_gemm beta_a=1)", "bound": "mfma",
+            "kernel": "mfma_split_gemm_kernel (hbmm_gemm, beta 1 or < 32 on one side)", "bound": "mfma",
             "achieved": mfma_flops / (t_gemm * 1e-3) / 1e12, "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": mfma_flops / (t_gemm * 1e-3) / 1e12 / BF16_PEAK_TFLOPS, "traffic": None,
         }
@@ -298,7 +299,7 @@ def extras(w, A, B, a_bits, a_s, b_bits, b_s, C, torch, hbmm, synth, args):
         if ww.beta_a != 1:
             ab, as_ = hbmm.quantize_pack(dA, ww.beta_a)
             tp = time_loop(lambda: hbmm.quantize_pack(dA, ww.beta_a, 0, ab, as_), 10, 2, torch)
-            tg = time_loop(lambda: hbmm.gemm(ab, as_, ww.beta_a, bb, bs, ww.beta_w, ww.K), 10, 2, torch)
+            tg = time_loop(lambda: hbmm.gemm(ab, as_, ww.beta_a, bb, bs, ww.beta_w, ww.K), 6 if ww.beta_a < 32 else 10, 2, torch)
             entry["pack_a_ms"] = min(tp)
             entry["pack_a_GBs"] = pack_bytes(ww.M, ww.K, ww.beta_a) / (min(tp) * 1e-3) / 1e9
         else:

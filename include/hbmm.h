@@ -84,15 +84,21 @@ int hbmm_quantize_pack(const float *x, int64_t rows, int64_t K, int64_t ldx, int
  *
  *   a_bits, a_scales  packed A (M rows), from hbmm_quantize_pack with beta_a.
  *   b_bits, b_scales  packed B (N rows), from hbmm_quantize_pack with beta_w.
- *   beta_a, beta_w    each in {32, 64, 128, 256}, K a multiple of both.
- *                     beta_a == 1 selects the binary-weight form (the paper's HBWN): a_bits must
- *                     be NULL, a_scales points at the raw fp32 A (M x K, leading dimension lds_a, a
- *                     multiple of 4)
- *                     and C[m, n] = sum_j sB[n, j] * sum_{k in j} A[m, k] * Sign(B)[n, k].
+ *   beta_a, beta_w    each a power of two in 2 .. 256, or 1; K a multiple of both and of 32.
+ *                     beta == 1 means that operand is not binarised (the paper's beta = 1; beta_a = 1
+ *                     is its HBWN): its bits pointer must be NULL, its scales pointer is the raw fp32
+ *                     operand (rows x K, leading dimension lds, a multiple of 4), and e.g. for
+ *                     beta_a = 1:  C[m, n] = sum_j sB[n, j] * sum_{k in j} A[m, k] * Sign(B)[n, k].
+ *                     Both >= 32: the XNOR + popcount kernel.  Otherwise (a segment shorter than a
+ *                     32-bit word, or an unquantised operand) the product runs on the matrix cores:
+ *                     the operand with the longer segment keeps its signs and must have beta >= 16,
+ *                     the other is rebuilt as fp32 values split exactly into three bf16 pieces.
+ *                     Both < 16 (and 1 with 1) is not supported.
  *   C                 out, M x N fp32, leading dimension ldc >= N.
- *   algo              0: XNOR + popcount on the vector ALU (the method's kernel).
- *                     1: the same d[m, n, g] from int8 +-1 matrix-core (MFMA) products, kept as a
- *                        comparison point; same epilogue, same result up to fp32 rounding order.
+ *   algo              0: the method's kernel as described above.
+ *                     1: (both beta >= 32 only) the same d[m, n, g] from int8 +-1 matrix-core (MFMA)
+ *                        products, kept as a comparison point; same epilogue, same result up to fp32
+ *                        rounding order.
  *
  * M == 0 or N == 0 is a valid no-op; K == 0 writes zeros.
  */

@@ -108,6 +108,43 @@ static bool b_is_lane_side(int64_t M, int64_t N)
     return cost_b <= cost_a;
 }
 
+// One operand of hbmm_gemm as the caller gave it; beta == 1 means `scales` is the raw fp32 operand.
+struct GemmOperand {
+    const uint32_t *bits;
+    const float *scales;
+    int64_t ldw, lds, rows;
+    int32_t beta;
+};
+
+static int check_operand(const GemmOperand &o, int64_t K)
+{
+    if (!o.scales || !aligned16(o.scales)) return HBMM_EINVAL;
+    if (o.lds >= ((int64_t)1 << 31)) return HBMM_EINVAL;
+    if (o.beta == 1) {
+        if (o.bits != nullptr) return HBMM_EINVAL;     // raw operand travels through `scales`
+        return o.lds < K ? HBMM_EINVAL : HBMM_OK;
+    }
+    if (o.lds < K / o.beta) return HBMM_EINVAL;
+    return check_packed(o.bits, o.rows, K, o.ldw);
+}
+
+static hbmm::SplitGemmOperand to_split(const GemmOperand &o)
+{
+    hbmm::SplitGemmOperand r{};
+    if (o.beta == 1) {
+        r.raw = o.scales;
+        r.ld_raw = o.lds;
+    } else {
+        r.bits = o.bits;
+        r.scales = o.scales;
+        r.ldw = o.ldw;
+        r.lds = o.lds;
+    }
+    r.rows = o.rows;
+    r.beta = o.beta;
+    return r;
+}
+
 int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int64_t lds_a,
               int32_t beta_a, const uint32_t *b_bits, const float *b_scales, int64_t ldw_b,
               int64_t lds_b, int32_t beta_w, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
@@ -116,26 +153,31 @@ int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int6
     if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim) return HBMM_EINVAL;
     if (beta_a < 1 || beta_w < 1) return HBMM_EINVAL;
     if (algo != 0 && algo != 1) return HBMM_EUNSUPPORTED;
-    if (!supported_beta(beta_w) || (beta_a != 1 && !supported_beta(beta_a))) return HBMM_EUNSUPPORTED;
-    if (K % beta_w != 0 || K % beta_a != 0) return HBMM_EUNSUPPORTED;
-    if (beta_a == 1 && algo != 0) return HBMM_EUNSUPPORTED;
+    const bool word_a = supported_beta(beta_a), word_w = supported_beta(beta_w);   // 32 .. 256
+    if (!(beta_a == 1 || supported_pack_beta(beta_a)) || !(beta_w == 1 || supported_pack_beta(beta_w)))
+        return HBMM_EUNSUPPORTED;
+    if (K % beta_w != 0 || K % beta_a != 0 || K % 32 != 0) return HBMM_EUNSUPPORTED;
+    if (algo == 1 && !(word_a && word_w)) return HBMM_EUNSUPPORTED;
+    // Off the popcount path one operand keeps its +-1 form and needs a segment of at least 16.
+    if (!(word_a && word_w) && beta_a < 16 && beta_w < 16) return HBMM_EUNSUPPORTED;
     if (M == 0 || N == 0) return HBMM_OK;
     if (!C || !aligned16(C) || ldc < N) return HBMM_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (K == 0) return from_hip(zero_block(C, ldc, M, N, s));
 
-    if (!b_scales || !aligned16(b_scales) || lds_b < K / beta_w) return HBMM_EINVAL;
-    if (int rc = check_packed(b_bits, N, K, ldw_b)) return rc;
+    const GemmOperand oa{a_bits, a_scales, ldw_a, lds_a, M, beta_a};
+    const GemmOperand ob{b_bits, b_scales, ldw_b, lds_b, N, beta_w};
+    if (int rc = check_operand(ob, K)) return rc;
+    if (int rc = check_operand(oa, K)) return rc;
 
-    if (beta_a == 1) {
-        if (a_bits != nullptr) return HBMM_EINVAL;
-        if (!a_scales || !aligned16(a_scales) || lds_a < K) return HBMM_EINVAL;
-        return from_hip(hbmm::launch_binary_weight_gemm(a_scales, lds_a, b_bits, b_scales, ldw_b, lds_b,
-                                                        beta_w, M, N, K, C, ldc, s));
+    if (!(word_a && word_w)) {
+        // Matrix-core path: the operand with the longer segment keeps its signs (its scale is applied
+        // once per segment), the other one is rebuilt as fp32 values.
+        const bool b_is_sign = beta_w >= 16 && (beta_w >= beta_a || beta_a < 16);
+        if (b_is_sign)
+            return from_hip(hbmm::launch_mfma_split_gemm(to_split(oa), to_split(ob), K, C, ldc, 1, s));
+        return from_hip(hbmm::launch_mfma_split_gemm(to_split(ob), to_split(oa), K, C, 1, ldc, s));
     }
-
-    if (!a_scales || !aligned16(a_scales) || lds_a < K / beta_a) return HBMM_EINVAL;
-    if (int rc = check_packed(a_bits, M, K, ldw_a)) return rc;
 
     if (algo == 1)
         return from_hip(hbmm::launch_mfma_i8_gemm(a_bits, a_scales, ldw_a, lds_a, beta_a, b_bits, b_scales,
@@ -157,7 +199,6 @@ int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int6
         g.Q = (int32_t)N; g.shift_q = log2_exact(beta_w / G);
         g.ld_out_p = ldc; g.ld_out_q = 1;
     }
-    if (lds_a >= ((int64_t)1 << 31) || lds_b >= ((int64_t)1 << 31)) return HBMM_EINVAL;
     g.out = C;
     g.kwords = (int32_t)hbmm::packed_words(K);
     g.ngran = (int32_t)(K / G);

@@ -1,0 +1,357 @@
+// HBMM on the matrix cores for the cases where one operand is not reduced to bits per 32-bit
+// word: beta_a = 1 (the paper's HBWN: activations stay fp32) and short segments (beta < 32, the
+// settings HadaNets trains with: 2, 4, 8, 16).
+//
+//   out[x, y] = sum_j sY[y, j] * sum_{k in segment j of Y} X~[x, k] * (+-1)_Y[y, k]
+//
+// X is the "dense" side: X~[x, k] is an fp32 number, either the raw operand (beta_x = 1) or
+// sX[x, k div beta_x] * Sign(x) rebuilt from the packed bits and scales (Eq. 2 / Eq. 4 of the
+// paper).  Y is the "sign" side: +-1 per element, its scale applied once per segment (beta_y >= 16).
+// With short segments the popcount formulation costs five vector-ALU instructions per segment per
+// output; here the cost does not depend on beta_x at all.
+//
+// The inner sum is a dense contraction, so it runs on v_mfma_f32_32x32x16_bf16.  An fp32 value is
+// split exactly into three bf16 pieces (8 + 8 + 8 significant bits: hi = top half of the fp32
+// pattern, mid = top half of (v - hi), lo = v - hi - mid); +-1 is exact in bf16; so every product is
+// exact and the three piece-products accumulate in the MFMA's fp32 accumulator: a segment sum is an
+// fp32 sum of exact terms, like the scalar definition.  At the end of a Y segment one FMA per
+// output applies sY and the next segment's first MFMA starts from a zero accumulator.
+//
+// Layout of the work.  Workgroup = 8 waves, tile 128 (X) x 256 (Y); wave = 64 x 64 = 2 x 2 MFMA tiles
+// (lane l feeds row (l mod 32) and 8 consecutive k at 8 * (l div 32); both operands use the same
+// map).  K is walked in stages of 32:
+//   * X: raw mode fetches 128 rows x 32 fp32 with 16-byte loads; packed mode fetches one word of bits
+//     and the 1..4 scales that cover a thread's 8 elements.  Either way the three bf16 pieces are
+//     produced once per workgroup while the stage is parked in LDS (row stride 80 bytes: the 16-byte
+//     fragment reads of 8 consecutive rows land on distinct banks).  In packed mode only the scale is
+//     split; the sign is a xor on the piece's sign bit.
+//   * Y: one packed word per row per stage; two threads expand it to 32 bf16 values +-1.0 in LDS
+//     (three ALU instructions per pair of elements), shared by the waves that use that row.
+// Global loads are unconditional (indices clamped, never guarded, so the compiler knows how many
+// are outstanding) and run three stages ahead through three rotating register sets: a stage is
+// only ~16 KB per workgroup and HBM latency is several stages long.  Tiles that share X rows get
+// consecutive slots on one XCD so that the repeat reads of X come from that XCD's L2.
+#include "kernels.h"
+
+namespace hbmm {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kBX = 128, kBY = 256;
+constexpr int kThreadsS = 512;
+constexpr int kStageK = 32;
+constexpr int kRowBytes = 80;                     // 32 bf16 + 16 bytes of padding
+constexpr int kPieceBytes = kBX * kRowBytes;      // one bf16 piece of the X tile
+constexpr int kNumXcdS = 8;
+
+// X modes: how the dense side is given
+constexpr int kXRaw = 0;      // fp32 operand itself (beta_x = 1)
+constexpr int kXScale1 = 1;   // packed, beta_x >= 8: one scale covers a thread's 8 elements
+constexpr int kXScale2 = 2;   // packed, beta_x = 4: two scales per 8 elements
+constexpr int kXScale4 = 3;   // packed, beta_x = 2: four scales per 8 elements
+
+// Sign masks for `n` (<= 8) pairs of elements: complemented bit 2i of `inv` -> bit 15 of dword i,
+// complemented bit 2i+1 -> bit 31 (the sign positions of a pair of bf16 values).
+template <int PAIRS>
+__device__ __forceinline__ void sign_masks(uint32_t inv, uint32_t (&m)[PAIRS])
+{
+#pragma unroll
+    for (int i = 0; i < PAIRS; ++i) m[i] = ((inv << (15 - 2 * i)) | (inv << (30 - 2 * i))) & 0x80008000u;
+}
+
+// Exact split of an fp32 value into three bf16 patterns (each returned in the HIGH half of a word).
+__device__ __forceinline__ void split3(float v, uint32_t &hi, uint32_t &mid, uint32_t &lo)
+{
+    hi = __builtin_bit_cast(uint32_t, v) & 0xffff0000u;
+    const float r1 = v - __builtin_bit_cast(float, hi);
+    mid = __builtin_bit_cast(uint32_t, r1) & 0xffff0000u;
+    const float r2 = r1 - __builtin_bit_cast(float, mid);
+    lo = __builtin_bit_cast(uint32_t, r2) & 0xffff0000u;
+}
+// Two high-half patterns -> one dword holding element a in the low half and element b in the high half.
+__device__ __forceinline__ uint32_t pair16(uint32_t a_hi, uint32_t b_hi) { return (a_hi >> 16) | b_hi; }
+
+struct SplitArgs {
+    const float *x_raw;          // kXRaw
+    const uint32_t *x_bits;      // packed modes
+    const float *x_scales;
+    const uint32_t *y_bits;
+    const float *y_scales;
+    float *out;
+    int64_t ldx_raw, ld_out_x, ld_out_y;
+    int32_t ldw_x, lds_x, ldw_y, lds_y;
+    int32_t X, Y, K;
+    int32_t log2_beta_x;         // packed modes
+    int32_t stages_per_yseg;     // beta_y / 32 (beta_y >= 32); unused when beta_y = 16
+    int32_t tiles_y, tiles_total, slots_per_xcd;
+};
+
+template <int XMODE, bool Y16>
+__global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitArgs a)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char sX[2][3 * kPieceBytes];
+    __shared__ __attribute__((aligned(16))) unsigned char sY[2][kBY * kRowBytes];
+
+    // slot -> tile: consecutive slots of one XCD walk tiles in row-major (x, y) order
+    const int slot = (blockIdx.x % kNumXcdS) * a.slots_per_xcd + blockIdx.x / kNumXcdS;
+    if (slot >= a.tiles_total) return;
+    const int x0 = (slot / a.tiles_y) * kBX, y0 = (slot % a.tiles_y) * kBY;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wx = wave >> 2, wy = wave & 3;
+    const int nstages = a.K / kStageK;
+
+    constexpr int kScalesPerThread = XMODE == kXScale4 ? 4 : XMODE == kXScale2 ? 2 : 1;
+    struct Staged {
+        float4 xr[XMODE == kXRaw ? 2 : 1];                 // raw: 2 x 4 fp32
+        uint32_t xb;                                       // packed: the row's word of this stage
+        float xs[kScalesPerThread];                        // packed: scales of this thread's 8 elements
+        uint32_t yb;                                       // the Y row's word of this stage
+    };
+
+    // ---- sources (clamped, so every load below is unconditional)
+    const float *xr_src[2] = {nullptr, nullptr};
+    const uint32_t *xb_src = nullptr;
+    const float *xs_src = nullptr;
+    const int prow = tid >> 2, poct = tid & 3;             // packed modes: row and 8-element group
+    if (XMODE == kXRaw) {
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int id = tid + r * kThreadsS;
+            xr_src[r] = a.x_raw + (int64_t)min(x0 + (id >> 3), a.X - 1) * a.ldx_raw + (id & 7) * 4;
+        }
+    } else {
+        const int64_t row = min(x0 + prow, a.X - 1);
+        xb_src = a.x_bits + row * a.ldw_x;
+        xs_src = a.x_scales + row * a.lds_x;
+    }
+    const int yrow_t = tid >> 1, yhalf = tid & 1;          // Y expansion: row and 16-element half
+    const uint32_t *yb_src = a.y_bits + (int64_t)min(y0 + yrow_t, a.Y - 1) * a.ldw_y;
+
+    auto fetch = [&](Staged &st, int stage) {
+        const int sg = min(stage, nstages - 1);
+        if (XMODE == kXRaw) {
+#pragma unroll
+            for (int r = 0; r < 2; ++r) st.xr[r] = *reinterpret_cast<const float4 *>(xr_src[r] + sg * kStageK);
+        } else {
+            st.xb = xb_src[sg];
+            const int sidx = (sg * kStageK + poct * 8) >> a.log2_beta_x;
+#pragma unroll
+            for (int j = 0; j < kScalesPerThread; ++j) st.xs[j] = xs_src[sidx + j];
+        }
+        st.yb = yb_src[sg];
+    };
+
+    auto park = [&](const Staged &st, int buf) {
+        if (XMODE == kXRaw) {
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                const int id = tid + r * kThreadsS;
+                const int row = id >> 3, c = id & 7;
+                uint32_t h[4], m[4], l[4];
+                split3(st.xr[r].x, h[0], m[0], l[0]);
+                split3(st.xr[r].y, h[1], m[1], l[1]);
+                split3(st.xr[r].z, h[2], m[2], l[2]);
+                split3(st.xr[r].w, h[3], m[3], l[3]);
+                unsigned char *dst = &sX[buf][row * kRowBytes + c * 8];
+                *reinterpret_cast<uint2 *>(dst) = make_uint2(pair16(h[0], h[1]), pair16(h[2], h[3]));
+                *reinterpret_cast<uint2 *>(dst + kPieceBytes) = make_uint2(pair16(m[0], m[1]), pair16(m[2], m[3]));
+                *reinterpret_cast<uint2 *>(dst + 2 * kPieceBytes) = make_uint2(pair16(l[0], l[1]), pair16(l[2], l[3]));
+            }
+        } else {
+            // 8 elements = 4 dwords per piece; the scale is split once, the sign is a xor
+            uint32_t sm[4];
+            sign_masks<4>(~(st.xb >> (8 * poct)) & 0xffu, sm);
+            uint32_t ph[kScalesPerThread], pm[kScalesPerThread], pl[kScalesPerThread];
+#pragma unroll
+            for (int j = 0; j < kScalesPerThread; ++j) {
+                uint32_t h, m, l;
+                split3(st.xs[j], h, m, l);
+                ph[j] = pair16(h, h);
+                pm[j] = pair16(m, m);
+                pl[j] = pair16(l, l);
+            }
+            u32x4 dh, dm, dl;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int j = i * kScalesPerThread / 4;    // scale that covers elements 2i, 2i+1
+                dh[i] = ph[j] ^ sm[i];
+                dm[i] = pm[j] ^ sm[i];
+                dl[i] = pl[j] ^ sm[i];
+            }
+            unsigned char *dst = &sX[buf][prow * kRowBytes + poct * 16];
+            *reinterpret_cast<u32x4 *>(dst) = dh;
+            *reinterpret_cast<u32x4 *>(dst + kPieceBytes) = dm;
+            *reinterpret_cast<u32x4 *>(dst + 2 * kPieceBytes) = dl;
+        }
+        // Y: 16 signs -> 16 bf16 values +-1.0
+        uint32_t ym[8];
+        sign_masks<8>(~(st.yb >> (16 * yhalf)) & 0xffffu, ym);
+        u32x4 y0v, y1v;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            y0v[i] = ym[i] | 0x3f803f80u;
+            y1v[i] = ym[4 + i] | 0x3f803f80u;
+        }
+        unsigned char *ydst = &sY[buf][yrow_t * kRowBytes + yhalf * 32];
+        *reinterpret_cast<u32x4 *>(ydst) = y0v;
+        *reinterpret_cast<u32x4 *>(ydst + 16) = y1v;
+    };
+
+    f32x16 acc[2][2], res[2][2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                acc[p][q][v] = 0.f;
+                res[p][q][v] = 0.f;
+            }
+
+    // per-lane Y scale rows: the output column of accumulator tile ty is y0 + wy*64 + 32*ty + lane%32
+    const float *srow[2];
+    bool col_ok[2];
+#pragma unroll
+    for (int ty = 0; ty < 2; ++ty) {
+        const int col = y0 + wy * 64 + ty * 32 + (lane & 31);
+        col_ok[ty] = col < a.Y;
+        srow[ty] = a.y_scales + (int64_t)min(col, a.Y - 1) * a.lds_y;
+    }
+
+    auto apply_scale = [&](const float (&sc)[2]) {
+#pragma unroll
+        for (int tx = 0; tx < 2; ++tx)
+#pragma unroll
+            for (int ty = 0; ty < 2; ++ty)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    res[tx][ty][v] = __builtin_fmaf(sc[ty], acc[tx][ty][v], res[tx][ty][v]);
+                    acc[tx][ty][v] = 0.f;
+                }
+    };
+
+    float sc_seg[2] = {0.f, 0.f};
+    // One K stage: multiply the tile parked in LDS buffer (stage mod 2), request stage + 3 into
+    // `incoming`, and park `ready` (stage + 1, requested three stages ago) in the other buffer.
+    auto run_stage = [&](int stage, const Staged &ready, Staged &incoming) {
+        const int buf = stage & 1;
+        fetch(incoming, stage + 3);
+        float sc16[2][2];
+        bool seg_last = false;
+        if (Y16) {
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                for (int ty = 0; ty < 2; ++ty) sc16[ks][ty] = srow[ty][stage * 2 + ks];
+        } else {
+            seg_last = (stage + 1) % a.stages_per_yseg == 0;
+            if (stage % a.stages_per_yseg == 0) {
+#pragma unroll
+                for (int ty = 0; ty < 2; ++ty) sc_seg[ty] = srow[ty][stage / a.stages_per_yseg];
+            }
+        }
+        const unsigned char *px = &sX[buf][(wx * 64 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
+        const unsigned char *py = &sY[buf][(wy * 64 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
+#pragma unroll
+        for (int ks = 0; ks < kStageK / 16; ++ks) {
+            bf16x8 fy[2];
+#pragma unroll
+            for (int ty = 0; ty < 2; ++ty)
+                fy[ty] = *reinterpret_cast<const bf16x8 *>(py + ty * 32 * kRowBytes + ks * 32);
+#pragma unroll
+            for (int p = 0; p < 3; ++p) {
+                bf16x8 fx[2];
+#pragma unroll
+                for (int tx = 0; tx < 2; ++tx)
+                    fx[tx] = *reinterpret_cast<const bf16x8 *>(px + p * kPieceBytes + tx * 32 * kRowBytes + ks * 32);
+#pragma unroll
+                for (int tx = 0; tx < 2; ++tx)
+#pragma unroll
+                    for (int ty = 0; ty < 2; ++ty)
+                        acc[tx][ty] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[tx], fy[ty], acc[tx][ty], 0, 0, 0);
+            }
+            if (Y16) apply_scale(sc16[ks]);
+        }
+        if (!Y16 && seg_last) apply_scale(sc_seg);
+        park(ready, buf ^ 1);   // past the last stage this parks data that nobody reads
+        __syncthreads();
+    };
+
+    Staged s0, s1, s2;
+    fetch(s0, 0);
+    park(s0, 0);
+    fetch(s0, 1);
+    fetch(s1, 2);
+    __syncthreads();
+    for (int stage = 0; stage < nstages; stage += 3) {
+        run_stage(stage, s0, s2);
+        if (stage + 1 < nstages) run_stage(stage + 1, s1, s0);
+        if (stage + 2 < nstages) run_stage(stage + 2, s2, s1);
+    }
+
+#pragma unroll
+    for (int tx = 0; tx < 2; ++tx)
+#pragma unroll
+        for (int ty = 0; ty < 2; ++ty) {
+            if (!col_ok[ty]) continue;
+            const int col = y0 + wy * 64 + ty * 32 + (lane & 31);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = x0 + wx * 64 + tx * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                if (row < a.X) a.out[(int64_t)row * a.ld_out_x + (int64_t)col * a.ld_out_y] = res[tx][ty][v];
+            }
+        }
+}
+
+template <int XMODE>
+hipError_t launch_mode(const SplitArgs &a, bool y16, unsigned grid, hipStream_t s)
+{
+    if (y16)
+        mfma_split_gemm_kernel<XMODE, true><<<dim3(grid), dim3(kThreadsS), 0, s>>>(a);
+    else
+        mfma_split_gemm_kernel<XMODE, false><<<dim3(grid), dim3(kThreadsS), 0, s>>>(a);
+    return hipGetLastError();
+}
+
+int ilog2s(int v)
+{
+    int s = 0;
+    while ((1 << s) < v) ++s;
+    return s;
+}
+
+}  // namespace
+
+hipError_t launch_mfma_split_gemm(const SplitGemmOperand &x, const SplitGemmOperand &y, int64_t K, float *out,
+                                  int64_t ld_out_x, int64_t ld_out_y, hipStream_t s)
+{
+    // x: dense side (beta 1 = raw fp32 through x.raw, or packed with any supported beta)
+    // y: sign side, packed, beta >= 16
+    if (y.beta < 16 || y.bits == nullptr || K % kStageK != 0) return hipErrorNotSupported;
+    if (x.beta == 1 && (x.raw == nullptr || x.ld_raw % 4 != 0)) return hipErrorNotSupported;
+    SplitArgs a{};
+    a.x_raw = x.raw; a.ldx_raw = x.ld_raw;
+    a.x_bits = x.bits; a.x_scales = x.scales; a.ldw_x = (int32_t)x.ldw; a.lds_x = (int32_t)x.lds;
+    a.y_bits = y.bits; a.y_scales = y.scales; a.ldw_y = (int32_t)y.ldw; a.lds_y = (int32_t)y.lds;
+    a.out = out; a.ld_out_x = ld_out_x; a.ld_out_y = ld_out_y;
+    a.X = (int32_t)x.rows; a.Y = (int32_t)y.rows; a.K = (int32_t)K;
+    a.log2_beta_x = ilog2s(x.beta);
+    a.stages_per_yseg = y.beta >= 32 ? y.beta / kStageK : 1;
+    const int64_t tiles_x = (x.rows + kBX - 1) / kBX, tiles_y = (y.rows + kBY - 1) / kBY;
+    const int64_t total = tiles_x * tiles_y;
+    const int64_t per_xcd = (total + kNumXcdS - 1) / kNumXcdS;
+    if (per_xcd * kNumXcdS > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    a.tiles_y = (int32_t)tiles_y; a.tiles_total = (int32_t)total; a.slots_per_xcd = (int32_t)per_xcd;
+    const unsigned grid = (unsigned)(per_xcd * kNumXcdS);
+    const bool y16 = y.beta == 16;
+    if (x.beta == 1) return launch_mode<kXRaw>(a, y16, grid, s);
+    if (x.beta == 2) return launch_mode<kXScale4>(a, y16, grid, s);
+    if (x.beta == 4) return launch_mode<kXScale2>(a, y16, grid, s);
+    return launch_mode<kXScale1>(a, y16, grid, s);
+}
+
+}  // namespace hbmm

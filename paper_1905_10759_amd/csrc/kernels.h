@@ -47,11 +47,22 @@ struct PopcountGemmArgs {
 // G = min(beta_p, beta_q) in {32, 64, 128, 256}; integer != 0 selects the unscaled whole-row mode.
 hipError_t launch_popcount_gemm(const PopcountGemmArgs &a, int G, int integer, hipStream_t s);
 
-// ---- gemm_binary_weight.hip -------------------------------------------------------------------
-hipError_t launch_binary_weight_gemm(const float *A, int64_t lda, const uint32_t *b_bits,
-                                     const float *b_scales, int64_t ldw_b, int64_t lds_b, int beta_w,
-                                     int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
-                                     hipStream_t s);
+// ---- gemm_mfma_split.hip ---------------------------------------------------------------------
+// One operand of the matrix-core HBMM.  beta == 1: `raw` is the fp32 operand itself (rows x K,
+// leading dimension ld_raw) and bits / scales are unused; otherwise the packed form.
+struct SplitGemmOperand {
+    const float *raw;
+    int64_t ld_raw;
+    const uint32_t *bits;
+    const float *scales;
+    int64_t ldw, lds;
+    int64_t rows;
+    int beta;
+};
+// out[x * ld_out_x + y * ld_out_y] = sum_j sY[y, j] * sum_{k in j} X~[x, k] * Sign(Y)[y, k].
+// x: any supported beta (1 = raw); y: packed with beta >= 16.  K must be a multiple of 32.
+hipError_t launch_mfma_split_gemm(const SplitGemmOperand &x, const SplitGemmOperand &y, int64_t K, float *out,
+                                  int64_t ld_out_x, int64_t ld_out_y, hipStream_t s);
 
 // ---- gemm_mfma_i8.hip -------------------------------------------------------------------------
 hipError_t launch_mfma_i8_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a,

@@ -108,22 +108,26 @@ def quantize_pack(x: torch.Tensor, beta: int, layout: int = 0, bits: torch.Tenso
 
 def gemm(a_bits, a_scales, beta_a: int, b_bits, b_scales, beta_w: int, K: int, algo: int = ALGO_POPCOUNT,
          out: torch.Tensor | None = None) -> torch.Tensor:
-    """hbmm_gemm.  For beta_a == 1 pass a_bits=None and a_scales = the raw fp32 A (M x K)."""
-    _dev(b_bits, torch.int32, "b_bits")
+    """hbmm_gemm.  An operand with beta == 1 is passed unquantised: bits=None and scales = the raw
+    fp32 matrix (rows x K)."""
     _dev(b_scales, torch.float32, "b_scales")
     _dev(a_scales, torch.float32, "a_scales")
-    M, N = a_scales.shape[0], b_bits.shape[0]
+    M, N = a_scales.shape[0], b_scales.shape[0]
     if out is None:
-        out = torch.empty((M, N), dtype=torch.float32, device=b_bits.device)
+        out = torch.empty((M, N), dtype=torch.float32, device=a_scales.device)
     _dev(out, torch.float32, "out")
-    a_ptr, ldw_a = (0, 0)
-    if a_bits is not None:
-        _dev(a_bits, torch.int32, "a_bits")
-        a_ptr, ldw_a = a_bits.data_ptr(), a_bits.stride(0) if M > 1 else a_bits.shape[1]
+
+    def packed(bits, rows, name):
+        if bits is None:
+            return 0, 0
+        _dev(bits, torch.int32, name)
+        return bits.data_ptr(), bits.stride(0) if rows > 1 else bits.shape[1]
+
+    a_ptr, ldw_a = packed(a_bits, M, "a_bits")
+    b_ptr, ldw_b = packed(b_bits, N, "b_bits")
     rc = lib.hbmm_gemm(a_ptr, a_scales.data_ptr(), ldw_a,
                        a_scales.stride(0) if M > 1 else max(a_scales.shape[1], 1), beta_a,
-                       b_bits.data_ptr(), b_scales.data_ptr(),
-                       b_bits.stride(0) if N > 1 else b_bits.shape[1],
+                       b_ptr, b_scales.data_ptr(), ldw_b,
                        b_scales.stride(0) if N > 1 else max(b_scales.shape[1], 1), beta_w,
                        M, N, K, out.data_ptr(), out.stride(0) if M > 1 else max(N, 1), algo, _stream())
     _check(rc, "hbmm_gemm")

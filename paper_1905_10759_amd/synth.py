@@ -21,6 +21,7 @@ c5x   12544, 4608, 512        128/128  max(0, N(0,1))                          N
 c5xw  12544, 4608, 512        1/128    max(0, N(0,1)) (kept fp32)              N x K, N(0, sqrt(2/K))
 sq4k  4096, 4096, 4096        64/64    N(0,1)                                  N x K, N(0,1)
 sq8k  8192, 8192, 8192        256/256  U[-1,1)                                 N x K, U[-1,1)
+sq4k16  4096, 4096, 4096      16/16    N(0,1)  (the paper's benchmark setting)  N x K, N(0,1)
 ====  ======================  =======  ======================================  ==========
 """
 from __future__ import annotations
@@ -148,5 +149,7 @@ WORKLOADS = {
         Workload("c5xw", 12544, 4608, 512, 1, 128, "relu_normal", "he_normal", 0, 3001, 3002),
         Workload("sq4k", 4096, 4096, 4096, 64, 64, "normal", "normal", 0, 4001, 4002),
         Workload("sq8k", 8192, 8192, 8192, 256, 256, "uniform_pm1", "uniform_pm1", 0, 5001, 5002),
+        # the setting of the paper's own speed figure (square matrices, beta = 16)
+        Workload("sq4k16", 4096, 4096, 4096, 16, 16, "normal", "normal", 0, 6001, 6002),
     )
 }

@@ -188,6 +188,48 @@ def test_gemm_binary_weight(beta_w, M, N, K):
     assert_close_to_oracle(got.cpu().numpy(), ref, T, "binary weight")
 
 
+def split_case(A, B, beta_a, beta_w):
+    """Matrix-core path (a segment shorter than 32 or an unquantised operand on one side): the
+    oracle is the dense definition; T = |A~| . |B~|^T."""
+    At, Bt = oracle.materialize(A, beta_a), oracle.materialize(B, beta_w)
+    ref, T = oracle.dense_f64_gemm(At, Bt), oracle.dense_f64_gemm(np.abs(At), np.abs(Bt))
+    K = A.shape[1]
+
+    def operand(x, beta):
+        if beta == 1:
+            return None, dev(x)
+        return dev(oracle.sign_pack(x).view(np.int32)), dev(oracle.block_scales(x, beta))
+
+    (ab, as_), (bb, bs) = operand(A, beta_a), operand(B, beta_w)
+    got = hbmm.gemm(ab, as_, beta_a, bb, bs, beta_w, K)
+    return assert_close_to_oracle(got.cpu().numpy(), ref, T, f"split {A.shape}x{B.shape} b=({beta_a},{beta_w})")
+
+
+@pytest.mark.parametrize("beta_a,beta_w", [(1, 16), (2, 16), (4, 16), (8, 16), (16, 16), (2, 32), (4, 64), (8, 128),
+                                           (16, 256), (2, 256), (16, 2), (32, 4), (256, 8), (64, 16), (16, 32),
+                                           (16, 1), (128, 1), (1, 256)])
+def test_gemm_short_segments(beta_a, beta_w):
+    """Segments of 2..16 on either side (the settings the paper trains with), mixed with long ones,
+    and an unquantised operand on either side."""
+    A = synth.normal(900 + beta_a, (200, 1280))
+    B = synth.normal(901 + beta_w, (300, 1280), std=0.05)
+    split_case(A, B, beta_a, beta_w)
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 32), (130, 260, 96), (257, 513, 1024), (64, 64, 4608)])
+def test_gemm_short_segments_shapes(M, N, K):
+    split_case(synth.relu_normal(910 + M, (M, K)), synth.normal(911 + N, (N, K)), 4, 16)
+    split_case(synth.normal(912 + M, (M, K)), synth.uniform_pm1(913 + N, (N, K)), 16, 2)
+
+
+def test_gemm_both_short_is_reported_unsupported():
+    x = torch.zeros((4, 4), dtype=torch.int32, device="cuda")
+    s = torch.ones((4, 16), dtype=torch.float32, device="cuda")
+    with pytest.raises(hbmm.HbmmError) as ei:
+        hbmm.gemm(x, s, 4, x, s, 8, 64)
+    assert ei.value.code == hbmm.EUNSUPPORTED
+
+
 def test_gemm_empty_and_zero_k():
     e = torch.empty((0, 4), dtype=torch.int32, device="cuda")
     s = torch.empty((0, 1), dtype=torch.float32, device="cuda")

@@ -66,6 +66,26 @@ def test_workload_full_size(hbmm, name):
     assert_close_to_oracle(got2[rows], dense, T[rows], name + " (dense f64, sampled rows)")
 
 
+def test_workload_paper_setting_beta16(hbmm):
+    """Square 4096^3 with beta = 16 on both sides (the paper's own benchmark setting): whole path on
+    the GPU; every output against the oracle's integer path, sampled rows against the dense path."""
+    w = synth.WORKLOADS["sq4k16"]
+    A, B = w.make_a(), w.make_b()
+    a_bits, a_s = hbmm.quantize_pack(dev(A), w.beta_a)
+    b_bits, b_s = hbmm.quantize_pack(dev(B), w.beta_w)
+    ra, rb = oracle.sign_pack(A), oracle.sign_pack(B)
+    sa, sb = oracle.block_scales(A, w.beta_a), oracle.block_scales(B, w.beta_w)
+    assert np.array_equal(words(a_bits), ra) and np.array_equal(words(b_bits), rb)
+    assert np.all(np.abs(a_s.cpu().numpy() - sa) <= scale_tol(16) * sa)
+    got = hbmm.gemm(a_bits, dev(sa), 16, b_bits, dev(sb), 16, w.K).cpu().numpy()
+    ref, T = oracle.popcount_gemm(ra, sa, 16, rb, sb, 16, w.K, want_T=True)
+    worst = assert_close_to_oracle(got, ref, T, "sq4k16")
+    print(f"[sq4k16] ok, worst err/(1e-5 T) = {worst:.3f}", flush=True)
+    rows = np.unique(np.linspace(0, w.M - 1, 16).astype(np.int64))
+    dense = oracle.dense_f64_gemm(oracle.materialize(A[rows], 16, sa[rows]), oracle.materialize(B, 16, sb))
+    assert_close_to_oracle(got[rows], dense, T[rows], "sq4k16 (dense f64, sampled rows)")
+
+
 def test_workload_binary_weight_full_size(hbmm):
     w = synth.WORKLOADS["c5xw"]
     A, B = w.make_a(), w.make_b()
