@@ -276,8 +276,10 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
             }
             if (Y16) apply_scale(sc16[ks]);
         }
-        if (!Y16 && seg_last) apply_scale(sc_seg);
+        // The next stage is parked before the (conditional) segment epilogue so that the splitting
+        // and sign-expansion arithmetic sits in the same scheduling region as the MFMAs.
         park(ready, buf ^ 1);   // past the last stage this parks data that nobody reads
+        if (!Y16 && seg_last) apply_scale(sc_seg);
         __syncthreads();
     };
 
