@@ -91,9 +91,10 @@ int hbmm_quantize_pack(const float *x, int64_t rows, int64_t K, int64_t ldx, int
  *                     beta_a = 1:  C[m, n] = sum_j sB[n, j] * sum_{k in j} A[m, k] * Sign(B)[n, k].
  *                     Both >= 32: the XNOR + popcount kernel.  Otherwise (a segment shorter than a
  *                     32-bit word, or an unquantised operand) the product runs on the matrix cores:
- *                     the operand with the longer segment keeps its signs and must have beta >= 16,
- *                     the other is rebuilt as fp32 values split exactly into three bf16 pieces.
- *                     Both < 16 (and 1 with 1) is not supported.
+ *                     the operand with the longer segment (>= 16) keeps its signs, the other is
+ *                     rebuilt as fp32 values split exactly into three bf16 pieces; if both segments
+ *                     are shorter than 16 both are rebuilt.  Not supported: beta = 1 for both (that is
+ *                     hbmm_dense_ref_gemm), and beta = 1 against a segment shorter than 16.
  *   C                 out, M x N fp32, leading dimension ldc >= N.
  *   algo              0: the method's kernel as described above.
  *                     1: (both beta >= 32 only) the same d[m, n, g] from int8 +-1 matrix-core (MFMA)

@@ -158,8 +158,9 @@ int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int6
         return HBMM_EUNSUPPORTED;
     if (K % beta_w != 0 || K % beta_a != 0 || K % 32 != 0) return HBMM_EUNSUPPORTED;
     if (algo == 1 && !(word_a && word_w)) return HBMM_EUNSUPPORTED;
-    // Off the popcount path one operand keeps its +-1 form and needs a segment of at least 16.
-    if (!(word_a && word_w) && beta_a < 16 && beta_w < 16) return HBMM_EUNSUPPORTED;
+    // Two unquantised operands are a plain dense product (hbmm_dense_ref_gemm), and an unquantised
+    // operand needs the other one to keep its +-1 form (segment of at least 16).
+    if ((beta_a == 1 && beta_w < 16) || (beta_w == 1 && beta_a < 16)) return HBMM_EUNSUPPORTED;
     if (M == 0 || N == 0) return HBMM_OK;
     if (!C || !aligned16(C) || ldc < N) return HBMM_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -173,6 +174,8 @@ int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int6
     if (!(word_a && word_w)) {
         // Matrix-core path: the operand with the longer segment keeps its signs (its scale is applied
         // once per segment), the other one is rebuilt as fp32 values.
+        if (beta_a < 16 && beta_w < 16)   // neither can keep its signs: both rebuilt as fp32 values
+            return from_hip(hbmm::launch_mfma_split2_gemm(to_split(oa), to_split(ob), K, C, ldc, 1, s));
         const bool b_is_sign = beta_w >= 16 && (beta_w >= beta_a || beta_a < 16);
         if (b_is_sign)
             return from_hip(hbmm::launch_mfma_split_gemm(to_split(oa), to_split(ob), K, C, ldc, 1, s));

@@ -74,6 +74,32 @@ __device__ __forceinline__ void split3(float v, uint32_t &hi, uint32_t &mid, uin
 // Two high-half patterns -> one dword holding element a in the low half and element b in the high half.
 __device__ __forceinline__ uint32_t pair16(uint32_t a_hi, uint32_t b_hi) { return (a_hi >> 16) | b_hi; }
 
+// The three bf16 piece rows of 8 consecutive elements of a packed operand: `byte` holds their sign
+// bits (1 = +), `sc` the SPT scales that cover them (8 / SPT elements each).  Only the scales are
+// split; the sign is a xor on each piece's sign bit.
+template <int SPT>
+__device__ __forceinline__ void packed_pieces(uint32_t byte, const float (&sc)[SPT], u32x4 &dh, u32x4 &dm, u32x4 &dl)
+{
+    uint32_t sm[4];
+    sign_masks<4>(~byte & 0xffu, sm);
+    uint32_t ph[SPT], pm[SPT], pl[SPT];
+#pragma unroll
+    for (int j = 0; j < SPT; ++j) {
+        uint32_t h, m, l;
+        split3(sc[j], h, m, l);
+        ph[j] = pair16(h, h);
+        pm[j] = pair16(m, m);
+        pl[j] = pair16(l, l);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int j = i * SPT / 4;    // scale that covers elements 2i, 2i+1
+        dh[i] = ph[j] ^ sm[i];
+        dm[i] = pm[j] ^ sm[i];
+        dl[i] = pl[j] ^ sm[i];
+    }
+}
+
 struct SplitArgs {
     const float *x_raw;          // kXRaw
     const uint32_t *x_bits;      // packed modes
@@ -162,26 +188,8 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
                 *reinterpret_cast<uint2 *>(dst + 2 * kPieceBytes) = make_uint2(pair16(l[0], l[1]), pair16(l[2], l[3]));
             }
         } else {
-            // 8 elements = 4 dwords per piece; the scale is split once, the sign is a xor
-            uint32_t sm[4];
-            sign_masks<4>(~(st.xb >> (8 * poct)) & 0xffu, sm);
-            uint32_t ph[kScalesPerThread], pm[kScalesPerThread], pl[kScalesPerThread];
-#pragma unroll
-            for (int j = 0; j < kScalesPerThread; ++j) {
-                uint32_t h, m, l;
-                split3(st.xs[j], h, m, l);
-                ph[j] = pair16(h, h);
-                pm[j] = pair16(m, m);
-                pl[j] = pair16(l, l);
-            }
             u32x4 dh, dm, dl;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int j = i * kScalesPerThread / 4;    // scale that covers elements 2i, 2i+1
-                dh[i] = ph[j] ^ sm[i];
-                dm[i] = pm[j] ^ sm[i];
-                dl[i] = pl[j] ^ sm[i];
-            }
+            packed_pieces<kScalesPerThread>(st.xb >> (8 * poct), st.xs, dh, dm, dl);
             unsigned char *dst = &sX[buf][prow * kRowBytes + poct * 16];
             *reinterpret_cast<u32x4 *>(dst) = dh;
             *reinterpret_cast<u32x4 *>(dst + kPieceBytes) = dm;
@@ -309,6 +317,139 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
         }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Both segments shorter than 16 (e.g. the paper's HadaNet beta_w = beta_a = 4): no operand can keep
+// its +-1 form, so both are rebuilt as fp32 values and split; the product keeps the six piece pairs
+// hi*hi, hi*mid, mid*hi, mid*mid, hi*lo, lo*hi (what is dropped is below 2^-24 of the term) and needs
+// no epilogue at all.  Tile 128 x 128, 8 waves of 64 (X) x 32 (Y); K stages of 32 as above.
+struct Split2Args {
+    const uint32_t *x_bits, *y_bits;
+    const float *x_scales, *y_scales;
+    float *out;
+    int64_t ld_out_x, ld_out_y;
+    int32_t ldw_x, lds_x, ldw_y, lds_y;
+    int32_t X, Y, K;
+    int32_t log2_beta_x, log2_beta_y;
+    int32_t tiles_y, tiles_total, slots_per_xcd;
+};
+
+template <int SPX, int SPY>
+__global__ __launch_bounds__(kThreadsS) void mfma_split2_gemm_kernel(const Split2Args a)
+{
+    constexpr int kB2 = 128;
+    __shared__ __attribute__((aligned(16))) unsigned char sX[2][3 * kPieceBytes];
+    __shared__ __attribute__((aligned(16))) unsigned char sY[2][3 * kPieceBytes];
+
+    const int slot = (blockIdx.x % kNumXcdS) * a.slots_per_xcd + blockIdx.x / kNumXcdS;
+    if (slot >= a.tiles_total) return;
+    const int x0 = (slot / a.tiles_y) * kB2, y0 = (slot % a.tiles_y) * kB2;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wx = wave >> 2, wy = wave & 3;
+    const int nstages = a.K / kStageK;
+    const int prow = tid >> 2, poct = tid & 3;
+
+    struct Staged {
+        uint32_t xb, yb;
+        float xs[SPX], ys[SPY];
+    };
+    const uint32_t *xb_src = a.x_bits + (int64_t)min(x0 + prow, a.X - 1) * a.ldw_x;
+    const float *xs_src = a.x_scales + (int64_t)min(x0 + prow, a.X - 1) * a.lds_x;
+    const uint32_t *yb_src = a.y_bits + (int64_t)min(y0 + prow, a.Y - 1) * a.ldw_y;
+    const float *ys_src = a.y_scales + (int64_t)min(y0 + prow, a.Y - 1) * a.lds_y;
+    auto fetch = [&](Staged &st, int stage) {
+        const int sg = min(stage, nstages - 1);
+        st.xb = xb_src[sg];
+        st.yb = yb_src[sg];
+        const int k = sg * kStageK + poct * 8;
+#pragma unroll
+        for (int j = 0; j < SPX; ++j) st.xs[j] = xs_src[(k >> a.log2_beta_x) + j];
+#pragma unroll
+        for (int j = 0; j < SPY; ++j) st.ys[j] = ys_src[(k >> a.log2_beta_y) + j];
+    };
+    auto park = [&](const Staged &st, int buf) {
+        u32x4 dh, dm, dl;
+        packed_pieces<SPX>(st.xb >> (8 * poct), st.xs, dh, dm, dl);
+        unsigned char *dx = &sX[buf][prow * kRowBytes + poct * 16];
+        *reinterpret_cast<u32x4 *>(dx) = dh;
+        *reinterpret_cast<u32x4 *>(dx + kPieceBytes) = dm;
+        *reinterpret_cast<u32x4 *>(dx + 2 * kPieceBytes) = dl;
+        packed_pieces<SPY>(st.yb >> (8 * poct), st.ys, dh, dm, dl);
+        unsigned char *dy = &sY[buf][prow * kRowBytes + poct * 16];
+        *reinterpret_cast<u32x4 *>(dy) = dh;
+        *reinterpret_cast<u32x4 *>(dy + kPieceBytes) = dm;
+        *reinterpret_cast<u32x4 *>(dy + 2 * kPieceBytes) = dl;
+    };
+
+    f32x16 res[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) res[t][v] = 0.f;
+
+    auto run_stage = [&](int stage, const Staged &ready, Staged &incoming) {
+        const int buf = stage & 1;
+        fetch(incoming, stage + 3);
+        const unsigned char *px = &sX[buf][(wx * 64 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
+        const unsigned char *py = &sY[buf][(wy * 32 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
+#pragma unroll
+        for (int ks = 0; ks < kStageK / 16; ++ks) {
+            bf16x8 fx[3][2], fy[3];
+#pragma unroll
+            for (int p = 0; p < 3; ++p) {
+                fy[p] = *reinterpret_cast<const bf16x8 *>(py + p * kPieceBytes + ks * 32);
+#pragma unroll
+                for (int tx = 0; tx < 2; ++tx)
+                    fx[p][tx] = *reinterpret_cast<const bf16x8 *>(px + p * kPieceBytes + tx * 32 * kRowBytes + ks * 32);
+            }
+            // smallest contributions first: (hi,lo) (lo,hi) (mid,mid) (hi,mid) (mid,hi) (hi,hi)
+            constexpr int kPairs[6][2] = {{0, 2}, {2, 0}, {1, 1}, {0, 1}, {1, 0}, {0, 0}};
+#pragma unroll
+            for (int q = 0; q < 6; ++q)
+#pragma unroll
+                for (int tx = 0; tx < 2; ++tx)
+                    res[tx] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[kPairs[q][0]][tx], fy[kPairs[q][1]], res[tx], 0, 0, 0);
+        }
+        park(ready, buf ^ 1);
+        __syncthreads();
+    };
+
+    Staged s0, s1, s2;
+    fetch(s0, 0);
+    park(s0, 0);
+    fetch(s0, 1);
+    fetch(s1, 2);
+    __syncthreads();
+    for (int stage = 0; stage < nstages; stage += 3) {
+        run_stage(stage, s0, s2);
+        if (stage + 1 < nstages) run_stage(stage + 1, s1, s0);
+        if (stage + 2 < nstages) run_stage(stage + 2, s2, s1);
+    }
+
+    const int col = y0 + wy * 32 + (lane & 31);
+    if (col < a.Y) {
+#pragma unroll
+        for (int tx = 0; tx < 2; ++tx)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = x0 + wx * 64 + tx * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                if (row < a.X) a.out[(int64_t)row * a.ld_out_x + (int64_t)col * a.ld_out_y] = res[tx][v];
+            }
+    }
+}
+
+template <int SPX>
+hipError_t launch_split2_y(const Split2Args &a, int spy, unsigned grid, hipStream_t s)
+{
+    if (spy == 4)
+        mfma_split2_gemm_kernel<SPX, 4><<<dim3(grid), dim3(kThreadsS), 0, s>>>(a);
+    else if (spy == 2)
+        mfma_split2_gemm_kernel<SPX, 2><<<dim3(grid), dim3(kThreadsS), 0, s>>>(a);
+    else
+        mfma_split2_gemm_kernel<SPX, 1><<<dim3(grid), dim3(kThreadsS), 0, s>>>(a);
+    return hipGetLastError();
+}
+
 template <int XMODE>
 hipError_t launch_mode(const SplitArgs &a, bool y16, unsigned grid, hipStream_t s)
 {
@@ -327,6 +468,30 @@ int ilog2s(int v)
 }
 
 }  // namespace
+
+hipError_t launch_mfma_split2_gemm(const SplitGemmOperand &x, const SplitGemmOperand &y, int64_t K, float *out,
+                                   int64_t ld_out_x, int64_t ld_out_y, hipStream_t s)
+{
+    // both operands packed with beta in {2, 4, 8, 16, ...}; used when neither can keep its signs
+    if (x.beta < 2 || y.beta < 2 || !x.bits || !y.bits || K % kStageK != 0) return hipErrorNotSupported;
+    Split2Args a{};
+    a.x_bits = x.bits; a.x_scales = x.scales; a.ldw_x = (int32_t)x.ldw; a.lds_x = (int32_t)x.lds;
+    a.y_bits = y.bits; a.y_scales = y.scales; a.ldw_y = (int32_t)y.ldw; a.lds_y = (int32_t)y.lds;
+    a.out = out; a.ld_out_x = ld_out_x; a.ld_out_y = ld_out_y;
+    a.X = (int32_t)x.rows; a.Y = (int32_t)y.rows; a.K = (int32_t)K;
+    a.log2_beta_x = ilog2s(x.beta); a.log2_beta_y = ilog2s(y.beta);
+    const int64_t tiles_x = (x.rows + 127) / 128, tiles_y = (y.rows + 127) / 128;
+    const int64_t total = tiles_x * tiles_y;
+    const int64_t per_xcd = (total + kNumXcdS - 1) / kNumXcdS;
+    if (per_xcd * kNumXcdS > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    a.tiles_y = (int32_t)tiles_y; a.tiles_total = (int32_t)total; a.slots_per_xcd = (int32_t)per_xcd;
+    const unsigned grid = (unsigned)(per_xcd * kNumXcdS);
+    auto spt = [](int beta) { return beta == 2 ? 4 : beta == 4 ? 2 : 1; };
+    const int spx = spt(x.beta), spy = spt(y.beta);
+    if (spx == 4) return launch_split2_y<4>(a, spy, grid, s);
+    if (spx == 2) return launch_split2_y<2>(a, spy, grid, s);
+    return launch_split2_y<1>(a, spy, grid, s);
+}
 
 hipError_t launch_mfma_split_gemm(const SplitGemmOperand &x, const SplitGemmOperand &y, int64_t K, float *out,
                                   int64_t ld_out_x, int64_t ld_out_y, hipStream_t s)

@@ -63,6 +63,10 @@ struct SplitGemmOperand {
 // x: any supported beta (1 = raw); y: packed with beta >= 16.  K must be a multiple of 32.
 hipError_t launch_mfma_split_gemm(const SplitGemmOperand &x, const SplitGemmOperand &y, int64_t K, float *out,
                                   int64_t ld_out_x, int64_t ld_out_y, hipStream_t s);
+// Same product with both operands rebuilt as fp32 values (both packed, any beta >= 2): for the case
+// where both segments are shorter than 16.
+hipError_t launch_mfma_split2_gemm(const SplitGemmOperand &x, const SplitGemmOperand &y, int64_t K, float *out,
+                                   int64_t ld_out_x, int64_t ld_out_y, hipStream_t s);
 
 // ---- gemm_mfma_i8.hip -------------------------------------------------------------------------
 hipError_t launch_mfma_i8_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a,

@@ -222,11 +222,23 @@ def test_gemm_short_segments_shapes(M, N, K):
     split_case(synth.normal(912 + M, (M, K)), synth.uniform_pm1(913 + N, (N, K)), 16, 2)
 
 
-def test_gemm_both_short_is_reported_unsupported():
-    x = torch.zeros((4, 4), dtype=torch.int32, device="cuda")
-    s = torch.ones((4, 16), dtype=torch.float32, device="cuda")
+@pytest.mark.parametrize("beta_a,beta_w", [(2, 2), (4, 4), (8, 8), (2, 8), (8, 2), (4, 2), (8, 4)])
+def test_gemm_both_segments_short(beta_a, beta_w):
+    """Both segments shorter than 16 (e.g. the paper's HadaNet with beta_w = beta_a = 4): both operands
+    are rebuilt as fp32 values on the fly."""
+    split_case(synth.normal(920 + beta_a, (200, 1280)), synth.normal(921 + beta_w, (300, 1280), std=0.05), beta_a, beta_w)
+    split_case(synth.relu_normal(922 + beta_a, (129, 96)), synth.uniform_pm1(923 + beta_w, (1, 96)), beta_a, beta_w)
+
+
+def test_gemm_two_unquantised_operands_are_reported_unsupported():
+    x = torch.zeros((4, 64), dtype=torch.float32, device="cuda")
     with pytest.raises(hbmm.HbmmError) as ei:
-        hbmm.gemm(x, s, 4, x, s, 8, 64)
+        hbmm.gemm(None, x, 1, None, x, 1, 64)
+    assert ei.value.code == hbmm.EUNSUPPORTED
+    bits = torch.zeros((4, 4), dtype=torch.int32, device="cuda")
+    sc = torch.ones((4, 16), dtype=torch.float32, device="cuda")
+    with pytest.raises(hbmm.HbmmError) as ei:
+        hbmm.gemm(None, x, 1, bits, sc, 4, 64)     # unquantised against a segment shorter than 16
     assert ei.value.code == hbmm.EUNSUPPORTED
 
 
