@@ -218,3 +218,37 @@ void oracle_binary_weight_gemm(const float *A, int64_t lda, const uint32_t *b_bi
         }
     }
 }
+
+/* Gradient through the Hadamard binarisation (Eq. 6, with the straight-through estimator of Eq. 5
+ * for Sign).  For a row x, incoming gradient g = dC/dx~ and segment s(i) of n elements (beta, or
+ * fewer in a ragged last segment; the printed upper limit of the sum is read as exclusive):
+ *   dC/dx_i = (1/n) * Sign(x_i) * sum_{j in s(i)} g_j * Sign(x_j)  +  delta_{s(i)} * g_i * [|x_i| <= 1]
+ * delta is the stored fp32 scale of the forward pass (mean |x| over the segment).  T (may be NULL)
+ * receives (1/n) * sum_j |g_j| + delta * |g_i| * [|x_i| <= 1], the scale of the fp32 rounding error. */
+void oracle_binarize_backward(const float *x, const float *g, int64_t rows, int64_t K, int64_t ldx,
+                              int64_t ldg, int64_t beta, double *gx, double *T)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t k0 = 0; k0 < K; k0 += beta) {
+            int64_t k1 = k0 + beta < K ? k0 + beta : K;
+            double n = (double)(k1 - k0), sabs = 0.0, sdot = 0.0, sg = 0.0;
+            for (int64_t k = k0; k < k1; ++k) {
+                double gv = (double)g[r * ldg + k];
+                sabs += fabs((double)x[r * ldx + k]);
+                sdot += sgn_ge0(x[r * ldx + k]) ? gv : -gv;
+                sg += fabs(gv);
+            }
+            double delta = (double)(float)(sabs / n);
+            for (int64_t k = k0; k < k1; ++k) {
+                float xv = x[r * ldx + k];
+                double gv = (double)g[r * ldg + k];
+                double ste = (fabsf(xv) <= 1.0f) ? 1.0 : 0.0;
+                double sign = sgn_ge0(xv) ? 1.0 : -1.0;
+                gx[r * K + k] = sign * sdot / n + delta * gv * ste;
+                if (T)
+                    T[r * K + k] = sg / n + delta * fabs(gv) * ste;
+            }
+        }
+    }
+}

@@ -16,7 +16,7 @@ from . import build as _build
 __all__ = [
     "num_threads", "num_blocks", "ld_words", "block_scales", "sign_pack", "materialize",
     "dense_f64_gemm", "popcount_gemm", "int_dot", "binary_weight_gemm", "hbmm_dense",
-    "hbmm_popcount", "as_rows_by_k",
+    "hbmm_popcount", "as_rows_by_k", "binarize_backward",
 ]
 
 _lib = None
@@ -36,6 +36,8 @@ def _load():
         lib.oracle_popcount_gemm.argtypes = [p, i64, p, i64, i64, p, i64, p, i64, i64, i64, i64, i64, p, p]
         lib.oracle_int_dot.argtypes = [p, i64, p, i64, i64, i64, i64, p]
         lib.oracle_binary_weight_gemm.argtypes = [p, i64, p, i64, p, i64, i64, i64, i64, i64, p, p]
+        lib.oracle_binarize_backward.argtypes = [p, p, i64, i64, i64, i64, i64, p, p]
+        lib.oracle_binarize_backward.restype = None
         for name in ("oracle_block_scales", "oracle_sign_pack", "oracle_materialize", "oracle_dense_f64_gemm",
                      "oracle_popcount_gemm", "oracle_int_dot", "oracle_binary_weight_gemm"):
             getattr(lib, name).restype = None
@@ -162,3 +164,16 @@ def hbmm_popcount(A, B, beta_a: int, beta_w: int, want_T: bool = False):
     A, B = _f32_rows(A), _f32_rows(B)
     return popcount_gemm(sign_pack(A), block_scales(A, beta_a), beta_a,
                          sign_pack(B), block_scales(B, beta_w), beta_w, A.shape[1], want_T)
+
+
+def binarize_backward(x, g, beta: int, want_T: bool = False):
+    """Eq. 6 (with the straight-through estimator of Eq. 5): gradient w.r.t. x of delta (.) Sign(x)
+    given the gradient g w.r.t. the binarised tensor; rows x K, segments along K."""
+    x, g = _f32_rows(x), _f32_rows(g)
+    if x.shape != g.shape:
+        raise ValueError("x and g must have the same shape")
+    rows, K = x.shape
+    gx = np.empty((rows, K), dtype=np.float64)
+    T = np.empty((rows, K), dtype=np.float64) if want_T else None
+    _load().oracle_binarize_backward(_ptr(x), _ptr(g), rows, K, K, K, beta, _ptr(gx), _ptr(T) if want_T else None)
+    return (gx, T) if want_T else gx

@@ -278,3 +278,73 @@ def test_layout_one_is_transpose():
     assert np.array_equal(oracle.as_rows_by_k(Bkn, 1), Bkn.T)
     assert np.array_equal(oracle.block_scales(oracle.as_rows_by_k(Bkn, 1), 32),
                           brute_scales(np.ascontiguousarray(Bkn.T), 32))
+
+
+# ------------------------------------------------------------ backward of the binarisation
+def _torch_binarize(x, beta):
+    """delta (.) Sign(x) written with library autograd pieces: mean |x| per segment, and Sign with the
+    straight-through derivative 1[|x| <= 1] (forward value sign, backward value of hardtanh)."""
+    import torch
+    rows, K = x.shape
+    seg = x.reshape(rows, K // beta, beta)
+    delta = seg.abs().mean(dim=2, keepdim=True)
+    hard = torch.nn.functional.hardtanh(seg)
+    sign = torch.where(seg >= 0, torch.ones_like(seg), -torch.ones_like(seg))
+    ste = hard + (sign - hard).detach()
+    return (delta * ste).reshape(rows, K)
+
+
+@pytest.mark.parametrize("beta", [1, 2, 4, 8, 32])
+def test_backward_matches_library_autograd(beta):
+    """Eq. 6 against torch autograd of the same function in float64 (catches: missing 1/beta, the sum
+    taken over the wrong segment, a dropped Sign(W_i), the STE mask on the wrong term)."""
+    import torch
+    x = synth.normal(71, (5, 64)) * 1.3          # some |x| > 1 so the mask matters
+    g = synth.normal(72, (5, 64))
+    xt = torch.tensor(x, dtype=torch.float64, requires_grad=True)
+    _torch_binarize(xt, beta).backward(torch.tensor(g, dtype=torch.float64))
+    want = xt.grad.numpy()
+    got = oracle.binarize_backward(x, g, beta)
+    # the oracle uses the stored fp32 delta: allow that rounding (2^-24 relative on the second term)
+    assert np.allclose(got, want, rtol=0, atol=2e-7 * (np.abs(g).max() * np.abs(x).max() + 1))
+    assert ((np.abs(x) > 1).sum() > 10) and ((np.abs(x) <= 1).sum() > 10)
+
+
+def test_backward_scale_path_is_the_true_derivative():
+    """With the signs frozen, the first term of Eq. 6 is the exact derivative of sum_j g_j delta s_j:
+    central differences in double."""
+    beta, K = 4, 16
+    z = synth.normal(73, (1, K)).astype(np.float64)
+    x = np.sign(z) * (1.5 + np.abs(z))                            # |x| > 1 everywhere (the STE term vanishes), mixed signs
+    g = synth.normal(74, (1, K)).astype(np.float64)
+    s = np.sign(x)
+
+    def f(xx):
+        delta = np.abs(xx).reshape(-1, beta).mean(1).repeat(beta)
+        return float((g[0] * delta * s[0]).sum())
+
+    num = np.zeros(K)
+    for i in range(K):
+        e = np.zeros(K)
+        e[i] = 1e-4
+        num[i] = (f(x[0] + e) - f(x[0] - e)) / 2e-4
+    got = oracle.binarize_backward(x.astype(np.float32), g.astype(np.float32), beta)[0]
+    assert np.allclose(got, num, rtol=1e-5, atol=1e-6)
+
+
+def test_backward_brute_force_ragged_and_mask_edges():
+    """Exact rationals on a ragged row; |x| = 1 is inside the straight-through window (Eq. 5: <=)."""
+    beta = 4
+    x = np.array([[0.5, -1.0, 1.0, -2.5, 0.0, -0.25, 3.0, 1.5, -0.75, 2.0]], dtype=np.float32)
+    g = np.array([[1.0, -2.0, 0.5, 4.0, -1.0, 0.25, 2.0, -3.0, 1.5, -0.5]], dtype=np.float32)
+    got, T = oracle.binarize_backward(x, g, beta, want_T=True)
+    K = x.shape[1]
+    for i in range(K):
+        k0 = (i // beta) * beta
+        k1 = min(k0 + beta, K)
+        n = k1 - k0
+        delta = Fraction(float(np.float32(float(sum(Fraction(float(abs(v))) for v in x[0, k0:k1]) / n))))
+        sdot = sum(Fraction(float(g[0, j])) * _sgn(x[0, j]) for j in range(k0, k1))
+        want = _sgn(x[0, i]) * sdot / n + (delta * Fraction(float(g[0, i])) if abs(x[0, i]) <= 1 else 0)
+        assert got[0, i] == pytest.approx(float(want), abs=1e-14), i
+        assert T[0, i] >= abs(got[0, i]) - 1e-14
