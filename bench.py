@@ -286,6 +286,17 @@ def extras(w, A, B, a_bits, a_s, b_bits, b_s, C, torch, hbmm, synth, args):
         ts = time_loop(lambda: torch.matmul(Ab, Bb.t()), steps, warm, torch)
         res["torch_matmul_bf16"] = {"ms": float(sum(ts) / len(ts)), "gflops": gops(sum(ts) / len(ts))}
         del Ab, Bb
+    # gradient through the binarisation (Eq. 5-6): 8 bytes read + 4 written per element
+    try:
+        gsrc, gout = torch.randn_like(A), torch.empty_like(A)
+        beta_b = max(w.beta_a, 2)
+        ts = time_loop(lambda: hbmm.binarize_backward(A, gsrc, beta_b, gout), steps, warm, torch)
+        ms = float(sorted(ts)[len(ts) // 2])
+        res["binarize_backward"] = {"ms": ms, "GBs": 12.0 * w.M * w.K / (ms * 1e-3) / 1e9, "beta": beta_b,
+                                    "frac_of_hbm_peak": 12.0 * w.M * w.K / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        del gsrc, gout
+    except hbmm.HbmmError as e:
+        res["binarize_backward"] = {"error": str(e)}
     res["paper_context"] = "paper reports ~10x for its CPU HBMM kernel over a classical fp32 matmul on a Xeon Gold 6128 (beta=16)"
 
     others = {}

@@ -74,6 +74,22 @@ int hbmm_quantize_pack(const float *x, int64_t rows, int64_t K, int64_t ldx, int
                        void *stream);
 
 /*
+ * Gradient through the Hadamard binarisation (Eq. 6, with the straight-through estimator of Eq. 5):
+ *
+ *   grad_in[r, i] = (1/beta) * Sign(x[r, i]) * sum_{j in segment(i)} grad_out[r, j] * Sign(x[r, j])
+ *                   + delta[r, segment(i)] * grad_out[r, i] * (|x[r, i]| <= 1 ? 1 : 0)
+ *
+ * x is the full-precision tensor that was binarised (rows x K, segments of beta along K, as in
+ * hbmm_quantize_pack layout 0), grad_out the gradient with respect to delta (.) Sign(x), delta the mean
+ * of |x| over the segment (recomputed from x).  The upper limit of the sum printed in Eq. 6 is read
+ * as exclusive (beta terms).  beta: a power of two in 1 .. 256, K a multiple of beta and of 4.
+ * grad_in may not alias x or grad_out.  fp32 arithmetic; error <= (log2(beta) + 3) * 2^-24 times
+ * ((1/beta) sum_j |grad_out_j| + delta |grad_out_i|).
+ */
+int hbmm_binarize_backward(const float *x, const float *grad_out, int64_t rows, int64_t K, int64_t ldx,
+                           int64_t ldg, int32_t beta, float *grad_in, int64_t ldgi, void *stream);
+
+/*
  * HBMM proper (Eq. 7, with popcount(xnor) read as the signed agreement count):
  *
  *   C[m, n] = sum over segments g of  sA[m, g*G / beta_a] * sB[n, g*G / beta_w] * d[m, n, g],

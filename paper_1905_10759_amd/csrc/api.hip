@@ -90,6 +90,21 @@ int hbmm_quantize_pack(const float *x, int64_t rows, int64_t K, int64_t ldx, int
     return from_hip(hbmm::launch_pack_cols(x, rows, K, ldx, beta, bits, ldw, scales, lds, s));
 }
 
+int hbmm_binarize_backward(const float *x, const float *grad_out, int64_t rows, int64_t K, int64_t ldx,
+                           int64_t ldg, int32_t beta, float *grad_in, int64_t ldgi, void *stream)
+{
+    if (rows < 0 || K < 0 || rows > kMaxDim || K > kMaxPackK) return HBMM_EINVAL;
+    if (beta < 1) return HBMM_EINVAL;
+    if (!(beta == 1 || supported_pack_beta(beta))) return HBMM_EUNSUPPORTED;
+    if (K % beta != 0 || K % 4 != 0) return HBMM_EUNSUPPORTED;
+    if (rows == 0 || K == 0) return HBMM_OK;
+    if (!x || !grad_out || !grad_in) return HBMM_EINVAL;
+    if (!aligned16(x) || !aligned16(grad_out) || !aligned16(grad_in)) return HBMM_EINVAL;
+    if (ldx < K || ldg < K || ldgi < K) return HBMM_EINVAL;
+    return from_hip(hbmm::launch_binarize_backward(x, grad_out, rows, K, ldx, ldg, beta, grad_in, ldgi,
+                                                   static_cast<hipStream_t>(stream)));
+}
+
 static int check_packed(const uint32_t *bits, int64_t rows, int64_t K, int64_t ldw)
 {
     if (!bits || !aligned16(bits)) return HBMM_EINVAL;

@@ -20,7 +20,7 @@ ALGO_POPCOUNT, ALGO_MFMA_I8 = 0, 1
 
 EXPORTS = (
     "hbmm_strerror", "hbmm_num_blocks", "hbmm_packed_ld_words", "hbmm_quantize_pack", "hbmm_gemm",
-    "hbmm_gemm_int", "hbmm_dense_ref_gemm",
+    "hbmm_gemm_int", "hbmm_dense_ref_gemm", "hbmm_binarize_backward",
 )
 
 
@@ -49,6 +49,8 @@ def _load() -> C.CDLL:
     lib.hbmm_gemm.argtypes = [p, p, i64, i64, i32, p, p, i64, i64, i32, i64, i64, i64, p, i64, i32, p]
     lib.hbmm_gemm_int.restype = C.c_int
     lib.hbmm_gemm_int.argtypes = [p, i64, p, i64, i64, i64, i64, p, i64, p]
+    lib.hbmm_binarize_backward.restype = C.c_int
+    lib.hbmm_binarize_backward.argtypes = [p, p, i64, i64, i64, i64, i32, p, i64, p]
     lib.hbmm_dense_ref_gemm.restype = C.c_int
     lib.hbmm_dense_ref_gemm.argtypes = [p, i64, p, i64, i32, i64, i64, i64, p, i64, p]
     return lib
@@ -162,4 +164,21 @@ def dense_ref_gemm(A: torch.Tensor, B: torch.Tensor, out: torch.Tensor | None = 
                                  B.stride(0) if N > 1 else K, 0 if A.dtype == torch.float32 else 1,
                                  M, N, K, out.data_ptr(), out.stride(0) if M > 1 else max(N, 1), _stream())
     _check(rc, "hbmm_dense_ref_gemm")
+    return out
+
+
+def binarize_backward(x: torch.Tensor, grad_out: torch.Tensor, beta: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    """hbmm_binarize_backward: gradient w.r.t. x of delta (.) Sign(x) (Eq. 6 with the STE of Eq. 5)."""
+    _dev(x, torch.float32, "x")
+    _dev(grad_out, torch.float32, "grad_out")
+    if x.dim() != 2 or x.shape != grad_out.shape or x.stride(1) != 1 or grad_out.stride(1) != 1:
+        raise ValueError("x and grad_out must be matching 2-D matrices with unit inner stride")
+    rows, K = x.shape
+    if out is None:
+        out = torch.empty((rows, K), dtype=torch.float32, device=x.device)
+    _dev(out, torch.float32, "out")
+    ld = lambda t: t.stride(0) if rows > 1 else K
+    rc = lib.hbmm_binarize_backward(x.data_ptr(), grad_out.data_ptr(), rows, K, ld(x), ld(grad_out), beta,
+                                    out.data_ptr(), ld(out), _stream())
+    _check(rc, "hbmm_binarize_backward")
     return out

@@ -108,6 +108,14 @@ def test_validation_rejects_before_launch(lib):
     assert gi(fake, 4, fake, 4, 8, 8, 64, fake, 4, None) == -1
     assert gi(fake, 4, fake, 4, 0, 8, 64, fake, 8, None) == 0
 
+    bw = lib.hbmm_binarize_backward
+    bw.argtypes = [p, p, i64, i64, i64, i64, i32, p, i64, p]
+    assert bw(fake, fake, 4, 64, 64, 64, 48, fake, 64, None) == -2     # beta not a power of two
+    assert bw(fake, fake, 4, 64, 64, 64, 128, fake, 64, None) == -2    # K not a multiple of beta
+    assert bw(fake, None, 4, 64, 64, 64, 8, fake, 64, None) == -1
+    assert bw(fake, fake, 4, 64, 32, 64, 8, fake, 64, None) == -1      # ldx < K
+    assert bw(fake, fake, 0, 64, 64, 64, 8, fake, 64, None) == 0
+
     d = lib.hbmm_dense_ref_gemm
     d.argtypes = [p, i64, p, i64, i32, i64, i64, i64, p, i64, p]
     assert d(fake, 64, fake, 64, 3, 8, 8, 64, fake, 8, None) == -2

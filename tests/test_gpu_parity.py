@@ -273,3 +273,27 @@ def test_dense_ref_gemm(dtype, M, N, K):
     ref = A.astype(np.float64) @ B.astype(np.float64).T
     T = np.abs(A.astype(np.float64)) @ np.abs(B.astype(np.float64)).T
     assert_close_to_oracle(got, ref, T, f"dense {dtype}")
+
+
+# ------------------------------------------------------------------- backward of the binarisation
+@pytest.mark.parametrize("beta", [1, 2, 4, 8, 16, 32, 64, 128, 256])
+@pytest.mark.parametrize("rows,K", [(1, 256), (7, 768), (33, 4608), (130, 1280)])
+def test_binarize_backward(beta, rows, K):
+    x = synth.normal(1000 + beta + rows, (rows, K)) * 1.2
+    x[0, :6] = [1.0, -1.0, 0.0, -0.0, 1.0000001, -0.99999994]
+    g = synth.normal(1001 + beta + K, (rows, K))
+    got = hbmm.binarize_backward(dev(x), dev(g), beta).cpu().numpy()
+    ref, T = oracle.binarize_backward(x, g, beta, want_T=True)
+    assert_close_to_oracle(got, ref, T, f"backward beta={beta}")
+
+
+def test_binarize_backward_ragged_and_strided():
+    K, beta = 96, 8
+    x, g = synth.normal(1010, (9, K)), synth.normal(1011, (9, K))
+    wide_x = torch.zeros((9, K + 3), dtype=torch.float32, device="cuda")
+    wide_x[:, :K] = dev(x)
+    out = torch.full((9, K + 8), 5.0, dtype=torch.float32, device="cuda")
+    hbmm.binarize_backward(wide_x[:, :K], dev(g), beta, out[:, :K])
+    ref, T = oracle.binarize_backward(x, g, beta, want_T=True)
+    assert_close_to_oracle(out[:, :K].cpu().numpy(), ref, T, "backward strided")
+    assert (out[:, K:] == 5.0).all()
