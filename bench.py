@@ -317,6 +317,47 @@ def extras(w, A, B, a_bits, a_s, b_bits, b_s, C, torch, hbmm, synth, args):
             tg = time_loop(lambda: hbmm.gemm(None, dA, 1, bb, bs, ww.beta_w, ww.K), 5, 1, torch)
         entry["gemm_ms"] = min(tg)
         entry["gemm_gops"] = 2.0 * ww.M * ww.N * ww.K / (min(tg) * 1e-3) / 1e9
+        if ww.M * ww.N * ww.K < 1e9 and ww.beta_a != 1:
+            # launch-bound shapes: the whole step (pack A, pack B, gemm) queued back to back, and the same
+            # three launches captured once into a HIP graph and replayed (the library allocates nothing
+            # and never synchronises, so it can be captured as is)
+            Cw = torch.empty((ww.M, ww.N), dtype=torch.float32, device="cuda")
+
+            def whole_step():
+                hbmm.quantize_pack(dA, ww.beta_a, 0, ab, as_)
+                hbmm.quantize_pack(dB, ww.beta_w, ww.b_layout, bb, bs)
+                hbmm.gemm(ab, as_, ww.beta_a, bb, bs, ww.beta_w, ww.K, hbmm.ALGO_POPCOUNT, Cw)
+
+            reps = 200
+            whole_step()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                whole_step()
+            e1.record()
+            torch.cuda.synchronize()
+            entry["step_ms_back_to_back"] = e0.elapsed_time(e1) / reps
+            try:
+                side = torch.cuda.Stream()
+                with torch.cuda.stream(side):
+                    whole_step()
+                    side.synchronize()
+                    graph = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(graph, stream=side):
+                        whole_step()
+                    graph.replay()
+                    side.synchronize()
+                    ref = Cw.clone()
+                    e0.record(side)
+                    for _ in range(reps):
+                        graph.replay()
+                    e1.record(side)
+                    side.synchronize()
+                entry["step_ms_hip_graph"] = e0.elapsed_time(e1) / reps
+                entry["hip_graph_matches_eager"] = bool(torch.equal(ref, Cw))
+            except Exception as e:   # graph capture is a convenience figure, never a failure of the bench
+                entry["step_ms_hip_graph"] = f"unavailable: {type(e).__name__}"
         others[name] = entry
         del dA, dB
     res["other_workloads"] = others

@@ -1,15 +1,18 @@
 // int8 +-1 matrix-core variant of the HBMM contraction (Eq. 7 of HadaNets), kept as a comparison
 // point for the XNOR + popcount kernel: the segment dot products d[m, n, g] come out of
 // v_mfma_i32_32x32x32_i8 on operands expanded from the packed bits to +-1 bytes, and the same
-// fp32 block-scale epilogue is applied.  Integer work is exact, so the result differs from the
-// popcount kernel only by nothing at all in d and by the same fp32 roundings in the epilogue.
+// fp32 block-scale epilogue is applied.  Integer work is exact, so d is identical to the popcount
+// kernel's and the outputs differ only by the order of the same fp32 roundings.
 //
-// Workgroup = 4 waves (2 x 2), tile 128 (M) x 128 (N); wave = 64 x 64 = 2 x 2 MFMA tiles.  K is walked
-// in stages of 128 bits: the 4 packed words of every row of both operand tiles (4 KB in all) and
-// the scales of the segments inside the stage go through LDS.  For each 32-bit step a lane takes
-// its 16 bits (lane l feeds row l mod 32 and the 16 consecutive k at 16 * (l div 32)), and turns
-// each nibble into four +-1 bytes with a 16-entry table held in LDS (16 consecutive banks: any
-// mix of indices is conflict-free).  At the end of a segment of G = min(beta_a, beta_w) bits:
+// Workgroup = 4 waves (2 x 2), tile 128 (M) x 128 (N), two workgroups per CU; wave = 64 x 64 = 2 x 2 MFMA
+// tiles.  K is walked in stages of 128 bits.  Each thread owns one row of one operand tile: it
+// fetches the row's 4 packed words and the scales of the segments inside the stage, and while
+// parking the stage in LDS expands every nibble into four +-1 bytes with a 16-entry table held in
+// LDS (16 consecutive banks: any mix of indices is conflict-free), so the expansion is done once
+// per workgroup and shared by the two waves that use the row.  The 16-byte chunks of a row are
+// XOR-swizzled with the row number, so the fragment reads of 8 consecutive rows (lane l feeds row
+// l mod 32 and the 16 consecutive k at 16 * (l div 32)) hit distinct banks without padding.
+// At the end of a segment of G = min(beta_a, beta_w) bits:
 //   C += float(d) * sA[m] * sB[n],   then the integer accumulator restarts from zero.
 #include "kernels.h"
 
@@ -24,6 +27,7 @@ constexpr int kBMi = 128, kBNi = 128;
 constexpr int kThreadsI = 256;
 constexpr int kStageWords = 4;    // 128 bits of K per stage
 constexpr int kMaxSeg = 4;        // segments per stage at G = 32
+constexpr int kRowBytesI = kStageWords * 32;   // one +-1 byte per bit
 
 struct MfmaI8Args {
     const uint32_t *a_bits, *b_bits;
@@ -37,9 +41,9 @@ struct MfmaI8Args {
     int32_t tiles_n;
 };
 
-__global__ __launch_bounds__(kThreadsI) void mfma_i8_gemm_kernel(const MfmaI8Args a)
+__global__ __launch_bounds__(kThreadsI, 2) void mfma_i8_gemm_kernel(const MfmaI8Args a)
 {
-    __shared__ __attribute__((aligned(16))) uint32_t s_bits[2][2][kBMi * kStageWords];   // [buf][operand][row*4 + w]
+    __shared__ __attribute__((aligned(16))) unsigned char s_bytes[2][2][kBMi * kRowBytesI];   // [buf][operand][row][128 swizzled bytes]
     __shared__ __attribute__((aligned(16))) float s_scale[2][2][kMaxSeg][kBMi];          // [buf][operand][seg][row]
     __shared__ uint32_t s_lut[16];
 
@@ -68,27 +72,43 @@ __global__ __launch_bounds__(kThreadsI) void mfma_i8_gemm_kernel(const MfmaI8Arg
     const float *gscale = op == 0 ? a.a_scales + (int64_t)min(m0 + srow, a.M - 1) * a.lds_a
                                   : a.b_scales + (int64_t)min(n0 + srow, a.N - 1) * a.lds_b;
     const int shift_op = op == 0 ? a.shift_a : a.shift_b;
-    uint4 st_bits;
-    float st_scale[kMaxSeg];
-    auto fetch = [&](int stage) {
-        st_bits = make_uint4(0, 0, 0, 0);
-        if (row_ok && stage * kStageWords < a.kwords)   // ldw is a multiple of 4 and pad words are zero
-            st_bits = *reinterpret_cast<const uint4 *>(gbits + stage * kStageWords);
-        // scale of segment s of this stage: global segment index gseg, operand block gseg >> shift
+    const int nseg_total = a.kwords / words_per_seg;            // K / G
+    const int nseg_stage = seg_per_stage > 0 ? seg_per_stage : 1;
+    // Loads are unconditional (indices clamped, results masked afterwards) so that the compiler knows
+    // how many are outstanding and three stages can be in flight; they rotate through three sets.
+    struct Staged {
+        uint4 bits;
+        float scale[kMaxSeg];
+    };
+    auto fetch = [&](Staged &st, int stage) {
+        const int sg = min(stage, nstages - 1);
+        st.bits = *reinterpret_cast<const uint4 *>(gbits + sg * kStageWords);   // ldw is a multiple of 4, pad words are zero
 #pragma unroll
         for (int s = 0; s < kMaxSeg; ++s) {
-            st_scale[s] = 0.f;
-            const int nseg = seg_per_stage > 0 ? seg_per_stage : 1;
-            if (s < nseg) {
-                const int gseg = seg_per_stage > 0 ? stage * seg_per_stage + s : stage >> 1;
-                if (row_ok && gseg * words_per_seg < a.kwords) st_scale[s] = gscale[gseg >> shift_op];
-            }
+            // segment s of this stage: global index gseg, this operand's block gseg >> shift
+            const int gseg = seg_per_stage > 0 ? sg * seg_per_stage + s : sg >> 1;
+            st.scale[s] = gscale[min(gseg, nseg_total - 1) >> shift_op];
         }
     };
-    auto park = [&](int buf) {
-        *reinterpret_cast<uint4 *>(&s_bits[buf][op][srow * kStageWords]) = st_bits;
+    auto park = [&](const Staged &st, int stage, int buf) {
+        // 4 words -> 8 chunks of 16 bytes; chunk c of row r lives at position c ^ (r & 7)
+        unsigned char *dst = &s_bytes[buf][op][srow * kRowBytesI];
+        const uint32_t wds[4] = {st.bits.x, st.bits.y, st.bits.z, st.bits.w};
 #pragma unroll
-        for (int s = 0; s < kMaxSeg; ++s) s_scale[buf][op][s][srow] = st_scale[s];
+        for (int c = 0; c < 2 * kStageWords; ++c) {
+            const uint32_t h = wds[c >> 1] >> (16 * (c & 1));
+            i32x4 v;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = (int)s_lut[(h >> (4 * i)) & 15u];
+            *reinterpret_cast<i32x4 *>(dst + ((c ^ (srow & 7)) << 4)) = v;
+        }
+        // a scale of 0 switches off segments past K (pad words expand to -1 bytes and would count) and rows past M / N
+#pragma unroll
+        for (int s = 0; s < kMaxSeg; ++s) {
+            const int gseg = seg_per_stage > 0 ? stage * seg_per_stage + s : stage >> 1;
+            const bool live = row_ok && s < nseg_stage && gseg < nseg_total;
+            s_scale[buf][op][s][srow] = live ? st.scale[s] : 0.f;
+        }
     };
 
     i32x16 acc[2][2];
@@ -103,37 +123,19 @@ __global__ __launch_bounds__(kThreadsI) void mfma_i8_gemm_kernel(const MfmaI8Arg
                 res[x][y][v] = 0.f;
             }
 
-    // 16 bits -> 16 bytes of +-1 through the nibble table
-    auto expand16 = [&](uint32_t bits16) {
-        i32x4 f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) f[i] = (int)s_lut[(bits16 >> (4 * i)) & 15u];
-        return f;
-    };
-
-    fetch(0);
-    park(0);
-    __syncthreads();
-    for (int stage = 0; stage < nstages; ++stage) {
+    auto run_stage = [&](int stage, const Staged &ready, Staged &incoming) {
         const int buf = stage & 1;
-        if (stage + 1 < nstages) fetch(stage + 1);
+        fetch(incoming, stage + 3);
 
-        uint4 wa[2], wb[2];
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            wa[t] = *reinterpret_cast<const uint4 *>(&s_bits[buf][0][(wm * 64 + t * 32 + (lane & 31)) * kStageWords]);
-            wb[t] = *reinterpret_cast<const uint4 *>(&s_bits[buf][1][(wn * 64 + t * 32 + (lane & 31)) * kStageWords]);
-        }
-        const int half = (lane >> 5) * 16;
+        const int rl = lane & 31, hi = lane >> 5;
 #pragma unroll
         for (int w = 0; w < kStageWords; ++w) {
             i32x4 fa[2], fb[2];
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
-                const uint32_t xa = w == 0 ? wa[t].x : w == 1 ? wa[t].y : w == 2 ? wa[t].z : wa[t].w;
-                const uint32_t xb = w == 0 ? wb[t].x : w == 1 ? wb[t].y : w == 2 ? wb[t].z : wb[t].w;
-                fa[t] = expand16((xa >> half) & 0xffffu);
-                fb[t] = expand16((xb >> half) & 0xffffu);
+                const int ra = wm * 64 + t * 32 + rl, rb = wn * 64 + t * 32 + rl;
+                fa[t] = *reinterpret_cast<const i32x4 *>(&s_bytes[buf][0][ra * kRowBytesI + (((2 * w + hi) ^ (ra & 7)) << 4)]);
+                fb[t] = *reinterpret_cast<const i32x4 *>(&s_bytes[buf][1][rb * kRowBytesI + (((2 * w + hi) ^ (rb & 7)) << 4)]);
             }
 #pragma unroll
             for (int x = 0; x < 2; ++x)
@@ -165,8 +167,21 @@ __global__ __launch_bounds__(kThreadsI) void mfma_i8_gemm_kernel(const MfmaI8Arg
                 }
             }
         }
-        if (stage + 1 < nstages) park(buf ^ 1);
+        park(ready, stage + 1, buf ^ 1);   // past the last stage this parks data that nobody reads
         __syncthreads();
+    };
+
+    Staged s0, s1, s2;
+    fetch(s0, 0);
+    __syncthreads();   // the table must be complete before the first expansion reads it
+    park(s0, 0, 0);
+    fetch(s0, 1);
+    fetch(s1, 2);
+    __syncthreads();
+    for (int stage = 0; stage < nstages; stage += 3) {
+        run_stage(stage, s0, s2);
+        if (stage + 1 < nstages) run_stage(stage + 1, s1, s0);
+        if (stage + 2 < nstages) run_stage(stage + 2, s2, s1);
     }
 
 #pragma unroll

@@ -297,3 +297,69 @@ def test_binarize_backward_ragged_and_strided():
     ref, T = oracle.binarize_backward(x, g, beta, want_T=True)
     assert_close_to_oracle(out[:, :K].cpu().numpy(), ref, T, "backward strided")
     assert (out[:, K:] == 5.0).all()
+
+
+# ------------------------------------------------------------------------------ streams and graphs
+def test_whole_path_in_a_hip_graph_replays_exactly():
+    """pack(A), pack(B), gemm captured once into a HIP graph: every replay (with eager work and
+    synchronisations of the program in between, and new input values written into the same buffers)
+    must reproduce the eager result bit for bit.  The library allocates nothing, issues no memset and
+    never synchronises, so it is capturable as is."""
+    M, N, K, beta = 300, 200, 1024, 64
+    A0, B0 = synth.normal(1100, (M, K)), synth.normal(1101, (N, K))
+    A1, B1 = synth.uniform_pm1(1102, (M, K)), synth.normal(1103, (N, K))
+    dA, dB = dev(A0), dev(B0)
+    ldw, nb = hbmm.packed_ld_words(K), hbmm.num_blocks(K, beta)
+    ab = torch.empty((M, ldw), dtype=torch.int32, device="cuda")
+    bb = torch.empty((N, ldw), dtype=torch.int32, device="cuda")
+    as_ = torch.empty((M, nb), dtype=torch.float32, device="cuda")
+    bs = torch.empty((N, nb), dtype=torch.float32, device="cuda")
+    C = torch.empty((M, N), dtype=torch.float32, device="cuda")
+
+    def step():
+        hbmm.quantize_pack(dA, beta, 0, ab, as_)
+        hbmm.quantize_pack(dB, beta, 0, bb, bs)
+        hbmm.gemm(ab, as_, beta, bb, bs, beta, K, out=C)
+
+    def eager(a, b):
+        dA.copy_(dev(a)); dB.copy_(dev(b))
+        step()
+        torch.cuda.synchronize()
+        return C.clone()
+
+    want0, want1 = eager(A0, B0), eager(A1, B1)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        step()
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    for rep in range(4):
+        a, b, want = (A0, B0, want0) if rep % 2 == 0 else (A1, B1, want1)
+        dA.copy_(dev(a)); dB.copy_(dev(b))
+        C.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            graph.replay()
+        side.synchronize()
+        assert torch.equal(C, want), f"replay {rep} differs from the eager result"
+        _ = (dA.sum() + dB.sum()).item()   # unrelated eager work between replays
+
+
+def test_calls_on_a_side_stream():
+    """Kernels go to the stream that is current when the call is made."""
+    M, N, K, beta = 130, 70, 512, 128
+    A, B = synth.normal(1110, (M, K)), synth.normal(1111, (N, K))
+    ref = None
+    for stream in (None, torch.cuda.Stream()):
+        ctx = torch.cuda.stream(stream) if stream is not None else torch.cuda.stream(torch.cuda.current_stream())
+        with ctx:
+            ab, as_ = hbmm.quantize_pack(dev(A), beta)
+            bb, bs = hbmm.quantize_pack(dev(B), beta)
+            C = hbmm.gemm(ab, as_, beta, bb, bs, beta, K)
+            torch.cuda.current_stream().synchronize()
+        got = C.cpu().numpy()
+        if ref is None:
+            ref = got
+        assert np.array_equal(ref, got)
