@@ -125,6 +125,21 @@ int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int6
               int32_t algo, void *stream);
 
 /*
+ * Fused form for the activation operand: the same C as
+ *     hbmm_quantize_pack(A, layout 0, beta_a)  followed by  hbmm_gemm(..., algo 0)
+ * (bit for bit: same scale arithmetic, same contraction, same epilogue order), but A is binarised
+ * inside the product kernel, tile by tile, and its packed form is never written to memory.  Meant
+ * for the im2col shapes with few output channels and many rows (N <= 128), where packing A costs
+ * more than the product and the product then hides behind the fp32 read of A; every group of 64
+ * columns of C re-reads A, hence the limit.
+ *   A        fp32, M x K, leading dimension lda (multiple of 4), not binarised beforehand.
+ *   beta_a, beta_w  each in {32, 64, 128, 256}; K a multiple of both.  N <= 128.
+ */
+int hbmm_gemm_fused(const float *A, int64_t lda, int32_t beta_a, const uint32_t *b_bits,
+                    const float *b_scales, int64_t ldw_b, int64_t lds_b, int32_t beta_w, int64_t M,
+                    int64_t N, int64_t K, float *C, int64_t ldc, void *stream);
+
+/*
  * Unscaled whole-row +-1 inner products, for exact parity checks of the contraction:
  *   D[m, n] = K - 2 * popcount(a_row xor b_row),  int32, M x N, leading dimension ldd >= N.
  * Uses the same inner loop as hbmm_gemm(algo 0).  K need not be a multiple of 32 (pad bits are 0

@@ -224,6 +224,37 @@ int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int6
     return from_hip(hbmm::launch_popcount_gemm(g, G, 0, s));
 }
 
+int hbmm_gemm_fused(const float *A, int64_t lda, int32_t beta_a, const uint32_t *b_bits,
+                    const float *b_scales, int64_t ldw_b, int64_t lds_b, int32_t beta_w, int64_t M,
+                    int64_t N, int64_t K, float *C, int64_t ldc, void *stream)
+{
+    if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim) return HBMM_EINVAL;
+    if (beta_a < 1 || beta_w < 1) return HBMM_EINVAL;
+    if (!supported_beta(beta_a) || !supported_beta(beta_w)) return HBMM_EUNSUPPORTED;
+    if (K % beta_a != 0 || K % beta_w != 0) return HBMM_EUNSUPPORTED;
+    if (N > 128) return HBMM_EUNSUPPORTED;
+    if (M == 0 || N == 0) return HBMM_OK;
+    if (!C || !aligned16(C) || ldc < N) return HBMM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (K == 0) return from_hip(zero_block(C, ldc, M, N, s));
+    if (!A || !aligned16(A) || lda < K || lda % 4 != 0) return HBMM_EINVAL;
+    if (!b_scales || !aligned16(b_scales) || lds_b < K / beta_w || lds_b >= ((int64_t)1 << 31)) return HBMM_EINVAL;
+    if (int rc = check_packed(b_bits, N, K, ldw_b)) return rc;
+
+    const int G = beta_a < beta_w ? beta_a : beta_w;
+    hbmm::PopcountGemmArgs g{};
+    g.p_src = A; g.ld_p_src = lda; g.beta_p = beta_a;
+    g.P = (int32_t)M; g.shift_p = log2_exact(beta_a / G);
+    g.q_bits = b_bits; g.q_scales = b_scales; g.ldw_q = (int32_t)ldw_b; g.lds_q = (int32_t)lds_b;
+    g.Q = (int32_t)N; g.shift_q = log2_exact(beta_w / G);
+    g.ld_out_p = ldc; g.ld_out_q = 1;
+    g.out = C;
+    g.kwords = (int32_t)hbmm::packed_words(K);
+    g.ngran = (int32_t)(K / G);
+    g.K = (int32_t)K;
+    return from_hip(hbmm::launch_popcount_gemm(g, G, 0, s));
+}
+
 int hbmm_gemm_int(const uint32_t *a_bits, int64_t ldw_a, const uint32_t *b_bits, int64_t ldw_b,
                   int64_t M, int64_t N, int64_t K, int32_t *D, int64_t ldd, void *stream)
 {

@@ -9,6 +9,7 @@
 // reduced pairwise over the beta/4 lanes of the segment with DPP, and each lane writes its four
 // results with one 16-byte store.
 #include "kernels.h"
+#include "wave_ops.h"
 
 namespace hbmm {
 namespace {
@@ -16,23 +17,6 @@ namespace {
 constexpr int kUnrollB = 4;
 constexpr int kChunkB = 256;
 constexpr int kWavesB = 4;
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_f(float v)
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
-}
-template <int LANES>
-__device__ __forceinline__ float seg_sum(float v)
-{
-    if (LANES >= 2) v += dpp_f<0xB1>(v);     // quad_perm [1,0,3,2]
-    if (LANES >= 4) v += dpp_f<0x4E>(v);     // quad_perm [2,3,0,1]
-    if (LANES >= 8) v += dpp_f<0x141>(v);    // row_half_mirror
-    if (LANES >= 16) v += dpp_f<0x140>(v);   // row_mirror
-    if (LANES >= 32) v += __shfl_xor(v, 16);
-    if (LANES >= 64) v += __shfl_xor(v, 32);
-    return v;
-}
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -93,8 +77,8 @@ __global__ __launch_bounds__(64 * kWavesB) void binarize_backward_kernel(
             float a = (fabsf(xv[u][0]) + fabsf(xv[u][1])) + (fabsf(xv[u][2]) + fabsf(xv[u][3]));
             float d = (sgn_apply(xv[u][0], gv[u][0]) + sgn_apply(xv[u][1], gv[u][1])) +
                       (sgn_apply(xv[u][2], gv[u][2]) + sgn_apply(xv[u][3], gv[u][3]));
-            a = seg_sum<kSegLanes>(a) * (1.0f / BETA);
-            d = seg_sum<kSegLanes>(d) * (1.0f / BETA);
+            a = segment_sum<kSegLanes>(a) * (1.0f / BETA);
+            d = segment_sum<kSegLanes>(d) * (1.0f / BETA);
 #pragma unroll
             for (int c = 0; c < 4; ++c)
                 r[c] = __builtin_fmaf(a * gv[u][c], ste(xv[u][c]), sgn_apply(xv[u][c], d));

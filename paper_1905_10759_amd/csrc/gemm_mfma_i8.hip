@@ -13,7 +13,8 @@
 // XOR-swizzled with the row number, so the fragment reads of 8 consecutive rows (lane l feeds row
 // l mod 32 and the 16 consecutive k at 16 * (l div 32)) hit distinct banks without padding.
 // At the end of a segment of G = min(beta_a, beta_w) bits:
-//   C += float(d) * sA[m] * sB[n],   then the integer accumulator restarts from zero.
+//   C += float(d) * (sA[m] * sB[n]),   then the integer accumulator restarts from zero (the same
+// rounding steps as the popcount kernel, so the two give bit-identical outputs).
 #include "kernels.h"
 
 namespace hbmm {
@@ -156,10 +157,10 @@ __global__ __launch_bounds__(kThreadsI, 2) void mfma_i8_gemm_kernel(const MfmaI8
 #pragma unroll
                         for (int q = 0; q < 4; ++q) {
                             const float4 sa4 = *reinterpret_cast<const float4 *>(sa + 8 * q);
-                            res[x][y][4 * q + 0] = __builtin_fmaf((float)acc[x][y][4 * q + 0] * sa4.x, sb, res[x][y][4 * q + 0]);
-                            res[x][y][4 * q + 1] = __builtin_fmaf((float)acc[x][y][4 * q + 1] * sa4.y, sb, res[x][y][4 * q + 1]);
-                            res[x][y][4 * q + 2] = __builtin_fmaf((float)acc[x][y][4 * q + 2] * sa4.z, sb, res[x][y][4 * q + 2]);
-                            res[x][y][4 * q + 3] = __builtin_fmaf((float)acc[x][y][4 * q + 3] * sa4.w, sb, res[x][y][4 * q + 3]);
+                            res[x][y][4 * q + 0] = __builtin_fmaf((float)acc[x][y][4 * q + 0], sa4.x * sb, res[x][y][4 * q + 0]);
+                            res[x][y][4 * q + 1] = __builtin_fmaf((float)acc[x][y][4 * q + 1], sa4.y * sb, res[x][y][4 * q + 1]);
+                            res[x][y][4 * q + 2] = __builtin_fmaf((float)acc[x][y][4 * q + 2], sa4.z * sb, res[x][y][4 * q + 2]);
+                            res[x][y][4 * q + 3] = __builtin_fmaf((float)acc[x][y][4 * q + 3], sa4.w * sb, res[x][y][4 * q + 3]);
                         }
 #pragma unroll
                         for (int v = 0; v < 16; ++v) acc[x][y][v] = 0;

@@ -27,6 +27,7 @@
 //     workgroups share a CU, so one group's barrier and LDS refill overlap the other's arithmetic.
 // Either of A / B can be P or Q: the host picks the role by output strides.
 #include "kernels.h"
+#include "wave_ops.h"
 
 namespace hbmm {
 namespace {
@@ -71,7 +72,11 @@ __device__ __forceinline__ int bcnt_seed(uint32_t x, int seed)
     return d;
 }
 
-template <int G, bool INTEGER>
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// FUSED: the P operand is given as fp32 (a.p_src) and is binarised inside the kernel, chunk by chunk,
+// straight into the LDS tile -- the packed form of P never exists in memory.
+template <int G, bool INTEGER, bool FUSED>
 __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel(const PopcountGemmArgs a)
 {
     constexpr int kWordsPerGran = G / 32;                       // 1, 2, 4, 8
@@ -137,24 +142,28 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
             st_qline = a.q_bits[(int64_t)row * a.ldw_q + w];
         }
 #endif
+        if constexpr (!FUSED) {
 #pragma unroll
-        for (int r = 0; r < kBitPieces; ++r) {
-            const int id = tid + r * kThreads;
-            const int row = p0 + id / (kCK / 4);
-            const int w = chunk * kCK + (id % (kCK / 4)) * 4;
-            st_bits[r] = make_uint4(0, 0, 0, 0);
-            if (row < a.P && w < a.kwords)
-                st_bits[r] = *reinterpret_cast<const uint4 *>(a.p_bits + (int64_t)row * a.ldw_p + w);
+            for (int r = 0; r < kBitPieces; ++r) {
+                const int id = tid + r * kThreads;
+                const int row = p0 + id / (kCK / 4);
+                const int w = chunk * kCK + (id % (kCK / 4)) * 4;
+                st_bits[r] = make_uint4(0, 0, 0, 0);
+                if (row < a.P && w < a.kwords)
+                    st_bits[r] = *reinterpret_cast<const uint4 *>(a.p_bits + (int64_t)row * a.ldw_p + w);
+            }
         }
         if constexpr (!INTEGER) {
+            if constexpr (!FUSED) {
 #pragma unroll
-            for (int r = 0; r < kPsPerThread; ++r) {
-                const int id = tid + r * kThreads;
-                const int row = p0 + id / kGranPerChunk;
-                const int e = id % kGranPerChunk;
-                const int blk = chunk * nsp + e;
-                st_ps[r] = 0.f;
-                if (e < nsp && row < a.P && blk < nblk_p) st_ps[r] = a.p_scales[(int64_t)row * a.lds_p + blk];
+                for (int r = 0; r < kPsPerThread; ++r) {
+                    const int id = tid + r * kThreads;
+                    const int row = p0 + id / kGranPerChunk;
+                    const int e = id % kGranPerChunk;
+                    const int blk = chunk * nsp + e;
+                    st_ps[r] = 0.f;
+                    if (e < nsp && row < a.P && blk < nblk_p) st_ps[r] = a.p_scales[(int64_t)row * a.lds_p + blk];
+                }
             }
 #pragma unroll
             for (int r = 0; r < kQsPerThread; ++r) {
@@ -172,27 +181,83 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
 #if HBMM_GEMM_Q_PREFETCH
         asm volatile("" ::"v"(st_qline));   // keeps the touch load alive; its value is not used
 #endif
+        if constexpr (!FUSED) {
 #pragma unroll
-        for (int r = 0; r < kBitPieces; ++r) {
-            const int id = tid + r * kThreads;
-            const int row = id / (kCK / 4);
-            const int w = (id % (kCK / 4)) * 4;
-            uint32_t *dst = &s_bits[buf][row * kBitsStride + w];
-            // rows start at an 8-byte boundary only (stride 18 words): two 8-byte stores
-            *reinterpret_cast<uint2 *>(dst) = make_uint2(st_bits[r].x, st_bits[r].y);
-            *reinterpret_cast<uint2 *>(dst + 2) = make_uint2(st_bits[r].z, st_bits[r].w);
+            for (int r = 0; r < kBitPieces; ++r) {
+                const int id = tid + r * kThreads;
+                const int row = id / (kCK / 4);
+                const int w = (id % (kCK / 4)) * 4;
+                uint32_t *dst = &s_bits[buf][row * kBitsStride + w];
+                // rows start at an 8-byte boundary only (stride 18 words): two 8-byte stores
+                *reinterpret_cast<uint2 *>(dst) = make_uint2(st_bits[r].x, st_bits[r].y);
+                *reinterpret_cast<uint2 *>(dst + 2) = make_uint2(st_bits[r].z, st_bits[r].w);
+            }
         }
         if constexpr (!INTEGER) {
+            if constexpr (!FUSED) {
 #pragma unroll
-            for (int r = 0; r < kPsPerThread; ++r) {
-                const int id = tid + r * kThreads;
-                s_ps[buf][(id / kGranPerChunk) * kScaleStrideP + id % kGranPerChunk] = st_ps[r];
+                for (int r = 0; r < kPsPerThread; ++r) {
+                    const int id = tid + r * kThreads;
+                    s_ps[buf][(id / kGranPerChunk) * kScaleStrideP + id % kGranPerChunk] = st_ps[r];
+                }
             }
 #pragma unroll
             for (int r = 0; r < kQsPerThread; ++r) {
                 const int id = tid + r * kThreads;
                 if (id < kTileQ * kGranPerChunk)
                     s_qs[buf][(id % kGranPerChunk) * kTileQ + id / kGranPerChunk] = st_qs[r];
+            }
+        }
+    };
+
+    // ---- FUSED: binarise chunk `chunk` of this workgroup's 256 P rows from fp32 into LDS buffer `buf`.
+    // A wave owns 64 rows; per row the chunk is 512 elements = two 16-byte loads per lane (lane l holds
+    // elements 4l .. 4l+3 of each half).  Signs, words and scales are produced exactly as in the
+    // stand-alone pack kernel (same nibble merge, same pairwise order of the |x| sums), so the scales
+    // are bit-identical to packing first.  8 rows (16 loads per lane) are in flight at a time.
+    auto pack_chunk = [&](int chunk, int buf) {
+        if constexpr (FUSED) {
+            if (chunk >= nchunks) return;
+            constexpr int kRowsInFlight = 8;
+            const int seg_lanes = a.beta_p >> 2;               // lanes per P segment: 8 .. 64
+            const float inv_beta = 1.0f / (float)a.beta_p;
+            const int k_lane = chunk * (kCK * 32) + 4 * lane;
+#pragma unroll 1
+            for (int b = 0; b < 64 / kRowsInFlight; ++b) {
+                f32x4 v[kRowsInFlight][2];
+#pragma unroll
+                for (int j = 0; j < kRowsInFlight; ++j) {
+                    const int row = p0 + wave * 64 + b * kRowsInFlight + j;
+                    const float *src = a.p_src + (int64_t)min(row, a.P - 1) * a.ld_p_src;
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+                        v[j][h] = __builtin_nontemporal_load(
+                            reinterpret_cast<const f32x4 *>(src + min(k_lane + h * 256, a.K - 4)));
+                }
+#pragma unroll
+                for (int j = 0; j < kRowsInFlight; ++j) {
+                    const int row_l = wave * 64 + b * kRowsInFlight + j;
+                    const bool row_ok = p0 + row_l < a.P;
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const bool live = row_ok && (k_lane + h * 256 < a.K);
+                        const f32x4 x = v[j][h];
+                        const uint32_t nib = !live ? 0u
+                                                   : ((x.x >= 0.f ? 1u : 0u) | (x.y >= 0.f ? 2u : 0u) |
+                                                      (x.z >= 0.f ? 4u : 0u) | (x.w >= 0.f ? 8u : 0u));
+                        const uint32_t word = pack_word_from_nibbles(nib, lane);
+                        if ((lane & 7) == 0) s_bits[buf][row_l * kBitsStride + h * 8 + (lane >> 3)] = word;
+                        if constexpr (!INTEGER) {
+                            float s = live ? (fabsf(x.x) + fabsf(x.y)) + (fabsf(x.z) + fabsf(x.w)) : 0.f;
+                            s = segment_sum<8>(s);                     // beta 32
+                            if (seg_lanes >= 16) s += dpp_f32<kDppRowMirror>(s);
+                            if (seg_lanes >= 32) s += __shfl_xor(s, 16);
+                            if (seg_lanes >= 64) s += __shfl_xor(s, 32);
+                            if (live && (lane & (seg_lanes - 1)) == 0)
+                                s_ps[buf][row_l * kScaleStrideP + (h * 256 + 4 * lane) / a.beta_p] = s * inv_beta;
+                        }
+                    }
+                }
             }
         }
     };
@@ -217,6 +282,7 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
 
     fetch(0);
     park(0);
+    pack_chunk(0, 0);
     __syncthreads();
 
     // Scales of segment g_local of the chunk in `buf`: sp = -2 * sP (folds d = -2 * acc), sq = sQ.
@@ -235,14 +301,15 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
             sq[4 * v + 3] = t.w;
         }
     };
-    // Epilogue of one segment: res += (acc * -2 sP) * sQ  (acc = hamming - G/2, so -2 acc = d).
+    // Epilogue of one segment: res += acc * (-2 sP * sQ)  (acc = hamming - G/2, so -2 acc = d).  The
+    // scale product is formed first so that the result does not depend on which operand is P.
     auto epilogue = [&](const float (&sp)[kTP], const float (&sq)[kTQ]) {
 #pragma unroll
         for (int i = 0; i < kTP; ++i) {
             const float sp2 = -2.0f * sp[i];
 #pragma unroll
             for (int q = 0; q < kTQ; ++q)
-                res[i][q] = __builtin_fmaf((float)acc[i][q] * sp2, sq[q], res[i][q]);
+                res[i][q] = __builtin_fmaf((float)acc[i][q], sp2 * sq[q], res[i][q]);
         }
         // Pin the results here: without a use at this point the optimiser sinks the whole epilogue
         // to the end of the chunk and keeps every segment's accumulators alive until then.
@@ -360,6 +427,7 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
             }
         }
         park(buf ^ 1);
+        pack_chunk(chunk + 1, buf ^ 1);
         __syncthreads();
     }
     // Ragged last chunk (at most one): word-at-a-time loop with explicit accumulator resets.
@@ -397,32 +465,40 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
         }
     }
 
-    // ---- store
+    // ---- store.  When Q runs along the rows of the output (ld_out_q == 1: P is the M side), a lane's 16
+    // results of one P row are contiguous: four 16-byte stores instead of sixteen 4-byte ones.
+    const bool row_vectors = a.ld_out_q == 1 && (a.ld_out_p & 3) == 0 && q0 + kTQ <= a.Q;
 #pragma unroll
     for (int i = 0; i < kTP; ++i) {
         const int p = p0 + lane + 64 * i;
         if (p >= a.P) continue;
+        uint32_t v[kTQ];
 #pragma unroll
-        for (int q = 0; q < kTQ; ++q) {
-            const int qq = q0 + q;
-            if (qq >= a.Q) continue;
-            const int64_t off = (int64_t)p * a.ld_out_p + (int64_t)qq * a.ld_out_q;
-            if (INTEGER)
-                reinterpret_cast<int32_t *>(a.out)[off] = a.K - 2 * acc[i][q];
-            else
-                reinterpret_cast<float *>(a.out)[off] = res[i][q];
+        for (int q = 0; q < kTQ; ++q)
+            v[q] = INTEGER ? (uint32_t)(a.K - 2 * acc[i][q]) : __builtin_bit_cast(uint32_t, res[INTEGER ? 0 : i][INTEGER ? 0 : q]);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(a.out);
+        if (row_vectors) {
+            uint4 *d4 = reinterpret_cast<uint4 *>(dst + (int64_t)p * a.ld_out_p + q0);
+#pragma unroll
+            for (int c = 0; c < kTQ / 4; ++c) d4[c] = make_uint4(v[4 * c], v[4 * c + 1], v[4 * c + 2], v[4 * c + 3]);
+        } else {
+#pragma unroll
+            for (int q = 0; q < kTQ; ++q) {
+                const int qq = q0 + q;
+                if (qq < a.Q) dst[(int64_t)p * a.ld_out_p + (int64_t)qq * a.ld_out_q] = v[q];
+            }
         }
     }
 }
 
-template <int G, bool INTEGER>
+template <int G, bool INTEGER, bool FUSED = false>
 hipError_t launch(const PopcountGemmArgs &a, hipStream_t s)
 {
     int64_t nblocks = (int64_t)a.tiles_p * a.tiles_q;
     if (nblocks <= 0) return hipSuccess;
     if (a.sup_p != 0) nblocks = (int64_t)((a.n_super + kNumXcd - 1) / kNumXcd) * kNumXcd * kSuperTiles;
     if (nblocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    popcount_gemm_kernel<G, INTEGER><<<dim3((unsigned)nblocks), dim3(kThreads), 0, s>>>(a);
+    popcount_gemm_kernel<G, INTEGER, FUSED><<<dim3((unsigned)nblocks), dim3(kThreads), 0, s>>>(a);
     return hipGetLastError();
 }
 
@@ -444,6 +520,15 @@ hipError_t launch_popcount_gemm(const PopcountGemmArgs &args, int G, int integer
     }
     a.step_words = kStep;
     if (integer) return launch<64, true>(a, s);
+    if (a.p_src != nullptr) {
+        switch (G) {
+        case 32: return launch<32, false, true>(a, s);
+        case 64: return launch<64, false, true>(a, s);
+        case 128: return launch<128, false, true>(a, s);
+        case 256: return launch<256, false, true>(a, s);
+        }
+        return hipErrorInvalidValue;
+    }
     switch (G) {
     case 32: return launch<32, false>(a, s);
     case 64: return launch<64, false>(a, s);

@@ -26,6 +26,9 @@ hipError_t launch_binarize_backward(const float *x, const float *g, int64_t rows
 // out[p * ld_out_p + q * ld_out_q] receives the result for P-row p and Q-row q, so either of
 // A / B can play either role.
 struct PopcountGemmArgs {
+    const float *p_src;  // fused mode: P as fp32 (rows x K, leading dimension ld_p_src); else nullptr
+    int64_t ld_p_src;
+    int32_t beta_p;      // fused mode: segment length of P
     const uint32_t *p_bits;
     const float *p_scales;
     const uint32_t *q_bits;

@@ -15,6 +15,7 @@
 //   every load is a coalesced 256-byte wave access; the word is built with shifts and the scale
 //   is a sequential double-precision sum rounded once.
 #include "kernels.h"
+#include "wave_ops.h"
 
 namespace hbmm {
 namespace {
@@ -22,34 +23,6 @@ namespace {
 constexpr int kUnroll = 4;          // 16-byte loads in flight per lane
 constexpr int kChunk = 256;         // K elements per wave per load
 constexpr int kWavesPerBlock = 4;
-
-template <int CTRL>
-__device__ __forceinline__ uint32_t dpp_u32(uint32_t v)
-{
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
-}
-template <int CTRL>
-__device__ __forceinline__ float dpp_f32(float v)
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
-}
-constexpr int kQuadSwap1 = 0xB1;    // quad_perm [1,0,3,2]
-constexpr int kQuadSwap2 = 0x4E;    // quad_perm [2,3,0,1]
-constexpr int kHalfMirror = 0x141;  // lane i <-> 7-i inside each group of 8
-constexpr int kRowMirror = 0x140;   // lane i <-> 15-i inside each group of 16
-
-// Sum over `LANES` consecutive lanes (a power of two, aligned); every lane gets the result.
-template <int LANES>
-__device__ __forceinline__ float segment_sum(float v)
-{
-    if (LANES >= 2) v += dpp_f32<kQuadSwap1>(v);
-    if (LANES >= 4) v += dpp_f32<kQuadSwap2>(v);
-    if (LANES >= 8) v += dpp_f32<kHalfMirror>(v);
-    if (LANES >= 16) v += dpp_f32<kRowMirror>(v);
-    if (LANES >= 32) v += __shfl_xor(v, 16);
-    if (LANES >= 64) v += __shfl_xor(v, 32);
-    return v;
-}
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -103,11 +76,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void pack_rows_kernel(
         // signs -> nibble -> 32-bit word, OR-ed over the 8 lanes that hold it
         const uint32_t nib = (v[u].x >= 0.f ? 1u : 0u) | (v[u].y >= 0.f ? 2u : 0u) |
                              (v[u].z >= 0.f ? 4u : 0u) | (v[u].w >= 0.f ? 8u : 0u);
-        uint32_t t = nib << (4 * (lane & 7));
-        t |= dpp_u32<kQuadSwap1>(t);
-        t |= dpp_u32<kQuadSwap2>(t);
-        t |= dpp_u32<kHalfMirror>(t);
-        w[u] = t;
+        w[u] = pack_word_from_nibbles(nib, lane);
         // sum of |x| over the beta-segment, every lane of the segment gets it
         const float lo = live ? fabsf(v[u].x) + fabsf(v[u].y) : 0.f;
         const float hi = live ? fabsf(v[u].z) + fabsf(v[u].w) : 0.f;

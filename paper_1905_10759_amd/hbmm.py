@@ -20,7 +20,7 @@ ALGO_POPCOUNT, ALGO_MFMA_I8 = 0, 1
 
 EXPORTS = (
     "hbmm_strerror", "hbmm_num_blocks", "hbmm_packed_ld_words", "hbmm_quantize_pack", "hbmm_gemm",
-    "hbmm_gemm_int", "hbmm_dense_ref_gemm", "hbmm_binarize_backward",
+    "hbmm_gemm_int", "hbmm_dense_ref_gemm", "hbmm_binarize_backward", "hbmm_gemm_fused",
 )
 
 
@@ -49,6 +49,8 @@ def _load() -> C.CDLL:
     lib.hbmm_gemm.argtypes = [p, p, i64, i64, i32, p, p, i64, i64, i32, i64, i64, i64, p, i64, i32, p]
     lib.hbmm_gemm_int.restype = C.c_int
     lib.hbmm_gemm_int.argtypes = [p, i64, p, i64, i64, i64, i64, p, i64, p]
+    lib.hbmm_gemm_fused.restype = C.c_int
+    lib.hbmm_gemm_fused.argtypes = [p, i64, i32, p, p, i64, i64, i32, i64, i64, i64, p, i64, p]
     lib.hbmm_binarize_backward.restype = C.c_int
     lib.hbmm_binarize_backward.argtypes = [p, p, i64, i64, i64, i64, i32, p, i64, p]
     lib.hbmm_dense_ref_gemm.restype = C.c_int
@@ -181,4 +183,20 @@ def binarize_backward(x: torch.Tensor, grad_out: torch.Tensor, beta: int, out: t
     rc = lib.hbmm_binarize_backward(x.data_ptr(), grad_out.data_ptr(), rows, K, ld(x), ld(grad_out), beta,
                                     out.data_ptr(), ld(out), _stream())
     _check(rc, "hbmm_binarize_backward")
+    return out
+
+
+def gemm_fused(A: torch.Tensor, beta_a: int, b_bits, b_scales, beta_w: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    """hbmm_gemm_fused: quantize_pack(A) + gemm in one kernel (N <= 128), A given as raw fp32 M x K."""
+    _dev(A, torch.float32, "A")
+    _dev(b_bits, torch.int32, "b_bits")
+    _dev(b_scales, torch.float32, "b_scales")
+    (M, K), N = A.shape, b_bits.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=A.device)
+    rc = lib.hbmm_gemm_fused(A.data_ptr(), A.stride(0) if M > 1 else K, beta_a, b_bits.data_ptr(), b_scales.data_ptr(),
+                             b_bits.stride(0) if N > 1 else b_bits.shape[1],
+                             b_scales.stride(0) if N > 1 else max(b_scales.shape[1], 1), beta_w, M, N, K,
+                             out.data_ptr(), out.stride(0) if M > 1 else max(N, 1), _stream())
+    _check(rc, "hbmm_gemm_fused")
     return out

@@ -140,8 +140,13 @@ def test_gemm_mixed_beta(beta_a, beta_w):
 @pytest.mark.parametrize("beta", [32, 64, 128, 256])
 @pytest.mark.parametrize("M,N,K", [(64, 64, 512), (300, 200, 1024), (129, 257, 1536), (5, 3, 256), (260, 140, 4608)])
 def test_gemm_mfma_i8_equal_beta(beta, M, N, K):
-    """The int8 matrix-core comparison variant must give the same product."""
-    run_gemm_case(synth.normal(400 + M, (M, K)), synth.uniform_pm1(401 + N, (N, K)), beta, beta, algo=1)
+    """The int8 matrix-core comparison variant must give the same product -- bit for bit, since its
+    integer dots are the same and its epilogue rounds in the same places."""
+    A, B = synth.normal(400 + M, (M, K)), synth.uniform_pm1(401 + N, (N, K))
+    run_gemm_case(A, B, beta, beta, algo=1)
+    ab, as_ = hbmm.quantize_pack(dev(A), beta)
+    bb, bs = hbmm.quantize_pack(dev(B), beta)
+    assert torch.equal(hbmm.gemm(ab, as_, beta, bb, bs, beta, K, algo=0), hbmm.gemm(ab, as_, beta, bb, bs, beta, K, algo=1))
 
 
 @pytest.mark.parametrize("beta_a,beta_w,K", [(32, 64, 1280), (256, 32, 1280), (128, 64, 1280), (64, 256, 1280),
@@ -363,3 +368,32 @@ def test_calls_on_a_side_stream():
         if ref is None:
             ref = got
         assert np.array_equal(ref, got)
+
+
+# ------------------------------------------------------------------------------------- fused
+@pytest.mark.parametrize("beta_a,beta_w", [(32, 32), (64, 64), (128, 128), (256, 256), (32, 128), (256, 64)])
+@pytest.mark.parametrize("M,N,K", [(3136, 64, 576), (300, 128, 1024), (257, 5, 256), (64, 64, 512), (1000, 100, 4608)])
+def test_gemm_fused_equals_pack_then_gemm(beta_a, beta_w, M, N, K):
+    """The fused call must give bit for bit what packing A first and multiplying gives, and both
+    must be within the tolerance of the oracle."""
+    if K % beta_a or K % beta_w:
+        pytest.skip("K not a multiple of beta")
+    A, B = synth.relu_normal(1200 + M, (M, K)) - 0.3, synth.normal(1201 + N, (N, K), std=0.06)
+    A = A.astype(np.float32)
+    dA = dev(A)
+    bb, bs = hbmm.quantize_pack(dev(B), beta_w)
+    ab, as_ = hbmm.quantize_pack(dA, beta_a)
+    two_step = hbmm.gemm(ab, as_, beta_a, bb, bs, beta_w, K)
+    fused = hbmm.gemm_fused(dA, beta_a, bb, bs, beta_w)
+    assert torch.equal(fused, two_step)
+    ref, T = oracle.hbmm_popcount(A, B, beta_a, beta_w, want_T=True)
+    assert_close_to_oracle(fused.cpu().numpy(), ref, T, "fused")
+
+
+def test_gemm_fused_limits():
+    A = torch.zeros((8, 64), dtype=torch.float32, device="cuda")
+    bb = torch.zeros((200, 4), dtype=torch.int32, device="cuda")
+    bs = torch.ones((200, 2), dtype=torch.float32, device="cuda")
+    with pytest.raises(hbmm.HbmmError) as ei:
+        hbmm.gemm_fused(A, 32, bb, bs, 32)      # N > 128
+    assert ei.value.code == hbmm.EUNSUPPORTED
