@@ -214,50 +214,110 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
     // A wave owns 64 rows; per row the chunk is 512 elements = two 16-byte loads per lane (lane l holds
     // elements 4l .. 4l+3 of each half).  Signs, words and scales are produced exactly as in the
     // stand-alone pack kernel (same nibble merge, same pairwise order of the |x| sums), so the scales
-    // are bit-identical to packing first.  8 rows (16 loads per lane) are in flight at a time.
+    // are bit-identical to packing first.
+    // Rows are handled in batches of kPackRows with two register sets: while one batch is turned into
+    // words the loads of the next are in flight, and the first batch of the next chunk is requested
+    // before the popcount phase of this one, so that the memory pipe is never idle.
+    constexpr int kPackRows = 4;
+    constexpr int kPackBatches = 64 / kPackRows;
+    f32x4 pv[FUSED ? 2 : 1][FUSED ? kPackRows : 1][2];
+    auto pack_issue = [&](int chunk, int b, f32x4 (&v)[FUSED ? kPackRows : 1][2]) {
+        if constexpr (FUSED) {
+            // past the end of K or P the addresses are clamped; such values are masked when used
+            const int k_lane = chunk * (kCK * 32) + 4 * lane;
+#pragma unroll
+            for (int j = 0; j < kPackRows; ++j) {
+                const int row = p0 + wave * 64 + b * kPackRows + j;
+                const float *src = a.p_src + (int64_t)min(row, a.P - 1) * a.ld_p_src;
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    v[j][h] = __builtin_nontemporal_load(
+                        reinterpret_cast<const f32x4 *>(src + min(k_lane + h * 256, a.K - 4)));
+            }
+        }
+    };
+    // The batch is worked through phase by phase (all words, then each level of the scale sums, then
+    // the LDS stores) so that the eight row-halves give eight independent dependency chains per phase
+    // and every branch is taken once per batch.  Lanes past K or rows past P work on clamped loads:
+    // K is a multiple of beta, so no word or segment mixes live and dead elements, and dead words and
+    // scales are never read.  A half that lies wholly past K (last chunk only) is skipped.
+    auto pack_words = [&](int chunk, int b, const f32x4 (&v)[FUSED ? kPackRows : 1][2], int buf) {
+        if constexpr (FUSED) {
+            const int seg_lanes = a.beta_p >> 2;               // lanes per P segment: 8 .. 64
+            const float inv_beta = 1.0f / (float)a.beta_p;
+            const int halves = (chunk * (kCK * 32) + 256 < a.K) ? 2 : 1;
+            uint32_t word[kPackRows][2];
+            float sum[kPackRows][2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                if (h < halves) {
+#pragma unroll
+                    for (int j = 0; j < kPackRows; ++j) {
+                        const f32x4 x = v[j][h];
+                        const uint32_t nib = (x.x >= 0.f ? 1u : 0u) | (x.y >= 0.f ? 2u : 0u) |
+                                             (x.z >= 0.f ? 4u : 0u) | (x.w >= 0.f ? 8u : 0u);
+                        word[j][h] = pack_word_from_nibbles(nib, lane);
+                        if constexpr (!INTEGER)
+                            sum[j][h] = segment_sum<8>((fabsf(x.x) + fabsf(x.y)) + (fabsf(x.z) + fabsf(x.w)));
+                    }
+                }
+            }
+            if constexpr (!INTEGER) {
+                if (seg_lanes >= 16) {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int j = 0; j < kPackRows; ++j)
+                            if (h < halves) sum[j][h] += dpp_f32<kDppRowMirror>(sum[j][h]);
+                }
+                if (seg_lanes >= 32) {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int j = 0; j < kPackRows; ++j)
+                            if (h < halves) sum[j][h] += __shfl_xor(sum[j][h], 16);
+                }
+                if (seg_lanes >= 64) {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int j = 0; j < kPackRows; ++j)
+                            if (h < halves) sum[j][h] += __shfl_xor(sum[j][h], 32);
+                }
+            }
+            const int row_l = wave * 64 + b * kPackRows;
+            if ((lane & 7) == 0) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int j = 0; j < kPackRows; ++j)
+                        if (h < halves) s_bits[buf][(row_l + j) * kBitsStride + h * 8 + (lane >> 3)] = word[j][h];
+            }
+            if constexpr (!INTEGER) {
+                if ((lane & (seg_lanes - 1)) == 0) {
+                    const int e = (4 * lane) / a.beta_p;
+                    const int e_half = 256 / a.beta_p;
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int j = 0; j < kPackRows; ++j)
+                            if (h < halves)
+                                s_ps[buf][(row_l + j) * kScaleStrideP + h * e_half + e] = sum[j][h] * inv_beta;
+                }
+            }
+        }
+    };
+    // Expects batch 0 of `chunk` to have been requested into pv[0]; leaves batch 0 of chunk + 1 there.
     auto pack_chunk = [&](int chunk, int buf) {
         if constexpr (FUSED) {
             if (chunk >= nchunks) return;
-            constexpr int kRowsInFlight = 8;
-            const int seg_lanes = a.beta_p >> 2;               // lanes per P segment: 8 .. 64
-            const float inv_beta = 1.0f / (float)a.beta_p;
-            const int k_lane = chunk * (kCK * 32) + 4 * lane;
 #pragma unroll 1
-            for (int b = 0; b < 64 / kRowsInFlight; ++b) {
-                f32x4 v[kRowsInFlight][2];
-#pragma unroll
-                for (int j = 0; j < kRowsInFlight; ++j) {
-                    const int row = p0 + wave * 64 + b * kRowsInFlight + j;
-                    const float *src = a.p_src + (int64_t)min(row, a.P - 1) * a.ld_p_src;
-#pragma unroll
-                    for (int h = 0; h < 2; ++h)
-                        v[j][h] = __builtin_nontemporal_load(
-                            reinterpret_cast<const f32x4 *>(src + min(k_lane + h * 256, a.K - 4)));
-                }
-#pragma unroll
-                for (int j = 0; j < kRowsInFlight; ++j) {
-                    const int row_l = wave * 64 + b * kRowsInFlight + j;
-                    const bool row_ok = p0 + row_l < a.P;
-#pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        const bool live = row_ok && (k_lane + h * 256 < a.K);
-                        const f32x4 x = v[j][h];
-                        const uint32_t nib = !live ? 0u
-                                                   : ((x.x >= 0.f ? 1u : 0u) | (x.y >= 0.f ? 2u : 0u) |
-                                                      (x.z >= 0.f ? 4u : 0u) | (x.w >= 0.f ? 8u : 0u));
-                        const uint32_t word = pack_word_from_nibbles(nib, lane);
-                        if ((lane & 7) == 0) s_bits[buf][row_l * kBitsStride + h * 8 + (lane >> 3)] = word;
-                        if constexpr (!INTEGER) {
-                            float s = live ? (fabsf(x.x) + fabsf(x.y)) + (fabsf(x.z) + fabsf(x.w)) : 0.f;
-                            s = segment_sum<8>(s);                     // beta 32
-                            if (seg_lanes >= 16) s += dpp_f32<kDppRowMirror>(s);
-                            if (seg_lanes >= 32) s += __shfl_xor(s, 16);
-                            if (seg_lanes >= 64) s += __shfl_xor(s, 32);
-                            if (live && (lane & (seg_lanes - 1)) == 0)
-                                s_ps[buf][row_l * kScaleStrideP + (h * 256 + 4 * lane) / a.beta_p] = s * inv_beta;
-                        }
-                    }
-                }
+            for (int b = 0; b < kPackBatches; b += 2) {
+                pack_issue(chunk, b + 1, pv[1]);
+                pack_words(chunk, b, pv[0], buf);
+                const bool more = b + 2 < kPackBatches;
+                pack_issue(more ? chunk : chunk + 1, more ? b + 2 : 0, pv[0]);
+                pack_words(chunk, b + 1, pv[1], buf);
             }
         }
     };
@@ -280,6 +340,7 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
 #pragma unroll
     for (int q = 0; q < kTQ; ++q) qoff[q] = (uint32_t)(min(q0 + q, a.Q - 1) * a.ldw_q) * 4u;
 
+    pack_issue(0, 0, pv[0]);
     fetch(0);
     park(0);
     pack_chunk(0, 0);
