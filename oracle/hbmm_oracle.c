@@ -252,3 +252,48 @@ void oracle_binarize_backward(const float *x, const float *g, int64_t rows, int6
         }
     }
 }
+
+/* Convolution of a Hadamard-binarised activation tensor with Hadamard-binarised filters, written
+ * from the definition of a (cross-correlation) convolution layer with zero padding:
+ *   O[b, n, oz, oy] = sum_{c, dz, dy} At[b, c, oz*stride - pad + dz, oy*stride - pad + dy] * Wt[n, c, dz, dy]
+ * where positions outside the input contribute nothing.  At (B x C x H x W, W contiguous: the
+ * width index y of Eq. 3 is the contiguous one) and Wt (N x C x KH x KW) are the materialised
+ * tensors delta (.) Sign(.): At by Eq. 3-4 (segments of beta_a along the width of each row of each
+ * channel), Wt by Eq. 1-2 (segments of beta_w along the filter flattened to C*KH*KW).  The caller
+ * materialises them with oracle_materialize on the corresponding rows x K views.  The terms are
+ * added in the order c, dz, dy (the flattened filter order).  T (may be NULL) receives the sum of
+ * the absolute values of the terms. */
+void oracle_conv2d_f64(const double *At, const double *Wt, int64_t B, int64_t C, int64_t H, int64_t W,
+                       int64_t N, int64_t KH, int64_t KW, int64_t stride, int64_t pad, double *O,
+                       double *T)
+{
+    const int64_t OH = (H + 2 * pad - KH) / stride + 1;
+    const int64_t OW = (W + 2 * pad - KW) / stride + 1;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t b = 0; b < B; ++b) {
+        for (int64_t n = 0; n < N; ++n) {
+            for (int64_t oz = 0; oz < OH; ++oz) {
+                for (int64_t oy = 0; oy < OW; ++oy) {
+                    double acc = 0.0, tabs = 0.0;
+                    for (int64_t c = 0; c < C; ++c) {
+                        for (int64_t dz = 0; dz < KH; ++dz) {
+                            for (int64_t dy = 0; dy < KW; ++dy) {
+                                const int64_t z = oz * stride - pad + dz;
+                                const int64_t y = oy * stride - pad + dy;
+                                if (z < 0 || z >= H || y < 0 || y >= W)
+                                    continue;
+                                const double term = At[((b * C + c) * H + z) * W + y] *
+                                                    Wt[((n * C + c) * KH + dz) * KW + dy];
+                                acc += term;
+                                tabs += fabs(term);
+                            }
+                        }
+                    }
+                    O[((b * N + n) * OH + oz) * OW + oy] = acc;
+                    if (T)
+                        T[((b * N + n) * OH + oz) * OW + oy] = tabs;
+                }
+            }
+        }
+    }
+}

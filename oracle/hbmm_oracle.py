@@ -16,7 +16,8 @@ from . import build as _build
 __all__ = [
     "num_threads", "num_blocks", "ld_words", "block_scales", "sign_pack", "materialize",
     "dense_f64_gemm", "popcount_gemm", "int_dot", "binary_weight_gemm", "hbmm_dense",
-    "hbmm_popcount", "as_rows_by_k", "binarize_backward",
+    "hbmm_popcount", "as_rows_by_k", "binarize_backward", "conv_out_size", "materialize_activations",
+    "materialize_filters", "conv2d_f64", "hbmm_conv2d",
 ]
 
 _lib = None
@@ -37,6 +38,7 @@ def _load():
         lib.oracle_int_dot.argtypes = [p, i64, p, i64, i64, i64, i64, p]
         lib.oracle_binary_weight_gemm.argtypes = [p, i64, p, i64, p, i64, i64, i64, i64, i64, p, p]
         lib.oracle_binarize_backward.argtypes = [p, p, i64, i64, i64, i64, i64, p, p]
+        lib.oracle_conv2d_f64.argtypes = [p, p, i64, i64, i64, i64, i64, i64, i64, i64, i64, p, p]
         lib.oracle_binarize_backward.restype = None
         for name in ("oracle_block_scales", "oracle_sign_pack", "oracle_materialize", "oracle_dense_f64_gemm",
                      "oracle_popcount_gemm", "oracle_int_dot", "oracle_binary_weight_gemm"):
@@ -177,3 +179,46 @@ def binarize_backward(x, g, beta: int, want_T: bool = False):
     T = np.empty((rows, K), dtype=np.float64) if want_T else None
     _load().oracle_binarize_backward(_ptr(x), _ptr(g), rows, K, K, K, beta, _ptr(gx), _ptr(T) if want_T else None)
     return (gx, T) if want_T else gx
+
+
+def conv_out_size(size: int, k: int, stride: int, pad: int) -> int:
+    return (size + 2 * pad - k) // stride + 1
+
+
+def materialize_activations(A, beta_a: int) -> np.ndarray:
+    """Eq. 3-4 for an activation tensor B x C x H x W (W, the width index y of Eq. 3, contiguous):
+    delta over segments of beta_a along the width of every row of every channel, times Sign(A)."""
+    A = np.ascontiguousarray(A, dtype=np.float32)
+    B, C, H, W = A.shape
+    if W % beta_a:
+        raise ValueError("beta_a must divide the input width")
+    return materialize(A.reshape(B * C * H, W), beta_a).reshape(B, C, H, W)
+
+
+def materialize_filters(Wf, beta_w: int) -> np.ndarray:
+    """Eq. 1-2 for filters N x C x KH x KW: each filter flattened to C*KH*KW, segments of beta_w."""
+    Wf = np.ascontiguousarray(Wf, dtype=np.float32)
+    N = Wf.shape[0]
+    return materialize(Wf.reshape(N, -1), beta_w).reshape(Wf.shape)
+
+
+def conv2d_f64(At: np.ndarray, Wt: np.ndarray, stride: int, pad: int, want_T: bool = False):
+    """Zero-padded convolution (cross-correlation) of materialised tensors, in double."""
+    At = np.ascontiguousarray(At, dtype=np.float64)
+    Wt = np.ascontiguousarray(Wt, dtype=np.float64)
+    B, C, H, W = At.shape
+    N, C2, KH, KW = Wt.shape
+    if C != C2:
+        raise ValueError("channel mismatch")
+    OH, OW = conv_out_size(H, KH, stride, pad), conv_out_size(W, KW, stride, pad)
+    out = np.empty((B, N, OH, OW), dtype=np.float64)
+    T = np.empty_like(out) if want_T else None
+    _load().oracle_conv2d_f64(_ptr(At), _ptr(Wt), B, C, H, W, N, KH, KW, stride, pad, _ptr(out),
+                              _ptr(T) if want_T else None)
+    return (out, T) if want_T else out
+
+
+def hbmm_conv2d(A, Wf, beta_a: int, beta_w: int, stride: int = 1, pad: int = 0, want_T: bool = False):
+    """A convolution layer of a HadaNet: activations binarised by Eq. 3-4, filters by Eq. 1-2, then
+    the plain convolution of the two materialised tensors."""
+    return conv2d_f64(materialize_activations(A, beta_a), materialize_filters(Wf, beta_w), stride, pad, want_T)

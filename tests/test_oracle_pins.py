@@ -348,3 +348,91 @@ def test_backward_brute_force_ragged_and_mask_edges():
         want = _sgn(x[0, i]) * sdot / n + (delta * Fraction(float(g[0, i])) if abs(x[0, i]) <= 1 else 0)
         assert got[0, i] == pytest.approx(float(want), abs=1e-14), i
         assert T[0, i] >= abs(got[0, i]) - 1e-14
+
+
+# ----------------------------------------------------------------------------- convolution (Eq. 1-4 on tensors)
+def _np_materialize_act(A: np.ndarray, beta: int) -> np.ndarray:
+    """delta (.) Sign(A) with segments along the last (width) axis, in numpy, independent of oracle/."""
+    B, C, H, W = A.shape
+    seg = np.abs(A.astype(np.float64)).reshape(B, C, H, W // beta, beta).mean(axis=-1).astype(np.float32)
+    return np.where(A >= 0, 1.0, -1.0) * np.repeat(seg.astype(np.float64), beta, axis=-1)
+
+
+def _np_materialize_filt(Wf: np.ndarray, beta: int) -> np.ndarray:
+    N = Wf.shape[0]
+    flat = Wf.reshape(N, -1)
+    seg = np.abs(flat.astype(np.float64)).reshape(N, -1, beta).mean(axis=-1).astype(np.float32)
+    return (np.where(flat >= 0, 1.0, -1.0) * np.repeat(seg.astype(np.float64), beta, axis=-1)).reshape(Wf.shape)
+
+
+@pytest.mark.parametrize("stride,pad,KH,KW", [(1, 1, 3, 3), (2, 1, 3, 3), (1, 0, 1, 1), (2, 0, 1, 1), (1, 2, 5, 3), (2, 0, 2, 2)])
+def test_conv_matches_library_convolution(stride, pad, KH, KW):
+    """Catches: swapped height/width, wrong stride/padding arithmetic, a flipped kernel (true
+    convolution instead of cross-correlation), wrong output size, segments along the wrong axis."""
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(11 * stride + pad + KH)
+    B, C, H, W, N = 2, 4, 7, 8, 3
+    A = rng.standard_normal((B, C, H, W)).astype(np.float32)
+    Wf = rng.standard_normal((N, C, KH, KW)).astype(np.float32)
+    beta_a, beta_w = 4, 2
+    At, Wt = _np_materialize_act(A, beta_a), _np_materialize_filt(Wf, beta_w)
+    ref = torch.nn.functional.conv2d(torch.from_numpy(At), torch.from_numpy(Wt), stride=stride, padding=pad).numpy()
+    got, T = oracle.hbmm_conv2d(A, Wf, beta_a, beta_w, stride, pad, want_T=True)
+    assert got.shape == ref.shape
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-12 * max(1.0, float(np.abs(ref).max())))
+    assert np.all(T >= np.abs(got) - 1e-12)
+
+
+def test_conv_activation_segments_run_along_the_width():
+    """|A| depends on the width index only, so segment means along the width differ from |A| while
+    means along the height (the wrong axis) would reproduce |A| itself.  Eq. 3: the segment index
+    is floor(y / beta_a) with y the width."""
+    B, C, H, W = 1, 2, 4, 8
+    A = np.broadcast_to(np.arange(1, W + 1, dtype=np.float32), (B, C, H, W)).copy()
+    A[:, :, 1::2, :] *= -1.0
+    At = oracle.materialize_activations(A, 4)
+    np.testing.assert_array_equal(np.abs(At[0, 0, 0]), [2.5] * 4 + [6.5] * 4)
+    np.testing.assert_array_equal(np.sign(At), np.sign(A))
+    # a 1x1 filter with a single +1 weight reads the materialised activations back
+    Wf = np.zeros((1, C, 1, 1), dtype=np.float32)
+    Wf[0, 0, 0, 0] = 3.0
+    out = oracle.hbmm_conv2d(A, Wf, 4, 1, 1, 0)
+    np.testing.assert_array_equal(out[0, 0], 3.0 * At[0, 0])
+
+
+def test_conv_filter_segments_run_over_the_flattened_filter():
+    """Eq. 1: the filter is reshaped to (filters, C*KH*KW) before it is cut into segments, so a
+    segment may cross kernel rows and channels.  With beta_w = C*KH*KW the scale is one per filter."""
+    rng = np.random.default_rng(5)
+    Wf = rng.standard_normal((2, 2, 3, 3)).astype(np.float32)
+    Wt = oracle.materialize_filters(Wf, 6)
+    flat = np.abs(Wf.reshape(2, 18).astype(np.float64))
+    for n in range(2):
+        for j in range(3):
+            np.testing.assert_allclose(np.abs(Wt.reshape(2, 18)[n, 6 * j:6 * j + 6]),
+                                       np.float32(flat[n, 6 * j:6 * j + 6].mean()), rtol=0, atol=0)
+    Wt_all = oracle.materialize_filters(Wf, 18)
+    for n in range(2):
+        assert np.unique(np.abs(Wt_all[n])).size == 1
+
+
+def test_conv_beta_one_is_plain_convolution_and_brute_force():
+    """beta = 1 on both sides leaves both tensors as they are; the result must equal a convolution
+    evaluated term by term with exact rationals (catches index or padding slips the library pin
+    could share, and dropped boundary terms)."""
+    rng = np.random.default_rng(9)
+    B, C, H, W, N, KH, KW, stride, pad = 1, 2, 4, 4, 2, 3, 3, 1, 1
+    A = rng.integers(-3, 4, (B, C, H, W)).astype(np.float32)
+    Wf = rng.integers(-2, 3, (N, C, KH, KW)).astype(np.float32)
+    got = oracle.hbmm_conv2d(A, Wf, 1, 1, stride, pad)
+    for n in range(N):
+        for oz in range(H):
+            for oy in range(W):
+                acc = Fraction(0)
+                for c in range(C):
+                    for dz in range(KH):
+                        for dy in range(KW):
+                            z, y = oz - pad + dz, oy - pad + dy
+                            if 0 <= z < H and 0 <= y < W:
+                                acc += Fraction(float(A[0, c, z, y])) * Fraction(float(Wf[n, c, dz, dy]))
+                assert got[0, n, oz, oy] == float(acc)
