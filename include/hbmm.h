@@ -125,6 +125,41 @@ int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int6
               int32_t algo, void *stream);
 
 /*
+ * Binarise a whole tensor stored contiguously (Eq. 3-4 for an activation tensor B x C x H x W whose
+ * width W is the contiguous axis and a multiple of beta: the segments of beta consecutive elements
+ * then are the width segments of Eq. 3 and never leave a row).
+ *   x       device, fp32, count elements, 16-byte aligned.
+ *   beta    power of two in 2 .. 256.
+ *   bits    out, device, count / 32 words: element e is bit (e mod 32) of word (e div 32), 1 = (x >= 0).
+ *   scales  out, device, count / beta fp32: mean |x| of elements [j * beta, (j + 1) * beta).
+ * count must be a multiple of 128 and of beta (else HBMM_EUNSUPPORTED) and below 2^31.
+ */
+int hbmm_quantize_pack_tensor(const float *x, int64_t count, int32_t beta, uint32_t *bits, float *scales,
+                              void *stream);
+
+/*
+ * A convolution layer of a HadaNet, computed directly from the packed tensors (no im2col matrix is
+ * formed): activations binarised by Eq. 3-4, filters by Eq. 1-2, then
+ *   out[b, n, oz, oy] = sum_{c, dz, dy} A~[b, c, oz*stride - pad + dz, oy*stride - pad + dy] * W~[n, c, dz, dy]
+ * with zero contribution from positions outside the input (zero padding).
+ *   a_bits, a_scales   the activation tensor B x C x H x W as written by hbmm_quantize_pack_tensor
+ *                      with beta_a (beta_a in 2 .. 256 must divide W).
+ *   w_bits, w_scales   the filters N x C x KH x KW as written by hbmm_quantize_pack (layout 0) on the
+ *                      N x (C*KH*KW) matrix with beta_w; ldw_w / lds_w its leading dimensions.
+ *                      beta_w in 16 .. 256.
+ *   out                device, fp32, B x N x OH x OW contiguous, OH = (H + 2 pad - KH) / stride + 1,
+ *                      OW likewise; 16-byte aligned.
+ * C*KH*KW must be a multiple of 32 and of beta_w, KH*KW <= 32, B*C*H*W and B*OH*OW below 2^31; other
+ * shapes return HBMM_EUNSUPPORTED.  The activation values run on the matrix cores as three exact
+ * bf16 pieces of the fp32 scale, the filter signs as +-1, the filter scale is applied per segment in
+ * fp32: every output is an fp32 sum of exact terms.
+ */
+int hbmm_conv2d(const uint32_t *a_bits, const float *a_scales, int32_t beta_a, const uint32_t *w_bits,
+                const float *w_scales, int64_t ldw_w, int64_t lds_w, int32_t beta_w, int64_t B, int64_t C,
+                int64_t H, int64_t W, int64_t N, int32_t KH, int32_t KW, int32_t stride, int32_t pad,
+                float *out, void *stream);
+
+/*
  * Fused form for the activation operand: the same C as
  *     hbmm_quantize_pack(A, layout 0, beta_a)  followed by  hbmm_gemm(..., algo 0)
  * (bit for bit: same scale arithmetic, same contraction, same epilogue order), but A is binarised

@@ -255,6 +255,57 @@ int hbmm_gemm_fused(const float *A, int64_t lda, int32_t beta_a, const uint32_t 
     return from_hip(hbmm::launch_popcount_gemm(g, G, 0, s));
 }
 
+// The 2-D view (rows x K) under which a flat tensor of `count` elements is packed: K the largest
+// power of two <= 4096 that divides count.  With K a multiple of 128 the packed rows carry no
+// padding, so the words and scales of the view are those of the flat tensor.
+static int64_t tensor_view_k(int64_t count)
+{
+    int64_t k = 4096;
+    while (k > 1 && count % k != 0) k >>= 1;
+    return k;
+}
+
+int hbmm_quantize_pack_tensor(const float *x, int64_t count, int32_t beta, uint32_t *bits, float *scales,
+                              void *stream)
+{
+    if (count < 0 || count > ((int64_t)1 << 31) - 1) return HBMM_EINVAL;
+    if (beta < 1) return HBMM_EINVAL;
+    if (!supported_pack_beta(beta)) return HBMM_EUNSUPPORTED;
+    const int64_t K = tensor_view_k(count);
+    if (count == 0) return HBMM_OK;
+    if (K < 128 || K % beta != 0) return HBMM_EUNSUPPORTED;
+    return hbmm_quantize_pack(x, count / K, K, K, 0, beta, bits, K / 32, scales, K / beta, stream);
+}
+
+int hbmm_conv2d(const uint32_t *a_bits, const float *a_scales, int32_t beta_a, const uint32_t *w_bits,
+                const float *w_scales, int64_t ldw_w, int64_t lds_w, int32_t beta_w, int64_t B, int64_t C,
+                int64_t H, int64_t W, int64_t N, int32_t KH, int32_t KW, int32_t stride, int32_t pad,
+                float *out, void *stream)
+{
+    if (B < 0 || C < 0 || H < 0 || W < 0 || N < 0 || KH < 1 || KW < 1 || stride < 1 || pad < 0) return HBMM_EINVAL;
+    if (B > kMaxDim || C > kMaxDim || H > kMaxDim || W > kMaxDim || N > kMaxDim) return HBMM_EINVAL;
+    if (KH > 32 || KW > 32 || pad > 32 || stride > 32) return HBMM_EINVAL;
+    if (beta_a < 1 || beta_w < 1) return HBMM_EINVAL;
+    if (!supported_pack_beta(beta_a) || !supported_pack_beta(beta_w) || beta_w < 16) return HBMM_EUNSUPPORTED;
+    if (H + 2 * pad < KH || W + 2 * pad < KW) return HBMM_EINVAL;
+    const int64_t OH = (H + 2 * pad - KH) / stride + 1, OW = (W + 2 * pad - KW) / stride + 1;
+    const int64_t K = C * KH * KW;
+    if ((double)B * (double)C * (double)H * (double)W > 2147483647.0) return HBMM_EUNSUPPORTED;
+    if ((double)B * (double)OH * (double)OW > 2147483647.0) return HBMM_EUNSUPPORTED;
+    if (B == 0 || N == 0) return HBMM_OK;
+    if (C == 0 || H == 0 || W == 0) return HBMM_EINVAL;
+    if (W % beta_a != 0 || K % beta_w != 0 || K % 32 != 0 || KH * KW > 32) return HBMM_EUNSUPPORTED;
+    if (!out || !aligned16(out)) return HBMM_EINVAL;
+    if (!a_bits || !aligned16(a_bits) || !a_scales || !aligned16(a_scales)) return HBMM_EINVAL;
+    if (!w_scales || !aligned16(w_scales) || lds_w < K / beta_w) return HBMM_EINVAL;
+    if (int rc = check_packed(w_bits, N, K, ldw_w)) return rc;
+    hbmm::ConvActivations x{a_bits, a_scales, beta_a};
+    hbmm::SplitGemmOperand y{};
+    y.bits = w_bits; y.scales = w_scales; y.ldw = ldw_w; y.lds = lds_w; y.rows = N; y.beta = beta_w;
+    hbmm::ConvGeometry g{B, C, H, W, KH, KW, stride, pad};
+    return from_hip(hbmm::launch_mfma_split_conv(x, y, g, out, static_cast<hipStream_t>(stream)));
+}
+
 int hbmm_gemm_int(const uint32_t *a_bits, int64_t ldw_a, const uint32_t *b_bits, int64_t ldw_b,
                   int64_t M, int64_t N, int64_t K, int32_t *D, int64_t ldd, void *stream)
 {

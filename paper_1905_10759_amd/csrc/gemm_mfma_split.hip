@@ -52,6 +52,7 @@ constexpr int kXRaw = 0;      // fp32 operand itself (beta_x = 1)
 constexpr int kXScale1 = 1;   // packed, beta_x >= 8: one scale covers a thread's 8 elements
 constexpr int kXScale2 = 2;   // packed, beta_x = 4: two scales per 8 elements
 constexpr int kXScale4 = 3;   // packed, beta_x = 2: four scales per 8 elements
+constexpr int kXConv = 4;     // packed activation tensor read through a convolution window (see below)
 
 // Sign masks for `n` (<= 8) pairs of elements: complemented bit 2i of `inv` -> bit 15 of dword i,
 // complemented bit 2i+1 -> bit 31 (the sign positions of a pair of bf16 values).
@@ -113,6 +114,14 @@ struct SplitArgs {
     int32_t log2_beta_x;         // packed modes
     int32_t stages_per_yseg;     // beta_y / 32 (beta_y >= 32); unused when beta_y = 16
     int32_t tiles_y, tiles_total, slots_per_xcd;
+    // kXConv: X row m = (b * OH + oz) * OW + oy is an output position, k = (c * KH + dz) * KW + dy a
+    // filter tap; X~[m, k] is the binarised activation at (b, c, oz*stride - pad + dz,
+    // oy*stride - pad + dy), or 0 outside the input.  x_bits / x_scales hold the whole tensor packed
+    // flat (element e: bit e mod 32 of word e div 32, scale e div beta_a; beta_a divides W, so a
+    // segment never leaves its row).  The output is B x Y x OH x OW.
+    int32_t cv_c, cv_h, cv_w, cv_hw, cv_ow, cv_ohw, cv_kw, cv_kk, cv_stride, cv_pad;
+    int32_t cv_magic_kk, cv_magic_kw;   // 65536 / d + 1: (t * magic) >> 16 == t / d for t < 64, d <= 32
+    int32_t cv_q32, cv_r32;             // 32 div KK, 32 mod KK: how (c, tap) moves from stage to stage
 };
 
 template <int XMODE, bool Y16>
@@ -136,6 +145,8 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
         uint32_t xb;                                       // packed: the row's word of this stage
         float xs[kScalesPerThread];                        // packed: scales of this thread's 8 elements
         uint32_t yb;                                       // the Y row's word of this stage
+        uint32_t cw[XMODE == kXConv ? 8 : 1];              // conv: the word holding each element's bit
+        float cs[XMODE == kXConv ? 8 : 1];                 // conv: each element's scale
     };
 
     // ---- sources (clamped, so every load below is unconditional)
@@ -149,11 +160,49 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
             const int id = tid + r * kThreadsS;
             xr_src[r] = a.x_raw + (int64_t)min(x0 + (id >> 3), a.X - 1) * a.ldx_raw + (id & 7) * 4;
         }
-    } else {
+    } else if (XMODE != kXConv) {
         const int64_t row = min(x0 + prow, a.X - 1);
         xb_src = a.x_bits + row * a.ldw_x;
         xs_src = a.x_scales + row * a.lds_x;
     }
+    // conv: this thread's output position, the flat index of the window's corner, and which taps
+    // fall inside the input.  (c, tap) of the thread's first element is tracked from call to call,
+    // once for the loads and once for the parking; both are called for consecutive stages.
+    int cv_base = 0;
+    uint32_t cv_mask = 0;
+    int fc0 = 0, fr0 = 0, pc0 = 0, pr0 = 0;
+    if (XMODE == kXConv) {
+        const int m = min(x0 + prow, a.X - 1);
+        const int b = m / a.cv_ohw, pos = m - b * a.cv_ohw;
+        const int oz = pos / a.cv_ow, oy = pos - oz * a.cv_ow;
+        const int z0 = oz * a.cv_stride - a.cv_pad, y0w = oy * a.cv_stride - a.cv_pad;
+        cv_base = (b * a.cv_c * a.cv_h + z0) * a.cv_w + y0w;
+        for (int r = 0; r < a.cv_kk; ++r) {
+            const int dz = r / a.cv_kw, dy = r - dz * a.cv_kw;
+            const bool in = z0 + dz >= 0 && z0 + dz < a.cv_h && y0w + dy >= 0 && y0w + dy < a.cv_w;
+            cv_mask |= (in ? 1u : 0u) << r;
+        }
+        fc0 = pc0 = (poct * 8) / a.cv_kk;
+        fr0 = pr0 = (poct * 8) % a.cv_kk;
+    }
+    // element i (0..7) of the thread's run: flat tensor index and whether it exists
+    auto conv_elem = [&](int c0, int r0, int i, int &e, bool &ok) {
+        const int t = r0 + i;
+        const int cq = (t * a.cv_magic_kk) >> 16;
+        const int r = t - cq * a.cv_kk;
+        const int c = c0 + cq;
+        const int dz = (r * a.cv_magic_kw) >> 16;
+        e = cv_base + c * a.cv_hw + r + dz * (a.cv_w - a.cv_kw);
+        ok = ((cv_mask >> r) & 1u) != 0 && c < a.cv_c;
+    };
+    auto conv_advance = [&](int &c0, int &r0) {
+        c0 += a.cv_q32;
+        r0 += a.cv_r32;
+        if (r0 >= a.cv_kk) {
+            r0 -= a.cv_kk;
+            c0 += 1;
+        }
+    };
     const int yrow_t = tid >> 1, yhalf = tid & 1;          // Y expansion: row and 16-element half
     const uint32_t *yb_src = a.y_bits + (int64_t)min(y0 + yrow_t, a.Y - 1) * a.ldw_y;
 
@@ -162,6 +211,18 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
         if (XMODE == kXRaw) {
 #pragma unroll
             for (int r = 0; r < 2; ++r) st.xr[r] = *reinterpret_cast<const float4 *>(xr_src[r] + sg * kStageK);
+        } else if (XMODE == kXConv) {
+            // past the last stage c >= C: every element reads index 0 and is parked as zero
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                int e;
+                bool ok;
+                conv_elem(fc0, fr0, i, e, ok);
+                e = ok ? e : 0;
+                st.cw[i] = a.x_bits[e >> 5];
+                st.cs[i] = a.x_scales[e >> a.log2_beta_x];
+            }
+            conv_advance(fc0, fr0);
         } else {
             st.xb = xb_src[sg];
             const int sidx = (sg * kStageK + poct * 8) >> a.log2_beta_x;
@@ -187,6 +248,31 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
                 *reinterpret_cast<uint2 *>(dst + kPieceBytes) = make_uint2(pair16(m[0], m[1]), pair16(m[2], m[3]));
                 *reinterpret_cast<uint2 *>(dst + 2 * kPieceBytes) = make_uint2(pair16(l[0], l[1]), pair16(l[2], l[3]));
             }
+        } else if (XMODE == kXConv) {
+            uint32_t h[8], m[8], l[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                int e;
+                bool ok;
+                conv_elem(pc0, pr0, i, e, ok);
+                const uint32_t minus = (~(st.cw[i] >> (e & 31)) & 1u) << 31;   // bit 0 = negative
+                split3(ok ? st.cs[i] : 0.f, h[i], m[i], l[i]);
+                h[i] ^= minus;
+                m[i] ^= minus;
+                l[i] ^= minus;
+            }
+            conv_advance(pc0, pr0);
+            u32x4 dh, dm, dl;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                dh[i] = pair16(h[2 * i], h[2 * i + 1]);
+                dm[i] = pair16(m[2 * i], m[2 * i + 1]);
+                dl[i] = pair16(l[2 * i], l[2 * i + 1]);
+            }
+            unsigned char *dst = &sX[buf][prow * kRowBytes + poct * 16];
+            *reinterpret_cast<u32x4 *>(dst) = dh;
+            *reinterpret_cast<u32x4 *>(dst + kPieceBytes) = dm;
+            *reinterpret_cast<u32x4 *>(dst + 2 * kPieceBytes) = dl;
         } else {
             u32x4 dh, dm, dl;
             packed_pieces<kScalesPerThread>(st.xb >> (8 * poct), st.xs, dh, dm, dl);
@@ -303,6 +389,40 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
         if (stage + 2 < nstages) run_stage(stage + 2, s2, s1);
     }
 
+    if (XMODE == kXConv) {
+        // Output is B x Y x OH x OW: positions are contiguous, filters are OH*OW apart.  The
+        // accumulator tiles hold filters across lanes, so each 32 x 32 tile is turned through LDS
+        // (row stride 33 words) and written with positions across lanes.
+        __syncthreads();   // every wave has finished reading the operand tiles
+        float *turn = reinterpret_cast<float *>(&sX[0][0]) + wave * (32 * 33);
+#pragma unroll
+        for (int tx = 0; tx < 2; ++tx) {
+            const int m = x0 + wx * 64 + tx * 32 + (lane & 31);
+            const int mc = min(m, a.X - 1);
+            const int b = mc / a.cv_ohw, pos = mc - b * a.cv_ohw;
+            float *dst = a.out + (int64_t)b * a.Y * a.cv_ohw + pos;
+#pragma unroll
+            for (int ty = 0; ty < 2; ++ty) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    turn[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * 33 + (lane & 31)] = res[tx][ty][v];
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const int cl = 2 * j + (lane >> 5);
+                    const int col = y0 + wy * 64 + ty * 32 + cl;
+                    const float val = turn[(lane & 31) * 33 + cl];
+                    if (m < a.X && col < a.Y) dst[(int64_t)col * a.cv_ohw] = val;
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int tx = 0; tx < 2; ++tx)
 #pragma unroll
@@ -519,6 +639,32 @@ hipError_t launch_mfma_split_gemm(const SplitGemmOperand &x, const SplitGemmOper
     if (x.beta == 2) return launch_mode<kXScale4>(a, y16, grid, s);
     if (x.beta == 4) return launch_mode<kXScale2>(a, y16, grid, s);
     return launch_mode<kXScale1>(a, y16, grid, s);
+}
+
+hipError_t launch_mfma_split_conv(const ConvActivations &x, const SplitGemmOperand &y, const ConvGeometry &g, float *out,
+                                  hipStream_t s)
+{
+    const int64_t OH = (g.H + 2 * g.pad - g.KH) / g.stride + 1, OW = (g.W + 2 * g.pad - g.KW) / g.stride + 1;
+    const int64_t K = g.C * g.KH * g.KW, M = g.B * OH * OW;
+    if (y.beta < 16 || y.bits == nullptr || K % kStageK != 0 || g.KH * g.KW > 32) return hipErrorNotSupported;
+    if (g.B * g.C * g.H * g.W > 0x7fffffffLL || M > 0x7fffffffLL) return hipErrorNotSupported;
+    SplitArgs a{};
+    a.x_bits = x.bits; a.x_scales = x.scales; a.log2_beta_x = ilog2s(x.beta);
+    a.y_bits = y.bits; a.y_scales = y.scales; a.ldw_y = (int32_t)y.ldw; a.lds_y = (int32_t)y.lds;
+    a.out = out;
+    a.X = (int32_t)M; a.Y = (int32_t)y.rows; a.K = (int32_t)K;
+    a.stages_per_yseg = y.beta >= 32 ? y.beta / kStageK : 1;
+    a.cv_c = (int32_t)g.C; a.cv_h = (int32_t)g.H; a.cv_w = (int32_t)g.W; a.cv_hw = (int32_t)(g.H * g.W);
+    a.cv_ow = (int32_t)OW; a.cv_ohw = (int32_t)(OH * OW);
+    a.cv_kw = g.KW; a.cv_kk = g.KH * g.KW; a.cv_stride = g.stride; a.cv_pad = g.pad;
+    a.cv_magic_kk = 65536 / a.cv_kk + 1; a.cv_magic_kw = 65536 / a.cv_kw + 1;
+    a.cv_q32 = kStageK / a.cv_kk; a.cv_r32 = kStageK % a.cv_kk;
+    const int64_t tiles_x = (M + kBX - 1) / kBX, tiles_y = (y.rows + kBY - 1) / kBY;
+    const int64_t total = tiles_x * tiles_y;
+    const int64_t per_xcd = (total + kNumXcdS - 1) / kNumXcdS;
+    if (per_xcd * kNumXcdS > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    a.tiles_y = (int32_t)tiles_y; a.tiles_total = (int32_t)total; a.slots_per_xcd = (int32_t)per_xcd;
+    return launch_mode<kXConv>(a, y.beta == 16, (unsigned)(per_xcd * kNumXcdS), s);
 }
 
 }  // namespace hbmm

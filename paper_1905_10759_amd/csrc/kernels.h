@@ -74,6 +74,21 @@ hipError_t launch_mfma_split_gemm(const SplitGemmOperand &x, const SplitGemmOper
 // where both segments are shorter than 16.
 hipError_t launch_mfma_split2_gemm(const SplitGemmOperand &x, const SplitGemmOperand &y, int64_t K, float *out,
                                    int64_t ld_out_x, int64_t ld_out_y, hipStream_t s);
+// Convolution layer on the same kernel: the dense side is an activation tensor B x C x H x W packed
+// flat with segments of `beta` along W (beta divides W), read through the KH x KW window of each
+// output position; the sign side holds the filters packed as rows of C*KH*KW (beta >= 16).
+// out is B x y.rows x OH x OW.  C*KH*KW must be a multiple of 32, KH*KW <= 32.
+struct ConvActivations {
+    const uint32_t *bits;
+    const float *scales;
+    int beta;
+};
+struct ConvGeometry {
+    int64_t B, C, H, W;
+    int KH, KW, stride, pad;
+};
+hipError_t launch_mfma_split_conv(const ConvActivations &x, const SplitGemmOperand &y, const ConvGeometry &g, float *out,
+                                  hipStream_t s);
 
 // ---- gemm_mfma_i8.hip -------------------------------------------------------------------------
 hipError_t launch_mfma_i8_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a,

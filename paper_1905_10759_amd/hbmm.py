@@ -21,6 +21,7 @@ ALGO_POPCOUNT, ALGO_MFMA_I8 = 0, 1
 EXPORTS = (
     "hbmm_strerror", "hbmm_num_blocks", "hbmm_packed_ld_words", "hbmm_quantize_pack", "hbmm_gemm",
     "hbmm_gemm_int", "hbmm_dense_ref_gemm", "hbmm_binarize_backward", "hbmm_gemm_fused",
+    "hbmm_quantize_pack_tensor", "hbmm_conv2d",
 )
 
 
@@ -51,6 +52,10 @@ def _load() -> C.CDLL:
     lib.hbmm_gemm_int.argtypes = [p, i64, p, i64, i64, i64, i64, p, i64, p]
     lib.hbmm_gemm_fused.restype = C.c_int
     lib.hbmm_gemm_fused.argtypes = [p, i64, i32, p, p, i64, i64, i32, i64, i64, i64, p, i64, p]
+    lib.hbmm_quantize_pack_tensor.restype = C.c_int
+    lib.hbmm_quantize_pack_tensor.argtypes = [p, i64, i32, p, p, p]
+    lib.hbmm_conv2d.restype = C.c_int
+    lib.hbmm_conv2d.argtypes = [p, p, i32, p, p, i64, i64, i32, i64, i64, i64, i64, i64, i32, i32, i32, i32, p, p]
     lib.hbmm_binarize_backward.restype = C.c_int
     lib.hbmm_binarize_backward.argtypes = [p, p, i64, i64, i64, i64, i32, p, i64, p]
     lib.hbmm_dense_ref_gemm.restype = C.c_int
@@ -199,4 +204,39 @@ def gemm_fused(A: torch.Tensor, beta_a: int, b_bits, b_scales, beta_w: int, out:
                              b_scales.stride(0) if N > 1 else max(b_scales.shape[1], 1), beta_w, M, N, K,
                              out.data_ptr(), out.stride(0) if M > 1 else max(N, 1), _stream())
     _check(rc, "hbmm_gemm_fused")
+    return out
+
+
+def quantize_pack_tensor(x: torch.Tensor, beta: int):
+    """hbmm_quantize_pack_tensor: a contiguous fp32 tensor -> (bits int32[count / 32], scales fp32[count / beta])."""
+    _dev(x, torch.float32, "x")
+    if not x.is_contiguous():
+        raise ValueError("x must be contiguous")
+    count = x.numel()
+    bits = torch.empty((count // 32,), dtype=torch.int32, device=x.device)
+    scales = torch.empty((count // max(beta, 1),), dtype=torch.float32, device=x.device)
+    rc = lib.hbmm_quantize_pack_tensor(x.data_ptr(), count, beta, bits.data_ptr(), scales.data_ptr(), _stream())
+    _check(rc, "hbmm_quantize_pack_tensor")
+    return bits, scales
+
+
+def conv2d(a_bits, a_scales, beta_a: int, shape, w_bits, w_scales, beta_w: int, kernel, stride: int = 1,
+           pad: int = 0, out: torch.Tensor | None = None) -> torch.Tensor:
+    """hbmm_conv2d: activations (B, C, H, W) = `shape` packed by quantize_pack_tensor, filters
+    (N, C, KH, KW) packed by quantize_pack on the N x (C*KH*KW) matrix; `kernel` = (KH, KW)."""
+    _dev(a_bits, torch.int32, "a_bits")
+    _dev(a_scales, torch.float32, "a_scales")
+    _dev(w_bits, torch.int32, "w_bits")
+    _dev(w_scales, torch.float32, "w_scales")
+    B, Cc, H, W = (int(v) for v in shape)
+    KH, KW = (int(v) for v in kernel)
+    N = w_bits.shape[0]
+    OH, OW = (H + 2 * pad - KH) // stride + 1, (W + 2 * pad - KW) // stride + 1
+    if out is None:
+        out = torch.empty((B, N, OH, OW), dtype=torch.float32, device=a_bits.device)
+    rc = lib.hbmm_conv2d(a_bits.data_ptr(), a_scales.data_ptr(), beta_a, w_bits.data_ptr(), w_scales.data_ptr(),
+                         w_bits.stride(0) if N > 1 else w_bits.shape[1],
+                         w_scales.stride(0) if N > 1 else max(w_scales.shape[1], 1), beta_w, B, Cc, H, W, N, KH, KW,
+                         stride, pad, out.data_ptr(), _stream())
+    _check(rc, "hbmm_conv2d")
     return out

@@ -397,3 +397,84 @@ def test_gemm_fused_limits():
     with pytest.raises(hbmm.HbmmError) as ei:
         hbmm.gemm_fused(A, 32, bb, bs, 32)      # N > 128
     assert ei.value.code == hbmm.EUNSUPPORTED
+
+
+# ------------------------------------------------------------------------------------- convolution
+def _conv_inputs(seed, B, C, H, W, N, KH, KW):
+    A = synth.relu_normal(seed, (B, C, H, W))
+    Wf = synth.normal(seed + 1, (N, C, KH, KW)) * np.float32(np.sqrt(2.0 / (C * KH * KW)))
+    return A, Wf.astype(np.float32)
+
+
+@pytest.mark.parametrize("beta", [2, 4, 8, 32, 256])
+@pytest.mark.parametrize("shape", [(1, 4, 8, 8), (2, 3, 16, 32), (1, 1, 4, 1024)])
+def test_quantize_pack_tensor(beta, shape):
+    """Flat tensor packing: bit e of the tensor is bit (e mod 32) of word (e div 32); segment j covers
+    elements [j beta, (j + 1) beta) -- for W a multiple of beta these are Eq. 3's width segments."""
+    if shape[-1] % beta:
+        pytest.skip("beta must divide the width")
+    x = synth.normal(7 + beta, shape)
+    x.reshape(-1)[:3] = [0.0, -0.0, -1e-30]
+    bits, scales = hbmm.quantize_pack_tensor(dev(x), beta)
+    flat = x.reshape(1, -1)
+    np.testing.assert_array_equal(words(bits), oracle.sign_pack(flat, ldw=flat.shape[1] // 32).reshape(-1))
+    ref = oracle.block_scales(x.reshape(-1, shape[-1]), beta).reshape(-1)
+    np.testing.assert_allclose(scales.cpu().numpy(), ref, rtol=scale_tol(beta), atol=0)
+
+
+CONV_CASES = [
+    # B, C, H, W, N, KH, KW, stride, pad, beta_a, beta_w
+    (2, 32, 8, 8, 40, 3, 3, 1, 1, 4, 32),       # one position tile, ragged filters
+    (3, 32, 6, 8, 72, 3, 3, 1, 1, 2, 16),       # ragged positions (144), beta_w = 16
+    (2, 32, 9, 16, 24, 3, 3, 2, 1, 8, 32),      # stride 2, odd height
+    (1, 64, 12, 12, 300, 1, 1, 1, 0, 4, 64),    # 1x1 kernel, two filter tiles
+    (2, 64, 10, 12, 16, 1, 1, 2, 0, 2, 32),     # 1x1, stride 2
+    (1, 32, 10, 16, 33, 5, 3, 1, 2, 16, 32),    # tall window, padding larger than the kernel's half width
+    (2, 32, 7, 8, 8, 2, 2, 2, 0, 8, 128),       # even window without padding
+    (1, 128, 14, 16, 130, 3, 3, 1, 1, 4, 128),  # K = 1152, 9 segments of 128
+    (5, 32, 12, 12, 20, 3, 3, 1, 1, 4, 32),     # several tiles of positions that cross images
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES, ids=lambda c: "x".join(str(v) for v in c))
+def test_conv2d(case):
+    B, C, H, W, N, KH, KW, stride, pad, beta_a, beta_w = case
+    A, Wf = _conv_inputs(31 + B + C + N, B, C, H, W, N, KH, KW)
+    A[0, 0, 0, :2] = [0.0, -0.0]
+    ref, T = oracle.hbmm_conv2d(A, Wf, beta_a, beta_w, stride, pad, want_T=True)
+    ab, asc = hbmm.quantize_pack_tensor(dev(A), beta_a)
+    wb, ws = hbmm.quantize_pack(dev(Wf.reshape(N, -1)), beta_w)
+    out = hbmm.conv2d(ab, asc, beta_a, A.shape, wb, ws, beta_w, (KH, KW), stride, pad)
+    assert tuple(out.shape) == ref.shape
+    assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d {case}")
+
+
+def test_conv2d_equals_gemm_on_im2col():
+    """For a 1x1 window with stride 1 the convolution is the matrix product of the positions x channels
+    matrix of materialised activations with the filters: the same kernel family must agree with
+    hbmm_gemm's unquantised-activation path on that matrix (each within 1e-5 T of the exact value), a check that does not go
+    through the oracle's convolution loops."""
+    B, C, H, W, N, beta_a, beta_w = 2, 64, 8, 8, 48, 4, 32
+    A, Wf = _conv_inputs(77, B, C, H, W, N, 1, 1)
+    ab, asc = hbmm.quantize_pack_tensor(dev(A), beta_a)
+    wb, ws = hbmm.quantize_pack(dev(Wf.reshape(N, -1)), beta_w)
+    out = hbmm.conv2d(ab, asc, beta_a, A.shape, wb, ws, beta_w, (1, 1), 1, 0)
+    At = oracle.materialize_activations(A, beta_a).astype(np.float32)          # exact: +-fp32 scale
+    X = np.ascontiguousarray(At.transpose(0, 2, 3, 1).reshape(B * H * W, C))
+    via_gemm = hbmm.gemm(None, dev(X), 1, wb, ws, beta_w, C)
+    got = out.permute(0, 2, 3, 1).reshape(B * H * W, N).cpu().numpy().astype(np.float64)
+    T = np.abs(X.astype(np.float64)) @ np.abs(oracle.materialize_filters(Wf, beta_w).reshape(N, C)).T
+    assert np.all(np.abs(got - via_gemm.cpu().numpy()) <= 2e-5 * T)
+
+
+def test_conv2d_unsupported():
+    A, Wf = _conv_inputs(5, 1, 32, 8, 8, 8, 3, 3)
+    ab, asc = hbmm.quantize_pack_tensor(dev(A), 4)
+    wb, ws = hbmm.quantize_pack(dev(Wf.reshape(8, -1)), 32)
+    with pytest.raises(hbmm.HbmmError):
+        hbmm.conv2d(ab, asc, 16, A.shape, wb, ws, 32, (3, 3), 1, 1)     # beta_a does not divide W
+    wb8, ws8 = hbmm.quantize_pack(dev(Wf.reshape(8, -1)), 8)
+    with pytest.raises(hbmm.HbmmError):
+        hbmm.conv2d(ab, asc, 4, A.shape, wb8, ws8, 8, (3, 3), 1, 1)     # beta_w < 16
+    with pytest.raises(hbmm.HbmmError):
+        hbmm.quantize_pack_tensor(dev(synth.normal(1, (3, 5, 8))), 4)   # 120 elements: not a multiple of 128
