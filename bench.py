@@ -361,6 +361,46 @@ def extras(w, A, B, a_bits, a_s, b_bits, b_s, C, torch, hbmm, synth, args):
         others[name] = entry
         del dA, dB
     res["other_workloads"] = others
+
+    # convolution layers computed directly from the packed tensors (no im2col matrix), and the fused
+    # quantise+pack+product on the im2col shape of the first of them
+    convs = {}
+    for name, cw in synth.CONV_WORKLOADS.items():
+        try:
+            dA = torch.from_numpy(cw.make_a()).cuda()
+            dW = torch.from_numpy(cw.make_w().reshape(cw.N, -1)).cuda()
+            wb, ws = hbmm.quantize_pack(dW, cw.beta_w)
+            ab, asc = hbmm.quantize_pack_tensor(dA, cw.beta_a)
+            out = hbmm.conv2d(ab, asc, cw.beta_a, dA.shape, wb, ws, cw.beta_w, (cw.KH, cw.KW), cw.stride, cw.pad)
+            tq = time_loop(lambda: hbmm.quantize_pack_tensor(dA, cw.beta_a), 10, 2, torch)
+            tc = time_loop(lambda: hbmm.conv2d(ab, asc, cw.beta_a, dA.shape, wb, ws, cw.beta_w, (cw.KH, cw.KW),
+                                               cw.stride, cw.pad, out), 10, 2, torch)
+            convs[name] = {"quantize_ms": min(tq), "conv_ms": min(tc),
+                           "conv_effective_gflops": 2.0 * cw.macs / (min(tc) * 1e-3) / 1e9,
+                           "beta_a": cw.beta_a, "beta_w": cw.beta_w}
+            del dA, dW, out
+        except Exception as e:
+            convs[name] = {"error": str(e)}
+    res["conv2d"] = convs
+    try:
+        M, K, N, beta = 3136 * 64, 576, 64, 64
+        dA = torch.from_numpy(synth.relu_normal(8001, (M, K))).cuda()
+        dB = torch.from_numpy(synth.normal(8002, (N, K))).cuda()
+        bb, bs = hbmm.quantize_pack(dB, beta)
+        ab, as_ = hbmm.quantize_pack(dA, beta)
+        Cw = torch.empty((M, N), dtype=torch.float32, device="cuda")
+
+        def two_step():
+            hbmm.quantize_pack(dA, beta, 0, ab, as_)
+            hbmm.gemm(ab, as_, beta, bb, bs, beta, K, hbmm.ALGO_POPCOUNT, Cw)
+
+        t2 = time_loop(two_step, 10, 2, torch)
+        tf = time_loop(lambda: hbmm.gemm_fused(dA, beta, bb, bs, beta, Cw), 10, 2, torch)
+        res["fused_im2col_conv2x_b64"] = {"M": M, "K": K, "N": N, "beta": beta, "pack_then_gemm_ms": min(t2),
+                                          "fused_ms": min(tf), "fused_GBs_of_A": 4.0 * M * K / (min(tf) * 1e-3) / 1e9}
+        del dA, dB, Cw
+    except Exception as e:
+        res["fused_im2col_conv2x_b64"] = {"error": str(e)}
     return res
 
 

@@ -153,3 +153,49 @@ WORKLOADS = {
         Workload("sq4k16", 4096, 4096, 4096, 16, 16, "normal", "normal", 0, 6001, 6002),
     )
 }
+
+
+@dataclass(frozen=True)
+class ConvWorkload:
+    """A convolution layer: activations batch x C x H x W (ReLU'd normal), filters N x C x KH x KW
+    (He-normal), activation segments of beta_a along W, filter segments of beta_w over C*KH*KW."""
+    name: str
+    batch: int
+    C: int
+    H: int
+    W: int
+    N: int
+    KH: int
+    KW: int
+    stride: int
+    pad: int
+    beta_a: int
+    beta_w: int
+    seed_a: int
+    seed_w: int
+
+    def make_a(self) -> np.ndarray:
+        return relu_normal(self.seed_a, (self.batch, self.C, self.H, self.W))
+
+    def make_w(self) -> np.ndarray:
+        K = self.C * self.KH * self.KW
+        return normal(self.seed_w, (self.N, self.C, self.KH, self.KW), std=float(np.sqrt(2.0 / K)))
+
+    @property
+    def macs(self) -> int:
+        oh = (self.H + 2 * self.pad - self.KH) // self.stride + 1
+        ow = (self.W + 2 * self.pad - self.KW) // self.stride + 1
+        return self.batch * oh * ow * self.N * self.C * self.KH * self.KW
+
+
+# ResNet-18 3x3 layers with the paper's convolution semantics; beta_a must divide the width.
+CONV_WORKLOADS = {
+    w.name: w
+    for w in (
+        ConvWorkload("conv2x_b1", 1, 64, 56, 56, 64, 3, 3, 1, 1, 8, 64, 7001, 7002),
+        ConvWorkload("conv2x_b64", 64, 64, 56, 56, 64, 3, 3, 1, 1, 8, 64, 7001, 7002),
+        ConvWorkload("conv3x_b64", 64, 128, 28, 28, 128, 3, 3, 1, 1, 4, 128, 7101, 7102),
+        ConvWorkload("conv4x_b64", 64, 256, 14, 14, 256, 3, 3, 1, 1, 2, 128, 7201, 7202),
+        ConvWorkload("conv3x_down_b64", 64, 64, 56, 56, 128, 3, 3, 2, 1, 8, 64, 7301, 7302),
+    )
+}

@@ -100,3 +100,21 @@ def test_workload_binary_weight_full_size(hbmm):
     rows = np.unique(np.linspace(0, w.M - 1, 16).astype(np.int64))
     dense = oracle.dense_f64_gemm(oracle.materialize(A[rows], 1), oracle.materialize(B, w.beta_w, sb))
     assert_close_to_oracle(got[rows], dense, T[rows], "c5xw (dense f64, sampled rows)")
+
+
+@pytest.mark.parametrize("name,batch", [("conv2x_b1", 1), ("conv3x_b64", 4), ("conv4x_b64", 8), ("conv3x_down_b64", 2)])
+def test_conv_workload(hbmm, name, batch):
+    """ResNet-18 convolution layers at their real geometry (batch cut to what the oracle's loops
+    finish in seconds): every output against the oracle's plain convolution."""
+    import dataclasses
+    w = dataclasses.replace(synth.CONV_WORKLOADS[name], batch=batch)
+    A, Wf = w.make_a(), w.make_w()
+    ab, asc = hbmm.quantize_pack_tensor(dev(A), w.beta_a)
+    wb, ws = hbmm.quantize_pack(dev(Wf.reshape(w.N, -1)), w.beta_w)
+    got = hbmm.conv2d(ab, asc, w.beta_a, A.shape, wb, ws, w.beta_w, (w.KH, w.KW), w.stride, w.pad).cpu().numpy()
+    print(f"[{name}] gpu done", flush=True)
+    # the oracle computes its own scales from the same inputs; the GPU's differ by their fp32
+    # summation order, (log2 beta + 1) * 2^-24 relative at most, far inside the bound
+    ref, T = oracle.hbmm_conv2d(A, Wf, w.beta_a, w.beta_w, w.stride, w.pad, want_T=True)
+    worst = assert_close_to_oracle(got, ref, T, name)
+    print(f"[{name}] ok, worst err/(1e-5 T) = {worst:.3f}", flush=True)
