@@ -124,7 +124,8 @@ struct SplitArgs {
     int32_t cv_q32, cv_r32;             // 32 div KK, 32 mod KK: how (c, tap) moves from stage to stage
 };
 
-template <int XMODE, bool Y16>
+// NARROW: Y has at most 192 rows (one tile, at least one dead 64-column strip), see below.
+template <int XMODE, bool Y16, bool NARROW>
 __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitArgs a)
 {
     __shared__ __attribute__((aligned(16))) unsigned char sX[2][3 * kPieceBytes];
@@ -135,8 +136,13 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
     if (slot >= a.tiles_total) return;
     const int x0 = (slot / a.tiles_y) * kBX, y0 = (slot % a.tiles_y) * kBY;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wx = wave >> 2, wy = wave & 3;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // Wave -> 64 x 64 sub-tile.  In the NARROW variant the waves of the dead 64-column strips skip
+    // the multiplications (they still stage operands), and waves 2j and 2j+1 share strip j: consecutive
+    // wave ids sit on different SIMDs, so the live strips' waves are spread over them.  The variant
+    // is a separate instantiation because the branch around the multiplications costs full tiles ~10 %.
+    const int wx = NARROW ? wave & 1 : wave >> 2, wy = NARROW ? wave >> 1 : wave & 3;
+    const bool strip_live = !NARROW || y0 + wy * 64 < a.Y;
     const int nstages = a.K / kStageK;
 
     constexpr int kScalesPerThread = XMODE == kXScale4 ? 4 : XMODE == kXScale2 ? 2 : 1;
@@ -153,7 +159,12 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
     const float *xr_src[2] = {nullptr, nullptr};
     const uint32_t *xb_src = nullptr;
     const float *xs_src = nullptr;
-    const int prow = tid >> 2, poct = tid & 3;             // packed modes: row and 8-element group
+    // packed modes: row and 8-element group of this thread.  In the conv mode the group is the same
+    // for a whole wave (and lanes run along output positions), so that everything that depends on
+    // k only -- channel, tap, offsets -- is computed once per wave on the scalar unit and the lanes'
+    // loads fall on neighbouring activations.
+    const int prow = XMODE == kXConv ? (tid & 127) : (tid >> 2);
+    const int poct = XMODE == kXConv ? __builtin_amdgcn_readfirstlane(tid >> 7) : (tid & 3);
     if (XMODE == kXRaw) {
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
@@ -185,15 +196,17 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
         fc0 = pc0 = (poct * 8) / a.cv_kk;
         fr0 = pr0 = (poct * 8) % a.cv_kk;
     }
-    // element i (0..7) of the thread's run: flat tensor index and whether it exists
-    auto conv_elem = [&](int c0, int r0, int i, int &e, bool &ok) {
+    // element i (0..7) of the thread's run: its flat tensor index, forced to 0 when the tap lies
+    // outside the input or past the last channel, and `keep` = all ones / zero accordingly
+    auto conv_elem = [&](int c0, int r0, int i, uint32_t &e, uint32_t &keep) {
         const int t = r0 + i;
         const int cq = (t * a.cv_magic_kk) >> 16;
         const int r = t - cq * a.cv_kk;
         const int c = c0 + cq;
         const int dz = (r * a.cv_magic_kw) >> 16;
-        e = cv_base + c * a.cv_hw + r + dz * (a.cv_w - a.cv_kw);
-        ok = ((cv_mask >> r) & 1u) != 0 && c < a.cv_c;
+        const uint32_t taps = c < a.cv_c ? cv_mask : 0u;
+        keep = (uint32_t)__builtin_amdgcn_sbfe((int)taps, (uint32_t)r, 1u);
+        e = (uint32_t)(cv_base + (c * a.cv_hw + r + dz * (a.cv_w - a.cv_kw))) & keep;
     };
     auto conv_advance = [&](int &c0, int &r0) {
         c0 += a.cv_q32;
@@ -215,10 +228,8 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
             // past the last stage c >= C: every element reads index 0 and is parked as zero
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                int e;
-                bool ok;
-                conv_elem(fc0, fr0, i, e, ok);
-                e = ok ? e : 0;
+                uint32_t e, keep;
+                conv_elem(fc0, fr0, i, e, keep);
                 st.cw[i] = a.x_bits[e >> 5];
                 st.cs[i] = a.x_scales[e >> a.log2_beta_x];
             }
@@ -252,14 +263,13 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
             uint32_t h[8], m[8], l[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                int e;
-                bool ok;
-                conv_elem(pc0, pr0, i, e, ok);
-                const uint32_t minus = (~(st.cw[i] >> (e & 31)) & 1u) << 31;   // bit 0 = negative
-                split3(ok ? st.cs[i] : 0.f, h[i], m[i], l[i]);
-                h[i] ^= minus;
-                m[i] ^= minus;
-                l[i] ^= minus;
+                uint32_t e, keep;
+                conv_elem(pc0, pr0, i, e, keep);
+                // value = +-scale (bit 0 = negative), or 0 for a tap that does not exist; the pieces
+                // of a negative value are the negated pieces of its magnitude
+                const uint32_t minus = ~(st.cw[i] >> (e & 31)) << 31;
+                const uint32_t value = (__builtin_bit_cast(uint32_t, st.cs[i]) & keep) | minus;
+                split3(__builtin_bit_cast(float, value), h[i], m[i], l[i]);
             }
             conv_advance(pc0, pr0);
             u32x4 dh, dm, dl;
@@ -350,30 +360,35 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
         }
         const unsigned char *px = &sX[buf][(wx * 64 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
         const unsigned char *py = &sY[buf][(wy * 64 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
+        if (strip_live) {
 #pragma unroll
-        for (int ks = 0; ks < kStageK / 16; ++ks) {
-            bf16x8 fy[2];
+            for (int ks = 0; ks < kStageK / 16; ++ks) {
+                bf16x8 fy[2];
 #pragma unroll
-            for (int ty = 0; ty < 2; ++ty)
-                fy[ty] = *reinterpret_cast<const bf16x8 *>(py + ty * 32 * kRowBytes + ks * 32);
+                for (int ty = 0; ty < 2; ++ty)
+                    fy[ty] = *reinterpret_cast<const bf16x8 *>(py + ty * 32 * kRowBytes + ks * 32);
 #pragma unroll
-            for (int p = 0; p < 3; ++p) {
-                bf16x8 fx[2];
+                for (int p = 0; p < 3; ++p) {
+                    bf16x8 fx[2];
 #pragma unroll
-                for (int tx = 0; tx < 2; ++tx)
-                    fx[tx] = *reinterpret_cast<const bf16x8 *>(px + p * kPieceBytes + tx * 32 * kRowBytes + ks * 32);
+                    for (int tx = 0; tx < 2; ++tx)
+                        fx[tx] = *reinterpret_cast<const bf16x8 *>(px + p * kPieceBytes + tx * 32 * kRowBytes + ks * 32);
 #pragma unroll
-                for (int tx = 0; tx < 2; ++tx)
+                    for (int tx = 0; tx < 2; ++tx)
 #pragma unroll
-                    for (int ty = 0; ty < 2; ++ty)
-                        acc[tx][ty] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[tx], fy[ty], acc[tx][ty], 0, 0, 0);
+                        for (int ty = 0; ty < 2; ++ty)
+                            acc[tx][ty] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[tx], fy[ty], acc[tx][ty], 0, 0, 0);
+                }
+                if (Y16) apply_scale(sc16[ks]);
             }
-            if (Y16) apply_scale(sc16[ks]);
+            // The next stage is parked before the (conditional) segment epilogue and inside this
+            // branch, so that the splitting and sign-expansion arithmetic sits in the same scheduling
+            // region as the MFMAs.
+            park(ready, buf ^ 1);   // past the last stage this parks data that nobody reads
+            if (!Y16 && seg_last) apply_scale(sc_seg);
+        } else {
+            park(ready, buf ^ 1);
         }
-        // The next stage is parked before the (conditional) segment epilogue so that the splitting
-        // and sign-expansion arithmetic sits in the same scheduling region as the MFMAs.
-        park(ready, buf ^ 1);   // past the last stage this parks data that nobody reads
-        if (!Y16 && seg_last) apply_scale(sc_seg);
         __syncthreads();
     };
 
@@ -394,6 +409,7 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
         // accumulator tiles hold filters across lanes, so each 32 x 32 tile is turned through LDS
         // (row stride 33 words) and written with positions across lanes.
         __syncthreads();   // every wave has finished reading the operand tiles
+        if (!strip_live) return;
         float *turn = reinterpret_cast<float *>(&sX[0][0]) + wave * (32 * 33);
 #pragma unroll
         for (int tx = 0; tx < 2; ++tx) {
@@ -573,10 +589,15 @@ hipError_t launch_split2_y(const Split2Args &a, int spy, unsigned grid, hipStrea
 template <int XMODE>
 hipError_t launch_mode(const SplitArgs &a, bool y16, unsigned grid, hipStream_t s)
 {
-    if (y16)
-        mfma_split_gemm_kernel<XMODE, true><<<dim3(grid), dim3(kThreadsS), 0, s>>>(a);
+    const bool narrow = a.Y <= kBY - 64;
+    if (y16 && narrow)
+        mfma_split_gemm_kernel<XMODE, true, true><<<dim3(grid), dim3(kThreadsS), 0, s>>>(a);
+    else if (y16)
+        mfma_split_gemm_kernel<XMODE, true, false><<<dim3(grid), dim3(kThreadsS), 0, s>>>(a);
+    else if (narrow)
+        mfma_split_gemm_kernel<XMODE, false, true><<<dim3(grid), dim3(kThreadsS), 0, s>>>(a);
     else
-        mfma_split_gemm_kernel<XMODE, false><<<dim3(grid), dim3(kThreadsS), 0, s>>>(a);
+        mfma_split_gemm_kernel<XMODE, false, false><<<dim3(grid), dim3(kThreadsS), 0, s>>>(a);
     return hipGetLastError();
 }
 
