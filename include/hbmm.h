@@ -153,11 +153,16 @@ int hbmm_quantize_pack_tensor(const float *x, int64_t count, int32_t beta, uint3
  * shapes return HBMM_EUNSUPPORTED.  The activation values run on the matrix cores as three exact
  * bf16 pieces of the fp32 scale, the filter signs as +-1, the filter scale is applied per segment in
  * fp32: every output is an fp32 sum of exact terms.
+ *   algo   0: each workgroup stages the input patch of its output rows once per channel in on-chip
+ *             memory and gathers the window elements from there (used when the layer fits: window of
+ *             at least 2 taps, OW <= 128, patch of at most 1024 elements per channel); otherwise as 1.
+ *          1: every window element is gathered from device memory (any supported shape).
+ *          Both give the same sums in the same order.
  */
 int hbmm_conv2d(const uint32_t *a_bits, const float *a_scales, int32_t beta_a, const uint32_t *w_bits,
                 const float *w_scales, int64_t ldw_w, int64_t lds_w, int32_t beta_w, int64_t B, int64_t C,
                 int64_t H, int64_t W, int64_t N, int32_t KH, int32_t KW, int32_t stride, int32_t pad,
-                float *out, void *stream);
+                float *out, int32_t algo, void *stream);
 
 /*
  * Fused form for the activation operand: the same C as

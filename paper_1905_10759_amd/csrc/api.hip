@@ -280,8 +280,9 @@ int hbmm_quantize_pack_tensor(const float *x, int64_t count, int32_t beta, uint3
 int hbmm_conv2d(const uint32_t *a_bits, const float *a_scales, int32_t beta_a, const uint32_t *w_bits,
                 const float *w_scales, int64_t ldw_w, int64_t lds_w, int32_t beta_w, int64_t B, int64_t C,
                 int64_t H, int64_t W, int64_t N, int32_t KH, int32_t KW, int32_t stride, int32_t pad,
-                float *out, void *stream)
+                float *out, int32_t algo, void *stream)
 {
+    if (algo != 0 && algo != 1) return HBMM_EINVAL;
     if (B < 0 || C < 0 || H < 0 || W < 0 || N < 0 || KH < 1 || KW < 1 || stride < 1 || pad < 0) return HBMM_EINVAL;
     if (B > kMaxDim || C > kMaxDim || H > kMaxDim || W > kMaxDim || N > kMaxDim) return HBMM_EINVAL;
     if (KH > 32 || KW > 32 || pad > 32 || stride > 32) return HBMM_EINVAL;
@@ -302,7 +303,7 @@ int hbmm_conv2d(const uint32_t *a_bits, const float *a_scales, int32_t beta_a, c
     hbmm::ConvActivations x{a_bits, a_scales, beta_a};
     hbmm::SplitGemmOperand y{};
     y.bits = w_bits; y.scales = w_scales; y.ldw = ldw_w; y.lds = lds_w; y.rows = N; y.beta = beta_w;
-    hbmm::ConvGeometry g{B, C, H, W, KH, KW, stride, pad};
+    hbmm::ConvGeometry g{B, C, H, W, KH, KW, stride, pad, algo};
     return from_hip(hbmm::launch_mfma_split_conv(x, y, g, out, static_cast<hipStream_t>(stream)));
 }
 

@@ -574,6 +574,339 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split2_gemm_kernel(const Split
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Convolution layer with the activations staged once per workgroup.
+//
+// The conv mode of mfma_split_gemm_kernel builds every element of the (positions x taps) operand
+// from memory, i.e. each activation KH*KW times.  Here a workgroup owns R whole output rows of one
+// image (R * OW <= 128 positions) and keeps, for the channels the current K stages touch, the
+// input patch those rows need -- ((R - 1) * stride + KH) rows x (W + 2 pad) columns, zero outside
+// the image -- in LDS as three planes of bf16 pieces (the exact split of +-scale, done once per
+// activation).  Channels live in a ring of NS slots.  The 128 x 32 operand tile of a stage is then
+// gathered LDS -> LDS: element (m, k) sits at
+//     slot(c) * PS + (orow * stride + dz) * PW + oy * stride + dy
+// = a per-position part (fixed per thread) + a per-k part (one table of 32 entries per stage,
+// written by 32 threads a stage ahead).  From there on -- fragment reads, MFMAs, filter scale per
+// segment, turned store -- it is the kernel above.
+//
+// Schedule of stage s (one barrier per stage): multiply tile s; gather tile s + 1 from the patch;
+// turn the loads requested two stages ago into the patch planes of the channels that stage s + 2
+// brings in, and expand the filter words of stage s + 1; write the k table of stage s + 2; request
+// the loads of stage s + 4.  A slot is overwritten only by a channel NS further on, and NS exceeds
+// the channel span of two consecutive stages, so the gather never reads a slot being rewritten.
+constexpr int kPatchPlane = 8192;           // bf16 elements per piece plane (16 KB)
+
+struct ConvPatchArgs {
+    const uint32_t *x_bits;
+    const float *x_scales;
+    const uint32_t *y_bits;
+    const float *y_scales;
+    float *out;
+    int32_t ldw_y, lds_y;
+    int32_t Y, K;
+    int32_t log2_beta_x, stages_per_yseg;
+    int32_t C, H, W, HW, OH, OW, OHW, KW, KK, stride, pad;
+    int32_t R, tiles_per_image, tiles_y, tiles_total, slots_per_xcd;
+    int32_t PW, P, PS, NS;
+    int32_t nch;                 // most channels a stage can bring in: ceil(32 / KK)
+    uint32_t last_elem;          // B*C*H*W - 1
+    int32_t q32, r32, magic_kw;
+};
+
+// IPT: (channel, patch element) items a thread stages per stage; IPT * 512 >= nch * P.
+template <int IPT, bool Y16, bool NARROW>
+__global__ __launch_bounds__(kThreadsS) void conv_patch_kernel(const ConvPatchArgs a)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char sX[2][3 * kPieceBytes];
+    __shared__ __attribute__((aligned(16))) unsigned char sY[2][kBY * kRowBytes];
+    __shared__ __attribute__((aligned(16))) unsigned short sPatch[3][kPatchPlane];
+    __shared__ __attribute__((aligned(16))) uint32_t sKoff[4][kStageK];
+
+    const int slot_id = (blockIdx.x % kNumXcdS) * a.slots_per_xcd + blockIdx.x / kNumXcdS;
+    if (slot_id >= a.tiles_total) return;
+    const int tile_x = slot_id / a.tiles_y, y0 = (slot_id % a.tiles_y) * kBY;
+    const int img = tile_x / a.tiles_per_image, oz0 = (tile_x % a.tiles_per_image) * a.R;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wx = NARROW ? wave & 1 : wave >> 2, wy = NARROW ? wave >> 1 : wave & 3;
+    const bool strip_live = !NARROW || y0 + wy * 64 < a.Y;
+    const int nstages = a.K / kStageK;
+    const int npos = a.R * a.OW;                            // positions of a full tile (<= 128)
+
+    // ---- role 1: owner of IPT staging items.  Item i = tid + 512 j is patch element (i mod P) of the
+    // (i div P)-th channel a stage brings in; the same items every stage.
+    uint32_t pe0[IPT], pkeep[IPT];
+    int pch[IPT], pat[IPT];
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) {
+        const int item = tid + j * kThreadsS;
+        const int ch = item / a.P, p = item - ch * a.P;
+        const int prow = p / a.PW, pcol = p - prow * a.PW;
+        const int z = oz0 * a.stride - a.pad + prow, y = pcol - a.pad;
+        const bool inside = z >= 0 && z < a.H && y >= 0 && y < a.W;
+        pch[j] = ch;                                   // >= nch: the item does not exist
+        pat[j] = p;
+        pkeep[j] = inside ? 0xffffffffu : 0u;
+        pe0[j] = inside ? (uint32_t)((img * a.C * a.H + z) * a.W + y) + (uint32_t)(ch * a.HW) : 0u;
+    }
+    // ---- role 2: gatherer of 8 consecutive k of one position
+    const int grow = tid & 127, goct = __builtin_amdgcn_readfirstlane(tid >> 7);
+    uint32_t gbase;   // byte offset of the position's window corner inside a patch slot
+    {
+        const int ml = min(grow, npos - 1);
+        const int orow = ml / a.OW, oy = ml - orow * a.OW;
+        gbase = (uint32_t)((orow * a.stride) * a.PW + oy * a.stride) * 2u;
+    }
+    // ---- role 3: expander of 16 filter signs
+    const int yrow_t = tid >> 1, yhalf = tid & 1;
+    const uint32_t *yb_src = a.y_bits + (int64_t)min(y0 + yrow_t, a.Y - 1) * a.ldw_y;
+
+    struct Staged {
+        uint32_t pw[IPT];
+        float ps[IPT];
+        uint32_t yb;
+    };
+    const char *xb_bytes = reinterpret_cast<const char *>(a.x_bits);
+    const char *xs_bytes = reinterpret_cast<const char *>(a.x_scales);
+
+    // Channels that stage sx brings in: (last channel of stage sx - 1, last channel of stage sx].
+    // Both walkers are advanced once per call, and the calls come in stage order.
+    struct Walker {
+        int q, r, prev;   // (32 sx + 31) div / mod KK, and the last channel of the previous stage
+    };
+    Walker fwalk{31 / a.KK, 31 % a.KK, -1}, pwalk{31 / a.KK, 31 % a.KK, -1};
+    int pslot = 0;        // ring slot of the first channel the next park brings in
+    auto advance = [&](Walker &w, int last) {
+        w.prev = last;
+        w.q += a.q32;
+        w.r += a.r32;
+        if (w.r >= a.KK) {
+            w.r -= a.KK;
+            w.q += 1;
+        }
+    };
+
+    auto fetch = [&](Staged &st, int sx) {
+        const int last = min(fwalk.q, a.C - 1);
+        const uint32_t first_off = (uint32_t)((fwalk.prev + 1) * a.HW);
+#pragma unroll
+        for (int j = 0; j < IPT; ++j) {
+            // unconditional loads; an item whose channel lies past the stage's (or the tensor's) last
+            // one reads a clamped index and is not parked
+            const uint32_t e = min((pe0[j] + first_off) & pkeep[j], a.last_elem);
+            st.pw[j] = *reinterpret_cast<const uint32_t *>(xb_bytes + ((e >> 5) << 2));
+            st.ps[j] = *reinterpret_cast<const float *>(xs_bytes + ((e >> a.log2_beta_x) << 2));
+        }
+        st.yb = yb_src[min(max(sx - 1, 0), nstages - 1)];
+        advance(fwalk, last);
+    };
+
+    const bool yrow_live = y0 + yrow_t < a.Y;
+    auto park = [&](const Staged &st, int sx) {
+        const int last = min(pwalk.q, a.C - 1);
+        const int nnew = last - pwalk.prev;
+        const uint32_t first_off = (uint32_t)((pwalk.prev + 1) * a.HW);
+#pragma unroll
+        for (int j = 0; j < IPT; ++j) {
+            const uint32_t e = (pe0[j] + first_off) & pkeep[j];
+            const uint32_t minus = ~(st.pw[j] >> (e & 31)) << 31;
+            const uint32_t value = (__builtin_bit_cast(uint32_t, st.ps[j]) & pkeep[j]) | minus;
+            uint32_t h, m, l;
+            split3(__builtin_bit_cast(float, value), h, m, l);
+            if (pch[j] < nnew) {
+                int slot = pslot + pch[j];
+                slot -= slot >= a.NS ? a.NS : 0;
+                const int at = slot * a.PS + pat[j];
+                sPatch[0][at] = (unsigned short)(h >> 16);
+                sPatch[1][at] = (unsigned short)(m >> 16);
+                sPatch[2][at] = (unsigned short)(l >> 16);
+            }
+        }
+        pslot += nnew;
+        pslot -= pslot >= a.NS ? a.NS : 0;
+        advance(pwalk, last);
+        // filter signs of stage sx - 1 -> +-1.0 (rows past Y are never multiplied into a stored column)
+        if (yrow_live) {
+            const int ybuf = max(sx - 1, 0) & 1;
+            uint32_t ym[8];
+            sign_masks<8>(~(st.yb >> (16 * yhalf)) & 0xffffu, ym);
+            u32x4 y0v, y1v;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                y0v[i] = ym[i] | 0x3f803f80u;
+                y1v[i] = ym[4 + i] | 0x3f803f80u;
+            }
+            unsigned char *ydst = &sY[ybuf][yrow_t * kRowBytes + yhalf * 32];
+            *reinterpret_cast<u32x4 *>(ydst) = y0v;
+            *reinterpret_cast<u32x4 *>(ydst + 16) = y1v;
+        }
+    };
+
+    // k table: thread t < 32 follows k = 32 j + t through the stages
+    int tc = tid / a.KK, tr = tid % a.KK;
+    auto write_table = [&](int j) {
+        if (tid < kStageK) {
+            const int dz = (tr * a.magic_kw) >> 16, dy = tr - dz * a.KW;
+            sKoff[j & 3][tid] = (uint32_t)((tc % a.NS) * a.PS + dz * a.PW + dy) * 2u;
+            tc += a.q32;
+            tr += a.r32;
+            if (tr >= a.KK) {
+                tr -= a.KK;
+                tc += 1;
+            }
+        }
+    };
+
+    auto gather = [&](int j) {
+        const u32x4 *tab = reinterpret_cast<const u32x4 *>(&sKoff[j & 3][goct * 8]);
+        const u32x4 t0 = tab[0], t1 = tab[1];
+        const uint32_t off[8] = {t0[0], t0[1], t0[2], t0[3], t1[0], t1[1], t1[2], t1[3]};
+        const unsigned char *plane = reinterpret_cast<const unsigned char *>(&sPatch[0][0]);
+        unsigned char *dst = &sX[j & 1][grow * kRowBytes + goct * 16];
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            uint32_t v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                v[i] = *reinterpret_cast<const unsigned short *>(plane + p * (kPatchPlane * 2) + gbase + off[i]);
+            u32x4 d;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) d[i] = v[2 * i] | (v[2 * i + 1] << 16);
+            *reinterpret_cast<u32x4 *>(dst + p * kPieceBytes) = d;
+        }
+    };
+
+    f32x16 acc[2][2], res[2][2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                acc[p][q][v] = 0.f;
+                res[p][q][v] = 0.f;
+            }
+    const float *srow[2];
+#pragma unroll
+    for (int ty = 0; ty < 2; ++ty)
+        srow[ty] = a.y_scales + (int64_t)min(y0 + wy * 64 + ty * 32 + (lane & 31), a.Y - 1) * a.lds_y;
+    auto apply_scale = [&](const float (&sc)[2]) {
+#pragma unroll
+        for (int tx = 0; tx < 2; ++tx)
+#pragma unroll
+            for (int ty = 0; ty < 2; ++ty)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    res[tx][ty][v] = __builtin_fmaf(sc[ty], acc[tx][ty][v], res[tx][ty][v]);
+                    acc[tx][ty][v] = 0.f;
+                }
+    };
+
+    float sc_seg[2] = {0.f, 0.f};
+    auto run_stage = [&](int stage, const Staged &ready, Staged &incoming) {
+        const int buf = stage & 1;
+        fetch(incoming, stage + 4);
+        float sc16[2][2];
+        bool seg_last = false;
+        if (Y16) {
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                for (int ty = 0; ty < 2; ++ty) sc16[ks][ty] = srow[ty][stage * 2 + ks];
+        } else {
+            seg_last = (stage + 1) % a.stages_per_yseg == 0;
+            if (stage % a.stages_per_yseg == 0) {
+#pragma unroll
+                for (int ty = 0; ty < 2; ++ty) sc_seg[ty] = srow[ty][stage / a.stages_per_yseg];
+            }
+        }
+        const unsigned char *px = &sX[buf][(wx * 64 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
+        const unsigned char *py = &sY[buf][(wy * 64 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
+        if (strip_live) {
+#pragma unroll
+            for (int ks = 0; ks < kStageK / 16; ++ks) {
+                bf16x8 fy[2];
+#pragma unroll
+                for (int ty = 0; ty < 2; ++ty)
+                    fy[ty] = *reinterpret_cast<const bf16x8 *>(py + ty * 32 * kRowBytes + ks * 32);
+#pragma unroll
+                for (int p = 0; p < 3; ++p) {
+                    bf16x8 fx[2];
+#pragma unroll
+                    for (int tx = 0; tx < 2; ++tx)
+                        fx[tx] = *reinterpret_cast<const bf16x8 *>(px + p * kPieceBytes + tx * 32 * kRowBytes + ks * 32);
+#pragma unroll
+                    for (int tx = 0; tx < 2; ++tx)
+#pragma unroll
+                        for (int ty = 0; ty < 2; ++ty)
+                            acc[tx][ty] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[tx], fy[ty], acc[tx][ty], 0, 0, 0);
+                }
+                if (Y16) apply_scale(sc16[ks]);
+            }
+            gather(stage + 1);
+            park(ready, stage + 2);
+            write_table(stage + 2);
+            if (!Y16 && seg_last) apply_scale(sc_seg);
+        } else {
+            gather(stage + 1);
+            park(ready, stage + 2);
+            write_table(stage + 2);
+        }
+        __syncthreads();
+    };
+
+    Staged s0, s1, s2;
+    fetch(s0, 0);
+    fetch(s1, 1);
+    write_table(0);
+    write_table(1);
+    park(s0, 0);
+    park(s1, 1);
+    __syncthreads();
+    fetch(s0, 2);
+    fetch(s1, 3);
+    gather(0);
+    __syncthreads();
+    for (int stage = 0; stage < nstages; stage += 3) {
+        run_stage(stage, s0, s2);
+        if (stage + 1 < nstages) run_stage(stage + 1, s1, s0);
+        if (stage + 2 < nstages) run_stage(stage + 2, s2, s1);
+    }
+
+    // ---- store: out is B x Y x OH x OW; each 32 x 32 accumulator tile is turned through LDS so that
+    // lanes run along positions
+    if (!strip_live) return;   // the loop's last barrier has passed; the turn areas are per wave,
+                               // inside sX, which nobody multiplies from any more
+    float *turn = reinterpret_cast<float *>(&sX[0][0]) + wave * (32 * 33);
+#pragma unroll
+    for (int tx = 0; tx < 2; ++tx) {
+        const int ml = wx * 64 + tx * 32 + (lane & 31);
+        const int mc = min(ml, npos - 1);
+        const int orow = mc / a.OW, oy = mc - orow * a.OW;
+        const bool pos_ok = ml < npos && oz0 + orow < a.OH;
+        float *dst = a.out + ((int64_t)img * a.Y * a.OH + (oz0 + orow)) * a.OW + oy;
+#pragma unroll
+        for (int ty = 0; ty < 2; ++ty) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                turn[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * 33 + (lane & 31)] = res[tx][ty][v];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const int cl = 2 * j + (lane >> 5);
+                const int col = y0 + wy * 64 + ty * 32 + cl;
+                const float val = turn[(lane & 31) * 33 + cl];
+                if (pos_ok && col < a.Y) dst[(int64_t)col * a.OHW] = val;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+    }
+}
+
 template <int SPX>
 hipError_t launch_split2_y(const Split2Args &a, int spy, unsigned grid, hipStream_t s)
 {
@@ -662,6 +995,60 @@ hipError_t launch_mfma_split_gemm(const SplitGemmOperand &x, const SplitGemmOper
     return launch_mode<kXScale1>(a, y16, grid, s);
 }
 
+// The staged-patch kernel when the layer fits it; false = use the gather kernel.
+static bool try_launch_conv_patch(const ConvActivations &x, const SplitGemmOperand &y, const ConvGeometry &g, int64_t OH,
+                                  int64_t OW, float *out, hipStream_t s, hipError_t &err)
+{
+    const int KK = g.KH * g.KW;
+    if (OW > 128 || KK < 2) return false;
+    if (y.beta == 16) return false;   // the per-16 epilogue's registers do not fit next to the staging
+    int R = (int)(128 / OW < OH ? 128 / OW : OH);
+    const int tiles_per_image = (int)((OH + R - 1) / R);
+    R = (int)((OH + tiles_per_image - 1) / tiles_per_image);
+    const int PW = (int)g.W + 2 * g.pad, PR = (R - 1) * g.stride + g.KH, P = PR * PW;
+    const int nch = (kStageK + KK - 1) / KK;
+    const int ipt = (nch * P + kThreadsS - 1) / kThreadsS;
+    if (ipt > 8) return false;
+    const int NS = (2 * kStageK - 1) / KK + 3, PS = (P + 7) / 8 * 8;
+    if (NS * PS > kPatchPlane) return false;
+    const int64_t tiles_x = g.B * tiles_per_image, tiles_y = (y.rows + kBY - 1) / kBY;
+    const int64_t total = tiles_x * tiles_y, per_xcd = (total + kNumXcdS - 1) / kNumXcdS;
+    if (per_xcd * kNumXcdS > 0x7fffffffLL) return false;
+    ConvPatchArgs a{};
+    a.x_bits = x.bits; a.x_scales = x.scales; a.log2_beta_x = ilog2s(x.beta);
+    a.y_bits = y.bits; a.y_scales = y.scales; a.ldw_y = (int32_t)y.ldw; a.lds_y = (int32_t)y.lds;
+    a.out = out; a.Y = (int32_t)y.rows; a.K = (int32_t)(g.C * KK);
+    a.stages_per_yseg = y.beta >= 32 ? y.beta / kStageK : 1;
+    a.C = (int32_t)g.C; a.H = (int32_t)g.H; a.W = (int32_t)g.W; a.HW = (int32_t)(g.H * g.W);
+    a.OH = (int32_t)OH; a.OW = (int32_t)OW; a.OHW = (int32_t)(OH * OW);
+    a.KW = g.KW; a.KK = KK; a.stride = g.stride; a.pad = g.pad;
+    a.R = R; a.tiles_per_image = tiles_per_image; a.tiles_y = (int32_t)tiles_y; a.tiles_total = (int32_t)total;
+    a.slots_per_xcd = (int32_t)per_xcd;
+    a.PW = PW; a.P = P; a.PS = PS; a.NS = NS; a.nch = nch;
+    a.last_elem = (uint32_t)(g.B * g.C * g.H * g.W - 1);
+    a.q32 = kStageK / KK; a.r32 = kStageK % KK; a.magic_kw = 65536 / g.KW + 1;
+    const dim3 grid((unsigned)(per_xcd * kNumXcdS)), block(kThreadsS);
+    const bool narrow = y.rows <= kBY - 64;
+#define HBMM_PATCH_LAUNCH(I)                                                \
+    do {                                                                    \
+        if (narrow)                                                         \
+            conv_patch_kernel<I, false, true><<<grid, block, 0, s>>>(a);    \
+        else                                                                \
+            conv_patch_kernel<I, false, false><<<grid, block, 0, s>>>(a);   \
+    } while (0)
+    if (ipt <= 2)
+        HBMM_PATCH_LAUNCH(2);
+    else if (ipt <= 4)
+        HBMM_PATCH_LAUNCH(4);
+    else if (ipt <= 6)
+        HBMM_PATCH_LAUNCH(6);
+    else
+        HBMM_PATCH_LAUNCH(8);
+#undef HBMM_PATCH_LAUNCH
+    err = hipGetLastError();
+    return true;
+}
+
 hipError_t launch_mfma_split_conv(const ConvActivations &x, const SplitGemmOperand &y, const ConvGeometry &g, float *out,
                                   hipStream_t s)
 {
@@ -669,6 +1056,10 @@ hipError_t launch_mfma_split_conv(const ConvActivations &x, const SplitGemmOpera
     const int64_t K = g.C * g.KH * g.KW, M = g.B * OH * OW;
     if (y.beta < 16 || y.bits == nullptr || K % kStageK != 0 || g.KH * g.KW > 32) return hipErrorNotSupported;
     if (g.B * g.C * g.H * g.W > 0x7fffffffLL || M > 0x7fffffffLL) return hipErrorNotSupported;
+    if (g.algo != 1) {
+        hipError_t err = hipSuccess;
+        if (try_launch_conv_patch(x, y, g, OH, OW, out, s, err)) return err;
+    }
     SplitArgs a{};
     a.x_bits = x.bits; a.x_scales = x.scales; a.log2_beta_x = ilog2s(x.beta);
     a.y_bits = y.bits; a.y_scales = y.scales; a.ldw_y = (int32_t)y.ldw; a.lds_y = (int32_t)y.lds;

@@ -86,6 +86,7 @@ struct ConvActivations {
 struct ConvGeometry {
     int64_t B, C, H, W;
     int KH, KW, stride, pad;
+    int algo;   // 0: activations staged once per workgroup when the layer fits, else 1; 1: per-tap gather
 };
 hipError_t launch_mfma_split_conv(const ConvActivations &x, const SplitGemmOperand &y, const ConvGeometry &g, float *out,
                                   hipStream_t s);

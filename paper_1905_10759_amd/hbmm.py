@@ -55,7 +55,7 @@ def _load() -> C.CDLL:
     lib.hbmm_quantize_pack_tensor.restype = C.c_int
     lib.hbmm_quantize_pack_tensor.argtypes = [p, i64, i32, p, p, p]
     lib.hbmm_conv2d.restype = C.c_int
-    lib.hbmm_conv2d.argtypes = [p, p, i32, p, p, i64, i64, i32, i64, i64, i64, i64, i64, i32, i32, i32, i32, p, p]
+    lib.hbmm_conv2d.argtypes = [p, p, i32, p, p, i64, i64, i32, i64, i64, i64, i64, i64, i32, i32, i32, i32, p, i32, p]
     lib.hbmm_binarize_backward.restype = C.c_int
     lib.hbmm_binarize_backward.argtypes = [p, p, i64, i64, i64, i64, i32, p, i64, p]
     lib.hbmm_dense_ref_gemm.restype = C.c_int
@@ -221,7 +221,7 @@ def quantize_pack_tensor(x: torch.Tensor, beta: int):
 
 
 def conv2d(a_bits, a_scales, beta_a: int, shape, w_bits, w_scales, beta_w: int, kernel, stride: int = 1,
-           pad: int = 0, out: torch.Tensor | None = None) -> torch.Tensor:
+           pad: int = 0, out: torch.Tensor | None = None, algo: int = 0) -> torch.Tensor:
     """hbmm_conv2d: activations (B, C, H, W) = `shape` packed by quantize_pack_tensor, filters
     (N, C, KH, KW) packed by quantize_pack on the N x (C*KH*KW) matrix; `kernel` = (KH, KW)."""
     _dev(a_bits, torch.int32, "a_bits")
@@ -237,6 +237,6 @@ def conv2d(a_bits, a_scales, beta_a: int, shape, w_bits, w_scales, beta_w: int, 
     rc = lib.hbmm_conv2d(a_bits.data_ptr(), a_scales.data_ptr(), beta_a, w_bits.data_ptr(), w_scales.data_ptr(),
                          w_bits.stride(0) if N > 1 else w_bits.shape[1],
                          w_scales.stride(0) if N > 1 else max(w_scales.shape[1], 1), beta_w, B, Cc, H, W, N, KH, KW,
-                         stride, pad, out.data_ptr(), _stream())
+                         stride, pad, out.data_ptr(), algo, _stream())
     _check(rc, "hbmm_conv2d")
     return out

@@ -436,17 +436,21 @@ CONV_CASES = [
 ]
 
 
+@pytest.mark.parametrize("algo", [0, 1])
 @pytest.mark.parametrize("case", CONV_CASES, ids=lambda c: "x".join(str(v) for v in c))
-def test_conv2d(case):
+def test_conv2d(case, algo):
     B, C, H, W, N, KH, KW, stride, pad, beta_a, beta_w = case
     A, Wf = _conv_inputs(31 + B + C + N, B, C, H, W, N, KH, KW)
     A[0, 0, 0, :2] = [0.0, -0.0]
     ref, T = oracle.hbmm_conv2d(A, Wf, beta_a, beta_w, stride, pad, want_T=True)
     ab, asc = hbmm.quantize_pack_tensor(dev(A), beta_a)
     wb, ws = hbmm.quantize_pack(dev(Wf.reshape(N, -1)), beta_w)
-    out = hbmm.conv2d(ab, asc, beta_a, A.shape, wb, ws, beta_w, (KH, KW), stride, pad)
+    out = hbmm.conv2d(ab, asc, beta_a, A.shape, wb, ws, beta_w, (KH, KW), stride, pad, algo=algo)
     assert tuple(out.shape) == ref.shape
-    assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d {case}")
+    assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d {case} algo {algo}")
+    if algo == 0:
+        # both kernels add the same exact products in the same order
+        assert torch.equal(out, hbmm.conv2d(ab, asc, beta_a, A.shape, wb, ws, beta_w, (KH, KW), stride, pad, algo=1))
 
 
 def test_conv2d_equals_gemm_on_im2col():
