@@ -124,8 +124,8 @@ struct SplitArgs {
     int32_t cv_q32, cv_r32;             // 32 div KK, 32 mod KK: how (c, tap) moves from stage to stage
 };
 
-// NARROW: Y has at most 192 rows (one tile, at least one dead 64-column strip), see below.
-template <int XMODE, bool Y16, bool NARROW>
+// NTY: 0 for the general case; 1, 2 or 3 when Y has at most 64, 128 or 192 rows (one tile), see below.
+template <int XMODE, bool Y16, int NTY>
 __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitArgs a)
 {
     __shared__ __attribute__((aligned(16))) unsigned char sX[2][3 * kPieceBytes];
@@ -137,12 +137,13 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
     const int x0 = (slot / a.tiles_y) * kBX, y0 = (slot % a.tiles_y) * kBY;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    // Wave -> 64 x 64 sub-tile.  In the NARROW variant the waves of the dead 64-column strips skip
-    // the multiplications (they still stage operands), and waves 2j and 2j+1 share strip j: consecutive
-    // wave ids sit on different SIMDs, so the live strips' waves are spread over them.  The variant
-    // is a separate instantiation because the branch around the multiplications costs full tiles ~10 %.
-    const int wx = NARROW ? wave & 1 : wave >> 2, wy = NARROW ? wave >> 1 : wave & 3;
-    const bool strip_live = !NARROW || y0 + wy * 64 < a.Y;
+    // Wave -> sub-tile of the 128 x 256 workgroup tile, as TX x TY accumulator tiles of 32 x 32.
+    // General case: 2 x 4 waves of 64 x 64.  When Y has at most 64 * NTY rows the live part of the tile
+    // is cut into 4 x 2 waves of 32 x (32 NTY) instead, so that all eight waves multiply (with 64 x 64
+    // sub-tiles only NTY of the four wave columns would).
+    constexpr int TX = NTY == 0 ? 2 : 1, TY = NTY == 0 ? 2 : NTY;
+    const int wrow0 = NTY == 0 ? (wave >> 2) * 64 : (wave & 3) * 32;
+    const int wcol0 = NTY == 0 ? (wave & 3) * 64 : (wave >> 2) * (32 * NTY);
     const int nstages = a.K / kStageK;
 
     constexpr int kScalesPerThread = XMODE == kXScale4 ? 4 : XMODE == kXScale2 ? 2 : 1;
@@ -305,32 +306,32 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
         *reinterpret_cast<u32x4 *>(ydst + 16) = y1v;
     };
 
-    f32x16 acc[2][2], res[2][2];
+    f32x16 acc[TX][TY], res[TX][TY];
 #pragma unroll
-    for (int p = 0; p < 2; ++p)
+    for (int p = 0; p < TX; ++p)
 #pragma unroll
-        for (int q = 0; q < 2; ++q)
+        for (int q = 0; q < TY; ++q)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 acc[p][q][v] = 0.f;
                 res[p][q][v] = 0.f;
             }
 
-    // per-lane Y scale rows: the output column of accumulator tile ty is y0 + wy*64 + 32*ty + lane%32
-    const float *srow[2];
-    bool col_ok[2];
+    // per-lane Y scale rows: the output column of accumulator tile ty is y0 + wcol0 + 32*ty + lane%32
+    const float *srow[TY];
+    bool col_ok[TY];
 #pragma unroll
-    for (int ty = 0; ty < 2; ++ty) {
-        const int col = y0 + wy * 64 + ty * 32 + (lane & 31);
+    for (int ty = 0; ty < TY; ++ty) {
+        const int col = y0 + wcol0 + ty * 32 + (lane & 31);
         col_ok[ty] = col < a.Y;
         srow[ty] = a.y_scales + (int64_t)min(col, a.Y - 1) * a.lds_y;
     }
 
-    auto apply_scale = [&](const float (&sc)[2]) {
+    auto apply_scale = [&](const float (&sc)[TY]) {
 #pragma unroll
-        for (int tx = 0; tx < 2; ++tx)
+        for (int tx = 0; tx < TX; ++tx)
 #pragma unroll
-            for (int ty = 0; ty < 2; ++ty)
+            for (int ty = 0; ty < TY; ++ty)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     res[tx][ty][v] = __builtin_fmaf(sc[ty], acc[tx][ty][v], res[tx][ty][v]);
@@ -338,57 +339,52 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
                 }
     };
 
-    float sc_seg[2] = {0.f, 0.f};
+    float sc_seg[TY] = {};
     // One K stage: multiply the tile parked in LDS buffer (stage mod 2), request stage + 3 into
     // `incoming`, and park `ready` (stage + 1, requested three stages ago) in the other buffer.
     auto run_stage = [&](int stage, const Staged &ready, Staged &incoming) {
         const int buf = stage & 1;
         fetch(incoming, stage + 3);
-        float sc16[2][2];
+        float sc16[2][TY];
         bool seg_last = false;
         if (Y16) {
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                for (int ty = 0; ty < 2; ++ty) sc16[ks][ty] = srow[ty][stage * 2 + ks];
+                for (int ty = 0; ty < TY; ++ty) sc16[ks][ty] = srow[ty][stage * 2 + ks];
         } else {
             seg_last = (stage + 1) % a.stages_per_yseg == 0;
             if (stage % a.stages_per_yseg == 0) {
 #pragma unroll
-                for (int ty = 0; ty < 2; ++ty) sc_seg[ty] = srow[ty][stage / a.stages_per_yseg];
+                for (int ty = 0; ty < TY; ++ty) sc_seg[ty] = srow[ty][stage / a.stages_per_yseg];
             }
         }
-        const unsigned char *px = &sX[buf][(wx * 64 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
-        const unsigned char *py = &sY[buf][(wy * 64 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
-        if (strip_live) {
+        const unsigned char *px = &sX[buf][(wrow0 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
+        const unsigned char *py = &sY[buf][(wcol0 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
 #pragma unroll
-            for (int ks = 0; ks < kStageK / 16; ++ks) {
-                bf16x8 fy[2];
+        for (int ks = 0; ks < kStageK / 16; ++ks) {
+            bf16x8 fy[TY];
 #pragma unroll
-                for (int ty = 0; ty < 2; ++ty)
-                    fy[ty] = *reinterpret_cast<const bf16x8 *>(py + ty * 32 * kRowBytes + ks * 32);
+            for (int ty = 0; ty < TY; ++ty)
+                fy[ty] = *reinterpret_cast<const bf16x8 *>(py + ty * 32 * kRowBytes + ks * 32);
 #pragma unroll
-                for (int p = 0; p < 3; ++p) {
-                    bf16x8 fx[2];
+            for (int p = 0; p < 3; ++p) {
+                bf16x8 fx[TX];
 #pragma unroll
-                    for (int tx = 0; tx < 2; ++tx)
-                        fx[tx] = *reinterpret_cast<const bf16x8 *>(px + p * kPieceBytes + tx * 32 * kRowBytes + ks * 32);
+                for (int tx = 0; tx < TX; ++tx)
+                    fx[tx] = *reinterpret_cast<const bf16x8 *>(px + p * kPieceBytes + tx * 32 * kRowBytes + ks * 32);
 #pragma unroll
-                    for (int tx = 0; tx < 2; ++tx)
+                for (int tx = 0; tx < TX; ++tx)
 #pragma unroll
-                        for (int ty = 0; ty < 2; ++ty)
-                            acc[tx][ty] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[tx], fy[ty], acc[tx][ty], 0, 0, 0);
-                }
-                if (Y16) apply_scale(sc16[ks]);
+                    for (int ty = 0; ty < TY; ++ty)
+                        acc[tx][ty] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[tx], fy[ty], acc[tx][ty], 0, 0, 0);
             }
-            // The next stage is parked before the (conditional) segment epilogue and inside this
-            // branch, so that the splitting and sign-expansion arithmetic sits in the same scheduling
-            // region as the MFMAs.
-            park(ready, buf ^ 1);   // past the last stage this parks data that nobody reads
-            if (!Y16 && seg_last) apply_scale(sc_seg);
-        } else {
-            park(ready, buf ^ 1);
+            if (Y16) apply_scale(sc16[ks]);
         }
+        // The next stage is parked before the (conditional) segment epilogue so that the splitting
+        // and sign-expansion arithmetic sits in the same scheduling region as the MFMAs.
+        park(ready, buf ^ 1);   // past the last stage this parks data that nobody reads
+        if (!Y16 && seg_last) apply_scale(sc_seg);
         __syncthreads();
     };
 
@@ -409,16 +405,15 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
         // accumulator tiles hold filters across lanes, so each 32 x 32 tile is turned through LDS
         // (row stride 33 words) and written with positions across lanes.
         __syncthreads();   // every wave has finished reading the operand tiles
-        if (!strip_live) return;
         float *turn = reinterpret_cast<float *>(&sX[0][0]) + wave * (32 * 33);
 #pragma unroll
-        for (int tx = 0; tx < 2; ++tx) {
-            const int m = x0 + wx * 64 + tx * 32 + (lane & 31);
+        for (int tx = 0; tx < TX; ++tx) {
+            const int m = x0 + wrow0 + tx * 32 + (lane & 31);
             const int mc = min(m, a.X - 1);
             const int b = mc / a.cv_ohw, pos = mc - b * a.cv_ohw;
             float *dst = a.out + (int64_t)b * a.Y * a.cv_ohw + pos;
 #pragma unroll
-            for (int ty = 0; ty < 2; ++ty) {
+            for (int ty = 0; ty < TY; ++ty) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v)
                     turn[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * 33 + (lane & 31)] = res[tx][ty][v];
@@ -428,7 +423,7 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
 #pragma unroll
                 for (int j = 0; j < 16; ++j) {
                     const int cl = 2 * j + (lane >> 5);
-                    const int col = y0 + wy * 64 + ty * 32 + cl;
+                    const int col = y0 + wcol0 + ty * 32 + cl;
                     const float val = turn[(lane & 31) * 33 + cl];
                     if (m < a.X && col < a.Y) dst[(int64_t)col * a.cv_ohw] = val;
                 }
@@ -440,14 +435,14 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
         return;
     }
 #pragma unroll
-    for (int tx = 0; tx < 2; ++tx)
+    for (int tx = 0; tx < TX; ++tx)
 #pragma unroll
-        for (int ty = 0; ty < 2; ++ty) {
+        for (int ty = 0; ty < TY; ++ty) {
             if (!col_ok[ty]) continue;
-            const int col = y0 + wy * 64 + ty * 32 + (lane & 31);
+            const int col = y0 + wcol0 + ty * 32 + (lane & 31);
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int row = x0 + wx * 64 + tx * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                const int row = x0 + wrow0 + tx * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
                 if (row < a.X) a.out[(int64_t)row * a.ld_out_x + (int64_t)col * a.ld_out_y] = res[tx][ty][v];
             }
         }
@@ -614,7 +609,7 @@ struct ConvPatchArgs {
 };
 
 // IPT: (channel, patch element) items a thread stages per stage; IPT * 512 >= nch * P.
-template <int IPT, bool Y16, bool NARROW>
+template <int IPT, bool Y16, int NTY>
 __global__ __launch_bounds__(kThreadsS) void conv_patch_kernel(const ConvPatchArgs a)
 {
     __shared__ __attribute__((aligned(16))) unsigned char sX[2][3 * kPieceBytes];
@@ -628,8 +623,10 @@ __global__ __launch_bounds__(kThreadsS) void conv_patch_kernel(const ConvPatchAr
     const int img = tile_x / a.tiles_per_image, oz0 = (tile_x % a.tiles_per_image) * a.R;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wx = NARROW ? wave & 1 : wave >> 2, wy = NARROW ? wave >> 1 : wave & 3;
-    const bool strip_live = !NARROW || y0 + wy * 64 < a.Y;
+    // wave -> sub-tile, as in mfma_split_gemm_kernel
+    constexpr int TX = NTY == 0 ? 2 : 1, TY = NTY == 0 ? 2 : NTY;
+    const int wrow0 = NTY == 0 ? (wave >> 2) * 64 : (wave & 3) * 32;
+    const int wcol0 = NTY == 0 ? (wave & 3) * 64 : (wave >> 2) * (32 * NTY);
     const int nstages = a.K / kStageK;
     const int npos = a.R * a.OW;                            // positions of a full tile (<= 128)
 
@@ -776,25 +773,25 @@ __global__ __launch_bounds__(kThreadsS) void conv_patch_kernel(const ConvPatchAr
         }
     };
 
-    f32x16 acc[2][2], res[2][2];
+    f32x16 acc[TX][TY], res[TX][TY];
 #pragma unroll
-    for (int p = 0; p < 2; ++p)
+    for (int p = 0; p < TX; ++p)
 #pragma unroll
-        for (int q = 0; q < 2; ++q)
+        for (int q = 0; q < TY; ++q)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 acc[p][q][v] = 0.f;
                 res[p][q][v] = 0.f;
             }
-    const float *srow[2];
+    const float *srow[TY];
 #pragma unroll
-    for (int ty = 0; ty < 2; ++ty)
-        srow[ty] = a.y_scales + (int64_t)min(y0 + wy * 64 + ty * 32 + (lane & 31), a.Y - 1) * a.lds_y;
-    auto apply_scale = [&](const float (&sc)[2]) {
+    for (int ty = 0; ty < TY; ++ty)
+        srow[ty] = a.y_scales + (int64_t)min(y0 + wcol0 + ty * 32 + (lane & 31), a.Y - 1) * a.lds_y;
+    auto apply_scale = [&](const float (&sc)[TY]) {
 #pragma unroll
-        for (int tx = 0; tx < 2; ++tx)
+        for (int tx = 0; tx < TX; ++tx)
 #pragma unroll
-            for (int ty = 0; ty < 2; ++ty)
+            for (int ty = 0; ty < TY; ++ty)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     res[tx][ty][v] = __builtin_fmaf(sc[ty], acc[tx][ty][v], res[tx][ty][v]);
@@ -802,56 +799,50 @@ __global__ __launch_bounds__(kThreadsS) void conv_patch_kernel(const ConvPatchAr
                 }
     };
 
-    float sc_seg[2] = {0.f, 0.f};
+    float sc_seg[TY] = {};
     auto run_stage = [&](int stage, const Staged &ready, Staged &incoming) {
         const int buf = stage & 1;
         fetch(incoming, stage + 4);
-        float sc16[2][2];
+        float sc16[2][TY];
         bool seg_last = false;
         if (Y16) {
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                for (int ty = 0; ty < 2; ++ty) sc16[ks][ty] = srow[ty][stage * 2 + ks];
+                for (int ty = 0; ty < TY; ++ty) sc16[ks][ty] = srow[ty][stage * 2 + ks];
         } else {
             seg_last = (stage + 1) % a.stages_per_yseg == 0;
             if (stage % a.stages_per_yseg == 0) {
 #pragma unroll
-                for (int ty = 0; ty < 2; ++ty) sc_seg[ty] = srow[ty][stage / a.stages_per_yseg];
+                for (int ty = 0; ty < TY; ++ty) sc_seg[ty] = srow[ty][stage / a.stages_per_yseg];
             }
         }
-        const unsigned char *px = &sX[buf][(wx * 64 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
-        const unsigned char *py = &sY[buf][(wy * 64 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
-        if (strip_live) {
+        const unsigned char *px = &sX[buf][(wrow0 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
+        const unsigned char *py = &sY[buf][(wcol0 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
 #pragma unroll
-            for (int ks = 0; ks < kStageK / 16; ++ks) {
-                bf16x8 fy[2];
+        for (int ks = 0; ks < kStageK / 16; ++ks) {
+            bf16x8 fy[TY];
 #pragma unroll
-                for (int ty = 0; ty < 2; ++ty)
-                    fy[ty] = *reinterpret_cast<const bf16x8 *>(py + ty * 32 * kRowBytes + ks * 32);
+            for (int ty = 0; ty < TY; ++ty)
+                fy[ty] = *reinterpret_cast<const bf16x8 *>(py + ty * 32 * kRowBytes + ks * 32);
 #pragma unroll
-                for (int p = 0; p < 3; ++p) {
-                    bf16x8 fx[2];
+            for (int p = 0; p < 3; ++p) {
+                bf16x8 fx[TX];
 #pragma unroll
-                    for (int tx = 0; tx < 2; ++tx)
-                        fx[tx] = *reinterpret_cast<const bf16x8 *>(px + p * kPieceBytes + tx * 32 * kRowBytes + ks * 32);
+                for (int tx = 0; tx < TX; ++tx)
+                    fx[tx] = *reinterpret_cast<const bf16x8 *>(px + p * kPieceBytes + tx * 32 * kRowBytes + ks * 32);
 #pragma unroll
-                    for (int tx = 0; tx < 2; ++tx)
+                for (int tx = 0; tx < TX; ++tx)
 #pragma unroll
-                        for (int ty = 0; ty < 2; ++ty)
-                            acc[tx][ty] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[tx], fy[ty], acc[tx][ty], 0, 0, 0);
-                }
-                if (Y16) apply_scale(sc16[ks]);
+                    for (int ty = 0; ty < TY; ++ty)
+                        acc[tx][ty] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[tx], fy[ty], acc[tx][ty], 0, 0, 0);
             }
-            gather(stage + 1);
-            park(ready, stage + 2);
-            write_table(stage + 2);
-            if (!Y16 && seg_last) apply_scale(sc_seg);
-        } else {
-            gather(stage + 1);
-            park(ready, stage + 2);
-            write_table(stage + 2);
+            if (Y16) apply_scale(sc16[ks]);
         }
+        gather(stage + 1);
+        park(ready, stage + 2);
+        write_table(stage + 2);
+        if (!Y16 && seg_last) apply_scale(sc_seg);
         __syncthreads();
     };
 
@@ -875,18 +866,18 @@ __global__ __launch_bounds__(kThreadsS) void conv_patch_kernel(const ConvPatchAr
 
     // ---- store: out is B x Y x OH x OW; each 32 x 32 accumulator tile is turned through LDS so that
     // lanes run along positions
-    if (!strip_live) return;   // the loop's last barrier has passed; the turn areas are per wave,
-                               // inside sX, which nobody multiplies from any more
+    // (the loop's last barrier has passed; the turn areas are per wave, inside sX, which nobody
+    // multiplies from any more)
     float *turn = reinterpret_cast<float *>(&sX[0][0]) + wave * (32 * 33);
 #pragma unroll
-    for (int tx = 0; tx < 2; ++tx) {
-        const int ml = wx * 64 + tx * 32 + (lane & 31);
+    for (int tx = 0; tx < TX; ++tx) {
+        const int ml = wrow0 + tx * 32 + (lane & 31);
         const int mc = min(ml, npos - 1);
         const int orow = mc / a.OW, oy = mc - orow * a.OW;
         const bool pos_ok = ml < npos && oz0 + orow < a.OH;
         float *dst = a.out + ((int64_t)img * a.Y * a.OH + (oz0 + orow)) * a.OW + oy;
 #pragma unroll
-        for (int ty = 0; ty < 2; ++ty) {
+        for (int ty = 0; ty < TY; ++ty) {
 #pragma unroll
             for (int v = 0; v < 16; ++v)
                 turn[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * 33 + (lane & 31)] = res[tx][ty][v];
@@ -896,7 +887,7 @@ __global__ __launch_bounds__(kThreadsS) void conv_patch_kernel(const ConvPatchAr
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 const int cl = 2 * j + (lane >> 5);
-                const int col = y0 + wy * 64 + ty * 32 + cl;
+                const int col = y0 + wcol0 + ty * 32 + cl;
                 const float val = turn[(lane & 31) * 33 + cl];
                 if (pos_ok && col < a.Y) dst[(int64_t)col * a.OHW] = val;
             }
@@ -922,15 +913,23 @@ hipError_t launch_split2_y(const Split2Args &a, int spy, unsigned grid, hipStrea
 template <int XMODE>
 hipError_t launch_mode(const SplitArgs &a, bool y16, unsigned grid, hipStream_t s)
 {
-    const bool narrow = a.Y <= kBY - 64;
-    if (y16 && narrow)
-        mfma_split_gemm_kernel<XMODE, true, true><<<dim3(grid), dim3(kThreadsS), 0, s>>>(a);
-    else if (y16)
-        mfma_split_gemm_kernel<XMODE, true, false><<<dim3(grid), dim3(kThreadsS), 0, s>>>(a);
-    else if (narrow)
-        mfma_split_gemm_kernel<XMODE, false, true><<<dim3(grid), dim3(kThreadsS), 0, s>>>(a);
+    const int nty = a.Y <= 64 ? 1 : a.Y <= 128 ? 2 : a.Y <= 192 ? 3 : 0;
+#define HBMM_SPLIT_LAUNCH(Y16V)                                                                        \
+    do {                                                                                               \
+        if (nty == 1)                                                                                  \
+            mfma_split_gemm_kernel<XMODE, Y16V, 1><<<dim3(grid), dim3(kThreadsS), 0, s>>>(a);          \
+        else if (nty == 2)                                                                             \
+            mfma_split_gemm_kernel<XMODE, Y16V, 2><<<dim3(grid), dim3(kThreadsS), 0, s>>>(a);          \
+        else if (nty == 3)                                                                             \
+            mfma_split_gemm_kernel<XMODE, Y16V, 3><<<dim3(grid), dim3(kThreadsS), 0, s>>>(a);          \
+        else                                                                                           \
+            mfma_split_gemm_kernel<XMODE, Y16V, 0><<<dim3(grid), dim3(kThreadsS), 0, s>>>(a);          \
+    } while (0)
+    if (y16)
+        HBMM_SPLIT_LAUNCH(true);
     else
-        mfma_split_gemm_kernel<XMODE, false, false><<<dim3(grid), dim3(kThreadsS), 0, s>>>(a);
+        HBMM_SPLIT_LAUNCH(false);
+#undef HBMM_SPLIT_LAUNCH
     return hipGetLastError();
 }
 
@@ -1028,13 +1027,17 @@ static bool try_launch_conv_patch(const ConvActivations &x, const SplitGemmOpera
     a.last_elem = (uint32_t)(g.B * g.C * g.H * g.W - 1);
     a.q32 = kStageK / KK; a.r32 = kStageK % KK; a.magic_kw = 65536 / g.KW + 1;
     const dim3 grid((unsigned)(per_xcd * kNumXcdS)), block(kThreadsS);
-    const bool narrow = y.rows <= kBY - 64;
+    const int nty = y.rows <= 64 ? 1 : y.rows <= 128 ? 2 : y.rows <= 192 ? 3 : 0;
 #define HBMM_PATCH_LAUNCH(I)                                                \
     do {                                                                    \
-        if (narrow)                                                         \
-            conv_patch_kernel<I, false, true><<<grid, block, 0, s>>>(a);    \
+        if (nty == 1)                                                       \
+            conv_patch_kernel<I, false, 1><<<grid, block, 0, s>>>(a);       \
+        else if (nty == 2)                                                  \
+            conv_patch_kernel<I, false, 2><<<grid, block, 0, s>>>(a);       \
+        else if (nty == 3)                                                  \
+            conv_patch_kernel<I, false, 3><<<grid, block, 0, s>>>(a);       \
         else                                                                \
-            conv_patch_kernel<I, false, false><<<grid, block, 0, s>>>(a);   \
+            conv_patch_kernel<I, false, 0><<<grid, block, 0, s>>>(a);       \
     } while (0)
     if (ipt <= 2)
         HBMM_PATCH_LAUNCH(2);
