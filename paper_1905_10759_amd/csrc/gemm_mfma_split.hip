@@ -113,6 +113,7 @@ struct SplitArgs {
     int32_t X, Y, K;
     int32_t log2_beta_x;         // packed modes
     int32_t stages_per_yseg;     // beta_y / 32 (beta_y >= 32); unused when beta_y = 16
+    int32_t log2_stages_per_yseg;
     int32_t tiles_y, tiles_total, slots_per_xcd;
     // kXConv: X row m = (b * OH + oz) * OW + oy is an output position, k = (c * KH + dz) * KW + dy a
     // filter tap; X~[m, k] is the binarised activation at (b, c, oz*stride - pad + dz,
@@ -353,11 +354,12 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
 #pragma unroll
                 for (int ty = 0; ty < TY; ++ty) sc16[ks][ty] = srow[ty][stage * 2 + ks];
         } else {
-            seg_last = (stage + 1) % a.stages_per_yseg == 0;
-            if (stage % a.stages_per_yseg == 0) {
+            // stages per Y segment is a power of two.  The scale is re-read every stage rather than
+            // at segment starts only: a load under a condition hides the number of outstanding loads
+            // from the compiler, which then waits for all of them, prefetches included.
+            seg_last = ((stage + 1) & (a.stages_per_yseg - 1)) == 0;
 #pragma unroll
-                for (int ty = 0; ty < TY; ++ty) sc_seg[ty] = srow[ty][stage / a.stages_per_yseg];
-            }
+            for (int ty = 0; ty < TY; ++ty) sc_seg[ty] = srow[ty][stage >> a.log2_stages_per_yseg];
         }
         const unsigned char *px = &sX[buf][(wrow0 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
         const unsigned char *py = &sY[buf][(wcol0 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
@@ -599,7 +601,7 @@ struct ConvPatchArgs {
     float *out;
     int32_t ldw_y, lds_y;
     int32_t Y, K;
-    int32_t log2_beta_x, stages_per_yseg;
+    int32_t log2_beta_x, stages_per_yseg, log2_stages_per_yseg;
     int32_t C, H, W, HW, OH, OW, OHW, KW, KK, stride, pad;
     int32_t R, tiles_per_image, tiles_y, tiles_total, slots_per_xcd;
     int32_t PW, P, PS, NS;
@@ -740,17 +742,18 @@ __global__ __launch_bounds__(kThreadsS) void conv_patch_kernel(const ConvPatchAr
     };
 
     // k table: thread t < 32 follows k = 32 j + t through the stages
-    int tc = tid / a.KK, tr = tid % a.KK;
+    int tslot = (tid / a.KK) % a.NS, tr = tid % a.KK;   // ring slot of the channel, tap
     auto write_table = [&](int j) {
         if (tid < kStageK) {
             const int dz = (tr * a.magic_kw) >> 16, dy = tr - dz * a.KW;
-            sKoff[j & 3][tid] = (uint32_t)((tc % a.NS) * a.PS + dz * a.PW + dy) * 2u;
-            tc += a.q32;
+            sKoff[j & 3][tid] = (uint32_t)(tslot * a.PS + dz * a.PW + dy) * 2u;
+            tslot += a.q32;
             tr += a.r32;
             if (tr >= a.KK) {
                 tr -= a.KK;
-                tc += 1;
+                tslot += 1;
             }
+            tslot -= tslot >= a.NS ? a.NS : 0;   // q32 + 1 < NS: one step back is enough
         }
     };
 
@@ -811,11 +814,12 @@ __global__ __launch_bounds__(kThreadsS) void conv_patch_kernel(const ConvPatchAr
 #pragma unroll
                 for (int ty = 0; ty < TY; ++ty) sc16[ks][ty] = srow[ty][stage * 2 + ks];
         } else {
-            seg_last = (stage + 1) % a.stages_per_yseg == 0;
-            if (stage % a.stages_per_yseg == 0) {
+            // stages per Y segment is a power of two.  The scale is re-read every stage rather than
+            // at segment starts only: a load under a condition hides the number of outstanding loads
+            // from the compiler, which then waits for all of them, prefetches included.
+            seg_last = ((stage + 1) & (a.stages_per_yseg - 1)) == 0;
 #pragma unroll
-                for (int ty = 0; ty < TY; ++ty) sc_seg[ty] = srow[ty][stage / a.stages_per_yseg];
-            }
+            for (int ty = 0; ty < TY; ++ty) sc_seg[ty] = srow[ty][stage >> a.log2_stages_per_yseg];
         }
         const unsigned char *px = &sX[buf][(wrow0 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
         const unsigned char *py = &sY[buf][(wcol0 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
@@ -981,6 +985,7 @@ hipError_t launch_mfma_split_gemm(const SplitGemmOperand &x, const SplitGemmOper
     a.X = (int32_t)x.rows; a.Y = (int32_t)y.rows; a.K = (int32_t)K;
     a.log2_beta_x = ilog2s(x.beta);
     a.stages_per_yseg = y.beta >= 32 ? y.beta / kStageK : 1;
+    a.log2_stages_per_yseg = ilog2s(a.stages_per_yseg);
     const int64_t tiles_x = (x.rows + kBX - 1) / kBX, tiles_y = (y.rows + kBY - 1) / kBY;
     const int64_t total = tiles_x * tiles_y;
     const int64_t per_xcd = (total + kNumXcdS - 1) / kNumXcdS;
@@ -1018,6 +1023,7 @@ static bool try_launch_conv_patch(const ConvActivations &x, const SplitGemmOpera
     a.y_bits = y.bits; a.y_scales = y.scales; a.ldw_y = (int32_t)y.ldw; a.lds_y = (int32_t)y.lds;
     a.out = out; a.Y = (int32_t)y.rows; a.K = (int32_t)(g.C * KK);
     a.stages_per_yseg = y.beta >= 32 ? y.beta / kStageK : 1;
+    a.log2_stages_per_yseg = ilog2s(a.stages_per_yseg);
     a.C = (int32_t)g.C; a.H = (int32_t)g.H; a.W = (int32_t)g.W; a.HW = (int32_t)(g.H * g.W);
     a.OH = (int32_t)OH; a.OW = (int32_t)OW; a.OHW = (int32_t)(OH * OW);
     a.KW = g.KW; a.KK = KK; a.stride = g.stride; a.pad = g.pad;
@@ -1069,6 +1075,7 @@ hipError_t launch_mfma_split_conv(const ConvActivations &x, const SplitGemmOpera
     a.out = out;
     a.X = (int32_t)M; a.Y = (int32_t)y.rows; a.K = (int32_t)K;
     a.stages_per_yseg = y.beta >= 32 ? y.beta / kStageK : 1;
+    a.log2_stages_per_yseg = ilog2s(a.stages_per_yseg);
     a.cv_c = (int32_t)g.C; a.cv_h = (int32_t)g.H; a.cv_w = (int32_t)g.W; a.cv_hw = (int32_t)(g.H * g.W);
     a.cv_ow = (int32_t)OW; a.cv_ohw = (int32_t)(OH * OW);
     a.cv_kw = g.KW; a.cv_kk = g.KH * g.KW; a.cv_stride = g.stride; a.cv_pad = g.pad;
