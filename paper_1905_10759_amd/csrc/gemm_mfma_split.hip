@@ -345,7 +345,8 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
     // `incoming`, and park `ready` (stage + 1, requested three stages ago) in the other buffer.
     auto run_stage = [&](int stage, const Staged &ready, Staged &incoming) {
         const int buf = stage & 1;
-        fetch(incoming, stage + 3);
+        // The scales are requested before the prefetch: loads return in order, so waiting for the
+        // scales at the end of the stage then leaves the prefetch in flight.
         float sc16[2][TY];
         bool seg_last = false;
         if (Y16) {
@@ -361,6 +362,7 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
 #pragma unroll
             for (int ty = 0; ty < TY; ++ty) sc_seg[ty] = srow[ty][stage >> a.log2_stages_per_yseg];
         }
+        fetch(incoming, stage + 3);
         const unsigned char *px = &sX[buf][(wrow0 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
         const unsigned char *py = &sY[buf][(wcol0 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
 #pragma unroll
@@ -805,7 +807,8 @@ __global__ __launch_bounds__(kThreadsS) void conv_patch_kernel(const ConvPatchAr
     float sc_seg[TY] = {};
     auto run_stage = [&](int stage, const Staged &ready, Staged &incoming) {
         const int buf = stage & 1;
-        fetch(incoming, stage + 4);
+        // The scales are requested before the prefetch: loads return in order, so waiting for the
+        // scales at the end of the stage then leaves the prefetch in flight.
         float sc16[2][TY];
         bool seg_last = false;
         if (Y16) {
@@ -821,6 +824,7 @@ __global__ __launch_bounds__(kThreadsS) void conv_patch_kernel(const ConvPatchAr
 #pragma unroll
             for (int ty = 0; ty < TY; ++ty) sc_seg[ty] = srow[ty][stage >> a.log2_stages_per_yseg];
         }
+        fetch(incoming, stage + 4);
         const unsigned char *px = &sX[buf][(wrow0 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
         const unsigned char *py = &sY[buf][(wcol0 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
 #pragma unroll
