@@ -82,7 +82,12 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
     constexpr int kWordsPerGran = G / 32;                       // 1, 2, 4, 8
     constexpr int kGranPerChunk = kCK / kWordsPerGran;          // 16, 8, 4, 2
     constexpr int kSteps = kCK / kStep;                         // 8
-    constexpr int kSeed = INTEGER ? 0 : -(G / 2);
+    // Scaled mode: a segment's accumulator starts at the bit pattern of 2^23 and v_bcnt adds the
+    // Hamming count to it as an integer, so the register always holds the *float* 2^23 + hamming
+    // (exact: counts are far below 2^23).  The epilogue gets hamming - G/2 with one fp32 subtraction,
+    // which issues at twice the rate of the integer-to-float conversion it replaces.
+    constexpr int kSeed = INTEGER ? 0 : 0x4b000000;
+    constexpr float kSeedValue = 8388608.0f + (float)(G / 2);
 
     __shared__ __attribute__((aligned(16))) uint32_t s_bits[2][kTileP * kBitsStride];
     constexpr int kScaleStrideP = kGranPerChunk + 1;   // odd => conflict-free b32 reads
@@ -362,7 +367,7 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
             sq[4 * v + 3] = t.w;
         }
     };
-    // Epilogue of one segment: res += acc * (-2 sP * sQ)  (acc = hamming - G/2, so -2 acc = d).  The
+    // Epilogue of one segment: res += (hamming - G/2) * (-2 sP * sQ)  (-2 (hamming - G/2) = d).  The
     // scale product is formed first so that the result does not depend on which operand is P.
     auto epilogue = [&](const float (&sp)[kTP], const float (&sq)[kTQ]) {
 #pragma unroll
@@ -370,7 +375,7 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
             const float sp2 = -2.0f * sp[i];
 #pragma unroll
             for (int q = 0; q < kTQ; ++q)
-                res[i][q] = __builtin_fmaf((float)acc[i][q], sp2 * sq[q], res[i][q]);
+                res[i][q] = __builtin_fmaf(__builtin_bit_cast(float, acc[i][q]) - kSeedValue, sp2 * sq[q], res[i][q]);
         }
         // Pin the results here: without a use at this point the optimiser sinks the whole epilogue
         // to the end of the chunk and keeps every segment's accumulators alive until then.
