@@ -123,6 +123,52 @@ def test_validation_rejects_before_launch(lib):
     assert d(fake, 32, fake, 64, 0, 8, 8, 64, fake, 8, None) == -1
 
 
+def test_validation_of_the_fused_tensor_and_convolution_entry_points(lib):
+    """Only calls that must fail (or are empty) before anything is launched: the pointers are fake."""
+    i64, i32, p = C.c_int64, C.c_int32, C.c_void_p
+    fake = 0x1000
+    gf = lib.hbmm_gemm_fused
+    gf.argtypes = [p, i64, i32, p, p, i64, i64, i32, i64, i64, i64, p, i64, p]
+    assert gf(fake, 64, 32, fake, fake, 4, 2, 32, 8, 200, 64, fake, 200, None) == -2     # N > 128
+    assert gf(fake, 64, 16, fake, fake, 4, 2, 32, 8, 8, 64, fake, 8, None) == -2         # beta_a < 32
+    assert gf(fake, 62, 32, fake, fake, 4, 2, 32, 8, 8, 64, fake, 8, None) == -1         # lda < K
+    assert gf(None, 64, 32, fake, fake, 4, 2, 32, 8, 8, 64, fake, 8, None) == -1
+    assert gf(fake, 64, 32, fake, fake, 4, 2, 32, 0, 8, 64, fake, 8, None) == 0
+
+    qt = lib.hbmm_quantize_pack_tensor
+    qt.argtypes = [p, i64, i32, p, p, p]
+    assert qt(fake, 120, 4, fake, fake, None) == -2          # not a multiple of 128
+    assert qt(fake, 256, 3, fake, fake, None) == -2          # beta not a power of two
+    assert qt(fake, 128, 256, fake, fake, None) == -2        # beta does not divide the 128-element view
+    assert qt(None, 1024, 4, fake, fake, None) == -1
+    assert qt(fake, -1, 4, fake, fake, None) == -1
+    assert qt(None, 0, 4, None, None, None) == 0
+
+    cv = lib.hbmm_conv2d
+    cv.argtypes = [p, p, i32, p, p, i64, i64, i32, i64, i64, i64, i64, i64, i32, i32, i32, i32, p, i32, p]
+    ok = dict(ab=fake, asc=fake, ba=4, wb=fake, ws=fake, ldw=12, lds=9, bw=32, B=1, C=32, H=8, W=8, N=8, KH=3, KW=3,
+              stride=1, pad=1, out=fake, algo=0)
+
+    def conv(**kw):
+        a = {**ok, **kw}
+        return cv(a["ab"], a["asc"], a["ba"], a["wb"], a["ws"], a["ldw"], a["lds"], a["bw"], a["B"], a["C"], a["H"],
+                  a["W"], a["N"], a["KH"], a["KW"], a["stride"], a["pad"], a["out"], a["algo"], None)
+
+    assert conv(ba=16) == -2                 # beta_a does not divide the width
+    assert conv(bw=8, lds=36) == -2          # filter segments shorter than 16
+    assert conv(C=20) == -2                  # C*KH*KW not a multiple of 32
+    assert conv(bw=64) == -2                 # 288 is not a multiple of 64
+    assert conv(KH=7, KW=7, pad=3) == -2     # more than 32 taps
+    assert conv(stride=0) == -1
+    assert conv(algo=2) == -1
+    assert conv(out=None) == -1
+    assert conv(ab=None) == -1
+    assert conv(lds=8) == -1                 # lds_w < K / beta_w
+    assert conv(ldw=8) == -1                 # ldw_w < K / 32 rounded up to a multiple of 4
+    assert conv(H=1, pad=0) == -1            # window larger than the padded input
+    assert conv(B=0) == 0 and conv(N=0) == 0
+
+
 def test_compiled_gemm_keeps_inflight_scalar_registers_untouched():
     """The popcount GEMM waits for its asm-issued scalar loads by hand; the compiled ISA must not touch
     their destination registers before that wait (checked on freshly compiled gfx950 assembly)."""
