@@ -143,7 +143,9 @@ int hbmm_quantize_pack_tensor(const float *x, int64_t count, int32_t beta, uint3
  *   out[b, n, oz, oy] = sum_{c, dz, dy} A~[b, c, oz*stride - pad + dz, oy*stride - pad + dy] * W~[n, c, dz, dy]
  * with zero contribution from positions outside the input (zero padding).
  *   a_bits, a_scales   the activation tensor B x C x H x W as written by hbmm_quantize_pack_tensor
- *                      with beta_a (beta_a in 2 .. 256 must divide W).
+ *                      with beta_a (beta_a in 2 .. 256 must divide W).  beta_a = 1: the activations are
+ *                      not binarised (binary-weight layer); a_bits must be NULL and a_scales is the
+ *                      fp32 tensor itself.
  *   w_bits, w_scales   the filters N x C x KH x KW as written by hbmm_quantize_pack (layout 0) on the
  *                      N x (C*KH*KW) matrix with beta_w; ldw_w / lds_w its leading dimensions.
  *                      beta_w in 16 .. 256.

@@ -287,7 +287,7 @@ int hbmm_conv2d(const uint32_t *a_bits, const float *a_scales, int32_t beta_a, c
     if (B > kMaxDim || C > kMaxDim || H > kMaxDim || W > kMaxDim || N > kMaxDim) return HBMM_EINVAL;
     if (KH > 32 || KW > 32 || pad > 32 || stride > 32) return HBMM_EINVAL;
     if (beta_a < 1 || beta_w < 1) return HBMM_EINVAL;
-    if (!supported_pack_beta(beta_a) || !supported_pack_beta(beta_w) || beta_w < 16) return HBMM_EUNSUPPORTED;
+    if (!(beta_a == 1 || supported_pack_beta(beta_a)) || !supported_pack_beta(beta_w) || beta_w < 16) return HBMM_EUNSUPPORTED;
     if (H + 2 * pad < KH || W + 2 * pad < KW) return HBMM_EINVAL;
     const int64_t OH = (H + 2 * pad - KH) / stride + 1, OW = (W + 2 * pad - KW) / stride + 1;
     const int64_t K = C * KH * KW;
@@ -297,7 +297,8 @@ int hbmm_conv2d(const uint32_t *a_bits, const float *a_scales, int32_t beta_a, c
     if (C == 0 || H == 0 || W == 0) return HBMM_EINVAL;
     if (W % beta_a != 0 || K % beta_w != 0 || K % 32 != 0 || KH * KW > 32) return HBMM_EUNSUPPORTED;
     if (!out || !aligned16(out)) return HBMM_EINVAL;
-    if (!a_bits || !aligned16(a_bits) || !a_scales || !aligned16(a_scales)) return HBMM_EINVAL;
+    if (!a_scales || !aligned16(a_scales)) return HBMM_EINVAL;
+    if (beta_a == 1 ? a_bits != nullptr : (!a_bits || !aligned16(a_bits))) return HBMM_EINVAL;
     if (!w_scales || !aligned16(w_scales) || lds_w < K / beta_w) return HBMM_EINVAL;
     if (int rc = check_packed(w_bits, N, K, ldw_w)) return rc;
     hbmm::ConvActivations x{a_bits, a_scales, beta_a};

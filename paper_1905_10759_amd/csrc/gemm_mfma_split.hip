@@ -123,6 +123,7 @@ struct SplitArgs {
     int32_t cv_c, cv_h, cv_w, cv_hw, cv_ow, cv_ohw, cv_kw, cv_kk, cv_stride, cv_pad;
     int32_t cv_magic_kk, cv_magic_kw;   // 65536 / d + 1: (t * magic) >> 16 == t / d for t < 64, d <= 32
     int32_t cv_q32, cv_r32;             // 32 div KK, 32 mod KK: how (c, tap) moves from stage to stage
+    uint32_t cv_sign;                   // 0x80000000; 0 when the tensor is unquantised (see launch_mfma_split_conv)
 };
 
 // NTY: 0 for the general case; 1, 2 or 3 when Y has at most 64, 128 or 192 rows (one tile), see below.
@@ -269,7 +270,7 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
                 conv_elem(pc0, pr0, i, e, keep);
                 // value = +-scale (bit 0 = negative), or 0 for a tap that does not exist; the pieces
                 // of a negative value are the negated pieces of its magnitude
-                const uint32_t minus = ~(st.cw[i] >> (e & 31)) << 31;
+                const uint32_t minus = (~(st.cw[i] >> (e & 31)) << 31) & a.cv_sign;
                 const uint32_t value = (__builtin_bit_cast(uint32_t, st.cs[i]) & keep) | minus;
                 split3(__builtin_bit_cast(float, value), h[i], m[i], l[i]);
             }
@@ -608,6 +609,7 @@ struct ConvPatchArgs {
     int32_t R, tiles_per_image, tiles_y, tiles_total, slots_per_xcd;
     int32_t PW, P, PS, NS;
     int32_t nch;                 // most channels a stage can bring in: ceil(32 / KK)
+    uint32_t sign;               // 0x80000000; 0 when the tensor is unquantised (see launch_mfma_split_conv)
     uint32_t last_elem;          // B*C*H*W - 1
     int32_t q32, r32, magic_kw;
 };
@@ -710,7 +712,7 @@ __global__ __launch_bounds__(kThreadsS) void conv_patch_kernel(const ConvPatchAr
 #pragma unroll
         for (int j = 0; j < IPT; ++j) {
             const uint32_t e = (pe0[j] + first_off) & pkeep[j];
-            const uint32_t minus = ~(st.pw[j] >> (e & 31)) << 31;
+            const uint32_t minus = (~(st.pw[j] >> (e & 31)) << 31) & a.sign;
             const uint32_t value = (__builtin_bit_cast(uint32_t, st.ps[j]) & pkeep[j]) | minus;
             uint32_t h, m, l;
             split3(__builtin_bit_cast(float, value), h, m, l);
@@ -1023,7 +1025,11 @@ static bool try_launch_conv_patch(const ConvActivations &x, const SplitGemmOpera
     const int64_t total = tiles_x * tiles_y, per_xcd = (total + kNumXcdS - 1) / kNumXcdS;
     if (per_xcd * kNumXcdS > 0x7fffffffLL) return false;
     ConvPatchArgs a{};
-    a.x_bits = x.bits; a.x_scales = x.scales; a.log2_beta_x = ilog2s(x.beta);
+    // beta = 1: `scales` is the unquantised tensor.  It then plays both parts: read as the "scale" of
+    // element e (segment length 1) it is the value itself, sign included, and the sign taken from the
+    // bit word is switched off; the word loads still happen and are pointed at the same memory.
+    a.x_bits = x.beta == 1 ? reinterpret_cast<const uint32_t *>(x.scales) : x.bits;
+    a.x_scales = x.scales; a.log2_beta_x = ilog2s(x.beta); a.sign = x.beta == 1 ? 0u : 0x80000000u;
     a.y_bits = y.bits; a.y_scales = y.scales; a.ldw_y = (int32_t)y.ldw; a.lds_y = (int32_t)y.lds;
     a.out = out; a.Y = (int32_t)y.rows; a.K = (int32_t)(g.C * KK);
     a.stages_per_yseg = y.beta >= 32 ? y.beta / kStageK : 1;
@@ -1074,7 +1080,8 @@ hipError_t launch_mfma_split_conv(const ConvActivations &x, const SplitGemmOpera
         if (try_launch_conv_patch(x, y, g, OH, OW, out, s, err)) return err;
     }
     SplitArgs a{};
-    a.x_bits = x.bits; a.x_scales = x.scales; a.log2_beta_x = ilog2s(x.beta);
+    a.x_bits = x.beta == 1 ? reinterpret_cast<const uint32_t *>(x.scales) : x.bits;   // as in the patch kernel
+    a.x_scales = x.scales; a.log2_beta_x = ilog2s(x.beta); a.cv_sign = x.beta == 1 ? 0u : 0x80000000u;
     a.y_bits = y.bits; a.y_scales = y.scales; a.ldw_y = (int32_t)y.ldw; a.lds_y = (int32_t)y.lds;
     a.out = out;
     a.X = (int32_t)M; a.Y = (int32_t)y.rows; a.K = (int32_t)K;

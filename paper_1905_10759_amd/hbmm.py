@@ -222,9 +222,11 @@ def quantize_pack_tensor(x: torch.Tensor, beta: int):
 
 def conv2d(a_bits, a_scales, beta_a: int, shape, w_bits, w_scales, beta_w: int, kernel, stride: int = 1,
            pad: int = 0, out: torch.Tensor | None = None, algo: int = 0) -> torch.Tensor:
-    """hbmm_conv2d: activations (B, C, H, W) = `shape` packed by quantize_pack_tensor, filters
-    (N, C, KH, KW) packed by quantize_pack on the N x (C*KH*KW) matrix; `kernel` = (KH, KW)."""
-    _dev(a_bits, torch.int32, "a_bits")
+    """hbmm_conv2d: activations (B, C, H, W) = `shape` packed by quantize_pack_tensor (or, with
+    beta_a = 1, a_bits=None and a_scales = the contiguous fp32 tensor), filters (N, C, KH, KW) packed
+    by quantize_pack on the N x (C*KH*KW) matrix; `kernel` = (KH, KW)."""
+    if a_bits is not None:
+        _dev(a_bits, torch.int32, "a_bits")
     _dev(a_scales, torch.float32, "a_scales")
     _dev(w_bits, torch.int32, "w_bits")
     _dev(w_scales, torch.float32, "w_scales")
@@ -233,8 +235,8 @@ def conv2d(a_bits, a_scales, beta_a: int, shape, w_bits, w_scales, beta_w: int, 
     N = w_bits.shape[0]
     OH, OW = (H + 2 * pad - KH) // stride + 1, (W + 2 * pad - KW) // stride + 1
     if out is None:
-        out = torch.empty((B, N, OH, OW), dtype=torch.float32, device=a_bits.device)
-    rc = lib.hbmm_conv2d(a_bits.data_ptr(), a_scales.data_ptr(), beta_a, w_bits.data_ptr(), w_scales.data_ptr(),
+        out = torch.empty((B, N, OH, OW), dtype=torch.float32, device=a_scales.device)
+    rc = lib.hbmm_conv2d(a_bits.data_ptr() if a_bits is not None else 0, a_scales.data_ptr(), beta_a, w_bits.data_ptr(), w_scales.data_ptr(),
                          w_bits.stride(0) if N > 1 else w_bits.shape[1],
                          w_scales.stride(0) if N > 1 else max(w_scales.shape[1], 1), beta_w, B, Cc, H, W, N, KH, KW,
                          stride, pad, out.data_ptr(), algo, _stream())

@@ -482,3 +482,18 @@ def test_conv2d_unsupported():
         hbmm.conv2d(ab, asc, 4, A.shape, wb8, ws8, 8, (3, 3), 1, 1)     # beta_w < 16
     with pytest.raises(hbmm.HbmmError):
         hbmm.quantize_pack_tensor(dev(synth.normal(1, (3, 5, 8))), 4)   # 120 elements: not a multiple of 128
+
+
+@pytest.mark.parametrize("algo", [0, 1])
+@pytest.mark.parametrize("case", [(2, 32, 8, 8, 40, 3, 3, 1, 1, 32), (1, 64, 12, 12, 70, 1, 1, 1, 0, 64),
+                                  (2, 32, 9, 16, 24, 3, 3, 2, 1, 32)], ids=str)
+def test_conv2d_unquantised_activations(case, algo):
+    """beta_a = 1 (binary-weight layer): activations stay fp32, filters are binarised."""
+    B, C, H, W, N, KH, KW, stride, pad, beta_w = case
+    A = synth.normal(91 + C + N, (B, C, H, W))
+    A[0, 0, 0, :3] = [0.0, -0.0, 1e-30]
+    Wf = synth.normal(92 + C, (N, C, KH, KW)).astype(np.float32)
+    ref, T = oracle.hbmm_conv2d(A, Wf, 1, beta_w, stride, pad, want_T=True)
+    wb, ws = hbmm.quantize_pack(dev(Wf.reshape(N, -1)), beta_w)
+    out = hbmm.conv2d(None, dev(A), 1, A.shape, wb, ws, beta_w, (KH, KW), stride, pad, algo=algo)
+    assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d beta_a=1 {case} algo {algo}")
