@@ -277,6 +277,14 @@ def extras(w, A, B, a_bits, a_s, b_bits, b_s, C, torch, hbmm, synth, args):
             res["hbmm_gemm_int8_mfma"] = {"ms": float(sum(ts) / len(ts)), "gops": gops(sum(ts) / len(ts))}
         except hbmm.HbmmError as e:
             res["hbmm_gemm_int8_mfma"] = {"error": str(e)}
+        try:
+            ts = time_loop(lambda: hbmm.gemm(a_bits, a_s, w.beta_a, b_bits, b_s, w.beta_w, w.K, hbmm.ALGO_MFMA_FP4, C),
+                           steps, warm, torch)
+            ms4 = float(sum(ts) / len(ts))
+            # dense fp4 MFMA peak 10.1 PFLOP/s; 2MNK flops per launch
+            res["hbmm_gemm_fp4_mfma"] = {"ms": ms4, "gops": gops(ms4), "frac_of_fp4_mfma_peak": gops(ms4) / 10.1e6}
+        except hbmm.HbmmError as e:
+            res["hbmm_gemm_fp4_mfma"] = {"error": str(e)}
         Ab, Bb = A.to(torch.bfloat16), B.to(torch.bfloat16)
         try:
             ts = time_loop(lambda: hbmm.dense_ref_gemm(Ab, Bb, C), steps, warm, torch)

@@ -114,8 +114,10 @@ int hbmm_binarize_backward(const float *x, const float *grad_out, int64_t rows, 
  *   C                 out, M x N fp32, leading dimension ldc >= N.
  *   algo              0: the method's kernel as described above.
  *                     1: (both beta >= 32 only) the same d[m, n, g] from int8 +-1 matrix-core (MFMA)
- *                        products, kept as a comparison point; same epilogue, same result up to fp32
- *                        rounding order.
+ *                        products, kept as a comparison point; same epilogue, bit-identical result.
+ *                     2: (both beta >= 64 only) the same d[m, n, g] from 4-bit-float +-1 matrix-core
+ *                        products (the operands are expanded from their bits on chip); same epilogue,
+ *                        bit-identical result.
  *
  * M == 0 or N == 0 is a valid no-op; K == 0 writes zeros.
  */

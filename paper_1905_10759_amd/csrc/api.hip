@@ -167,12 +167,13 @@ int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int6
 {
     if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim) return HBMM_EINVAL;
     if (beta_a < 1 || beta_w < 1) return HBMM_EINVAL;
-    if (algo != 0 && algo != 1) return HBMM_EUNSUPPORTED;
+    if (algo != 0 && algo != 1 && algo != 2) return HBMM_EUNSUPPORTED;
     const bool word_a = supported_beta(beta_a), word_w = supported_beta(beta_w);   // 32 .. 256
     if (!(beta_a == 1 || supported_pack_beta(beta_a)) || !(beta_w == 1 || supported_pack_beta(beta_w)))
         return HBMM_EUNSUPPORTED;
     if (K % beta_w != 0 || K % beta_a != 0 || K % 32 != 0) return HBMM_EUNSUPPORTED;
-    if (algo == 1 && !(word_a && word_w)) return HBMM_EUNSUPPORTED;
+    if (algo != 0 && !(word_a && word_w)) return HBMM_EUNSUPPORTED;
+    if (algo == 2 && (beta_a < 64 || beta_w < 64)) return HBMM_EUNSUPPORTED;   // one fp4 MFMA step is 64 bits of K
     // Two unquantised operands are a plain dense product (hbmm_dense_ref_gemm), and an unquantised
     // operand needs the other one to keep its +-1 form (segment of at least 16).
     if ((beta_a == 1 && beta_w < 16) || (beta_w == 1 && beta_a < 16)) return HBMM_EUNSUPPORTED;
@@ -200,6 +201,9 @@ int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int6
     if (algo == 1)
         return from_hip(hbmm::launch_mfma_i8_gemm(a_bits, a_scales, ldw_a, lds_a, beta_a, b_bits, b_scales,
                                                   ldw_b, lds_b, beta_w, M, N, K, C, ldc, s));
+    if (algo == 2)
+        return from_hip(hbmm::launch_mfma_fp4_gemm(a_bits, a_scales, ldw_a, lds_a, beta_a, b_bits, b_scales,
+                                                   ldw_b, lds_b, beta_w, M, N, K, C, ldc, s));
 
     const int G = beta_a < beta_w ? beta_a : beta_w;
     hbmm::PopcountGemmArgs g{};

@@ -156,6 +156,34 @@ def test_gemm_mfma_i8_mixed_and_ragged(beta_a, beta_w, K):
     run_gemm_case(synth.normal(510, (150, K)), synth.normal(511, (270, K), std=0.04), beta_a, beta_w, algo=1)
 
 
+@pytest.mark.parametrize("beta", [64, 128, 256])
+@pytest.mark.parametrize("M,N,K", [(64, 64, 512), (300, 200, 1024), (129, 257, 1536), (5, 3, 256), (260, 140, 4608), (513, 130, 768)])
+def test_gemm_mfma_fp4_equal_beta(beta, M, N, K):
+    """The 4-bit-float matrix-core variant: +-1 products are exact, segment sums are exact small
+    integers in fp32 and the epilogue is the popcount kernel's, so the result is the same bit for bit."""
+    A, B = synth.normal(600 + M, (M, K)), synth.uniform_pm1(601 + N, (N, K))
+    run_gemm_case(A, B, beta, beta, algo=2)
+    ab, as_ = hbmm.quantize_pack(dev(A), beta)
+    bb, bs = hbmm.quantize_pack(dev(B), beta)
+    assert torch.equal(hbmm.gemm(ab, as_, beta, bb, bs, beta, K, algo=0), hbmm.gemm(ab, as_, beta, bb, bs, beta, K, algo=2))
+
+
+@pytest.mark.parametrize("beta_a,beta_w,K", [(64, 128, 1280), (256, 64, 1280), (128, 64, 1280), (64, 256, 1280),
+                                             (64, 64, 576), (128, 128, 640), (64, 64, 64), (64, 64, 1984)])
+def test_gemm_mfma_fp4_mixed_and_ragged(beta_a, beta_w, K):
+    """Mixed segment lengths, and K whose word count is not a multiple of the 8-word stage (the
+    stage's tail words lie past the row or are pad words: they must not count)."""
+    run_gemm_case(synth.normal(610, (150, K)), synth.normal(611, (270, K), std=0.04), beta_a, beta_w, algo=2)
+
+
+def test_gemm_mfma_fp4_unsupported():
+    A, B = synth.normal(1, (8, 64)), synth.normal(2, (8, 64))
+    ab, as_ = hbmm.quantize_pack(dev(A), 32)
+    bb, bs = hbmm.quantize_pack(dev(B), 64)
+    with pytest.raises(hbmm.HbmmError):
+        hbmm.gemm(ab, as_, 32, bb, bs, 64, 64, algo=2)
+
+
 def test_gemm_against_dense_f64_path_end_to_end():
     """Whole hot path on the GPU (pack A, pack B, gemm) against the dense double-precision oracle
     that materialises delta (.) Sign(.) and multiplies.  GPU-made scales differ from the oracle's
