@@ -11,9 +11,11 @@
 // feeds row (l mod 32) and the 32 consecutive k at 32 * (l div 32) -- exactly one packed word of
 // that row -- as 32 nibbles in four registers, k ascending from the low nibble of the first one.
 //
-// Expansion of 8 sign bits into one register of 8 nibbles, five vector instructions: the byte is
-// spread into four 2-bit selectors ((x | x << 12), (t | t << 6), & 0x03030303) and v_perm_b32 looks
-// each up in a 4-entry table of bytes (two nibbles per byte: 0xAA, 0xA2, 0x2A, 0x22).
+// Expansion of a packed word into four registers of 8 nibbles, eleven vector instructions: both
+// operands are expanded the same way, so the order of the 32 elements inside an MFMA step is free,
+// and register s takes the bit pairs (8j + 2s, 8j + 2s + 1), j = 0..3: ((w >> 2s) & 0x03030303) is
+// then already the four 2-bit selectors that v_perm_b32 looks up in a 4-entry table of bytes (two
+// nibbles per byte: 0xAA, 0xA2, 0x2A, 0x22).
 //
 // Workgroup = 8 waves (4 x 2), tile 256 (M) x 128 (N), one per CU; wave = 64 x 64 = 2 x 2 MFMA tiles.
 // K is walked in stages of 256 bits = 8 words = 4 MFMA steps, one barrier per stage.  Global loads
@@ -35,6 +37,7 @@ constexpr int kThreads4 = 512;
 constexpr int kStageWords4 = 8;
 constexpr int kItems4 = 3;                 // (row, pair of words) items per thread per stage
 constexpr int kNumXcd4 = 8;
+constexpr int kPlaneA = kBM4 * 16 + 32, kPlaneB = kBN4 * 16 + 32;   // bytes per word plane
 
 struct MfmaFp4Args {
     const uint32_t *a_bits, *b_bits;
@@ -47,12 +50,13 @@ struct MfmaFp4Args {
     int32_t tiles_n, tiles_total, slots_per_xcd;
 };
 
-// 8 sign bits (bit = 1: +1) -> 8 fp4 values, element i in nibble i
-__device__ __forceinline__ uint32_t expand8(uint32_t byte)
+// 32 sign bits (bit = 1: +1) -> 32 fp4 values in the order described above
+__device__ __forceinline__ i32x4v expand32(uint32_t w)
 {
-    const uint32_t t = byte | (byte << 12);
-    const uint32_t sel = (t | (t << 6)) & 0x03030303u;
-    return __builtin_amdgcn_perm(0u, 0x222aa2aau, sel);
+    i32x4v e;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) e[s] = (int)__builtin_amdgcn_perm(0u, 0x222aa2aau, (w >> (2 * s)) & 0x03030303u);
+    return e;
 }
 
 // SEG = segments of G = min(beta_a, beta_w) bits per stage: 1, 2 or 4 (G = 256, 128, 64).
@@ -60,8 +64,10 @@ template <int SEG>
 __global__ __launch_bounds__(kThreads4) void mfma_fp4_gemm_kernel(const MfmaFp4Args a)
 {
     constexpr int kStepsPerSeg = 4 / SEG;   // MFMA steps (64 bits) per segment
-    __shared__ __attribute__((aligned(16))) unsigned char s_a[2][kStageWords4 * kBM4 * 16];   // [buf][word][row][16 B]
-    __shared__ __attribute__((aligned(16))) unsigned char s_b[2][kStageWords4 * kBN4 * 16];
+    // [buf][word][row][16 B]; every word plane is padded by 32 bytes so that the four word pairs a
+    // wave parks at once (16 rows each) start on different banks
+    __shared__ __attribute__((aligned(16))) unsigned char s_a[2][kStageWords4 * kPlaneA];
+    __shared__ __attribute__((aligned(16))) unsigned char s_b[2][kStageWords4 * kPlaneB];
     __shared__ __attribute__((aligned(16))) float s_sa[2][SEG][kBM4];
     __shared__ __attribute__((aligned(16))) float s_sb[2][SEG][kBN4];
 
@@ -90,7 +96,7 @@ __global__ __launch_bounds__(kThreads4) void mfma_fp4_gemm_kernel(const MfmaFp4A
         ildw[j] = is_a ? a.ldw_a : a.ldw_b;
         ibits[j] = is_a ? a.a_bits + (int64_t)min(m0 + r, a.M - 1) * a.ldw_a : a.b_bits + (int64_t)min(n0 + r, a.N - 1) * a.ldw_b;
         // LDS byte offset of (word iword, row r) inside the operand's buffer; the second word is one plane further
-        idst[j] = (iword[j] * (is_a ? kBM4 : kBN4) + r) * 16;
+        idst[j] = iword[j] * (is_a ? kPlaneA : kPlaneB) + r * 16;
     }
     // ---- scale rows: thread t < 256 owns A row t, 256 <= t < 384 owns B row t - 256
     const bool s_is_a = tid < kBM4, s_any = tid < kBM4 + kBN4;
@@ -120,17 +126,11 @@ __global__ __launch_bounds__(kThreads4) void mfma_fp4_gemm_kernel(const MfmaFp4A
         for (int j = 0; j < kItems4; ++j) {
             const bool is_a = tid + j * kThreads4 < 4 * kBM4;   // uniform per j
             unsigned char *base = (is_a ? &s_a[buf][0] : &s_b[buf][0]) + idst[j];
-            const int plane = (is_a ? kBM4 : kBN4) * 16;
+            const int plane = is_a ? kPlaneA : kPlaneB;
             const bool in_row = stage * kStageWords4 + iword[j] < ildw[j];   // else: words past the row, never counted (scale 0)
             const uint32_t w0 = in_row ? st.bits[j].x : 0u, w1 = in_row ? st.bits[j].y : 0u;
-            i32x4v e0, e1;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                e0[q] = (int)expand8((w0 >> (8 * q)) & 0xffu);
-                e1[q] = (int)expand8((w1 >> (8 * q)) & 0xffu);
-            }
-            *reinterpret_cast<i32x4v *>(base) = e0;
-            *reinterpret_cast<i32x4v *>(base + plane) = e1;
+            *reinterpret_cast<i32x4v *>(base) = expand32(w0);
+            *reinterpret_cast<i32x4v *>(base + plane) = expand32(w1);
         }
         // a scale of 0 switches off segments past K (their pad bits expand to -1 and would count) and rows past M / N
         if (s_any) {
@@ -167,8 +167,8 @@ __global__ __launch_bounds__(kThreads4) void mfma_fp4_gemm_kernel(const MfmaFp4A
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 const int ra = wm * 64 + t * 32 + rl, rb = wn * 64 + t * 32 + rl;
-                const i32x4v va = *reinterpret_cast<const i32x4v *>(&s_a[buf][((2 * ks + hi) * kBM4 + ra) * 16]);
-                const i32x4v vb = *reinterpret_cast<const i32x4v *>(&s_b[buf][((2 * ks + hi) * kBN4 + rb) * 16]);
+                const i32x4v va = *reinterpret_cast<const i32x4v *>(&s_a[buf][(2 * ks + hi) * kPlaneA + ra * 16]);
+                const i32x4v vb = *reinterpret_cast<const i32x4v *>(&s_b[buf][(2 * ks + hi) * kPlaneB + rb * 16]);
                 fa[t] = i32x8{va[0], va[1], va[2], va[3], 0, 0, 0, 0};
                 fb[t] = i32x8{vb[0], vb[1], vb[2], vb[3], 0, 0, 0, 0};
             }
