@@ -17,7 +17,8 @@
 // then already the four 2-bit selectors that v_perm_b32 looks up in a 4-entry table of bytes (two
 // nibbles per byte: 0xAA, 0xA2, 0x2A, 0x22).
 //
-// Workgroup = 8 waves (4 x 2), tile 256 (M) x 128 (N), one per CU; wave = 64 x 64 = 2 x 2 MFMA tiles.
+// Workgroup = 8 waves (4 x 2), tile 256 (M) x 128 (N), one per CU (or 4 waves, 128 x 128, two per CU, for
+// problems with few tiles); wave = 64 x 64 = 2 x 2 MFMA tiles.
 // K is walked in stages of 256 bits = 8 words = 4 MFMA steps, one barrier per stage.  Global loads
 // (8 bytes of packed bits per item, three items per thread, plus the scales of the stage's segments)
 // run three stages ahead through rotating register sets and are unconditional (clamped indices).
@@ -32,12 +33,10 @@ typedef int i32x8 __attribute__((ext_vector_type(8)));
 typedef int i32x4v __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kBM4 = 256, kBN4 = 128;
-constexpr int kThreads4 = 512;
+constexpr int kBN4 = 128;
 constexpr int kStageWords4 = 8;
-constexpr int kItems4 = 3;                 // (row, pair of words) items per thread per stage
 constexpr int kNumXcd4 = 8;
-constexpr int kPlaneA = kBM4 * 16 + 32, kPlaneB = kBN4 * 16 + 32;   // bytes per word plane
+constexpr int kPlaneB = kBN4 * 16 + 32;   // bytes per word plane
 
 struct MfmaFp4Args {
     const uint32_t *a_bits, *b_bits;
@@ -60,9 +59,13 @@ __device__ __forceinline__ i32x4v expand32(uint32_t w)
 }
 
 // SEG = segments of G = min(beta_a, beta_w) bits per stage: 1, 2 or 4 (G = 256, 128, 64).
-template <int SEG>
-__global__ __launch_bounds__(kThreads4) void mfma_fp4_gemm_kernel(const MfmaFp4Args a)
+// kBM4 = rows of A per workgroup: 256 (8 waves, one workgroup per CU) or 128 (4 waves, two per CU).
+template <int SEG, int kBM4>
+__global__ __launch_bounds__(2 * kBM4, kBM4 == 128 ? 2 : 1) void mfma_fp4_gemm_kernel(const MfmaFp4Args a)
 {
+    constexpr int kThreads4 = 2 * kBM4;
+    constexpr int kItems4 = (4 * kBM4 + 4 * kBN4) / kThreads4;   // (row, pair of words) items per thread per stage
+    constexpr int kPlaneA = kBM4 * 16 + 32;
     constexpr int kStepsPerSeg = 4 / SEG;   // MFMA steps (64 bits) per segment
     // [buf][word][row][16 B]; every word plane is padded by 32 bytes so that the four word pairs a
     // wave parks at once (16 rows each) start on different banks
@@ -160,9 +163,6 @@ __global__ __launch_bounds__(kThreads4) void mfma_fp4_gemm_kernel(const MfmaFp4A
         const int rl = lane & 31, hi = lane >> 5;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            // keeps the next step's fragment and scale reads from being hoisted above this step
-            // (registers: four steps' worth of operands would not fit next to the two accumulator sets)
-            __builtin_amdgcn_sched_barrier(0);
             i32x8 fa[2], fb[2];
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
@@ -202,7 +202,9 @@ __global__ __launch_bounds__(kThreads4) void mfma_fp4_gemm_kernel(const MfmaFp4A
                             res[x][y][4 * q + 2] = __builtin_fmaf(acc[x][y][4 * q + 2], sa4.z * sb, res[x][y][4 * q + 2]);
                             res[x][y][4 * q + 3] = __builtin_fmaf(acc[x][y][4 * q + 3], sa4.w * sb, res[x][y][4 * q + 3]);
                         }
-                        asm volatile("" : "+v"(res[x][y]));   // same reason
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(res[x][y][v]));   // same reason; per element,
+                        // so that each FMA can stay in its two-address form (v_fmac_f32 issues faster than v_fma_f32)
                     }
                 }
             }
@@ -259,17 +261,30 @@ hipError_t launch_mfma_fp4_gemm(const uint32_t *a_bits, const float *a_scales, i
     a.M = (int32_t)M; a.N = (int32_t)N; a.kwords = (int32_t)(K / 32);
     a.shift_a = ilog2f4(beta_a / G);
     a.shift_b = ilog2f4(beta_w / G);
-    const int64_t tiles_m = (M + kBM4 - 1) / kBM4, tiles_n = (N + kBN4 - 1) / kBN4;
+    // 256-row workgroups, or 128-row ones (twice as many, two per CU; same speed on large problems)
+    // when the larger tile would leave compute units without a workgroup
+    const int64_t tiles_n = (N + kBN4 - 1) / kBN4;
+    const bool small = ((M + 255) / 256) * tiles_n < 256;
+    const int bm = small ? 128 : 256;
+    const int64_t tiles_m = (M + bm - 1) / bm;
     const int64_t total = tiles_m * tiles_n, per_xcd = (total + kNumXcd4 - 1) / kNumXcd4;
     if (per_xcd * kNumXcd4 > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     a.tiles_n = (int32_t)tiles_n; a.tiles_total = (int32_t)total; a.slots_per_xcd = (int32_t)per_xcd;
-    const dim3 grid((unsigned)(per_xcd * kNumXcd4)), block(kThreads4);
+    const dim3 grid((unsigned)(per_xcd * kNumXcd4)), block(2 * bm);
+#define HBMM_FP4_LAUNCH(SEGV)                                          \
+    do {                                                               \
+        if (small)                                                     \
+            mfma_fp4_gemm_kernel<SEGV, 128><<<grid, block, 0, s>>>(a); \
+        else                                                           \
+            mfma_fp4_gemm_kernel<SEGV, 256><<<grid, block, 0, s>>>(a); \
+    } while (0)
     if (G == 256)
-        mfma_fp4_gemm_kernel<1><<<grid, block, 0, s>>>(a);
+        HBMM_FP4_LAUNCH(1);
     else if (G == 128)
-        mfma_fp4_gemm_kernel<2><<<grid, block, 0, s>>>(a);
+        HBMM_FP4_LAUNCH(2);
     else
-        mfma_fp4_gemm_kernel<4><<<grid, block, 0, s>>>(a);
+        HBMM_FP4_LAUNCH(4);
+#undef HBMM_FP4_LAUNCH
     return hipGetLastError();
 }
 

@@ -59,6 +59,14 @@ def test_workload_full_size(hbmm, name):
     worst = assert_close_to_oracle(got, ref, T, name)
     print(f"[{name}] gemm ok, worst err/(1e-5 T) = {worst:.3f}", flush=True)
 
+    # --- the matrix-core variants reach the same segment sums and round in the same places
+    same = torch.from_numpy(got).cuda()
+    assert torch.equal(hbmm.gemm(a_bits, dev(sa), w.beta_a, b_bits, dev(sb), w.beta_w, w.K, algo=1), same)
+    if min(w.beta_a, w.beta_w) >= 64:
+        assert torch.equal(hbmm.gemm(a_bits, dev(sa), w.beta_a, b_bits, dev(sb), w.beta_w, w.K, algo=2), same)
+    del same
+    print(f"[{name}] matrix-core variants identical", flush=True)
+
     # --- whole path with the GPU's own scales against the dense f64 definition, sampled rows
     got2 = hbmm.gemm(a_bits, a_s, w.beta_a, b_bits, b_s, w.beta_w, w.K).cpu().numpy()
     rows = np.unique(np.linspace(0, w.M - 1, 24).astype(np.int64))
