@@ -29,6 +29,7 @@ VALU_LANE_OPS = 256 * 64 * 2.4e9
 POPCOUNT_PEAK_TOPS = VALU_LANE_OPS * 32 / 1e12      # 1258.3
 HBM_PEAK_GBS = 8000.0
 BF16_PEAK_TFLOPS = 2500.0
+FP4_PEAK_TFLOPS = 10100.0                           # dense fp4 MFMA
 
 
 def parse():
@@ -252,6 +253,35 @@ def main():
             "ms_per_launch": t_pack, "launches": n_pack,
         }
 
+    if binary_act and w.b_layout == 0 and min(w.beta_a, w.beta_w) >= 64:
+        # The same step with the product on the matrix cores in 4-bit floats (hbmm_gemm algo 2: same
+        # result bit for bit).  Reported next to the headline, which stays on the XNOR + popcount kernel.
+        def step4():
+            hbmm.quantize_pack(A, w.beta_a, 0, a_bits, a_s)
+            hbmm.quantize_pack(B, w.beta_w, 0, b_bits, b_s)
+            hbmm.gemm(a_bits, a_s, w.beta_a, b_bits, b_s, w.beta_w, w.K, hbmm.ALGO_MFMA_FP4, C)
+
+        for _ in range(args.warmup):
+            step4()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            step4()
+        e1.record()
+        torch.cuda.synchronize()
+        ms4 = e0.elapsed_time(e1) / args.steps
+        tg = time_loop(lambda: hbmm.gemm(a_bits, a_s, w.beta_a, b_bits, b_s, w.beta_w, w.K, hbmm.ALGO_MFMA_FP4, C),
+                       args.steps, 2, torch)
+        g4 = float(np.mean(tg))
+        out["step_with_fp4_mfma_variant"] = {
+            "ms_per_step": ms4, "value": ops / (ms4 * 1e-3) / 1e9, "unit": "GOPS", "gemm_ms": g4,
+            "speedup_vs_headline_step": ms_per_step / ms4,
+            "roofline": {"kernel": "mfma_fp4_gemm_kernel (hbmm_gemm algo 2)", "bound": "mfma",
+                         "achieved": ops / (g4 * 1e-3) / 1e12, "peak": FP4_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": ops / (g4 * 1e-3) / 1e12 / FP4_PEAK_TFLOPS, "traffic": None},
+        }
+
     if not args.no_extras:
         out["comparisons"] = extras(w, A, B, a_bits, a_s, b_bits, b_s, C, torch, hbmm, synth, args)
     if not args.no_cpu_baseline:
@@ -293,6 +323,12 @@ def extras(w, A, B, a_bits, a_s, b_bits, b_s, C, torch, hbmm, synth, args):
             res["dense_ref_bf16"] = {"error": str(e)}
         ts = time_loop(lambda: torch.matmul(Ab, Bb.t()), steps, warm, torch)
         res["torch_matmul_bf16"] = {"ms": float(sum(ts) / len(ts)), "gflops": gops(sum(ts) / len(ts))}
+        # "speedup vs bf16 GEMM": the library GEMM on the same shape against each HBMM product kernel
+        t_lib = res["torch_matmul_bf16"]["ms"]
+        tg0 = time_loop(lambda: hbmm.gemm(a_bits, a_s, w.beta_a, b_bits, b_s, w.beta_w, w.K, hbmm.ALGO_POPCOUNT, C), steps, warm, torch)
+        res["speedup_vs_torch_matmul_bf16"] = {"popcount": t_lib / float(sum(tg0) / len(tg0))}
+        if "ms" in res.get("hbmm_gemm_fp4_mfma", {}):
+            res["speedup_vs_torch_matmul_bf16"]["fp4_mfma"] = t_lib / res["hbmm_gemm_fp4_mfma"]["ms"]
         del Ab, Bb
     # gradient through the binarisation (Eq. 5-6): 8 bytes read + 4 written per element
     try:
