@@ -161,6 +161,8 @@ __global__ __launch_bounds__(2 * kBM4, kBM4 == 128 ? 2 : 1) void mfma_fp4_gemm_k
         const int buf = stage & 1;
         fetch(incoming, stage + 3);
         const int rl = lane & 31, hi = lane >> 5;
+        float sb_r[2];
+        float4 sa_r[2][4];
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             i32x8 fa[2], fb[2];
@@ -173,6 +175,18 @@ __global__ __launch_bounds__(2 * kBM4, kBM4 == 128 ? 2 : 1) void mfma_fp4_gemm_k
                 fb[t] = i32x8{vb[0], vb[1], vb[2], vb[3], 0, 0, 0, 0};
             }
             const bool seg_first = ks % kStepsPerSeg == 0;   // compile-time: the segment's first step starts from 0
+            if (seg_first) {
+                // the segment's scales are requested before its MFMAs, so that they are in registers
+                // when the epilogue starts instead of costing an LDS round trip per group of rows
+                const int sgm = ks / kStepsPerSeg;
+#pragma unroll
+                for (int y = 0; y < 2; ++y) sb_r[y] = s_sb[buf][sgm][wn * 64 + y * 32 + (lane & 31)];
+#pragma unroll
+                for (int x = 0; x < 2; ++x)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        sa_r[x][q] = *reinterpret_cast<const float4 *>(&s_sa[buf][sgm][wm * 64 + x * 32 + 4 * (lane >> 5) + 8 * q]);
+            }
 #pragma unroll
             for (int x = 0; x < 2; ++x)
 #pragma unroll
@@ -187,16 +201,14 @@ __global__ __launch_bounds__(2 * kBM4, kBM4 == 128 ? 2 : 1) void mfma_fp4_gemm_k
 #pragma unroll
                 for (int y = 0; y < 2; ++y) asm volatile("" : "+v"(acc[x][y]));
             if ((ks + 1) % kStepsPerSeg == 0) {
-                const int s = ks / kStepsPerSeg;
 #pragma unroll
                 for (int y = 0; y < 2; ++y) {
-                    const float sb = s_sb[buf][s][wn * 64 + y * 32 + (lane & 31)];
+                    const float sb = sb_r[y];
 #pragma unroll
                     for (int x = 0; x < 2; ++x) {
-                        const float *sa = &s_sa[buf][s][wm * 64 + x * 32 + 4 * (lane >> 5)];
 #pragma unroll
                         for (int q = 0; q < 4; ++q) {
-                            const float4 sa4 = *reinterpret_cast<const float4 *>(sa + 8 * q);
+                            const float4 sa4 = sa_r[x][q];
                             res[x][y][4 * q + 0] = __builtin_fmaf(acc[x][y][4 * q + 0], sa4.x * sb, res[x][y][4 * q + 0]);
                             res[x][y][4 * q + 1] = __builtin_fmaf(acc[x][y][4 * q + 1], sa4.y * sb, res[x][y][4 * q + 1]);
                             res[x][y][4 * q + 2] = __builtin_fmaf(acc[x][y][4 * q + 2], sa4.z * sb, res[x][y][4 * q + 2]);
