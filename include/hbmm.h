@@ -118,6 +118,8 @@ int hbmm_binarize_backward(const float *x, const float *grad_out, int64_t rows, 
  *                     2: (both beta >= 64 only) the same d[m, n, g] from 4-bit-float +-1 matrix-core
  *                        products (the operands are expanded from their bits on chip); same epilogue,
  *                        bit-identical result.
+ *                    -1: the fastest of these for the given segment lengths (2 when both beta >= 64,
+ *                        else 0).
  *
  * M == 0 or N == 0 is a valid no-op; K == 0 writes zeros.
  */

@@ -167,7 +167,9 @@ int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int6
 {
     if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim) return HBMM_EINVAL;
     if (beta_a < 1 || beta_w < 1) return HBMM_EINVAL;
-    if (algo != 0 && algo != 1 && algo != 2) return HBMM_EUNSUPPORTED;
+    if (algo != 0 && algo != 1 && algo != 2 && algo != -1) return HBMM_EUNSUPPORTED;
+    // -1: whichever kernel is fastest for these segment lengths (all of them give the same bits)
+    if (algo == -1) algo = (beta_a >= 64 && beta_w >= 64) ? 2 : 0;
     const bool word_a = supported_beta(beta_a), word_w = supported_beta(beta_w);   // 32 .. 256
     if (!(beta_a == 1 || supported_pack_beta(beta_a)) || !(beta_w == 1 || supported_pack_beta(beta_w)))
         return HBMM_EUNSUPPORTED;

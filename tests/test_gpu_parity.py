@@ -176,6 +176,18 @@ def test_gemm_mfma_fp4_mixed_and_ragged(beta_a, beta_w, K):
     run_gemm_case(synth.normal(610, (150, K)), synth.normal(611, (270, K), std=0.04), beta_a, beta_w, algo=2)
 
 
+@pytest.mark.parametrize("beta_a,beta_w", [(32, 64), (64, 64), (256, 128), (8, 32), (1, 64)])
+def test_gemm_fastest_algo_gives_the_same_bits(beta_a, beta_w):
+    A, B = synth.normal(620, (140, 512)), synth.normal(621, (200, 512), std=0.05)
+    bb, bs = hbmm.quantize_pack(dev(B), beta_w)
+    if beta_a == 1:
+        ab, as_ = None, dev(A)
+    else:
+        ab, as_ = hbmm.quantize_pack(dev(A), beta_a)
+    assert torch.equal(hbmm.gemm(ab, as_, beta_a, bb, bs, beta_w, 512, algo=hbmm.ALGO_FASTEST),
+                       hbmm.gemm(ab, as_, beta_a, bb, bs, beta_w, 512, algo=hbmm.ALGO_POPCOUNT))
+
+
 def test_gemm_mfma_fp4_unsupported():
     A, B = synth.normal(1, (8, 64)), synth.normal(2, (8, 64))
     ab, as_ = hbmm.quantize_pack(dev(A), 32)
