@@ -118,8 +118,11 @@ int hbmm_binarize_backward(const float *x, const float *grad_out, int64_t rows, 
  *                     2: (both beta >= 64 only) the same d[m, n, g] from 4-bit-float +-1 matrix-core
  *                        products (the operands are expanded from their bits on chip); same epilogue,
  *                        bit-identical result.
+ *                     3: (both beta >= 16, the shorter one 16 or 32, K a multiple of 128) the same
+ *                        d[m, n, g] from 8-bit-float +-1 matrix-core products, 16 elements of K per step;
+ *                        same epilogue (bit-identical to 0 when both beta >= 32).
  *                    -1: the fastest of these for the given segment lengths (2 when both beta >= 64,
- *                        else 0).
+ *                        3 when both are 16 or 32 and K is a multiple of 128, else 0).
  *
  * M == 0 or N == 0 is a valid no-op; K == 0 writes zeros.
  */

@@ -167,15 +167,25 @@ int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int6
 {
     if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim) return HBMM_EINVAL;
     if (beta_a < 1 || beta_w < 1) return HBMM_EINVAL;
-    if (algo != 0 && algo != 1 && algo != 2 && algo != -1) return HBMM_EUNSUPPORTED;
-    // -1: whichever kernel is fastest for these segment lengths (all of them give the same bits)
-    if (algo == -1) algo = (beta_a >= 64 && beta_w >= 64) ? 2 : 0;
+    if (algo < -1 || algo > 3) return HBMM_EUNSUPPORTED;
+    // -1: whichever kernel is fastest for these segment lengths
+    if (algo == -1) {
+        const int g = beta_a < beta_w ? beta_a : beta_w;
+        const int gmax = beta_a < beta_w ? beta_w : beta_a;
+        // (a short segment against a long one is as fast on the bf16 kernel: its epilogue is rare there)
+        algo = g >= 64 ? 2 : (g >= 16 && gmax <= 32 && K % 128 == 0) ? 3 : 0;
+    }
     const bool word_a = supported_beta(beta_a), word_w = supported_beta(beta_w);   // 32 .. 256
     if (!(beta_a == 1 || supported_pack_beta(beta_a)) || !(beta_w == 1 || supported_pack_beta(beta_w)))
         return HBMM_EUNSUPPORTED;
     if (K % beta_w != 0 || K % beta_a != 0 || K % 32 != 0) return HBMM_EUNSUPPORTED;
-    if (algo != 0 && !(word_a && word_w)) return HBMM_EUNSUPPORTED;
+    if ((algo == 1 || algo == 2) && !(word_a && word_w)) return HBMM_EUNSUPPORTED;
     if (algo == 2 && (beta_a < 64 || beta_w < 64)) return HBMM_EUNSUPPORTED;   // one fp4 MFMA step is 64 bits of K
+    if (algo == 3) {
+        // one fp8 MFMA step is 16 bits of K; the kernel is written for segments of 16 or 32 and whole 128-bit stages
+        const int g = beta_a < beta_w ? beta_a : beta_w;
+        if (beta_a < 16 || beta_w < 16 || g > 32 || K % 128 != 0) return HBMM_EUNSUPPORTED;
+    }
     // Two unquantised operands are a plain dense product (hbmm_dense_ref_gemm), and an unquantised
     // operand needs the other one to keep its +-1 form (segment of at least 16).
     if ((beta_a == 1 && beta_w < 16) || (beta_w == 1 && beta_a < 16)) return HBMM_EUNSUPPORTED;
@@ -188,6 +198,10 @@ int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int6
     const GemmOperand ob{b_bits, b_scales, ldw_b, lds_b, N, beta_w};
     if (int rc = check_operand(ob, K)) return rc;
     if (int rc = check_operand(oa, K)) return rc;
+
+    if (algo == 3)
+        return from_hip(hbmm::launch_mfma_fp8_gemm(a_bits, a_scales, ldw_a, lds_a, beta_a, b_bits, b_scales,
+                                                   ldw_b, lds_b, beta_w, M, N, K, C, ldc, s));
 
     if (!(word_a && word_w)) {
         // Matrix-core path: the operand with the longer segment keeps its signs (its scale is applied

@@ -104,6 +104,13 @@ hipError_t launch_mfma_fp4_gemm(const uint32_t *a_bits, const float *a_scales, i
                                 const float *b_scales, int64_t ldw_b, int64_t lds_b, int beta_w,
                                 int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, hipStream_t s);
 
+// ---- gemm_mfma_fp8.hip ------------------------------------------------------------------------
+// Same contract; both beta >= 16, min(beta_a, beta_w) in {16, 32}, K a multiple of 128.
+hipError_t launch_mfma_fp8_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a,
+                                int64_t lds_a, int beta_a, const uint32_t *b_bits,
+                                const float *b_scales, int64_t ldw_b, int64_t lds_b, int beta_w,
+                                int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, hipStream_t s);
+
 // ---- dense_ref.hip ----------------------------------------------------------------------------
 hipError_t launch_dense_ref(const void *A, int64_t lda, const void *B, int64_t ldb, int dtype,
                             int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, hipStream_t s);

@@ -16,7 +16,7 @@ _HERE = Path(__file__).resolve().parent
 LIB_PATH = _HERE / "libhbmm.so"
 
 OK, EINVAL, EUNSUPPORTED, ELAUNCH = 0, -1, -2, -3
-ALGO_POPCOUNT, ALGO_MFMA_I8, ALGO_MFMA_FP4, ALGO_FASTEST = 0, 1, 2, -1
+ALGO_POPCOUNT, ALGO_MFMA_I8, ALGO_MFMA_FP4, ALGO_MFMA_FP8, ALGO_FASTEST = 0, 1, 2, 3, -1
 
 EXPORTS = (
     "hbmm_strerror", "hbmm_num_blocks", "hbmm_packed_ld_words", "hbmm_quantize_pack", "hbmm_gemm",

@@ -188,6 +188,38 @@ def test_gemm_fastest_algo_gives_the_same_bits(beta_a, beta_w):
                        hbmm.gemm(ab, as_, beta_a, bb, bs, beta_w, 512, algo=hbmm.ALGO_POPCOUNT))
 
 
+@pytest.mark.parametrize("beta_a,beta_w", [(16, 16), (32, 32), (16, 32), (32, 16), (16, 256), (128, 32), (64, 16)])
+@pytest.mark.parametrize("M,N,K", [(64, 64, 512), (300, 200, 1024), (129, 257, 1536), (5, 3, 128), (513, 130, 640)])
+def test_gemm_mfma_fp8_short_segments(beta_a, beta_w, M, N, K):
+    """8-bit-float matrix-core kernel for segments of 16 or 32: against the oracle, and bit for bit
+    against the popcount kernel where that one applies (both beta >= 32)."""
+    if K % max(beta_a, beta_w):
+        pytest.skip("K must be a multiple of both segment lengths")
+    A, B = synth.normal(700 + M, (M, K)), synth.uniform_pm1(701 + N, (N, K))
+    run_gemm_case(A, B, beta_a, beta_w, algo=3)
+    if beta_a >= 32 and beta_w >= 32:
+        ab, as_ = hbmm.quantize_pack(dev(A), beta_a)
+        bb, bs = hbmm.quantize_pack(dev(B), beta_w)
+        assert torch.equal(hbmm.gemm(ab, as_, beta_a, bb, bs, beta_w, K, algo=0), hbmm.gemm(ab, as_, beta_a, bb, bs, beta_w, K, algo=3))
+
+
+def test_gemm_mfma_fp8_unsupported():
+    A, B = synth.normal(1, (8, 96)), synth.normal(2, (8, 96))
+    ab, as_ = hbmm.quantize_pack(dev(A), 16)
+    bb, bs = hbmm.quantize_pack(dev(B), 16)
+    with pytest.raises(hbmm.HbmmError):
+        hbmm.gemm(ab, as_, 16, bb, bs, 16, 96, algo=3)       # K not a multiple of 128
+    A, B = synth.normal(1, (8, 128)), synth.normal(2, (8, 128))
+    ab, as_ = hbmm.quantize_pack(dev(A), 8)
+    bb, bs = hbmm.quantize_pack(dev(B), 16)
+    with pytest.raises(hbmm.HbmmError):
+        hbmm.gemm(ab, as_, 8, bb, bs, 16, 128, algo=3)       # a segment shorter than 16
+    ab, as_ = hbmm.quantize_pack(dev(A), 64)
+    bb, bs = hbmm.quantize_pack(dev(B), 64)
+    with pytest.raises(hbmm.HbmmError):
+        hbmm.gemm(ab, as_, 64, bb, bs, 64, 128, algo=3)      # both segments longer than 32
+
+
 def test_gemm_mfma_fp4_unsupported():
     A, B = synth.normal(1, (8, 64)), synth.normal(2, (8, 64))
     ab, as_ = hbmm.quantize_pack(dev(A), 32)
