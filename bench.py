@@ -357,6 +357,10 @@ def extras(w, A, B, a_bits, a_s, b_bits, b_s, C, torch, hbmm, synth, args):
             tg = time_loop(lambda: hbmm.gemm(ab, as_, ww.beta_a, bb, bs, ww.beta_w, ww.K), 6 if ww.beta_a < 32 else 10, 2, torch)
             entry["pack_a_ms"] = min(tp)
             entry["pack_a_GBs"] = pack_bytes(ww.M, ww.K, ww.beta_a) / (min(tp) * 1e-3) / 1e9
+            # the fastest kernel for these segment lengths (hbmm_gemm algo -1: fp4 / fp8 matrix-core variants)
+            tf = time_loop(lambda: hbmm.gemm(ab, as_, ww.beta_a, bb, bs, ww.beta_w, ww.K, hbmm.ALGO_FASTEST), 10, 2, torch)
+            entry["gemm_fastest_algo_ms"] = min(tf)
+            entry["gemm_fastest_algo_gops"] = 2.0 * ww.M * ww.N * ww.K / (min(tf) * 1e-3) / 1e9
         else:
             tg = time_loop(lambda: hbmm.gemm(None, dA, 1, bb, bs, ww.beta_w, ww.K), 5, 1, torch)
         entry["gemm_ms"] = min(tg)
