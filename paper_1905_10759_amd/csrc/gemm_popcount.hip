@@ -34,19 +34,10 @@ namespace {
 
 constexpr int kTP = 4;                 // P rows per lane
 constexpr int kTQ = 16;                // Q rows per wave
-#ifndef HBMM_GEMM_ASM_SMEM
-#define HBMM_GEMM_ASM_SMEM 1
-#endif
-#ifndef HBMM_GEMM_Q_PREFETCH
-#define HBMM_GEMM_Q_PREFETCH 1
-#endif
-#ifndef HBMM_GEMM_WAVES
-#define HBMM_GEMM_WAVES 4
-#endif
-constexpr int kWaves = HBMM_GEMM_WAVES;
-constexpr int kThreads = 64 * kWaves;  // 512
+constexpr int kWaves = 4;
+constexpr int kThreads = 64 * kWaves;  // 256
 constexpr int kTileP = 64 * kTP;       // 256 P rows per workgroup
-constexpr int kTileQ = kTQ * kWaves;   // 128 Q rows per workgroup
+constexpr int kTileQ = kTQ * kWaves;   // 64 Q rows per workgroup
 constexpr int kCK = 16;                // 32-bit words of K per chunk (512 bits)
 constexpr int kNumXcd = 8;
 constexpr int kSuperTiles = 64;          // tiles per super-tile (two workgroups per CU x 32 CUs of an XCD)
@@ -55,7 +46,6 @@ constexpr int kBitsStride = kCK + 2;   // LDS row stride in words: 2 * odd => co
 
 typedef const uint32_t __attribute__((address_space(4))) *const_u32_ptr;
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef const u32x2 __attribute__((address_space(4))) *const_u32x2_ptr;
 
 // popcount(x) + acc in one instruction.  Written as asm so that the optimiser cannot re-associate
 // chains of these into separate popcounts plus three-operand adds.
@@ -137,7 +127,6 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
 
     uint32_t st_qline = 0;
     auto fetch = [&](int chunk) {
-#if HBMM_GEMM_Q_PREFETCH
         // Touch the 64-byte line of this wave's Q rows that the scalar loads of `chunk` will read,
         // one chunk ahead, through the vector path (its counter is separate from the scalar one), so
         // that those scalar loads find the line in L2.
@@ -146,7 +135,6 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
             const int w = min(chunk * kCK, a.kwords - 4);
             st_qline = a.q_bits[(int64_t)row * a.ldw_q + w];
         }
-#endif
         if constexpr (!FUSED) {
 #pragma unroll
             for (int r = 0; r < kBitPieces; ++r) {
@@ -183,9 +171,7 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
         }
     };
     auto park = [&](int buf) {
-#if HBMM_GEMM_Q_PREFETCH
         asm volatile("" ::"v"(st_qline));   // keeps the touch load alive; its value is not used
-#endif
         if constexpr (!FUSED) {
 #pragma unroll
             for (int r = 0; r < kBitPieces; ++r) {
@@ -385,7 +371,6 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
             for (int q = 0; q < kTQ; ++q) asm volatile("" : "+v"(res[i][q]));
         __builtin_amdgcn_sched_barrier(0);
     };
-#if HBMM_GEMM_ASM_SMEM
     // Scalar loads of Q words, written as asm so that the row offset can ride in the instruction's
     // SGPR-offset field (no address arithmetic per load).  The compiler does not count these loads,
     // so wait_q() must run before their results are read: it waits for every outstanding scalar /
@@ -403,17 +388,6 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
                        "+s"(qw[7]), "+s"(qw[8]), "+s"(qw[9]), "+s"(qw[10]), "+s"(qw[11]), "+s"(qw[12]),
                        "+s"(qw[13]), "+s"(qw[14]), "+s"(qw[15]));
     };
-#else
-    // Scalar loads of Q words.  `a.step_words` is kStep at run time; passing it as an argument keeps
-    // the compiler from fusing the loads of consecutive steps into wider ones, which would need more
-    // scalar registers than exist.
-    auto load_q = [&](u32x2 (&qw)[kTQ], int step_index, int wbase) {
-        const const_byte_ptr base = qbase + (int64_t)(wbase + step_index * a.step_words) * 4;
-#pragma unroll
-        for (int q = 0; q < kTQ; ++q) qw[q] = *(const_u32x2_ptr)(base + (uint64_t)qoff[q]);
-    };
-    auto wait_q = [&](u32x2 (&)[kTQ]) {};
-#endif
     auto load_p = [&](u32x2 (&pw)[kTP], int buf, int s) {
         const uint32_t *lbits = &s_bits[buf][lane * kBitsStride + s * kStep];
 #pragma unroll
@@ -584,7 +558,6 @@ hipError_t launch_popcount_gemm(const PopcountGemmArgs &args, int G, int integer
         const int sup_q = kSuperTiles / a.sup_p;
         a.n_super = a.n_super_p * ((a.tiles_q + sup_q - 1) / sup_q);
     }
-    a.step_words = kStep;
     if (integer) return launch<64, true>(a, s);
     if (a.p_src != nullptr) {
         switch (G) {

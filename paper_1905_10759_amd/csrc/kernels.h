@@ -49,7 +49,6 @@ struct PopcountGemmArgs {
     int32_t sup_p;       // P tiles per super-tile (super-tile = 64 tiles placed on one XCD)
     int32_t n_super_p;   // super-tiles along P
     int32_t n_super;     // super-tiles in all
-    int32_t step_words;  // always 2; a run-time value on purpose (see load_q in the kernel)
 };
 // G = min(beta_p, beta_q) in {32, 64, 128, 256}; integer != 0 selects the unscaled whole-row mode.
 hipError_t launch_popcount_gemm(const PopcountGemmArgs &a, int G, int integer, hipStream_t s);
