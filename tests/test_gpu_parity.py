@@ -505,6 +505,10 @@ CONV_CASES = [
     (2, 32, 7, 8, 8, 2, 2, 2, 0, 8, 128),       # even window without padding
     (1, 128, 14, 16, 130, 3, 3, 1, 1, 4, 128),  # K = 1152, 9 segments of 128
     (5, 32, 12, 12, 20, 3, 3, 1, 1, 4, 32),     # several tiles of positions that cross images
+    (1, 32, 12, 44, 20, 3, 3, 2, 1, 4, 32),     # stride 2 on a wide input: 506 patch elements, 4 staging items per thread
+    (1, 32, 9, 60, 12, 3, 3, 2, 1, 4, 32),      # 558 patch elements: 6 staging items per thread
+    (2, 32, 8, 8, 9, 2, 3, 1, 1, 8, 32),        # 2 x 3 window: up to 6 channels enter per stage
+    (1, 32, 6, 132, 10, 3, 3, 1, 1, 4, 32),     # output rows wider than a position tile: per-tap gather kernel
 ]
 
 
