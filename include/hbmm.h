@@ -145,6 +145,14 @@ int hbmm_quantize_pack_tensor(const float *x, int64_t count, int32_t beta, uint3
                               void *stream);
 
 /*
+ * hbmm_binarize_backward for a whole tensor stored contiguously, segments of beta consecutive elements
+ * (the counterpart of hbmm_quantize_pack_tensor: for an activation tensor whose width is a multiple
+ * of beta this is the gradient through Eq. 3-4).  count: a multiple of 128 and of beta, below 2^31.
+ */
+int hbmm_binarize_backward_tensor(const float *x, const float *grad_out, int64_t count, int32_t beta, float *grad_in,
+                                   void *stream);
+
+/*
  * A convolution layer of a HadaNet, computed directly from the packed tensors (no im2col matrix is
  * formed): activations binarised by Eq. 3-4, filters by Eq. 1-2, then
  *   out[b, n, oz, oy] = sum_{c, dz, dy} A~[b, c, oz*stride - pad + dz, oy*stride - pad + dy] * W~[n, c, dz, dy]

@@ -297,6 +297,18 @@ int hbmm_quantize_pack_tensor(const float *x, int64_t count, int32_t beta, uint3
     return hbmm_quantize_pack(x, count / K, K, K, 0, beta, bits, K / 32, scales, K / beta, stream);
 }
 
+int hbmm_binarize_backward_tensor(const float *x, const float *grad_out, int64_t count, int32_t beta, float *grad_in,
+                                   void *stream)
+{
+    if (count < 0 || count > ((int64_t)1 << 31) - 1) return HBMM_EINVAL;
+    if (beta < 1) return HBMM_EINVAL;
+    if (!(beta == 1 || supported_pack_beta(beta))) return HBMM_EUNSUPPORTED;
+    const int64_t K = tensor_view_k(count);
+    if (count == 0) return HBMM_OK;
+    if (K < 128 || K % beta != 0) return HBMM_EUNSUPPORTED;
+    return hbmm_binarize_backward(x, grad_out, count / K, K, K, K, beta, grad_in, K, stream);
+}
+
 int hbmm_conv2d(const uint32_t *a_bits, const float *a_scales, int32_t beta_a, const uint32_t *w_bits,
                 const float *w_scales, int64_t ldw_w, int64_t lds_w, int32_t beta_w, int64_t B, int64_t C,
                 int64_t H, int64_t W, int64_t N, int32_t KH, int32_t KW, int32_t stride, int32_t pad,

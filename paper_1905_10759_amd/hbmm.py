@@ -21,7 +21,7 @@ ALGO_POPCOUNT, ALGO_MFMA_I8, ALGO_MFMA_FP4, ALGO_MFMA_FP8, ALGO_FASTEST = 0, 1, 
 EXPORTS = (
     "hbmm_strerror", "hbmm_num_blocks", "hbmm_packed_ld_words", "hbmm_quantize_pack", "hbmm_gemm",
     "hbmm_gemm_int", "hbmm_dense_ref_gemm", "hbmm_binarize_backward", "hbmm_gemm_fused",
-    "hbmm_quantize_pack_tensor", "hbmm_conv2d",
+    "hbmm_quantize_pack_tensor", "hbmm_conv2d", "hbmm_binarize_backward_tensor",
 )
 
 
@@ -54,6 +54,8 @@ def _load() -> C.CDLL:
     lib.hbmm_gemm_fused.argtypes = [p, i64, i32, p, p, i64, i64, i32, i64, i64, i64, p, i64, p]
     lib.hbmm_quantize_pack_tensor.restype = C.c_int
     lib.hbmm_quantize_pack_tensor.argtypes = [p, i64, i32, p, p, p]
+    lib.hbmm_binarize_backward_tensor.restype = C.c_int
+    lib.hbmm_binarize_backward_tensor.argtypes = [p, p, i64, i32, p, p]
     lib.hbmm_conv2d.restype = C.c_int
     lib.hbmm_conv2d.argtypes = [p, p, i32, p, p, i64, i64, i32, i64, i64, i64, i64, i64, i32, i32, i32, i32, p, i32, p]
     lib.hbmm_binarize_backward.restype = C.c_int
@@ -241,4 +243,16 @@ def conv2d(a_bits, a_scales, beta_a: int, shape, w_bits, w_scales, beta_w: int, 
                          w_scales.stride(0) if N > 1 else max(w_scales.shape[1], 1), beta_w, B, Cc, H, W, N, KH, KW,
                          stride, pad, out.data_ptr(), algo, _stream())
     _check(rc, "hbmm_conv2d")
+    return out
+
+
+def binarize_backward_tensor(x: torch.Tensor, grad_out: torch.Tensor, beta: int) -> torch.Tensor:
+    """hbmm_binarize_backward_tensor: contiguous tensors of any shape, segments of beta consecutive elements."""
+    _dev(x, torch.float32, "x")
+    _dev(grad_out, torch.float32, "grad_out")
+    if x.shape != grad_out.shape or not x.is_contiguous() or not grad_out.is_contiguous():
+        raise ValueError("x and grad_out must be contiguous tensors of the same shape")
+    out = torch.empty_like(x)
+    rc = lib.hbmm_binarize_backward_tensor(x.data_ptr(), grad_out.data_ptr(), x.numel(), beta, out.data_ptr(), _stream())
+    _check(rc, "hbmm_binarize_backward_tensor")
     return out

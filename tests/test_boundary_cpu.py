@@ -144,6 +144,13 @@ def test_validation_of_the_fused_tensor_and_convolution_entry_points(lib):
     assert qt(fake, -1, 4, fake, fake, None) == -1
     assert qt(None, 0, 4, None, None, None) == 0
 
+    bt = lib.hbmm_binarize_backward_tensor
+    bt.argtypes = [p, p, i64, i32, p, p]
+    assert bt(fake, fake, 120, 4, fake, None) == -2
+    assert bt(fake, fake, 1024, 3, fake, None) == -2
+    assert bt(fake, None, 1024, 4, fake, None) == -1
+    assert bt(None, None, 0, 4, None, None) == 0
+
     cv = lib.hbmm_conv2d
     cv.argtypes = [p, p, i32, p, p, i64, i64, i32, i64, i64, i64, i64, i64, i32, i32, i32, i32, p, i32, p]
     ok = dict(ab=fake, asc=fake, ba=4, wb=fake, ws=fake, ldw=12, lds=9, bw=32, B=1, C=32, H=8, W=8, N=8, KH=3, KW=3,

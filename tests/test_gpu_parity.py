@@ -573,3 +573,14 @@ def test_conv2d_unquantised_activations(case, algo):
     wb, ws = hbmm.quantize_pack(dev(Wf.reshape(N, -1)), beta_w)
     out = hbmm.conv2d(None, dev(A), 1, A.shape, wb, ws, beta_w, (KH, KW), stride, pad, algo=algo)
     assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d beta_a=1 {case} algo {algo}")
+
+
+@pytest.mark.parametrize("beta", [2, 8, 16])
+def test_binarize_backward_tensor(beta):
+    """Gradient through Eq. 3-4 for an activation tensor (segments along the width)."""
+    shape = (2, 3, 8, 32)
+    x, g = synth.normal(95, shape, std=0.8), synth.normal(96, shape)
+    ref, T = oracle.binarize_backward(x.reshape(-1, shape[-1]), g.reshape(-1, shape[-1]), beta, want_T=True)
+    got = hbmm.binarize_backward_tensor(dev(x), dev(g), beta).cpu().numpy().reshape(-1, shape[-1])
+    err = np.abs(got.astype(np.float64) - ref)
+    assert np.all(err <= (np.log2(beta) + 3) * 2.0 ** -24 * T + 1e-30)
