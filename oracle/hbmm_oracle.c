@@ -24,7 +24,7 @@
  *            prints popcount(xnor(.)), the number p of agreeing signs; the +-1 inner
  *            product it stands for is 2p - n = n - 2*popcount(xor), n the segment length.
  *
- * Readings taken where the paper is silent (all listed in the design document):
+ * Readings taken where the paper is silent:
  *   - a last segment shorter than beta is averaged over its own length;
  *   - bit k of a row is bit (k mod 32) of 32-bit word (k div 32), -1 -> 0, +1 -> 1
  *     (the 6-element example of section 4 fixes the value mapping, not the endianness);
