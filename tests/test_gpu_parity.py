@@ -424,6 +424,60 @@ def test_whole_path_in_a_hip_graph_replays_exactly():
         _ = (dA.sum() + dB.sum()).item()   # unrelated eager work between replays
 
 
+def test_layer_pipeline_in_a_hip_graph_replays_exactly():
+    """A layer as it would run in inference -- binarise the activation tensor, convolution from the
+    packed tensors, and a matrix-core product of the flattened result -- captured once and replayed:
+    none of these entry points allocates, clears memory with a memset or synchronises."""
+    B, C, H, W, N, beta_a, beta_w = 2, 32, 8, 16, 64, 4, 32
+    X0, X1 = synth.relu_normal(1200, (B, C, H, W)), synth.relu_normal(1201, (B, C, H, W))
+    F = synth.normal(1202, (N, C, 3, 3), std=0.1)
+    L = synth.normal(1203, (40, N * H * W // 16), std=0.1)     # a "linear layer" over 1/16 of the features per row
+    dX = dev(X0)
+    fb, fs = hbmm.quantize_pack(dev(F.reshape(N, -1)), beta_w)
+    lb, ls = hbmm.quantize_pack(dev(L), 64)
+    xb = torch.empty((dX.numel() // 32,), dtype=torch.int32, device="cuda")
+    xs = torch.empty((dX.numel() // beta_a,), dtype=torch.float32, device="cuda")
+    Y = torch.empty((B, N, H, W), dtype=torch.float32, device="cuda")
+    rows, K2 = 16 * B, N * H * W // 16
+    yb = torch.empty((rows, hbmm.packed_ld_words(K2)), dtype=torch.int32, device="cuda")
+    ys = torch.empty((rows, K2 // 64), dtype=torch.float32, device="cuda")
+    Z = torch.empty((rows, 40), dtype=torch.float32, device="cuda")
+    lib = hbmm.lib
+
+    def step():
+        assert lib.hbmm_quantize_pack_tensor(dX.data_ptr(), dX.numel(), beta_a, xb.data_ptr(), xs.data_ptr(),
+                                             torch.cuda.current_stream().cuda_stream) == 0
+        hbmm.conv2d(xb, xs, beta_a, dX.shape, fb, fs, beta_w, (3, 3), 1, 1, out=Y)
+        hbmm.quantize_pack(Y.view(rows, K2), 64, 0, yb, ys)
+        hbmm.gemm(yb, ys, 64, lb, ls, 64, K2, algo=hbmm.ALGO_MFMA_FP4, out=Z)
+
+    def eager(x):
+        dX.copy_(dev(x))
+        step()
+        torch.cuda.synchronize()
+        return Z.clone()
+
+    want0, want1 = eager(X0), eager(X1)
+    assert not torch.equal(want0, want1)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        step()
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    for rep in range(4):
+        x, want = (X0, want0) if rep % 2 == 0 else (X1, want1)
+        dX.copy_(dev(x))
+        Z.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            graph.replay()
+        side.synchronize()
+        assert torch.equal(Z, want), f"replay {rep} differs from the eager result"
+        _ = dX.sum().item()   # unrelated eager work between replays
+
+
 def test_calls_on_a_side_stream():
     """Kernels go to the stream that is current when the call is made."""
     M, N, K, beta = 130, 70, 512, 128
