@@ -209,14 +209,22 @@ def gemm_fused(A: torch.Tensor, beta_a: int, b_bits, b_scales, beta_w: int, out:
     return out
 
 
-def quantize_pack_tensor(x: torch.Tensor, beta: int):
-    """hbmm_quantize_pack_tensor: a contiguous fp32 tensor -> (bits int32[count / 32], scales fp32[count / beta])."""
+def quantize_pack_tensor(x: torch.Tensor, beta: int, bits: torch.Tensor | None = None,
+                         scales: torch.Tensor | None = None):
+    """hbmm_quantize_pack_tensor: a contiguous fp32 tensor -> (bits int32[count / 32], scales fp32[count / beta]);
+    existing output tensors of those sizes may be passed in."""
     _dev(x, torch.float32, "x")
     if not x.is_contiguous():
         raise ValueError("x must be contiguous")
     count = x.numel()
-    bits = torch.empty((count // 32,), dtype=torch.int32, device=x.device)
-    scales = torch.empty((count // max(beta, 1),), dtype=torch.float32, device=x.device)
+    if bits is None:
+        bits = torch.empty((count // 32,), dtype=torch.int32, device=x.device)
+    if scales is None:
+        scales = torch.empty((count // max(beta, 1),), dtype=torch.float32, device=x.device)
+    _dev(bits, torch.int32, "bits")
+    _dev(scales, torch.float32, "scales")
+    if bits.numel() < count // 32 or scales.numel() < count // max(beta, 1) or not bits.is_contiguous() or not scales.is_contiguous():
+        raise ValueError("bits / scales too small or not contiguous")
     rc = lib.hbmm_quantize_pack_tensor(x.data_ptr(), count, beta, bits.data_ptr(), scales.data_ptr(), _stream())
     _check(rc, "hbmm_quantize_pack_tensor")
     return bits, scales

@@ -442,11 +442,9 @@ def test_layer_pipeline_in_a_hip_graph_replays_exactly():
     yb = torch.empty((rows, hbmm.packed_ld_words(K2)), dtype=torch.int32, device="cuda")
     ys = torch.empty((rows, K2 // 64), dtype=torch.float32, device="cuda")
     Z = torch.empty((rows, 40), dtype=torch.float32, device="cuda")
-    lib = hbmm.lib
 
     def step():
-        assert lib.hbmm_quantize_pack_tensor(dX.data_ptr(), dX.numel(), beta_a, xb.data_ptr(), xs.data_ptr(),
-                                             torch.cuda.current_stream().cuda_stream) == 0
+        hbmm.quantize_pack_tensor(dX, beta_a, xb, xs)
         hbmm.conv2d(xb, xs, beta_a, dX.shape, fb, fs, beta_w, (3, 3), 1, 1, out=Y)
         hbmm.quantize_pack(Y.view(rows, K2), 64, 0, yb, ys)
         hbmm.gemm(yb, ys, 64, lb, ls, 64, K2, algo=hbmm.ALGO_MFMA_FP4, out=Z)
