@@ -244,15 +244,17 @@ def test_binary_weight_form():
     """beta_a = 1 (HBWN): C = A . (delta (.) Sign(B))^T with A untouched; the segmented
     add/subtract form, the dense path and a library matmul agree."""
     K = 96
-    A, B = synth.relu_normal(57, (11, K)), synth.normal(58, (6, K))
-    for beta_w in (4, 32, 96, 40):
-        sb = oracle.block_scales(B, beta_w)
-        Bt = oracle.materialize(B, beta_w, sb)
-        want = A.astype(np.float64) @ Bt.T
-        got, T = oracle.binary_weight_gemm(A, oracle.sign_pack(B), sb, beta_w, want_T=True)
-        assert np.allclose(got, want, rtol=0, atol=1e-12)
-        assert np.allclose(oracle.hbmm_dense(A, B, 1, beta_w), want, rtol=0, atol=1e-12)
-        assert np.allclose(T, np.abs(A.astype(np.float64)) @ np.abs(Bt).T, rtol=1e-12)
+    B = synth.normal(58, (6, K))
+    # rectified activations (the benchmark's kind) and signed ones (a lost sign of A shows only there)
+    for A in (synth.relu_normal(57, (11, K)), synth.normal(157, (11, K))):
+        for beta_w in (4, 32, 96, 40):
+            sb = oracle.block_scales(B, beta_w)
+            Bt = oracle.materialize(B, beta_w, sb)
+            want = A.astype(np.float64) @ Bt.T
+            got, T = oracle.binary_weight_gemm(A, oracle.sign_pack(B), sb, beta_w, want_T=True)
+            assert np.allclose(got, want, rtol=0, atol=1e-12)
+            assert np.allclose(oracle.hbmm_dense(A, B, 1, beta_w), want, rtol=0, atol=1e-12)
+            assert np.allclose(T, np.abs(A.astype(np.float64)) @ np.abs(Bt).T, rtol=1e-12)
 
 
 def test_paths_agree_and_T_bounds():
