@@ -393,6 +393,22 @@ def extras(w, A, B, a_bits, a_s, b_bits, b_s, C, torch, hbmm, synth, args):
             e1.record()
             torch.cuda.synchronize()
             entry["step_ms_back_to_back"] = e0.elapsed_time(e1) / reps
+            if ww.N <= 128 and min(ww.beta_a, ww.beta_w) >= 32:
+                # weights packed once, activations quantised, packed and multiplied by one launch
+                try:
+                    Cf = torch.empty_like(Cw)
+                    hbmm.gemm_fused(dA, ww.beta_a, bb, bs, ww.beta_w, Cf)
+                    torch.cuda.synchronize()
+                    e0.record()
+                    for _ in range(reps):
+                        hbmm.gemm_fused(dA, ww.beta_a, bb, bs, ww.beta_w, Cf)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    entry["step_ms_fused_single_launch"] = e0.elapsed_time(e1) / reps
+                    entry["fused_matches_three_launches"] = bool(torch.equal(Cf, Cw))
+                    del Cf
+                except hbmm.HbmmError as e:
+                    entry["step_ms_fused_single_launch"] = f"unavailable: {e}"
             try:
                 side = torch.cuda.Stream()
                 with torch.cuda.stream(side):

@@ -11,11 +11,10 @@
 // feeds row (l mod 32) and the 32 consecutive k at 32 * (l div 32) -- exactly one packed word of
 // that row -- as 32 nibbles in four registers, k ascending from the low nibble of the first one.
 //
-// Expansion of a packed word into four registers of 8 nibbles, eleven vector instructions: both
+// Expansion of a packed word into four registers of 8 nibbles, seven vector instructions: both
 // operands are expanded the same way, so the order of the 32 elements inside an MFMA step is free,
-// and register s takes the bit pairs (8j + 2s, 8j + 2s + 1), j = 0..3: ((w >> 2s) & 0x03030303) is
-// then already the four 2-bit selectors that v_perm_b32 looks up in a 4-entry table of bytes (two
-// nibbles per byte: 0xAA, 0xA2, 0x2A, 0x22).
+// and register s takes the bits 4i + s, i = 0..7, of the word: shifted left by 3 - s they sit on the
+// sign bits of the eight nibbles.
 //
 // Workgroup = 8 waves (4 x 2), tile 256 (M) x 128 (N), one per CU (or 4 waves, 128 x 128, two per CU, for
 // problems with few tiles); wave = 64 x 64 = 2 x 2 MFMA tiles.
@@ -36,7 +35,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kBN4 = 128;
 constexpr int kStageWords4 = 8;
 constexpr int kNumXcd4 = 8;
-constexpr int kPlaneB = kBN4 * 16 + 32;   // bytes per word plane
+constexpr int kPlaneB = kBN4 * 16 + 16;   // bytes per word plane
 
 struct MfmaFp4Args {
     const uint32_t *a_bits, *b_bits;
@@ -49,12 +48,15 @@ struct MfmaFp4Args {
     int32_t tiles_m, tiles_n, n_super_n, n_super;
 };
 
-// 32 sign bits (bit = 1: +1) -> 32 fp4 values in the order described above
+// 32 sign bits -> 32 fp4 values in the order described above: E2M1 +1.0 (0x2) and -1.0 (0xA) differ in
+// the top bit of the nibble only, so a register is 0x22222222 with eight bits of the word dropped into
+// bits 4i + 3 (a shift and one and-or).  A set bit gives -1 and a clear bit +1 -- for both operands, so
+// every product (+-1)(+-1) is the one the signs define.
 __device__ __forceinline__ i32x4v expand32(uint32_t w)
 {
     i32x4v e;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) e[s] = (int)__builtin_amdgcn_perm(0u, 0x222aa2aau, (w >> (2 * s)) & 0x03030303u);
+    for (int s = 0; s < 4; ++s) e[s] = (int)(((w << (3 - s)) & 0x88888888u) | 0x22222222u);
     return e;
 }
 
@@ -65,10 +67,11 @@ __global__ __launch_bounds__(2 * kBM4, kBM4 == 128 ? 2 : 1) void mfma_fp4_gemm_k
 {
     constexpr int kThreads4 = 2 * kBM4;
     constexpr int kItems4 = (4 * kBM4 + 4 * kBN4) / kThreads4;   // (row, pair of words) items per thread per stage
-    constexpr int kPlaneA = kBM4 * 16 + 32;
+    constexpr int kPlaneA = kBM4 * 16 + 16;
     constexpr int kStepsPerSeg = 4 / SEG;   // MFMA steps (64 bits) per segment
-    // [buf][word][row][16 B]; every word plane is padded by 32 bytes so that the four word pairs a
-    // wave parks at once (16 rows each) start on different banks
+    // [buf][word][row][16 B]; every word plane is padded by 16 bytes: eight consecutive lanes park two
+    // rows x four word pairs (two planes apart), which then fall into eight different 16-byte bank groups
+    // (measured: no LDS bank conflicts left)
     __shared__ __attribute__((aligned(16))) unsigned char s_a[2][kStageWords4 * kPlaneA];
     __shared__ __attribute__((aligned(16))) unsigned char s_b[2][kStageWords4 * kPlaneB];
     __shared__ __attribute__((aligned(16))) float s_sa[2][SEG][kBM4];
