@@ -103,6 +103,20 @@ def test_pack_all_zero_and_negative():
     assert np.array_equal(scales.cpu().numpy(), np.array([[0, 0], [1, 1], [0, 0], [0, 0]], dtype=np.float32))
 
 
+def test_pack_non_finite_inputs():
+    """NaN and infinities are outside the method's domain, but the pass must treat them as the
+    comparison x >= 0 does and keep their damage inside their own segment."""
+    x = synth.normal(77, (70, 1024))
+    x[3, 5], x[3, 300], x[40, 1023], x[69, 0] = np.nan, np.inf, -np.inf, -np.nan
+    for beta in (4, 32, 256):
+        bits, scales = hbmm.quantize_pack(dev(x), beta)
+        assert np.array_equal(words(bits), oracle.sign_pack(x))
+        got, ref = scales.cpu().numpy(), oracle.block_scales(x, beta)
+        bad = ~np.isfinite(ref)
+        assert bad.sum() == 4 and np.array_equal(np.isnan(got), np.isnan(ref)) and np.array_equal(np.isinf(got), np.isinf(ref))
+        assert np.all(np.abs(got[~bad] - ref[~bad]) <= 16 * 2.0 ** -24 * ref[~bad])
+
+
 # ---------------------------------------------------------------------------------- gemm_int
 @pytest.mark.parametrize("M,N,K", [(64, 64, 512), (1, 1, 32), (300, 130, 1000), (257, 129, 544), (40, 600, 4608),
                                    (513, 17, 96)])

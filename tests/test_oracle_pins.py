@@ -88,6 +88,15 @@ def test_pack_roundtrip_ragged_and_pad_zero():
     assert not full[:, K:].any()
 
 
+def test_pack_non_finite_inputs_follow_the_comparison():
+    """Sign is the comparison x >= 0: +inf gives 1, -inf and NaN give 0 (outside the method's
+    domain, but the reading is fixed so that both sides of the parity tests agree on it)."""
+    x = np.array([[np.inf, -np.inf, np.nan, -np.nan, 1.0, -1.0, 0.0, 2.0]], dtype=np.float32)
+    assert unpack(oracle.sign_pack(x), 8)[0].tolist() == [1, 0, 0, 0, 1, 0, 1, 1]
+    s = oracle.block_scales(x, 4)
+    assert np.isnan(s[0, 0]) and s[0, 1] == np.float32(1.0)
+
+
 def test_pack_word_boundaries():
     """Catches: off-by-one at bit 31/32 and between words."""
     K = 96
