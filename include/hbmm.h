@@ -27,8 +27,8 @@
  *           Words [0, hbmm_packed_ld_words(K)) of every row are written; bits at k >= K
  *           inside them are 0.  Words past that (if ldw is larger) are not touched.
  *   scales  rows x lds fp32, entry j of a row = mean |x| over k in [j*beta, (j+1)*beta);
- *           hbmm_num_blocks(K, beta) entries per row are written ("the full precision vector
- *           can be compressed beta times", section 4.2).
+ *           hbmm_num_blocks(K, beta) entries per row are written (section 4.2: the
+ *           full-precision side shrinks by the factor beta).
  */
 #ifndef HBMM_H
 #define HBMM_H
@@ -206,8 +206,8 @@ int hbmm_gemm_int(const uint32_t *a_bits, int64_t ldw_a, const uint32_t *b_bits,
                   int64_t M, int64_t N, int64_t K, int32_t *D, int64_t ldd, void *stream);
 
 /*
- * Dense comparison product on unquantised operands (the role the paper's "classical matrix
- * multiply" plays in section 4.2):  C = A . B^T, A M x K, B N x K, both K contiguous.
+ * Dense comparison product on unquantised operands (the full-precision matrix multiply that
+ * section 4.2 times its kernel against):  C = A . B^T, A M x K, B N x K, both K contiguous.
  *   dtype 0: fp32 operands.  dtype 1: bf16 operands (raw uint16 bit patterns).
  * fp32 accumulation and fp32 C in both cases.  K must be a multiple of 32 (fp32) or 64 (bf16); lda and
  * ldb must be multiples of 8 elements.

@@ -12,13 +12,14 @@
  * the definition states.
  *
  * Notation (paper section 3 and section 4.2):
- *   x        full-precision operand, `rows` x K, row-major, K contiguous (section 4,
- *            "row-major order", "row-wise binarization").
- *   beta     segment length ("binarization aggression"), segments are consecutive runs
- *            of beta elements along K inside one row.
+ *   x        full-precision operand, `rows` x K, row-major, K contiguous (section 4:
+ *            tensors are stored row-major and binarised row by row).
+ *   beta     segment length (the paper's measure of how aggressive the binarisation is);
+ *            segments are consecutive runs of beta elements along K inside one row.
  *   delta    scale of a segment = mean of |x| over the segment (Eq. 1 / Eq. 3; the sums
  *            there are read as beta terms, r = 0 .. beta-1, to agree with the 1/beta
- *            factor and with "mean of the absolute value of segments" in section 3).
+ *            factor and with section 3, which describes delta as a mean of absolute
+ *            values over a segment).
  *   x~       delta (Hadamard product) Sign(x)  (Eq. 2 / Eq. 4), Sign(0) = +1.
  *   O        Eq. 7: sum over segments of W_f,j * A_f,j * (signed agreement count).  Eq. 7
  *            prints popcount(xnor(.)), the number p of agreeing signs; the +-1 inner
@@ -30,7 +31,7 @@
  *     (the 6-element example of section 4 fixes the value mapping, not the endianness);
  *   - bits past K inside the last word, and pad words, are 0;
  *   - the stored scale is fp32 (sum in double, divide, round once);
- *   - beta = 1 means "not binarised": x~ = x (with -0.0 -> +0.0).
+ *   - beta = 1 means no binarisation: x~ = x (with -0.0 -> +0.0).
  *
  * Parity pins: every function below is pinned by tests/test_oracle_pins.py (brute
  * force on tiny inputs, closed forms, the paper's packing example, special cases that
@@ -75,7 +76,7 @@ void oracle_block_scales(const float *x, int64_t rows, int64_t K, int64_t ldx, i
     }
 }
 
-/* Sign + bit-pack (section 4: the row "-1 1 1 -1 -1 1" is stored as 011001).
+/* Sign + bit-pack (section 4's example: the row -1 1 1 -1 -1 1 is stored as 011001).
  * bits is rows x ldw uint32; every word of the row, pad words included, is written. */
 void oracle_sign_pack(const float *x, int64_t rows, int64_t K, int64_t ldx,
                       uint32_t *bits, int64_t ldw)

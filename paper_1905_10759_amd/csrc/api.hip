@@ -41,7 +41,8 @@ hipError_t zero_block(void *dst, int64_t ld, int64_t M, int64_t N, hipStream_t s
 }
 
 constexpr int64_t kMaxDim = (int64_t)1 << 30;   // rows, K: index arithmetic stays inside 32/64 bits
-constexpr int64_t kMaxPackK = (int64_t)1 << 26; // pack grid: K / 1024 must fit gridDim.y
+constexpr int64_t kMaxPackK = (int64_t)1 << 26; // pack: K and k-offsets inside a row are 32-bit
+constexpr int64_t kMaxPackColsK = (int64_t)65535 * 256;   // layout 1 walks K in gridDim.y slices of 256
 
 }  // namespace
 
@@ -76,6 +77,7 @@ int hbmm_quantize_pack(const float *x, int64_t rows, int64_t K, int64_t ldx, int
 {
     if (rows < 0 || K < 0 || rows > kMaxDim || K > kMaxPackK) return HBMM_EINVAL;
     if (layout != 0 && layout != 1) return HBMM_EINVAL;
+    if (layout == 1 && K > kMaxPackColsK) return HBMM_EINVAL;
     if (beta < 1) return HBMM_EINVAL;
     if (!supported_pack_beta(beta)) return HBMM_EUNSUPPORTED;
     if (K % beta != 0 || K % 32 != 0) return HBMM_EUNSUPPORTED;

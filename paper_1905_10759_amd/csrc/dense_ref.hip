@@ -1,6 +1,6 @@
 // Dense comparison GEMM on unquantised operands: C = A . B^T, A M x K, B N x K, both K contiguous,
-// fp32 accumulate and fp32 C.  It plays the role of the paper's "classical matrix multiply" (section
-// 4.2) next to the HBMM kernels; it is not part of the HBMM path.
+// fp32 accumulate and fp32 C.  It plays the role of the full-precision matrix multiply that section
+// 4.2 times its kernel against; it is not part of the HBMM path.
 //
 // Matrix-core kernel for gfx950.  A workgroup of 4 waves owns a 128 x 128 tile of C; K is walked in
 // stages of 128 bytes per operand row, staged through LDS (row stride padded by 16 bytes so that
