@@ -372,6 +372,26 @@ def extras(w, A, B, a_bits, a_s, b_bits, b_s, C, torch, hbmm, synth, args):
             tg = time_loop(lambda: hbmm.gemm(None, dA, 1, bb, bs, ww.beta_w, ww.K), 5, 1, torch)
         entry["gemm_ms"] = min(tg)
         entry["gemm_gops"] = 2.0 * ww.M * ww.N * ww.K / (min(tg) * 1e-3) / 1e9
+        if min(ww.beta_a, ww.beta_w) >= 32:   # the XNOR + popcount kernel
+            entry["gemm_frac_of_popcount_peak"] = entry["gemm_gops"] / (POPCOUNT_PEAK_TOPS * 1e3)
+        # the full-precision comparison on the same shape: the library's bf16 GEMM and this
+        # repository's own dense kernel (operands in the same rows x K form)
+        try:
+            dBr = dB.t().contiguous() if ww.b_layout == 1 else dB
+            Ab16, Bb16 = dA.to(torch.bfloat16), dBr.to(torch.bfloat16)
+            tl = time_loop(lambda: torch.matmul(Ab16, Bb16.t()), 10, 2, torch)
+            entry["torch_matmul_bf16_ms"] = min(tl)
+            entry["speedup_vs_torch_matmul_bf16"] = {"gemm": min(tl) / entry["gemm_ms"]}
+            if "gemm_fastest_algo_ms" in entry:
+                entry["speedup_vs_torch_matmul_bf16"]["gemm_fastest_algo"] = min(tl) / entry["gemm_fastest_algo_ms"]
+            if ww.K % 64 == 0:
+                Cd = torch.empty((ww.M, ww.N), dtype=torch.float32, device="cuda")
+                td = time_loop(lambda: hbmm.dense_ref_gemm(Ab16, Bb16, Cd), 10, 2, torch)
+                entry["dense_ref_bf16_ms"] = min(td)
+                del Cd
+            del Ab16, Bb16, dBr
+        except (hbmm.HbmmError, RuntimeError) as e:
+            entry["torch_matmul_bf16_ms"] = f"unavailable: {type(e).__name__}"
         if ww.M * ww.N * ww.K < 1e9 and ww.beta_a != 1:
             # launch-bound shapes: the whole step (pack A, pack B, gemm) queued back to back, and the same
             # three launches captured once into a HIP graph and replayed (the library allocates nothing
