@@ -32,11 +32,9 @@
 namespace hbmm {
 namespace {
 
-constexpr int kTP = 4;                 // P rows per lane
 constexpr int kTQ = 16;                // Q rows per wave
 constexpr int kWaves = 4;
 constexpr int kThreads = 64 * kWaves;  // 256
-constexpr int kTileP = 64 * kTP;       // 256 P rows per workgroup
 constexpr int kTileQ = kTQ * kWaves;   // 64 Q rows per workgroup
 constexpr int kCK = 16;                // 32-bit words of K per chunk (512 bits)
 constexpr int kNumXcd = 8;
@@ -66,9 +64,15 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // FUSED: the P operand is given as fp32 (a.p_src) and is binarised inside the kernel, chunk by chunk,
 // straight into the LDS tile -- the packed form of P never exists in memory.
-template <int G, bool INTEGER, bool FUSED>
+//
+// TP = P rows per lane: 4 (a workgroup owns 256 rows of P) for grids that fill the chip, 1 (64 rows)
+// for small problems, which then spread over four times as many workgroups.
+template <int G, bool INTEGER, bool FUSED, int TP>
 __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel(const PopcountGemmArgs a)
 {
+    constexpr int kTP = TP;
+    constexpr int kTileP = 64 * TP;                             // P rows per workgroup
+    static_assert(!FUSED || TP == 4, "the fused pack phase is written for 64 rows per wave");
     constexpr int kWordsPerGran = G / 32;                       // 1, 2, 4, 8
     constexpr int kGranPerChunk = kCK / kWordsPerGran;          // 16, 8, 4, 2
     constexpr int kSteps = kCK / kStep;                         // 8
@@ -119,7 +123,7 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
 
     // ---- staging registers for the next chunk
     constexpr int kBitPieces = kTileP * (kCK / 4) / kThreads;             // 2 x 16 bytes per thread
-    constexpr int kPsPerThread = kTileP * kGranPerChunk / kThreads;       // <= 8
+    constexpr int kPsPerThread = (kTileP * kGranPerChunk + kThreads - 1) / kThreads;   // <= 8
     constexpr int kQsPerThread = (kTileQ * kGranPerChunk + kThreads - 1) / kThreads;  // <= 4
     uint4 st_bits[kBitPieces];
     float st_ps[INTEGER ? 1 : kPsPerThread];
@@ -155,7 +159,8 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
                     const int e = id % kGranPerChunk;
                     const int blk = chunk * nsp + e;
                     st_ps[r] = 0.f;
-                    if (e < nsp && row < a.P && blk < nblk_p) st_ps[r] = a.p_scales[(int64_t)row * a.lds_p + blk];
+                    if (id < kTileP * kGranPerChunk && e < nsp && row < a.P && blk < nblk_p)
+                        st_ps[r] = a.p_scales[(int64_t)row * a.lds_p + blk];
                 }
             }
 #pragma unroll
@@ -189,7 +194,8 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
 #pragma unroll
                 for (int r = 0; r < kPsPerThread; ++r) {
                     const int id = tid + r * kThreads;
-                    s_ps[buf][(id / kGranPerChunk) * kScaleStrideP + id % kGranPerChunk] = st_ps[r];
+                    if (id < kTileP * kGranPerChunk)
+                        s_ps[buf][(id / kGranPerChunk) * kScaleStrideP + id % kGranPerChunk] = st_ps[r];
                 }
             }
 #pragma unroll
@@ -531,14 +537,14 @@ __global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel
     }
 }
 
-template <int G, bool INTEGER, bool FUSED = false>
+template <int G, bool INTEGER, bool FUSED = false, int TP = 4>
 hipError_t launch(const PopcountGemmArgs &a, hipStream_t s)
 {
     int64_t nblocks = (int64_t)a.tiles_p * a.tiles_q;
     if (nblocks <= 0) return hipSuccess;
     if (a.sup_p != 0) nblocks = (int64_t)((a.n_super + kNumXcd - 1) / kNumXcd) * kNumXcd * kSuperTiles;
     if (nblocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    popcount_gemm_kernel<G, INTEGER, FUSED><<<dim3((unsigned)nblocks), dim3(kThreads), 0, s>>>(a);
+    popcount_gemm_kernel<G, INTEGER, FUSED, TP><<<dim3((unsigned)nblocks), dim3(kThreads), 0, s>>>(a);
     return hipGetLastError();
 }
 
@@ -547,8 +553,12 @@ hipError_t launch(const PopcountGemmArgs &a, hipStream_t s)
 hipError_t launch_popcount_gemm(const PopcountGemmArgs &args, int G, int integer, hipStream_t s)
 {
     PopcountGemmArgs a = args;
-    a.tiles_p = (a.P + kTileP - 1) / kTileP;
     a.tiles_q = (a.Q + kTileQ - 1) / kTileQ;
+    // 256 rows of P per workgroup, or 64 when that grid would leave more than half of the compute
+    // units without a workgroup (small problems are bound by the length of one workgroup's work)
+    const bool narrow = a.p_src == nullptr && (int64_t)((a.P + 255) / 256) * a.tiles_q < 128;
+    const int tile_p = narrow ? 64 : 256;
+    a.tiles_p = (a.P + tile_p - 1) / tile_p;
     // super-tile shape: sup_p x (64 / sup_p); a P tile is 4x the rows of a Q tile, so 4 x 16 balances
     // the two footprints; narrower when P has fewer tiles
     a.sup_p = a.tiles_p >= 4 ? 4 : (a.tiles_p >= 2 ? 2 : 1);
@@ -558,13 +568,22 @@ hipError_t launch_popcount_gemm(const PopcountGemmArgs &args, int G, int integer
         const int sup_q = kSuperTiles / a.sup_p;
         a.n_super = a.n_super_p * ((a.tiles_q + sup_q - 1) / sup_q);
     }
-    if (integer) return launch<64, true>(a, s);
+    if (integer) return narrow ? launch<64, true, false, 1>(a, s) : launch<64, true>(a, s);
     if (a.p_src != nullptr) {
         switch (G) {
         case 32: return launch<32, false, true>(a, s);
         case 64: return launch<64, false, true>(a, s);
         case 128: return launch<128, false, true>(a, s);
         case 256: return launch<256, false, true>(a, s);
+        }
+        return hipErrorInvalidValue;
+    }
+    if (narrow) {
+        switch (G) {
+        case 32: return launch<32, false, false, 1>(a, s);
+        case 64: return launch<64, false, false, 1>(a, s);
+        case 128: return launch<128, false, false, 1>(a, s);
+        case 256: return launch<256, false, false, 1>(a, s);
         }
         return hipErrorInvalidValue;
     }

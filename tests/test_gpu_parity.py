@@ -119,7 +119,7 @@ def test_pack_non_finite_inputs():
 
 # ---------------------------------------------------------------------------------- gemm_int
 @pytest.mark.parametrize("M,N,K", [(64, 64, 512), (1, 1, 32), (300, 130, 1000), (257, 129, 544), (40, 600, 4608),
-                                   (513, 17, 96)])
+                                   (513, 17, 96), (2100, 1990, 1000), (700, 4100, 352)])
 def test_gemm_int_bit_exact(M, N, K):
     A, B = synth.normal(300 + M, (M, K)), synth.normal(301 + N, (N, K))
     a, b = oracle.sign_pack(A), oracle.sign_pack(B)
@@ -140,8 +140,11 @@ def run_gemm_case(A, B, beta_a, beta_w, algo=0):
     return assert_close_to_oracle(got.cpu().numpy(), ref, T, f"gemm {A.shape}x{B.shape} b=({beta_a},{beta_w})")
 
 
+# (small grids run on 64-row workgroups, large ones on 256-row workgroups: the last two shapes are ragged
+# in both dimensions and large enough for the latter)
 @pytest.mark.parametrize("beta", [32, 64, 128, 256])
-@pytest.mark.parametrize("M,N,K", [(64, 64, 512), (300, 200, 1024), (129, 257, 1536), (5, 3, 256), (260, 140, 4608)])
+@pytest.mark.parametrize("M,N,K", [(64, 64, 512), (300, 200, 1024), (129, 257, 1536), (5, 3, 256), (260, 140, 4608),
+                                   (2100, 1990, 1024), (4100, 700, 768)])
 def test_gemm_equal_beta(beta, M, N, K):
     run_gemm_case(synth.normal(400 + M, (M, K)), synth.uniform_pm1(401 + N, (N, K)), beta, beta)
 
@@ -149,6 +152,7 @@ def test_gemm_equal_beta(beta, M, N, K):
 @pytest.mark.parametrize("beta_a,beta_w", [(32, 64), (64, 32), (32, 256), (256, 32), (128, 64), (64, 256)])
 def test_gemm_mixed_beta(beta_a, beta_w):
     run_gemm_case(synth.relu_normal(500, (150, 1280)), synth.normal(501, (270, 1280), std=0.04), beta_a, beta_w)
+    run_gemm_case(synth.relu_normal(502, (2050, 1280)), synth.normal(503, (1100, 1280), std=0.04), beta_a, beta_w)
 
 
 @pytest.mark.parametrize("beta", [32, 64, 128, 256])
