@@ -11,7 +11,7 @@
 // feeds row (l mod 32) and the 32 consecutive k at 32 * (l div 32) -- exactly one packed word of
 // that row -- as 32 nibbles in four registers, k ascending from the low nibble of the first one.
 //
-// Expansion of a packed word into four registers of 8 nibbles, seven vector instructions: both
+// Expansion of a packed word into four registers of 8 nibbles, eight vector instructions: both
 // operands are expanded the same way, so the order of the 32 elements inside an MFMA step is free,
 // and register s takes the bits 4i + s, i = 0..7, of the word: shifted left by 3 - s they sit on the
 // sign bits of the eight nibbles.
@@ -50,13 +50,25 @@ struct MfmaFp4Args {
 
 // 32 sign bits -> 32 fp4 values in the order described above: E2M1 +1.0 (0x2) and -1.0 (0xA) differ in
 // the top bit of the nibble only, so a register is 0x22222222 with eight bits of the word dropped into
-// bits 4i + 3 (a shift and one and-or).  A set bit gives -1 and a clear bit +1 -- for both operands, so
-// every product (+-1)(+-1) is the one the signs define.
+// bits 4i + 3: mask them where they are (v_and_b32 with a literal), then shift and merge in one
+// v_lshl_or_b32 -- written as asm, because the optimiser rewrites the C expression into shift, and, or.
+// A set bit gives -1 and a clear bit +1 -- for both operands, so every product (+-1)(+-1) is the one
+// the signs define.
+template <int SHIFT>
+__device__ __forceinline__ int lshl_or(uint32_t x, uint32_t c)
+{
+    int d;
+    asm("v_lshl_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(x), "n"(SHIFT), "s"(c));
+    return d;
+}
 __device__ __forceinline__ i32x4v expand32(uint32_t w)
 {
+    constexpr uint32_t kOnes = 0x22222222u;   // eight times +1.0
     i32x4v e;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) e[s] = (int)(((w << (3 - s)) & 0x88888888u) | 0x22222222u);
+    e[0] = lshl_or<3>(w & 0x11111111u, kOnes);
+    e[1] = lshl_or<2>(w & 0x22222222u, kOnes);
+    e[2] = lshl_or<1>(w & 0x44444444u, kOnes);
+    e[3] = lshl_or<0>(w & 0x88888888u, kOnes);
     return e;
 }
 
@@ -139,8 +151,9 @@ __global__ __launch_bounds__(2 * kBM4, kBM4 == 128 ? 2 : 1) void mfma_fp4_gemm_k
             const bool is_a = tid + j * kThreads4 < 4 * kBM4;   // uniform per j
             unsigned char *base = (is_a ? &s_a[buf][0] : &s_b[buf][0]) + idst[j];
             const int plane = is_a ? kPlaneA : kPlaneB;
-            const bool in_row = stage * kStageWords4 + iword[j] < ildw[j];   // else: words past the row, never counted (scale 0)
-            const uint32_t w0 = in_row ? st.bits[j].x : 0u, w1 = in_row ? st.bits[j].y : 0u;
+            // (word pairs past the end of the row hold whatever the clamped load returned: they lie in
+            // segments past K, whose scale is parked as 0)
+            const uint32_t w0 = st.bits[j].x, w1 = st.bits[j].y;
             *reinterpret_cast<i32x4v *>(base) = expand32(w0);
             *reinterpret_cast<i32x4v *>(base + plane) = expand32(w1);
         }
@@ -166,8 +179,9 @@ __global__ __launch_bounds__(2 * kBM4, kBM4 == 128 ? 2 : 1) void mfma_fp4_gemm_k
             }
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-    auto run_stage = [&](int stage, const Staged &ready, Staged &incoming) {
-        const int buf = stage & 1;
+    // buf = stage mod 2 is passed as a literal, so that every LDS address of the stage is a register
+    // plus an immediate offset
+    auto run_stage = [&](int stage, const int buf, const Staged &ready, Staged &incoming) {
         fetch(incoming, stage + 3);
         const int rl = lane & 31, hi = lane >> 5;
         float sb_r[2];
@@ -240,10 +254,13 @@ __global__ __launch_bounds__(2 * kBM4, kBM4 == 128 ? 2 : 1) void mfma_fp4_gemm_k
     fetch(s0, 1);
     fetch(s1, 2);
     __syncthreads();
-    for (int stage = 0; stage < nstages; stage += 3) {
-        run_stage(stage, s0, s2);
-        if (stage + 1 < nstages) run_stage(stage + 1, s1, s0);
-        if (stage + 2 < nstages) run_stage(stage + 2, s2, s1);
+    for (int stage = 0; stage < nstages; stage += 6) {
+        run_stage(stage, 0, s0, s2);
+        if (stage + 1 < nstages) run_stage(stage + 1, 1, s1, s0);
+        if (stage + 2 < nstages) run_stage(stage + 2, 0, s2, s1);
+        if (stage + 3 < nstages) run_stage(stage + 3, 1, s0, s2);
+        if (stage + 4 < nstages) run_stage(stage + 4, 0, s1, s0);
+        if (stage + 5 < nstages) run_stage(stage + 5, 1, s2, s1);
     }
 
 #pragma unroll
