@@ -325,6 +325,40 @@ def test_gemm_both_segments_short(beta_a, beta_w):
     split_case(synth.relu_normal(922 + beta_a, (129, 96)), synth.uniform_pm1(923 + beta_w, (1, 96)), beta_a, beta_w)
 
 
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    betas = [1, 2, 4, 8, 16, 32, 64, 128, 256]
+    cases = []
+    while len(cases) < n:
+        beta_a, beta_w = int(rng.choice(betas)), int(rng.choice(betas))
+        if (beta_a == 1 and beta_w < 16) or (beta_w == 1 and beta_a < 16):
+            continue                      # reported as unsupported (tested elsewhere)
+        unit = max(32, beta_a, beta_w)
+        K = unit * int(rng.integers(1, max(2, 1536 // unit) + 1))
+        M, N = int(rng.integers(1, 420)), int(rng.integers(1, 420))
+        cases.append((M, N, K, beta_a, beta_w, int(rng.choice([0, -1])), int(rng.integers(0, 3)), int(rng.integers(0, 3))))
+    return cases
+
+
+@pytest.mark.parametrize("M,N,K,beta_a,beta_w,algo,kind_a,kind_b", _random_cases(48, 20260101))
+def test_gemm_seeded_random_sweep(M, N, K, beta_a, beta_w, algo, kind_a, kind_b):
+    """Shapes, segment lengths, kernel choice and value distributions drawn from a fixed seed, against
+    the dense double-precision definition."""
+    make = [lambda s, sh: synth.normal(s, sh), lambda s, sh: synth.relu_normal(s, sh), lambda s, sh: synth.uniform_pm1(s, sh)]
+    A, B = make[kind_a](4000 + M, (M, K)), make[kind_b](5000 + N, (N, K))
+    At, Bt = oracle.materialize(A, beta_a), oracle.materialize(B, beta_w)
+    ref, T = oracle.dense_f64_gemm(At, Bt), oracle.dense_f64_gemm(np.abs(At), np.abs(Bt))
+
+    def operand(x, beta):
+        if beta == 1:
+            return None, dev(x)
+        return dev(oracle.sign_pack(x).view(np.int32)), dev(oracle.block_scales(x, beta))
+
+    (ab, as_), (bb, bs) = operand(A, beta_a), operand(B, beta_w)
+    got = hbmm.gemm(ab, as_, beta_a, bb, bs, beta_w, K, algo=algo)
+    assert_close_to_oracle(got.cpu().numpy(), ref, T, f"sweep {M}x{N}x{K} b=({beta_a},{beta_w}) algo {algo}")
+
+
 def test_gemm_two_unquantised_operands_are_reported_unsupported():
     x = torch.zeros((4, 64), dtype=torch.float32, device="cuda")
     with pytest.raises(hbmm.HbmmError) as ei:
