@@ -633,6 +633,38 @@ def test_conv2d(case, algo):
         assert torch.equal(out, hbmm.conv2d(ab, asc, beta_a, A.shape, wb, ws, beta_w, (KH, KW), stride, pad, algo=1))
 
 
+def _random_conv_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < n:
+        C = int(rng.choice([32, 64, 96]))
+        KH, KW = (int(v) for v in rng.choice([1, 2, 3], size=2))
+        beta_w = int(rng.choice([16, 32, 64, 128]))
+        if (C * KH * KW) % beta_w:
+            continue
+        beta_a = int(rng.choice([2, 4, 8]))
+        W = beta_a * int(rng.integers(1, 7)) * (2 if beta_a == 2 else 1)      # a multiple of beta_a and of 4
+        H = int(rng.integers(3, 13))
+        stride, pad = int(rng.integers(1, 3)), int(rng.integers(0, 3))
+        if H + 2 * pad < KH or W + 2 * pad < KW:
+            continue
+        cases.append((int(rng.integers(1, 4)), C, H, W, int(rng.integers(1, 90)), KH, KW, stride, pad, beta_a, beta_w))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_conv_cases(20, 20260102), ids=lambda c: "x".join(str(v) for v in c))
+def test_conv2d_seeded_random_sweep(case):
+    """Layer geometries drawn from a fixed seed; the library picks the kernel."""
+    B, C, H, W, N, KH, KW, stride, pad, beta_a, beta_w = case
+    A, Wf = _conv_inputs(700 + H + W + N, B, C, H, W, N, KH, KW)
+    ref, T = oracle.hbmm_conv2d(A, Wf, beta_a, beta_w, stride, pad, want_T=True)
+    ab, asc = hbmm.quantize_pack_tensor(dev(A), beta_a)
+    wb, ws = hbmm.quantize_pack(dev(Wf.reshape(N, -1)), beta_w)
+    out = hbmm.conv2d(ab, asc, beta_a, A.shape, wb, ws, beta_w, (KH, KW), stride, pad)
+    assert tuple(out.shape) == ref.shape
+    assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d sweep {case}")
+
+
 def test_conv2d_equals_gemm_on_im2col():
     """For a 1x1 window with stride 1 the convolution is the matrix product of the positions x channels
     matrix of materialised activations with the filters: the same kernel family must agree with
