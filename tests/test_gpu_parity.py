@@ -93,6 +93,38 @@ def test_pack_cols(beta):
     assert np.array_equal(scales.cpu().numpy(), oracle.block_scales(xt, beta))
 
 
+def _random_pack_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        beta = int(rng.choice([2, 4, 8, 16, 32, 64, 128, 256]))
+        K = max(32, beta) * int(rng.integers(1, 40))
+        cases.append((int(rng.integers(1, 300)), K, beta, int(rng.integers(0, 2)), int(rng.choice([0, 4, 5, 64])), int(rng.integers(0, 3))))
+    return cases
+
+
+@pytest.mark.parametrize("rows,K,beta,layout,pad,kind", _random_pack_cases(32, 20260103))
+def test_pack_seeded_random_sweep(rows, K, beta, layout, pad, kind):
+    """Shapes, segment lengths, both source layouts and padded (aligned and unaligned) leading dimensions
+    drawn from a fixed seed; backward of the same operand on the way."""
+    make = [synth.normal, synth.relu_normal, synth.uniform_pm1]
+    x = make[kind](6000 + rows + K, (rows, K))
+    src_shape = (rows, K) if layout == 0 else (K, rows)
+    wide = torch.zeros((src_shape[0], src_shape[1] + pad), dtype=torch.float32, device="cuda")
+    wide[:, :src_shape[1]] = dev(x if layout == 0 else np.ascontiguousarray(x.T))
+    bits, scales = hbmm.quantize_pack(wide[:, :src_shape[1]], beta, layout=layout)
+    assert np.array_equal(words(bits), oracle.sign_pack(x))
+    ref = oracle.block_scales(x, beta)
+    assert np.all(np.abs(scales.cpu().numpy() - ref) <= scale_tol(beta) * ref + 1e-30)
+    if layout == 0:
+        g = synth.normal(6001 + rows, (rows, K))
+        gw = torch.zeros_like(wide)
+        gw[:, :K] = dev(g)
+        rb, Tb = oracle.binarize_backward(x, g, beta, want_T=True)
+        got = hbmm.binarize_backward(wide[:, :K], gw[:, :K], beta).cpu().numpy()
+        assert np.all(np.abs(got.astype(np.float64) - rb) <= (np.log2(beta) + 3) * 2.0 ** -24 * Tb + 1e-30)
+
+
 def test_pack_all_zero_and_negative():
     x = np.zeros((4, 256), dtype=np.float32)
     x[1] = -1.0
