@@ -12,10 +12,10 @@
 // Operand layout of the instruction (checked on the device with single-entry operands): lane l
 // feeds row (l mod 32) and the 8 consecutive k at 8 * (l div 32), one byte each, k ascending.
 //
-// Expansion of a 16-bit segment h into 16 bytes, thirteen vector instructions: both operands are
+// Expansion of a 16-bit segment h into 16 bytes, nine vector instructions: both operands are
 // expanded the same way, so the order of the 16 elements inside a step is free.  With
-// x = h | (h << 12), (x >> p) & 0x01010101 picks bits {p, p + 8, p + 4, p + 12} of h into the low bit of
-// the four bytes: four 1-bit selectors that v_perm_b32 looks up in a 2-entry table (0xB8, 0x38).
+// x = h | (h << 12), the mask 0x01010101 << p picks bits {p, p + 8, p + 4, p + 12} of h, one per byte,
+// and a shift by 7 - p puts them on the sign bits of four bytes that are otherwise 0x38 (expand16).
 // p = 0, 1 give the 8 bytes of lanes 0..31, p = 2, 3 those of lanes 32..63.
 //
 // Workgroup = 8 waves (4 x 2), tile 256 (M) x 128 (N); wave = 64 x 64 = 2 x 2 MFMA tiles.  K is walked
@@ -48,14 +48,28 @@ struct MfmaFp8Args {
     int32_t tiles_m, tiles_n, n_super_n, n_super;
 };
 
-// 16 sign bits (bit = 1: +1) -> 16 fp8 values; lo = the 8 bytes of lanes 0..31, hi = those of lanes 32..63
+// 16 sign bits -> 16 fp8 values; lo = the 8 bytes of lanes 0..31, hi = those of lanes 32..63.  E4M3 +1.0
+// (0x38) and -1.0 (0xB8) differ in the top bit of the byte only, so a register is 0x38383838 with four
+// bits dropped into bits 7, 15, 23, 31: with x = h | h << 12 the bits p, p + 8, p + 16, p + 24 of x are
+// the segment's bits p, p + 8, p + 4, p + 12, and one mask plus one v_lshl_or_b32 (written as asm: the
+// optimiser turns the C expression into shift, and, or) moves them there.  A set bit gives -1 and a
+// clear bit +1 -- for both operands, so every product is the one the signs define; which element of
+// the segment sits in which byte does not matter as long as both operands agree.
+template <int SHIFT>
+__device__ __forceinline__ uint32_t lshl_or8(uint32_t x, uint32_t c)
+{
+    uint32_t d;
+    asm("v_lshl_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(x), "n"(SHIFT), "s"(c));
+    return d;
+}
 __device__ __forceinline__ void expand16(uint32_t h, uint2 &lo, uint2 &hi)
 {
+    constexpr uint32_t kOnes = 0x38383838u;   // four times +1.0
     const uint32_t x = h | (h << 12);
-    lo.x = __builtin_amdgcn_perm(0u, 0x000038b8u, x & 0x01010101u);
-    lo.y = __builtin_amdgcn_perm(0u, 0x000038b8u, (x >> 1) & 0x01010101u);
-    hi.x = __builtin_amdgcn_perm(0u, 0x000038b8u, (x >> 2) & 0x01010101u);
-    hi.y = __builtin_amdgcn_perm(0u, 0x000038b8u, (x >> 3) & 0x01010101u);
+    lo.x = lshl_or8<7>(x & 0x01010101u, kOnes);
+    lo.y = lshl_or8<6>(x & 0x02020202u, kOnes);
+    hi.x = lshl_or8<5>(x & 0x04040404u, kOnes);
+    hi.y = lshl_or8<4>(x & 0x08080808u, kOnes);
 }
 
 // SEG = segments per stage: 8 (G = 16) or 4 (G = 32).
@@ -150,8 +164,9 @@ __global__ __launch_bounds__(kThreads8) void mfma_fp8_gemm_kernel(const MfmaFp8A
             }
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-    auto run_stage = [&](int stage, const Staged &ready, Staged &incoming) {
-        const int buf = stage & 1;
+    // buf = stage mod 2 is passed as a literal, so that every LDS address of the stage is a register
+    // plus an immediate offset
+    auto run_stage = [&](int stage, const int buf, const Staged &ready, Staged &incoming) {
         fetch(incoming, stage + 2);
         const int rl = lane & 31, hi = lane >> 5;
         float sb_r[2];
@@ -216,8 +231,8 @@ __global__ __launch_bounds__(kThreads8) void mfma_fp8_gemm_kernel(const MfmaFp8A
     fetch(s0, 1);
     __syncthreads();
     for (int stage = 0; stage < nstages; stage += 2) {
-        run_stage(stage, s0, s1);
-        if (stage + 1 < nstages) run_stage(stage + 1, s1, s0);
+        run_stage(stage, 0, s0, s1);
+        if (stage + 1 < nstages) run_stage(stage + 1, 1, s1, s0);
     }
 
 #pragma unroll
