@@ -115,13 +115,13 @@ static int check_packed(const uint32_t *bits, int64_t rows, int64_t K, int64_t l
     return HBMM_OK;
 }
 
-// Pick which operand is held per lane (tile 256) and which is broadcast (tile 128): the one that
+// Pick which operand is held per lane (tile 128) and which is broadcast (tile 64): the one that
 // wastes fewer padded outputs; B per lane is preferred because then a wave stores along a row of C.
 static bool b_is_lane_side(int64_t M, int64_t N)
 {
     auto up = [](int64_t v, int64_t t) { return (v + t - 1) / t * t; };
-    const double cost_b = (double)up(N, 256) * (double)up(M, 128);
-    const double cost_a = (double)up(M, 256) * (double)up(N, 128) * 1.05;
+    const double cost_b = (double)up(N, 128) * (double)up(M, 64);
+    const double cost_a = (double)up(M, 128) * (double)up(N, 64) * 1.05;
     return cost_b <= cost_a;
 }
 

@@ -23,8 +23,8 @@
 //     factor -2 is folded into the P scale.  Epilogue per accumulator per segment: cvt, mul, fma.
 //   * K is walked in chunks of kCK words; the next chunk's P words and both operands' scales are
 //     fetched from global memory while the current chunk is being reduced, then parked in the
-//     other LDS buffer (one barrier per chunk).  A workgroup is 4 waves (tile 256 x 64) and two
-//     workgroups share a CU, so one group's barrier and LDS refill overlap the other's arithmetic.
+//     other LDS buffer (one barrier per chunk).  A workgroup is 4 waves (tile 128 x 64) and three or
+//     four workgroups share a CU, so one group's barrier and LDS refill overlap the others' arithmetic.
 // Either of A / B can be P or Q: the host picks the role by output strides.
 #include "kernels.h"
 #include "wave_ops.h"
@@ -65,10 +65,14 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // FUSED: the P operand is given as fp32 (a.p_src) and is binarised inside the kernel, chunk by chunk,
 // straight into the LDS tile -- the packed form of P never exists in memory.
 //
-// TP = P rows per lane: 4 (a workgroup owns 256 rows of P) for grids that fill the chip, 1 (64 rows)
-// for small problems, which then spread over four times as many workgroups.
+// TP = P rows per lane.  2 (a workgroup owns 128 rows of P; 128 to 166 registers per lane, so three or
+// four workgroups share a compute unit and cover each other's waits) is the form for grids that fill
+// the chip: it is 6 to 15 % faster than 4 rows per lane with two workgroups per compute unit, and
+// 1 row per lane is slower again (the scalar loads of Q are then shared by too little arithmetic).
+// 1 (64 rows) is used for small problems, which then spread over twice as many workgroups; 4 is
+// what the fused form is written for.
 template <int G, bool INTEGER, bool FUSED, int TP>
-__global__ __launch_bounds__(kThreads, 512 / kThreads) void popcount_gemm_kernel(const PopcountGemmArgs a)
+__global__ __launch_bounds__(kThreads, TP == 2 ? 3 : 2) void popcount_gemm_kernel(const PopcountGemmArgs a)
 {
     constexpr int kTP = TP;
     constexpr int kTileP = 64 * TP;                             // P rows per workgroup
@@ -554,13 +558,19 @@ hipError_t launch_popcount_gemm(const PopcountGemmArgs &args, int G, int integer
 {
     PopcountGemmArgs a = args;
     a.tiles_q = (a.Q + kTileQ - 1) / kTileQ;
-    // 256 rows of P per workgroup, or 64 when that grid would leave more than half of the compute
-    // units without a workgroup (small problems are bound by the length of one workgroup's work)
-    const bool narrow = a.p_src == nullptr && (int64_t)((a.P + 255) / 256) * a.tiles_q < 128;
-    const int tile_p = narrow ? 64 : 256;
+    // 128 rows of P per workgroup (three workgroups share a compute unit), or 64 when that grid would
+    // leave compute units without a workgroup (small problems are bound by the length of one
+    // workgroup's work); the fused form is written for 256.
+    const bool fused = a.p_src != nullptr;
+    const bool narrow = !fused && (int64_t)((a.P + 127) / 128) * a.tiles_q < 256;
+    // (a K of at most two chunks on a grid that fills the chip either way: 256 rows, i.e. half as many
+    // workgroup starts and ends, measured 10 % faster on 200704 x 576 x 64)
+    // (not for 32-bit segments: four rows per lane do not fit the registers there)
+    const bool wide = !fused && !narrow && !integer && G != 32 && a.kwords <= 2 * kCK &&
+                      (int64_t)((a.P + 255) / 256) * a.tiles_q >= 512;
+    const int tile_p = fused || wide ? 256 : narrow ? 64 : 128;
     a.tiles_p = (a.P + tile_p - 1) / tile_p;
-    // super-tile shape: sup_p x (64 / sup_p); a P tile is 4x the rows of a Q tile, so 4 x 16 balances
-    // the two footprints; narrower when P has fewer tiles
+    // super-tile shape: sup_p x (64 / sup_p) tiles; narrower when P has fewer tiles
     a.sup_p = a.tiles_p >= 4 ? 4 : (a.tiles_p >= 2 ? 2 : 1);
     if ((int64_t)a.tiles_p * a.tiles_q <= 2 * kNumXcd * kSuperTiles) a.sup_p = 0;   // at most two rounds: plain map
     if (a.sup_p != 0) {
@@ -568,8 +578,8 @@ hipError_t launch_popcount_gemm(const PopcountGemmArgs &args, int G, int integer
         const int sup_q = kSuperTiles / a.sup_p;
         a.n_super = a.n_super_p * ((a.tiles_q + sup_q - 1) / sup_q);
     }
-    if (integer) return narrow ? launch<64, true, false, 1>(a, s) : launch<64, true>(a, s);
-    if (a.p_src != nullptr) {
+    if (integer) return narrow ? launch<64, true, false, 1>(a, s) : launch<64, true, false, 2>(a, s);
+    if (fused) {
         switch (G) {
         case 32: return launch<32, false, true>(a, s);
         case 64: return launch<64, false, true>(a, s);
@@ -587,11 +597,19 @@ hipError_t launch_popcount_gemm(const PopcountGemmArgs &args, int G, int integer
         }
         return hipErrorInvalidValue;
     }
+    if (wide) {
+        switch (G) {
+        case 64: return launch<64, false, false, 4>(a, s);
+        case 128: return launch<128, false, false, 4>(a, s);
+        case 256: return launch<256, false, false, 4>(a, s);
+        }
+        return hipErrorInvalidValue;
+    }
     switch (G) {
-    case 32: return launch<32, false>(a, s);
-    case 64: return launch<64, false>(a, s);
-    case 128: return launch<128, false>(a, s);
-    case 256: return launch<256, false>(a, s);
+    case 32: return launch<32, false, false, 2>(a, s);
+    case 64: return launch<64, false, false, 2>(a, s);
+    case 128: return launch<128, false, false, 2>(a, s);
+    case 256: return launch<256, false, false, 2>(a, s);
     }
     return hipErrorInvalidValue;
 }

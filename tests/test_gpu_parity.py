@@ -752,3 +752,12 @@ def test_binarize_backward_tensor(beta):
     got = hbmm.binarize_backward_tensor(dev(x), dev(g), beta).cpu().numpy().reshape(-1, shape[-1])
     err = np.abs(got.astype(np.float64) - ref)
     assert np.all(err <= (np.log2(beta) + 3) * 2.0 ** -24 * T + 1e-30)
+
+
+@pytest.mark.parametrize("beta", [32, 64, 128, 256])
+def test_gemm_short_k_on_a_large_grid(beta):
+    """A K of at most two chunks on a grid that fills the chip takes the 256-row workgroups (except for
+    32-bit segments): ragged in both dimensions, against the oracle's integer path."""
+    M, N, K = 33000, 1000, 768
+    A, B = synth.normal(8100 + beta, (M, K)), synth.uniform_pm1(8101 + beta, (N, K))
+    run_gemm_case(A, B, beta, beta)
