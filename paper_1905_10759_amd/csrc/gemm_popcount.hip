@@ -38,7 +38,7 @@ constexpr int kThreads = 64 * kWaves;  // 256
 constexpr int kTileQ = kTQ * kWaves;   // 64 Q rows per workgroup
 constexpr int kCK = 16;                // 32-bit words of K per chunk (512 bits)
 constexpr int kNumXcd = 8;
-constexpr int kSuperTiles = 64;          // tiles per super-tile (two workgroups per CU x 32 CUs of an XCD)
+constexpr int kSuperTiles = 128;         // tiles per super-tile (about the workgroups resident on one XCD: 32 CUs x 3..4)
 constexpr int kStep = 2;               // words per inner step (one 8-byte LDS read, one s_load_dwordx2)
 constexpr int kBitsStride = kCK + 2;   // LDS row stride in words: 2 * odd => conflict-free b64 reads
 
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(kThreads, TP == 2 ? 3 : 2) void popcount_gemm_kerne
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // Workgroup -> tile.  Workgroups are dealt to the 8 XCDs round-robin and every XCD has its own
-    // L2, so tiles are grouped into super-tiles of sup_p x sup_q = 64 tiles whose workgroups all land
+    // L2, so tiles are grouped into super-tiles of sup_p x sup_q = 128 tiles whose workgroups all land
     // on one XCD at about the same time: a P tile is then fetched into that L2 once for sup_q
     // workgroups and a Q tile once for sup_p of them.
     // Small grids (sup_p == 0) are mapped plainly.
@@ -570,8 +570,10 @@ hipError_t launch_popcount_gemm(const PopcountGemmArgs &args, int G, int integer
                       (int64_t)((a.P + 255) / 256) * a.tiles_q >= 512;
     const int tile_p = fused || wide ? 256 : narrow ? 64 : 128;
     a.tiles_p = (a.P + tile_p - 1) / tile_p;
-    // super-tile shape: sup_p x (64 / sup_p) tiles; narrower when P has fewer tiles
-    a.sup_p = a.tiles_p >= 4 ? 4 : (a.tiles_p >= 2 ? 2 : 1);
+    // super-tile shape: sup_p x (128 / sup_p) tiles, 16 x 8 when P has that many tiles (2048 rows of P and
+    // 512 of Q: 2.5 MB of packed bits at K = 8192, inside one XCD's 4 MB L2); measured against 4 x 16,
+    // 8 x 8, 32 x 4 and super-tiles of 64, 256 and 512 tiles
+    a.sup_p = a.tiles_p >= 16 ? 16 : a.tiles_p >= 4 ? 4 : (a.tiles_p >= 2 ? 2 : 1);
     if ((int64_t)a.tiles_p * a.tiles_q <= 2 * kNumXcd * kSuperTiles) a.sup_p = 0;   // at most two rounds: plain map
     if (a.sup_p != 0) {
         a.n_super_p = (a.tiles_p + a.sup_p - 1) / a.sup_p;
