@@ -69,14 +69,14 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // four workgroups share a compute unit and cover each other's waits) is the form for grids that fill
 // the chip: it is 6 to 15 % faster than 4 rows per lane with two workgroups per compute unit, and
 // 1 row per lane is slower again (the scalar loads of Q are then shared by too little arithmetic).
-// 1 (64 rows) is used for small problems, which then spread over twice as many workgroups; 4 is
-// what the fused form is written for.
+// 1 (64 rows) is used for small problems, which then spread over twice as many workgroups; 4 (256
+// rows) for a K of at most two chunks on a large grid.  The fused form uses 2 and 1 the same way.
 template <int G, bool INTEGER, bool FUSED, int TP>
 __global__ __launch_bounds__(kThreads, TP == 2 ? 3 : 2) void popcount_gemm_kernel(const PopcountGemmArgs a)
 {
     constexpr int kTP = TP;
     constexpr int kTileP = 64 * TP;                             // P rows per workgroup
-    static_assert(!FUSED || TP == 4, "the fused pack phase is written for 64 rows per wave");
+    constexpr int kRowsPerWave = kTileP / kWaves;                // rows of P a wave binarises in the fused form
     constexpr int kWordsPerGran = G / 32;                       // 1, 2, 4, 8
     constexpr int kGranPerChunk = kCK / kWordsPerGran;          // 16, 8, 4, 2
     constexpr int kSteps = kCK / kStep;                         // 8
@@ -211,8 +211,8 @@ __global__ __launch_bounds__(kThreads, TP == 2 ? 3 : 2) void popcount_gemm_kerne
         }
     };
 
-    // ---- FUSED: binarise chunk `chunk` of this workgroup's 256 P rows from fp32 into LDS buffer `buf`.
-    // A wave owns 64 rows; per row the chunk is 512 elements = two 16-byte loads per lane (lane l holds
+    // ---- FUSED: binarise chunk `chunk` of this workgroup's P rows from fp32 into LDS buffer `buf`.
+    // A wave owns kRowsPerWave rows; per row the chunk is 512 elements = two 16-byte loads per lane (lane l holds
     // elements 4l .. 4l+3 of each half).  Signs, words and scales are produced exactly as in the
     // stand-alone pack kernel (same nibble merge, same pairwise order of the |x| sums), so the scales
     // are bit-identical to packing first.
@@ -220,7 +220,8 @@ __global__ __launch_bounds__(kThreads, TP == 2 ? 3 : 2) void popcount_gemm_kerne
     // words the loads of the next are in flight, and the first batch of the next chunk is requested
     // before the popcount phase of this one, so that the memory pipe is never idle.
     constexpr int kPackRows = 4;
-    constexpr int kPackBatches = 64 / kPackRows;
+    constexpr int kPackBatches = kRowsPerWave / kPackRows;
+    static_assert(kPackBatches % 2 == 0, "batches are worked in pairs");
     f32x4 pv[FUSED ? 2 : 1][FUSED ? kPackRows : 1][2];
     auto pack_issue = [&](int chunk, int b, f32x4 (&v)[FUSED ? kPackRows : 1][2]) {
         if constexpr (FUSED) {
@@ -228,7 +229,7 @@ __global__ __launch_bounds__(kThreads, TP == 2 ? 3 : 2) void popcount_gemm_kerne
             const int k_lane = chunk * (kCK * 32) + 4 * lane;
 #pragma unroll
             for (int j = 0; j < kPackRows; ++j) {
-                const int row = p0 + wave * 64 + b * kPackRows + j;
+                const int row = p0 + wave * kRowsPerWave + b * kPackRows + j;
                 const float *src = a.p_src + (int64_t)min(row, a.P - 1) * a.ld_p_src;
 #pragma unroll
                 for (int h = 0; h < 2; ++h)
@@ -286,7 +287,7 @@ __global__ __launch_bounds__(kThreads, TP == 2 ? 3 : 2) void popcount_gemm_kerne
                             if (h < halves) sum[j][h] += __shfl_xor(sum[j][h], 32);
                 }
             }
-            const int row_l = wave * 64 + b * kPackRows;
+            const int row_l = wave * kRowsPerWave + b * kPackRows;
             if ((lane & 7) == 0) {
 #pragma unroll
                 for (int h = 0; h < 2; ++h)
@@ -560,15 +561,15 @@ hipError_t launch_popcount_gemm(const PopcountGemmArgs &args, int G, int integer
     a.tiles_q = (a.Q + kTileQ - 1) / kTileQ;
     // 128 rows of P per workgroup (three workgroups share a compute unit), or 64 when that grid would
     // leave compute units without a workgroup (small problems are bound by the length of one
-    // workgroup's work); the fused form is written for 256.
+    // workgroup's work).
     const bool fused = a.p_src != nullptr;
-    const bool narrow = !fused && (int64_t)((a.P + 127) / 128) * a.tiles_q < 256;
+    const bool narrow = (int64_t)((a.P + 127) / 128) * a.tiles_q < 256;
     // (a K of at most two chunks on a grid that fills the chip either way: 256 rows, i.e. half as many
     // workgroup starts and ends, measured 10 % faster on 200704 x 576 x 64)
     // (not for 32-bit segments: four rows per lane do not fit the registers there)
     const bool wide = !fused && !narrow && !integer && G != 32 && a.kwords <= 2 * kCK &&
                       (int64_t)((a.P + 255) / 256) * a.tiles_q >= 512;
-    const int tile_p = fused || wide ? 256 : narrow ? 64 : 128;
+    const int tile_p = wide ? 256 : narrow ? 64 : 128;
     a.tiles_p = (a.P + tile_p - 1) / tile_p;
     // super-tile shape: sup_p x (128 / sup_p) tiles, 16 x 8 when P has that many tiles (2048 rows of P and
     // 512 of Q: 2.5 MB of packed bits at K = 8192, inside one XCD's 4 MB L2); measured against 4 x 16,
@@ -583,10 +584,10 @@ hipError_t launch_popcount_gemm(const PopcountGemmArgs &args, int G, int integer
     if (integer) return narrow ? launch<64, true, false, 1>(a, s) : launch<64, true, false, 2>(a, s);
     if (fused) {
         switch (G) {
-        case 32: return launch<32, false, true>(a, s);
-        case 64: return launch<64, false, true>(a, s);
-        case 128: return launch<128, false, true>(a, s);
-        case 256: return launch<256, false, true>(a, s);
+        case 32: return narrow ? launch<32, false, true, 1>(a, s) : launch<32, false, true, 2>(a, s);
+        case 64: return narrow ? launch<64, false, true, 1>(a, s) : launch<64, false, true, 2>(a, s);
+        case 128: return narrow ? launch<128, false, true, 1>(a, s) : launch<128, false, true, 2>(a, s);
+        case 256: return narrow ? launch<256, false, true, 1>(a, s) : launch<256, false, true, 2>(a, s);
         }
         return hipErrorInvalidValue;
     }
