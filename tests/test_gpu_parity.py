@@ -238,13 +238,14 @@ def test_gemm_fastest_algo_gives_the_same_bits(beta_a, beta_w):
                        hbmm.gemm(ab, as_, beta_a, bb, bs, beta_w, 512, algo=hbmm.ALGO_POPCOUNT))
 
 
-@pytest.mark.parametrize("beta_a,beta_w", [(16, 16), (32, 32), (16, 32), (32, 16), (16, 256), (128, 32), (64, 16)])
-@pytest.mark.parametrize("M,N,K", [(64, 64, 512), (300, 200, 1024), (129, 257, 1536), (5, 3, 128), (513, 130, 640)])
+@pytest.mark.parametrize("beta_a,beta_w,M,N,K", [
+    (ba, bw, M, N, K)
+    for (ba, bw) in [(16, 16), (32, 32), (16, 32), (32, 16), (16, 256), (128, 32), (64, 16)]
+    for (M, N, K) in [(64, 64, 512), (300, 200, 1024), (129, 257, 1536), (5, 3, 128), (513, 130, 640)]
+    if K % max(ba, bw) == 0])
 def test_gemm_mfma_fp8_short_segments(beta_a, beta_w, M, N, K):
     """8-bit-float matrix-core kernel for segments of 16 or 32: against the oracle, and bit for bit
     against the popcount kernel where that one applies (both beta >= 32)."""
-    if K % max(beta_a, beta_w):
-        pytest.skip("K must be a multiple of both segment lengths")
     A, B = synth.normal(700 + M, (M, K)), synth.uniform_pm1(701 + N, (N, K))
     run_gemm_case(A, B, beta_a, beta_w, algo=3)
     if beta_a >= 32 and beta_w >= 32:
@@ -579,13 +580,14 @@ def test_calls_on_a_side_stream():
 
 
 # ------------------------------------------------------------------------------------- fused
-@pytest.mark.parametrize("beta_a,beta_w", [(32, 32), (64, 64), (128, 128), (256, 256), (32, 128), (256, 64)])
-@pytest.mark.parametrize("M,N,K", [(3136, 64, 576), (300, 128, 1024), (257, 5, 256), (64, 64, 512), (1000, 100, 4608)])
+@pytest.mark.parametrize("beta_a,beta_w,M,N,K", [
+    (ba, bw, M, N, K)
+    for (ba, bw) in [(32, 32), (64, 64), (128, 128), (256, 256), (32, 128), (256, 64)]
+    for (M, N, K) in [(3136, 64, 576), (300, 128, 1024), (257, 5, 256), (64, 64, 512), (1000, 100, 4608), (33000, 64, 768)]
+    if K % ba == 0 and K % bw == 0])
 def test_gemm_fused_equals_pack_then_gemm(beta_a, beta_w, M, N, K):
     """The fused call must give bit for bit what packing A first and multiplying gives, and both
-    must be within the tolerance of the oracle."""
-    if K % beta_a or K % beta_w:
-        pytest.skip("K not a multiple of beta")
+    must be within the tolerance of the oracle.  (The shapes cover the 64-row and the 128-row form.)"""
     A, B = synth.relu_normal(1200 + M, (M, K)) - 0.3, synth.normal(1201 + N, (N, K), std=0.06)
     A = A.astype(np.float32)
     dA = dev(A)
@@ -614,13 +616,11 @@ def _conv_inputs(seed, B, C, H, W, N, KH, KW):
     return A, Wf.astype(np.float32)
 
 
-@pytest.mark.parametrize("beta", [2, 4, 8, 32, 256])
-@pytest.mark.parametrize("shape", [(1, 4, 8, 8), (2, 3, 16, 32), (1, 1, 4, 1024)])
+@pytest.mark.parametrize("beta,shape", [(b, sh) for b in [2, 4, 8, 32, 256]
+                                        for sh in [(1, 4, 8, 8), (2, 3, 16, 32), (1, 1, 4, 1024)] if sh[-1] % b == 0])
 def test_quantize_pack_tensor(beta, shape):
     """Flat tensor packing: bit e of the tensor is bit (e mod 32) of word (e div 32); segment j covers
     elements [j beta, (j + 1) beta) -- for W a multiple of beta these are Eq. 3's width segments."""
-    if shape[-1] % beta:
-        pytest.skip("beta must divide the width")
     x = synth.normal(7 + beta, shape)
     x.reshape(-1)[:3] = [0.0, -0.0, -1e-30]
     bits, scales = hbmm.quantize_pack_tensor(dev(x), beta)
