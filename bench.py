@@ -35,8 +35,8 @@ FP4_PEAK_TFLOPS = 10100.0                           # dense fp4 MFMA
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="sq8k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip comparison kernels and the other configs")
@@ -208,7 +208,9 @@ def main():
             "M": w.M, "K": w.K, "N": w.N, "beta_a": w.beta_a, "beta_w": w.beta_w,
         },
         "wall_ms_per_step": wall_ms / args.steps,
-        "kernel_ms": {"pack_a": t_pack_a, "pack_b": t_pack_b, "gemm": t_gemm},
+        "kernel_ms": {"pack_a": t_pack_a, "pack_b": t_pack_b, "gemm": t_gemm,
+                      "gemm_median": float(np.median([e[2].elapsed_time(e[3]) for e in marks])),
+                      "gemm_min": float(np.min([e[2].elapsed_time(e[3]) for e in marks]))},
     }
     word_sized = w.beta_a >= 32 and w.beta_w >= 32
     if word_sized:
