@@ -1,0 +1,39 @@
+"""bench.py's output contract, checked on the device with a short run: one JSON line with the metric,
+the roofline of the dominant kernel and the CPU baseline, internally consistent."""
+from __future__ import annotations
+
+import json
+import subprocess
+import sys
+from pathlib import Path
+
+import pytest
+
+pytestmark = pytest.mark.gpu
+ROOT = Path(__file__).resolve().parent.parent
+
+
+def test_bench_prints_one_consistent_json_line():
+    r = subprocess.run([sys.executable, str(ROOT / "bench.py"), "--steps", "3", "--warmup", "1", "--no-extras"],
+                       capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [ln for ln in r.stdout.splitlines() if ln.strip()]
+    assert len(lines) == 1, lines
+    d = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in d, key
+    assert d["n_gpus"] == 1 and d["steps"] == 3 and d["warmup"] == 1 and d["higher_is_better"] is True
+    assert d["vs_baseline"] is None and d["data"] == "synthetic" and "workload" in d["config"]
+    M, N, K = d["config"]["M"], d["config"]["N"], d["config"]["K"]
+    assert d["value"] == pytest.approx(2.0 * M * N * K / (d["ms_per_step"] * 1e-3) / 1e9, rel=1e-9)
+    rf = d["roofline"]
+    assert rf["bound"] == "alu" and rf["unit"] == "TOP/s" and rf["peak"] == pytest.approx(1258.2912)
+    assert rf["frac"] == pytest.approx(rf["achieved"] / rf["peak"], rel=1e-9)
+    assert rf["achieved"] == pytest.approx(2.0 * M * N * K / (d["kernel_ms"]["gemm"] * 1e-3) / 1e12, rel=1e-6)
+    assert 0.3 < rf["frac"] < 1.2                      # a healthy device lands near 0.85
+    assert rf["traffic"] is None or rf["traffic"] > 0
+    rp = d["roofline_pack"]
+    assert rp["bound"] == "hbm" and rp["peak"] == 8000.0 and rp["frac"] == pytest.approx(rp["achieved"] / 8000.0, rel=1e-9)
+    cb = d["cpu_baseline"]
+    assert cb["kind"] == "oracle" and cb["cores"] >= 1 and cb["value"] > 0 and cb["unit"] == d["unit"] and cb["sample"]
