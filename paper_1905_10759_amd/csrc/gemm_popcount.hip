@@ -27,6 +27,7 @@
 //     four workgroups share a CU, so one group's barrier and LDS refill overlap the others' arithmetic.
 // Either of A / B can be P or Q: the host picks the role by output strides.
 #include "kernels.h"
+#include "tile_map.h"
 #include "wave_ops.h"
 
 namespace hbmm {
@@ -37,8 +38,6 @@ constexpr int kWaves = 4;
 constexpr int kThreads = 64 * kWaves;  // 256
 constexpr int kTileQ = kTQ * kWaves;   // 64 Q rows per workgroup
 constexpr int kCK = 16;                // 32-bit words of K per chunk (512 bits)
-constexpr int kNumXcd = 8;
-constexpr int kSuperTiles = 128;         // tiles per super-tile (about the workgroups resident on one XCD: 32 CUs x 3..4)
 constexpr int kStep = 2;               // words per inner step (one 8-byte LDS read, one s_load_dwordx2)
 constexpr int kBitsStride = kCK + 2;   // LDS row stride in words: 2 * odd => conflict-free b64 reads
 
@@ -95,25 +94,9 @@ __global__ __launch_bounds__(kThreads, TP == 2 ? 3 : 2) void popcount_gemm_kerne
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    // Workgroup -> tile.  Workgroups are dealt to the 8 XCDs round-robin and every XCD has its own
-    // L2, so tiles are grouped into super-tiles of sup_p x sup_q = 128 tiles whose workgroups all land
-    // on one XCD at about the same time: a P tile is then fetched into that L2 once for sup_q
-    // workgroups and a Q tile once for sup_p of them.
-    // Small grids (sup_p == 0) are mapped plainly.
+    // Workgroup -> tile: super-tiles of 128 tiles, dealt evenly to the 8 XCDs (tile_map.h).
     int tile_p, tile_q;
-    if (a.sup_p == 0) {
-        tile_p = blockIdx.x % a.tiles_p;
-        tile_q = blockIdx.x / a.tiles_p;
-    } else {
-        const int xcd = blockIdx.x % kNumXcd;
-        const int in_xcd = blockIdx.x / kNumXcd;
-        const int super = (in_xcd / kSuperTiles) * kNumXcd + xcd;
-        if (super >= a.n_super) return;
-        const int r_in_super = in_xcd % kSuperTiles;
-        tile_p = (super % a.n_super_p) * a.sup_p + r_in_super % a.sup_p;
-        tile_q = (super / a.n_super_p) * (kSuperTiles / a.sup_p) + r_in_super / a.sup_p;
-        if (tile_p >= a.tiles_p || tile_q >= a.tiles_q) return;
-    }
+    if (!popcount_map_tile(blockIdx.x, a.tiles_p, a.tiles_q, a.sup_p, tile_p, tile_q)) return;
     const int p0 = tile_p * kTileP;
     const int q0_wg = tile_q * kTileQ;
     const int q0 = q0_wg + wave * kTQ;
@@ -547,8 +530,8 @@ hipError_t launch(const PopcountGemmArgs &a, hipStream_t s)
 {
     int64_t nblocks = (int64_t)a.tiles_p * a.tiles_q;
     if (nblocks <= 0) return hipSuccess;
-    if (a.sup_p != 0) nblocks = (int64_t)((a.n_super + kNumXcd - 1) / kNumXcd) * kNumXcd * kSuperTiles;
-    if (nblocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    if (nblocks > 0x7fffff00LL) return hipErrorInvalidConfiguration;
+    nblocks = popcount_map_blocks(a.tiles_p, a.tiles_q, a.sup_p);
     popcount_gemm_kernel<G, INTEGER, FUSED, TP><<<dim3((unsigned)nblocks), dim3(kThreads), 0, s>>>(a);
     return hipGetLastError();
 }
@@ -575,12 +558,7 @@ hipError_t launch_popcount_gemm(const PopcountGemmArgs &args, int G, int integer
     // 512 of Q: 2.5 MB of packed bits at K = 8192, inside one XCD's 4 MB L2); measured against 4 x 16,
     // 8 x 8, 32 x 4 and super-tiles of 64, 256 and 512 tiles
     a.sup_p = a.tiles_p >= 16 ? 16 : a.tiles_p >= 4 ? 4 : (a.tiles_p >= 2 ? 2 : 1);
-    if ((int64_t)a.tiles_p * a.tiles_q <= 2 * kNumXcd * kSuperTiles) a.sup_p = 0;   // at most two rounds: plain map
-    if (a.sup_p != 0) {
-        a.n_super_p = (a.tiles_p + a.sup_p - 1) / a.sup_p;
-        const int sup_q = kSuperTiles / a.sup_p;
-        a.n_super = a.n_super_p * ((a.tiles_q + sup_q - 1) / sup_q);
-    }
+    if ((int64_t)a.tiles_p * a.tiles_q <= 2 * kMapXcds * kMapSuperTiles) a.sup_p = 0;   // at most two rounds: plain map
     if (integer) return narrow ? launch<64, true, false, 1>(a, s) : launch<64, true, false, 2>(a, s);
     if (fused) {
         switch (G) {

@@ -46,9 +46,7 @@ struct PopcountGemmArgs {
     int32_t K;           // bits (integer mode: D = K - 2 * hamming)
     int32_t tiles_p;     // ceil(P / tile)        (this and the fields below are filled by the launcher)
     int32_t tiles_q;
-    int32_t sup_p;       // P tiles per super-tile (super-tile = 64 tiles placed on one XCD)
-    int32_t n_super_p;   // super-tiles along P
-    int32_t n_super;     // super-tiles in all
+    int32_t sup_p;       // P tiles per super-tile (128 tiles that one XCD works on together); 0: plain map
 };
 // G = min(beta_p, beta_q) in {32, 64, 128, 256}; integer != 0 selects the unscaled whole-row mode.
 hipError_t launch_popcount_gemm(const PopcountGemmArgs &a, int G, int integer, hipStream_t s);

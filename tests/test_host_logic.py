@@ -41,3 +41,60 @@ def test_workload_tables_satisfy_the_library_constraints():
     for c in synth.CONV_WORKLOADS.values():
         assert c.W % c.beta_a == 0 and (c.C * c.KH * c.KW) % c.beta_w == 0 and (c.C * c.KH * c.KW) % 32 == 0
         assert (c.batch * c.C * c.H * c.W) % 128 == 0 and c.KH * c.KW <= 32
+
+
+def test_workgroup_to_tile_map_covers_every_tile_once(tmp_path):
+    """The XCD-balanced workgroup -> tile map of the popcount product (csrc/tile_map.h), built for the
+    host: over ragged grids every tile is produced exactly once, every XCD gets the same share (+-1),
+    and consecutive workgroups of one XCD stay inside few super-tiles."""
+    src = tmp_path / "map_check.cpp"
+    src.write_text(r'''
+#include <cstdio>
+#include <cstdlib>
+#include <vector>
+#include "tile_map.h"
+int main(int argc, char **argv) {
+    const int tp = atoi(argv[1]), tq = atoi(argv[2]), sup_p = atoi(argv[3]);
+    const long long blocks = hbmm::popcount_map_blocks(tp, tq, sup_p);
+    std::vector<int> seen((size_t)tp * tq, 0);
+    long long per_xcd[8] = {0};
+    long long none = 0, windows_bad = 0;
+    for (long long b = 0; b < blocks; ++b) {
+        int p = -1, q = -1;
+        if (!hbmm::popcount_map_tile((int)b, tp, tq, sup_p, p, q)) { ++none; continue; }
+        if (p < 0 || p >= tp || q < 0 || q >= tq) { printf("out of range at %lld\n", b); return 1; }
+        ++seen[(size_t)q * tp + p];
+        ++per_xcd[b % 8];
+    }
+    for (int v : seen) if (v != 1) { printf("tile seen %d times\n", v); return 1; }
+    long long lo = per_xcd[0], hi = per_xcd[0];
+    for (long long v : per_xcd) { lo = v < lo ? v : lo; hi = v > hi ? v : hi; }
+    if (sup_p != 0) {
+        // 128 consecutive workgroups of one XCD: distinct P tiles + distinct Q tiles they touch
+        for (int x = 0; x < 8; ++x)
+            for (long long s = 0; (s + 128) * 8 <= blocks; s += 128) {
+                std::vector<char> ps(tp, 0), qs(tq, 0);
+                int np = 0, nq = 0, p, q;
+                for (long long j = s; j < s + 128; ++j)
+                    if (hbmm::popcount_map_tile((int)(j * 8 + x), tp, tq, sup_p, p, q)) {
+                        if (!ps[p]) { ps[p] = 1; ++np; }
+                        if (!qs[q]) { qs[q] = 1; ++nq; }
+                    }
+                if (np + nq > 3 * (sup_p + 128 / sup_p)) ++windows_bad;
+            }
+    }
+    printf("%lld %lld %lld %lld %lld\n", blocks, none, lo, hi, windows_bad);
+    return 0;
+}
+''')
+    exe = tmp_path / "map_check"
+    subprocess.run(["g++", "-O1", "-std=c++17", "-I", str(ROOT / "paper_1905_10759_amd" / "csrc"), str(src), "-o", str(exe)],
+                   check=True, timeout=120)
+    for tp, tq, sup_p in [(64, 128, 16), (48, 96, 16), (33, 67, 16), (17, 1000, 16), (5, 700, 4), (3, 999, 2),
+                          (1, 4099, 1), (363, 727, 16), (32, 64, 0), (7, 11, 0), (16, 129, 16), (100, 3, 16)]:
+        r = subprocess.run([str(exe), str(tp), str(tq), str(sup_p)], capture_output=True, text=True, timeout=120)
+        assert r.returncode == 0, (tp, tq, sup_p, r.stdout)
+        blocks, none, lo, hi, bad = map(int, r.stdout.split())
+        assert blocks - none == tp * tq and none < 8, (tp, tq, sup_p)
+        assert hi - lo <= 1 or sup_p == 0, (tp, tq, sup_p, lo, hi)
+        assert bad == 0, (tp, tq, sup_p, bad)
