@@ -24,6 +24,7 @@
 // LDS holds, per stage and operand, eight planes (one per word) of 16 bytes per row, so the
 // fragment read of 32 consecutive rows is one contiguous 512-byte run.
 #include "kernels.h"
+#include "tile_map.h"
 
 namespace hbmm {
 namespace {
@@ -34,7 +35,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kBN4 = 128;
 constexpr int kStageWords4 = 8;
-constexpr int kNumXcd4 = 8;
 constexpr int kPlaneB = kBN4 * 16 + 16;   // bytes per word plane
 
 struct MfmaFp4Args {
@@ -45,7 +45,7 @@ struct MfmaFp4Args {
     int32_t ldw_a, ldw_b, lds_a, lds_b;
     int32_t M, N, kwords;       // kwords = K / 32
     int32_t shift_a, shift_b;   // log2(beta / G)
-    int32_t tiles_m, tiles_n, n_super_n, n_super;
+    int32_t tiles_m, tiles_n;
 };
 
 // 32 sign bits -> 32 fp4 values in the order described above: E2M1 +1.0 (0x2) and -1.0 (0xA) differ in
@@ -90,13 +90,11 @@ __global__ __launch_bounds__(2 * kBM4, kBM4 == 128 ? 2 : 1) void mfma_fp4_gemm_k
     __shared__ __attribute__((aligned(16))) float s_sb[2][SEG][kBN4];
 
     // Workgroup -> tile.  Workgroups are dealt to the 8 XCDs round-robin and every XCD has its own L2,
-    // so tiles are grouped into super-tiles of 4 (M) x 8 (N) whose 32 workgroups land on one XCD at about
-    // the same time: their 4 A tiles and 8 B tiles fit that L2 and are fetched into it once.
-    const int xcd = blockIdx.x % kNumXcd4, local = blockIdx.x / kNumXcd4;
-    const int super = (local / 32) * kNumXcd4 + xcd, r_in = local % 32;
-    if (super >= a.n_super) return;
-    const int tile_m = (super / a.n_super_n) * 4 + r_in / 8, tile_n = (super % a.n_super_n) * 8 + r_in % 8;
-    if (tile_m >= a.tiles_m || tile_n >= a.tiles_n) return;
+    // so tiles are grouped into super-tiles of 4 (M) x 8 (N) that one XCD works on at a time (their 4 A
+    // tiles and 8 B tiles fit that L2 and are fetched into it once), and every XCD gets an equal
+    // share of the sequence of super-tiles (tile_map.h).
+    int tile_m, tile_n;
+    if (!xcd_map_tile(blockIdx.x, a.tiles_n, a.tiles_m, 8, 4, tile_n, tile_m)) return;
     const int m0 = tile_m * kBM4, n0 = tile_n * kBN4;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -305,10 +303,9 @@ hipError_t launch_mfma_fp4_gemm(const uint32_t *a_bits, const float *a_scales, i
     const bool small = ((M + 255) / 256) * tiles_n < 256;
     const int bm = small ? 128 : 256;
     const int64_t tiles_m = (M + bm - 1) / bm;
-    const int64_t n_super_n = (tiles_n + 7) / 8, n_super = ((tiles_m + 3) / 4) * n_super_n;
-    const int64_t nblocks = (n_super + kNumXcd4 - 1) / kNumXcd4 * kNumXcd4 * 32;
-    if (nblocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    a.tiles_m = (int32_t)tiles_m; a.tiles_n = (int32_t)tiles_n; a.n_super_n = (int32_t)n_super_n; a.n_super = (int32_t)n_super;
+    if (tiles_m * tiles_n > 0x7fffff00LL) return hipErrorInvalidConfiguration;
+    const int64_t nblocks = xcd_map_blocks(tiles_m * tiles_n);
+    a.tiles_m = (int32_t)tiles_m; a.tiles_n = (int32_t)tiles_n;
     const dim3 grid((unsigned)nblocks), block(2 * bm);
 #define HBMM_FP4_LAUNCH(SEGV)                                          \
     do {                                                               \

@@ -24,6 +24,7 @@
 // two alternating register sets and are unconditional (clamped indices).  LDS holds, per stage, operand, step and lane half,
 // 8 bytes per row (planes padded so that parks and fragment reads are conflict-free).
 #include "kernels.h"
+#include "tile_map.h"
 
 namespace hbmm {
 namespace {
@@ -34,7 +35,6 @@ constexpr int kBM8 = 256, kBN8 = 128;
 constexpr int kThreads8 = 512;
 constexpr int kStageWords8 = 4;
 constexpr int kSteps8 = 8;                         // MFMA steps (16 bits) per stage
-constexpr int kNumXcd8 = 8;
 constexpr int kPlaneA8 = kBM8 * 8 + 16, kPlaneB8 = kBN8 * 8 + 16;   // bytes per (step, half) plane
 
 struct MfmaFp8Args {
@@ -45,7 +45,7 @@ struct MfmaFp8Args {
     int32_t ldw_a, ldw_b, lds_a, lds_b;
     int32_t M, N, kwords;       // kwords = K / 32
     int32_t shift_a, shift_b;   // log2(beta / G)
-    int32_t tiles_m, tiles_n, n_super_n, n_super;
+    int32_t tiles_m, tiles_n;
 };
 
 // 16 sign bits -> 16 fp8 values; lo = the 8 bytes of lanes 0..31, hi = those of lanes 32..63.  E4M3 +1.0
@@ -82,12 +82,9 @@ __global__ __launch_bounds__(kThreads8) void mfma_fp8_gemm_kernel(const MfmaFp8A
     __shared__ __attribute__((aligned(16))) float s_sa[2][SEG][kBM8];
     __shared__ __attribute__((aligned(16))) float s_sb[2][SEG][kBN8];
 
-    // workgroup -> tile: super-tiles of 4 (M) x 8 (N) tiles per XCD, as in the fp4 kernel
-    const int xcd = blockIdx.x % kNumXcd8, local = blockIdx.x / kNumXcd8;
-    const int super = (local / 32) * kNumXcd8 + xcd, r_in = local % 32;
-    if (super >= a.n_super) return;
-    const int tile_m = (super / a.n_super_n) * 4 + r_in / 8, tile_n = (super % a.n_super_n) * 8 + r_in % 8;
-    if (tile_m >= a.tiles_m || tile_n >= a.tiles_n) return;
+    // workgroup -> tile: super-tiles of 4 (M) x 8 (N) tiles, an equal share of them per XCD, as in the fp4 kernel
+    int tile_m, tile_n;
+    if (!xcd_map_tile(blockIdx.x, a.tiles_n, a.tiles_m, 8, 4, tile_n, tile_m)) return;
     const int m0 = tile_m * kBM8, n0 = tile_n * kBN8;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -273,10 +270,9 @@ hipError_t launch_mfma_fp8_gemm(const uint32_t *a_bits, const float *a_scales, i
     a.shift_a = ilog2f8(beta_a / G);
     a.shift_b = ilog2f8(beta_w / G);
     const int64_t tiles_m = (M + kBM8 - 1) / kBM8, tiles_n = (N + kBN8 - 1) / kBN8;
-    const int64_t n_super_n = (tiles_n + 7) / 8, n_super = ((tiles_m + 3) / 4) * n_super_n;
-    const int64_t nblocks = (n_super + kNumXcd8 - 1) / kNumXcd8 * kNumXcd8 * 32;
-    if (nblocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    a.tiles_m = (int32_t)tiles_m; a.tiles_n = (int32_t)tiles_n; a.n_super_n = (int32_t)n_super_n; a.n_super = (int32_t)n_super;
+    if (tiles_m * tiles_n > 0x7fffff00LL) return hipErrorInvalidConfiguration;
+    const int64_t nblocks = xcd_map_blocks(tiles_m * tiles_n);
+    a.tiles_m = (int32_t)tiles_m; a.tiles_n = (int32_t)tiles_n;
     const dim3 grid((unsigned)nblocks), block(kThreads8);
     if (G == 16)
         mfma_fp8_gemm_kernel<8><<<grid, block, 0, s>>>(a);
