@@ -254,6 +254,21 @@ def main():
             "traffic": profiled_traffic("pack_rows_kernel_sq8k.txt") if w.name == "sq8k" else None,
             "ms_per_launch": t_pack, "launches": n_pack,
         }
+        # context for that fraction: what a plain device-to-device copy of the same sources reaches on this
+        # device (library copy kernel; bytes read + bytes written per second)
+        dst = torch.empty_like(A)
+        dst.copy_(A)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(n_pack // 2):
+            dst.copy_(A)
+            dst.copy_(B)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_gbs = 2.0 * A.numel() * 4 / (e0.elapsed_time(e1) / n_pack * 1e-3) / 1e9
+        out["roofline_pack"]["device_copy_GBs"] = copy_gbs
+        out["roofline_pack"]["achieved_vs_device_copy"] = gbs / copy_gbs
+        del dst
 
     if binary_act and w.b_layout == 0 and min(w.beta_a, w.beta_w) >= 64:
         try:
