@@ -22,17 +22,28 @@ HBMM_HOST_DEVICE inline long long xcd_map_blocks(long long tiles)
 // The tile of workgroup `block`, or false when the workgroup has none.
 // Every XCD has its own L2.  The tiles are put in one sequence, super-tile after super-tile
 // (sup_p x sup_q tiles: bands of sup_q tiles along Q, in a band groups of sup_p tiles along P, ragged
-// at the edges, P fastest inside a group), and XCD x takes the x-th eighth of that sequence in order:
-// every XCD gets the same number of tiles (+-1) whatever the shape, and its resident workgroups sit in
-// one or two super-tiles, so a P tile is fetched into that L2 once for sup_q workgroups and a Q tile
-// once for sup_p of them.
+// at the edges, P fastest inside a group).  The sequence is cut into pieces of one super-tile's
+// length; in every round the 8 XCDs take 8 consecutive pieces, so that at any time each XCD works
+// inside one or two super-tiles (a P tile is fetched into its L2 once for sup_q workgroups and a Q
+// tile once for sup_p of them) and the 8 XCDs together work on neighbouring super-tiles (which
+// share their Q band: what one XCD has fetched from HBM, the others find in the memory-side cache
+// while it is still there).  What is left after the last full round is dealt in 8 equal slices:
+// every XCD gets the same number of tiles (+-1) whatever the shape.
 HBMM_HOST_DEVICE inline bool xcd_map_tile(int block, int tiles_p, int tiles_q, int sup_p, int sup_q, int &tile_p, int &tile_q)
 {
     const int xcd = block % kMapXcds, in_xcd = block / kMapXcds;
     const int tiles = tiles_p * tiles_q;
-    const int share = tiles / kMapXcds, extra = tiles % kMapXcds;
-    if (in_xcd >= share + (xcd < extra ? 1 : 0)) return false;
-    const int i = xcd * share + (xcd < extra ? xcd : extra) + in_xcd;
+    const int piece = sup_p * sup_q, round = piece * kMapXcds;
+    const int full = tiles / round;                              // rounds in which every XCD takes a whole piece
+    int i;
+    if (in_xcd < full * piece) {
+        i = (in_xcd / piece) * round + xcd * piece + in_xcd % piece;
+    } else {
+        const int left = tiles - full * round, j = in_xcd - full * piece;
+        const int share = left / kMapXcds, extra = left % kMapXcds;
+        if (j >= share + (xcd < extra ? 1 : 0)) return false;
+        i = full * round + xcd * share + (xcd < extra ? xcd : extra) + j;
+    }
     const int band_tiles = tiles_p * sup_q;
     const int band = i / band_tiles, in_band = i - band * band_tiles;
     const int left_q = tiles_q - band * sup_q;
