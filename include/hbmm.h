@@ -108,9 +108,11 @@ int hbmm_binarize_backward(const float *x, const float *grad_out, int64_t rows, 
  *                     Both >= 32: the XNOR + popcount kernel.  Otherwise (a segment shorter than a
  *                     32-bit word, or an unquantised operand) the product runs on the matrix cores:
  *                     the operand with the longer segment (>= 16) keeps its signs, the other is
- *                     rebuilt as fp32 values split exactly into three bf16 pieces; if both segments
- *                     are shorter than 16 both are rebuilt.  Not supported: beta = 1 for both (that is
- *                     hbmm_dense_ref_gemm), and beta = 1 against a segment shorter than 16.
+ *                     rebuilt as fp32 values (or is the unquantised operand itself) split exactly
+ *                     into three bf16 pieces; if neither segment reaches 16 both are rebuilt (this
+ *                     covers the paper's binary-weight networks, beta_a = 1 with beta_w = 4 or 8, and
+ *                     its HadaNets with beta_a = beta_w = 4).  Not supported: beta = 1 for both (that
+ *                     is hbmm_dense_ref_gemm).
  *   C                 out, M x N fp32, leading dimension ldc >= N.
  *   algo              0: the method's kernel as described above.
  *                     1: (both beta >= 32 only) the same d[m, n, g] from int8 +-1 matrix-core (MFMA)
@@ -163,13 +165,15 @@ int hbmm_binarize_backward_tensor(const float *x, const float *grad_out, int64_t
  *                      fp32 tensor itself.
  *   w_bits, w_scales   the filters N x C x KH x KW as written by hbmm_quantize_pack (layout 0) on the
  *                      N x (C*KH*KW) matrix with beta_w; ldw_w / lds_w its leading dimensions.
- *                      beta_w in 16 .. 256.
+ *                      beta_w in 2 .. 256.
  *   out                device, fp32, B x N x OH x OW contiguous, OH = (H + 2 pad - KH) / stride + 1,
  *                      OW likewise; 16-byte aligned.
  * C*KH*KW must be a multiple of 32 and of beta_w, KH*KW <= 32, B*C*H*W and B*OH*OW below 2^31; other
  * shapes return HBMM_EUNSUPPORTED.  The activation values run on the matrix cores as three exact
  * bf16 pieces of the fp32 scale, the filter signs as +-1, the filter scale is applied per segment in
- * fp32: every output is an fp32 sum of exact terms.
+ * fp32: every output is an fp32 sum of exact terms.  With beta_w < 16 (a filter segment shorter than
+ * one matrix-core step) the filter values are rebuilt and split the same way and the six largest of
+ * the nine piece products are added (what is dropped is below 2^-24 of a term); algo is then ignored.
  *   algo   0: each workgroup stages the input patch of its output rows once per channel in on-chip
  *             memory and gathers the window elements from there (used when the layer fits: window of
  *             at least 2 taps, OW <= 128, patch of at most 1024 elements per channel); otherwise as 1.

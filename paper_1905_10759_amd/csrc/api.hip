@@ -188,9 +188,8 @@ int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int6
         const int g = beta_a < beta_w ? beta_a : beta_w;
         if (beta_a < 16 || beta_w < 16 || g > 32 || K % 128 != 0) return HBMM_EUNSUPPORTED;
     }
-    // Two unquantised operands are a plain dense product (hbmm_dense_ref_gemm), and an unquantised
-    // operand needs the other one to keep its +-1 form (segment of at least 16).
-    if ((beta_a == 1 && beta_w < 16) || (beta_w == 1 && beta_a < 16)) return HBMM_EUNSUPPORTED;
+    // Two unquantised operands are a plain dense product (hbmm_dense_ref_gemm).
+    if (beta_a == 1 && beta_w == 1) return HBMM_EUNSUPPORTED;
     if (M == 0 || N == 0) return HBMM_OK;
     if (!C || !aligned16(C) || ldc < N) return HBMM_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -206,12 +205,14 @@ int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int6
                                                    ldw_b, lds_b, beta_w, M, N, K, C, ldc, s));
 
     if (!(word_a && word_w)) {
-        // Matrix-core path: the operand with the longer segment keeps its signs (its scale is applied
-        // once per segment), the other one is rebuilt as fp32 values.
-        if (beta_a < 16 && beta_w < 16)   // neither can keep its signs: both rebuilt as fp32 values
-            return from_hip(hbmm::launch_mfma_split2_gemm(to_split(oa), to_split(ob), K, C, ldc, 1, s));
-        const bool b_is_sign = beta_w >= 16 && (beta_w >= beta_a || beta_a < 16);
-        if (b_is_sign)
+        // Matrix-core path.  The operand with the longer segment (at least 16) keeps its signs and has
+        // its scale applied once per segment; the other one is rebuilt as fp32 values.  If neither
+        // segment reaches 16 both are rebuilt; an unquantised operand is always the rebuilt ("x") side.
+        const bool b_is_y = beta_a == 1 ? true
+                          : beta_w == 1 ? false
+                          : (beta_a < 16 && beta_w < 16) ? true
+                          : beta_w >= 16 && (beta_w >= beta_a || beta_a < 16);
+        if (b_is_y)
             return from_hip(hbmm::launch_mfma_split_gemm(to_split(oa), to_split(ob), K, C, ldc, 1, s));
         return from_hip(hbmm::launch_mfma_split_gemm(to_split(ob), to_split(oa), K, C, 1, ldc, s));
     }
@@ -321,7 +322,7 @@ int hbmm_conv2d(const uint32_t *a_bits, const float *a_scales, int32_t beta_a, c
     if (B > kMaxDim || C > kMaxDim || H > kMaxDim || W > kMaxDim || N > kMaxDim) return HBMM_EINVAL;
     if (KH > 32 || KW > 32 || pad > 32 || stride > 32) return HBMM_EINVAL;
     if (beta_a < 1 || beta_w < 1) return HBMM_EINVAL;
-    if (!(beta_a == 1 || supported_pack_beta(beta_a)) || !supported_pack_beta(beta_w) || beta_w < 16) return HBMM_EUNSUPPORTED;
+    if (!(beta_a == 1 || supported_pack_beta(beta_a)) || !supported_pack_beta(beta_w)) return HBMM_EUNSUPPORTED;
     if (H + 2 * pad < KH || W + 2 * pad < KW) return HBMM_EINVAL;
     const int64_t OH = (H + 2 * pad - KH) / stride + 1, OW = (W + 2 * pad - KW) / stride + 1;
     const int64_t K = C * KH * KW;

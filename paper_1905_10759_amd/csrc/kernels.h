@@ -63,17 +63,15 @@ struct SplitGemmOperand {
     int64_t rows;
     int beta;
 };
-// out[x * ld_out_x + y * ld_out_y] = sum_j sY[y, j] * sum_{k in j} X~[x, k] * Sign(Y)[y, k].
-// x: any supported beta (1 = raw); y: packed with beta >= 16.  K must be a multiple of 32.
+// out[x * ld_out_x + y * ld_out_y] = sum_k X~[x, k] * Y~[y, k] on the matrix cores.
+// x: any supported beta (1 = raw fp32).  y: packed, beta >= 2; with beta >= 16 it keeps its signs and
+// its scale is applied once per segment, with a shorter segment it is rebuilt as fp32 values like x.
+// K must be a multiple of 32.
 hipError_t launch_mfma_split_gemm(const SplitGemmOperand &x, const SplitGemmOperand &y, int64_t K, float *out,
                                   int64_t ld_out_x, int64_t ld_out_y, hipStream_t s);
-// Same product with both operands rebuilt as fp32 values (both packed, any beta >= 2): for the case
-// where both segments are shorter than 16.
-hipError_t launch_mfma_split2_gemm(const SplitGemmOperand &x, const SplitGemmOperand &y, int64_t K, float *out,
-                                   int64_t ld_out_x, int64_t ld_out_y, hipStream_t s);
 // Convolution layer on the same kernel: the dense side is an activation tensor B x C x H x W packed
 // flat with segments of `beta` along W (beta divides W), read through the KH x KW window of each
-// output position; the sign side holds the filters packed as rows of C*KH*KW (beta >= 16).
+// output position; the other side holds the filters packed as rows of C*KH*KW (beta >= 2).
 // out is B x y.rows x OH x OW.  C*KH*KW must be a multiple of 32, KH*KW <= 32.
 struct ConvActivations {
     const uint32_t *bits;

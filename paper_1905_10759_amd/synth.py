@@ -147,6 +147,8 @@ WORKLOADS = {
         Workload("c2x", 3136, 576, 64, 64, 64, "relu_normal", "he_normal", 0, 2001, 2002),
         Workload("c5x", 12544, 4608, 512, 128, 128, "relu_normal", "he_normal", 0, 3001, 3002),
         Workload("c5xw", 12544, 4608, 512, 1, 128, "relu_normal", "he_normal", 0, 3001, 3002),
+        # the paper's best binary-weight setting (Table 3: beta_w = 4, beta_a = 1) on the same layer shape
+        Workload("c5xw4", 12544, 4608, 512, 1, 4, "relu_normal", "he_normal", 0, 3001, 3002),
         Workload("sq4k", 4096, 4096, 4096, 64, 64, "normal", "normal", 0, 4001, 4002),
         Workload("sq8k", 8192, 8192, 8192, 256, 256, "uniform_pm1", "uniform_pm1", 0, 5001, 5002),
         # the setting of the paper's own speed figure (square matrices, beta = 16)
@@ -197,5 +199,8 @@ CONV_WORKLOADS = {
         ConvWorkload("conv3x_b64", 64, 128, 28, 28, 128, 3, 3, 1, 1, 4, 128, 7101, 7102),
         ConvWorkload("conv4x_b64", 64, 256, 14, 14, 256, 3, 3, 1, 1, 2, 128, 7201, 7202),
         ConvWorkload("conv3x_down_b64", 64, 64, 56, 56, 128, 3, 3, 2, 1, 8, 64, 7301, 7302),
+        # the paper's own settings on conv3_x: HadaNet (beta_w, beta_a) = (4, 4) and the binary-weight (4, 1)
+        ConvWorkload("conv3x_hadanet44_b64", 64, 128, 28, 28, 128, 3, 3, 1, 1, 4, 4, 7101, 7102),
+        ConvWorkload("conv3x_hbwn41_b64", 64, 128, 28, 28, 128, 3, 3, 1, 1, 1, 4, 7101, 7102),
     )
 }

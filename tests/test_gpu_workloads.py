@@ -94,23 +94,26 @@ def test_workload_paper_setting_beta16(hbmm):
     assert_close_to_oracle(got[rows], dense, T[rows], "sq4k16 (dense f64, sampled rows)")
 
 
-def test_workload_binary_weight_full_size(hbmm):
-    w = synth.WORKLOADS["c5xw"]
+@pytest.mark.parametrize("name", ["c5xw", "c5xw4"])
+def test_workload_binary_weight_full_size(hbmm, name):
+    """beta_a = 1 at full size: with beta_w = 128, and with the paper's own beta_w = 4 (Table 3)."""
+    w = synth.WORKLOADS[name]
     A, B = w.make_a(), w.make_b()
     b_bits, b_s = hbmm.quantize_pack(dev(B), w.beta_w)
     rb, sb = oracle.sign_pack(B), oracle.block_scales(B, w.beta_w)
     assert np.array_equal(words(b_bits), rb)
     got = hbmm.gemm(None, dev(A), 1, b_bits, dev(sb), w.beta_w, w.K).cpu().numpy()
-    print("[c5xw] gpu done", flush=True)
+    print(f"[{name}] gpu done", flush=True)
     ref, T = oracle.binary_weight_gemm(A, rb, sb, w.beta_w, want_T=True)
-    worst = assert_close_to_oracle(got, ref, T, "c5xw")
-    print(f"[c5xw] ok, worst err/(1e-5 T) = {worst:.3f}", flush=True)
+    worst = assert_close_to_oracle(got, ref, T, name)
+    print(f"[{name}] ok, worst err/(1e-5 T) = {worst:.3f}", flush=True)
     rows = np.unique(np.linspace(0, w.M - 1, 16).astype(np.int64))
     dense = oracle.dense_f64_gemm(oracle.materialize(A[rows], 1), oracle.materialize(B, w.beta_w, sb))
-    assert_close_to_oracle(got[rows], dense, T[rows], "c5xw (dense f64, sampled rows)")
+    assert_close_to_oracle(got[rows], dense, T[rows], name + " (dense f64, sampled rows)")
 
 
-@pytest.mark.parametrize("name,batch", [("conv2x_b1", 1), ("conv3x_b64", 4), ("conv4x_b64", 8), ("conv3x_down_b64", 2)])
+@pytest.mark.parametrize("name,batch", [("conv2x_b1", 1), ("conv3x_b64", 4), ("conv4x_b64", 8), ("conv3x_down_b64", 2),
+                                        ("conv3x_hadanet44_b64", 4), ("conv3x_hbwn41_b64", 4)])
 def test_conv_workload(hbmm, name, batch):
     """ResNet-18 convolution layers at their real geometry (batch cut to what the oracle's loops
     finish in seconds): every output against the oracle's plain convolution."""
