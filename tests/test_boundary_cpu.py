@@ -162,7 +162,7 @@ def test_validation_of_the_fused_tensor_and_convolution_entry_points(lib):
                   a["W"], a["N"], a["KH"], a["KW"], a["stride"], a["pad"], a["out"], a["algo"], None)
 
     assert conv(ba=16) == -2                 # beta_a does not divide the width
-    assert conv(bw=8, lds=36) == -2          # filter segments shorter than 16
+    assert conv(bw=48) == -2                 # beta_w not a power of two
     assert conv(C=20) == -2                  # C*KH*KW not a multiple of 32
     assert conv(bw=64) == -2                 # 288 is not a multiple of 64
     assert conv(KH=7, KW=7, pad=3) == -2     # more than 32 taps
