@@ -101,13 +101,6 @@ __device__ __forceinline__ void packed_pieces(uint32_t byte, const float (&sc)[S
     }
 }
 
-// Y modes: how the other side is given
-constexpr int kYSign = 0;     // packed, beta_y >= 32: +-1 per element, its scale applied once per segment
-constexpr int kYSign16 = 1;   // packed, beta_y = 16: the same with a segment per MFMA step
-constexpr int kYPieces1 = 2;  // packed, beta_y = 8 (or longer): rebuilt as fp32 values like X, one scale per 8 elements
-constexpr int kYPieces2 = 3;  // packed, beta_y = 4
-constexpr int kYPieces4 = 4;  // packed, beta_y = 2
-
 struct SplitArgs {
     const float *x_raw;          // kXRaw
     const uint32_t *x_bits;      // packed modes
@@ -119,8 +112,9 @@ struct SplitArgs {
     int32_t ldw_x, lds_x, ldw_y, lds_y;
     int32_t X, Y, K;
     int32_t log2_beta_x;         // packed modes
-    int32_t log2_beta_y;
-    int32_t stages_per_yseg;     // beta_y / 32 (beta_y >= 32); 1 otherwise
+    int32_t log2_beta_y;         // Y as pieces
+    int32_t stages_per_yseg;     // beta_y / 32 (beta_y >= 32); unused when beta_y = 16
+    int32_t log2_stages_per_yseg;
     int32_t tiles_y, tiles_total, slots_per_xcd;
     // kXConv: X row m = (b * OH + oz) * OW + oy is an output position, k = (c * KH + dz) * KW + dy a
     // filter tap; X~[m, k] is the binarised activation at (b, c, oz*stride - pad + dz,
@@ -133,32 +127,23 @@ struct SplitArgs {
     uint32_t cv_sign;                   // 0x80000000; 0 when the tensor is unquantised (see launch_mfma_split_conv)
 };
 
-// The kernel.  Tile 128 (X) x 256 (Y) when Y keeps its signs, 128 x 128 when Y is rebuilt as pieces
-// (its LDS tile is then three planes).  NTY: 0 for the general case; 1, 2 or 3 when Y keeps its signs
-// and has at most 64, 128 or 192 rows (one tile), see below.
-//
-// A K stage has two parts.  compute(s): fragment reads and MFMAs on the tiles of stage s parked in
-// LDS buffer s mod 2.  memory(s): the per-segment epilogue of what was just computed, the request
-// for the operands of stage s + 3, and the parking of stage s + 1 (splitting, sign expansion, LDS
-// writes) into the other buffer.  PP = false runs them back to back with one barrier per stage.
-// PP = true ("ping-pong") puts a barrier after each part and lets waves 0-3 run compute | memory
-// while waves 4-7 run memory | compute: the two waves that share a SIMD are then always in opposite
-// parts, so the matrix pipe of every SIMD has one wave feeding it while the other wave does the
-// vector-ALU and LDS-write work, instead of all eight waves competing for the same unit at the same
-// time.  Buffer use: in the first half of stage s waves 0-3 read buffer s mod 2 and waves 4-7 write
-// their share of stage s + 1 into the other buffer; in the second half the roles swap; buffer s mod 2
-// is next written in the first half of stage s + 1, after both groups have passed a barrier since
-// their last read of it.  Every wave passes exactly two barriers per stage in either role.
-template <int XMODE, int YMODE, int NTY, bool PP>
+// Y modes: how the other side is given
+constexpr int kYSign = 0;     // packed, beta_y >= 32: +-1 per element, its scale applied once per segment
+constexpr int kYSign16 = 1;   // packed, beta_y = 16: the same with a segment per MFMA step
+constexpr int kYPieces1 = 2;  // packed, beta_y = 8: a segment is shorter than an MFMA step, so Y is rebuilt as fp32
+constexpr int kYPieces2 = 3;  // packed, beta_y = 4   values and split into pieces like X; the six largest of the
+constexpr int kYPieces4 = 4;  // packed, beta_y = 2   nine piece products are added and there is no epilogue
+
+// NTY: 0 for the general case; 1, 2 or 3 when Y keeps its signs and has at most 64, 128 or 192 rows
+// (one tile), see below.  With Y as pieces the tile is 128 x 128 (the Y tile is three planes in LDS).
+template <int XMODE, int YMODE, int NTY>
 __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitArgs a)
 {
-    constexpr bool YP = YMODE >= kYPieces1;          // Y rebuilt as three bf16 pieces
-    constexpr bool Y16 = YMODE == kYSign16;
+    constexpr bool Y16 = YMODE == kYSign16, YP = YMODE >= kYPieces1;
     constexpr int BY = YP ? 128 : kBY;
     constexpr int kYPlane = BY * kRowBytes;
     __shared__ __attribute__((aligned(16))) unsigned char sX[2][3 * kPieceBytes];
     __shared__ __attribute__((aligned(16))) unsigned char sY[2][(YP ? 3 : 1) * kYPlane];
-    __shared__ float sYs[2][YP ? 2 : 2 * kBY];       // sign modes: scale of each 16-element half stage of each Y row
 
     // slot -> tile: consecutive slots of one XCD walk tiles in row-major (x, y) order
     const int slot = (blockIdx.x % kNumXcdS) * a.slots_per_xcd + blockIdx.x / kNumXcdS;
@@ -166,13 +151,13 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
     const int x0 = (slot / a.tiles_y) * kBX, y0 = (slot % a.tiles_y) * BY;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    // Wave -> sub-tile of the workgroup tile, as TX x TY accumulator tiles of 32 x 32.
-    // Signs, general case: 2 x 4 waves of 64 x 64.  When Y has at most 64 * NTY rows the live part of
-    // the tile is cut into 4 x 2 waves of 32 x (32 NTY) instead, so that all eight waves multiply
-    // (with 64 x 64 sub-tiles only NTY of the four wave columns would).  Pieces: 2 x 4 waves of 64 x 32.
-    constexpr bool kWide = YP || NTY == 0;
-    constexpr int TX = kWide ? 2 : 1, TY = YP ? 1 : NTY == 0 ? 2 : NTY;
-    const int wrow0 = kWide ? (wave >> 2) * 64 : (wave & 3) * 32;
+    // Wave -> sub-tile of the 128 x 256 workgroup tile, as TX x TY accumulator tiles of 32 x 32.
+    // General case: 2 x 4 waves of 64 x 64.  When Y has at most 64 * NTY rows the live part of the tile
+    // is cut into 4 x 2 waves of 32 x (32 NTY) instead, so that all eight waves multiply (with 64 x 64
+    // sub-tiles only NTY of the four wave columns would).
+    // Pieces: 2 x 4 waves of 64 x 32.
+    constexpr int TX = NTY == 0 ? 2 : 1, TY = YP ? 1 : NTY == 0 ? 2 : NTY;
+    const int wrow0 = NTY == 0 ? (wave >> 2) * 64 : (wave & 3) * 32;
     const int wcol0 = YP ? (wave & 3) * 32 : NTY == 0 ? (wave & 3) * 64 : (wave >> 2) * (32 * NTY);
     const int nstages = a.K / kStageK;
 
@@ -183,7 +168,7 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
         uint32_t xb;                                       // packed: the row's word of this stage
         float xs[kScalesPerThread];                        // packed: scales of this thread's 8 elements
         uint32_t yb;                                       // the Y row's word of this stage
-        float ys[kYScalesPerThread];                       // signs: the scale of this thread's 16 elements; pieces: of its 8
+        float ys[kYScalesPerThread];                       // pieces: the scales of this thread's 8 elements of Y
         uint32_t cw[XMODE == kXConv ? 8 : 1];              // conv: the word holding each element's bit
         float cs[XMODE == kXConv ? 8 : 1];                 // conv: each element's scale
     };
@@ -231,7 +216,7 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
     }
     // element i (0..7) of the thread's run: its flat tensor index, forced to 0 when the tap lies
     // outside the input or past the last channel, and `keep` = all ones / zero accordingly
-    auto conv_elem = [&](int c0, int r0, int i, uint32_t &e, uint32_t &keep) __attribute__((always_inline)) {
+    auto conv_elem = [&](int c0, int r0, int i, uint32_t &e, uint32_t &keep) {
         const int t = r0 + i;
         const int cq = (t * a.cv_magic_kk) >> 16;
         const int r = t - cq * a.cv_kk;
@@ -241,7 +226,7 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
         keep = (uint32_t)__builtin_amdgcn_sbfe((int)taps, (uint32_t)r, 1u);
         e = (uint32_t)(cv_base + (c * a.cv_hw + r + dz * (a.cv_w - a.cv_kw))) & keep;
     };
-    auto conv_advance = [&](int &c0, int &r0) __attribute__((always_inline)) {
+    auto conv_advance = [&](int &c0, int &r0) {
         c0 += a.cv_q32;
         r0 += a.cv_r32;
         if (r0 >= a.cv_kk) {
@@ -249,13 +234,12 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
             c0 += 1;
         }
     };
-    // Y staging.  Signs: thread = (row, 16-element half); pieces: thread = (row, 8-element group) like X.
-    const int yrow_t = YP ? (tid >> 2) : (tid >> 1), ypart = YP ? (tid & 3) : (tid & 1);
-    const int64_t yrow_g = min(y0 + yrow_t, a.Y - 1);
-    const uint32_t *yb_src = a.y_bits + yrow_g * a.ldw_y;
-    const float *ys_src = a.y_scales + yrow_g * a.lds_y;
+    // Y expansion.  Signs: thread = (row, 16-element half); pieces: thread = (row, 8-element group) like X.
+    const int yrow_t = YP ? (tid >> 2) : (tid >> 1), yhalf = tid & 1, yoct = tid & 3;
+    const uint32_t *yb_src = a.y_bits + (int64_t)min(y0 + yrow_t, a.Y - 1) * a.ldw_y;
+    const float *ys_src = a.y_scales + (int64_t)min(y0 + yrow_t, a.Y - 1) * a.lds_y;
 
-    auto fetch = [&](Staged &st, int stage) __attribute__((always_inline)) {
+    auto fetch = [&](Staged &st, int stage) {
         const int sg = min(stage, nstages - 1);
         if (XMODE == kXRaw) {
 #pragma unroll
@@ -277,12 +261,14 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
             for (int j = 0; j < kScalesPerThread; ++j) st.xs[j] = xs_src[sidx + j];
         }
         st.yb = yb_src[sg];
-        const int yidx = (sg * kStageK + ypart * (YP ? 8 : 16)) >> a.log2_beta_y;
+        if (YP) {
+            const int yidx = (sg * kStageK + yoct * 8) >> a.log2_beta_y;
 #pragma unroll
-        for (int j = 0; j < kYScalesPerThread; ++j) st.ys[j] = ys_src[yidx + j];
+            for (int j = 0; j < kYScalesPerThread; ++j) st.ys[j] = ys_src[yidx + j];
+        }
     };
 
-    auto park = [&](const Staged &st, int buf) __attribute__((always_inline)) {
+    auto park = [&](const Staged &st, int buf) {
         if (XMODE == kXRaw) {
 #pragma unroll
             for (int r = 0; r < 2; ++r) {
@@ -332,26 +318,25 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
         }
         if (YP) {
             u32x4 dh, dm, dl;
-            packed_pieces<kYScalesPerThread>(st.yb >> (8 * ypart), st.ys, dh, dm, dl);
-            unsigned char *dst = &sY[buf][yrow_t * kRowBytes + ypart * 16];
+            packed_pieces<kYScalesPerThread>(st.yb >> (8 * yoct), st.ys, dh, dm, dl);
+            unsigned char *dst = &sY[buf][yrow_t * kRowBytes + yoct * 16];
             *reinterpret_cast<u32x4 *>(dst) = dh;
             *reinterpret_cast<u32x4 *>(dst + kYPlane) = dm;
             *reinterpret_cast<u32x4 *>(dst + 2 * kYPlane) = dl;
-        } else {
-            // 16 signs -> 16 bf16 values +-1.0, and the scale that covers them
-            uint32_t ym[8];
-            sign_masks<8>(~(st.yb >> (16 * ypart)) & 0xffffu, ym);
-            u32x4 y0v, y1v;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                y0v[i] = ym[i] | 0x3f803f80u;
-                y1v[i] = ym[4 + i] | 0x3f803f80u;
-            }
-            unsigned char *ydst = &sY[buf][yrow_t * kRowBytes + ypart * 32];
-            *reinterpret_cast<u32x4 *>(ydst) = y0v;
-            *reinterpret_cast<u32x4 *>(ydst + 16) = y1v;
-            sYs[buf][tid] = st.ys[0];     // tid = 2 * row + half
+            return;
         }
+        // Y: 16 signs -> 16 bf16 values +-1.0
+        uint32_t ym[8];
+        sign_masks<8>(~(st.yb >> (16 * yhalf)) & 0xffffu, ym);
+        u32x4 y0v, y1v;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            y0v[i] = ym[i] | 0x3f803f80u;
+            y1v[i] = ym[4 + i] | 0x3f803f80u;
+        }
+        unsigned char *ydst = &sY[buf][yrow_t * kRowBytes + yhalf * 32];
+        *reinterpret_cast<u32x4 *>(ydst) = y0v;
+        *reinterpret_cast<u32x4 *>(ydst + 16) = y1v;
     };
 
     f32x16 acc[TX][TY], res[TX][TY];
@@ -364,6 +349,16 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
                 acc[p][q][v] = 0.f;
                 res[p][q][v] = 0.f;
             }
+
+    // per-lane Y scale rows: the output column of accumulator tile ty is y0 + wcol0 + 32*ty + lane%32
+    const float *srow[TY];
+    bool col_ok[TY];
+#pragma unroll
+    for (int ty = 0; ty < TY; ++ty) {
+        const int col = y0 + wcol0 + ty * 32 + (lane & 31);
+        col_ok[ty] = col < a.Y;
+        srow[ty] = a.y_scales + (int64_t)min(col, a.Y - 1) * a.lds_y;
+    }
 
     auto apply_scale = [&](const float (&sc)[TY]) {
 #pragma unroll
@@ -378,76 +373,82 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
     };
 
     float sc_seg[TY] = {};
-    bool pending = false;   // a finished Y segment sits in acc and still has to be scaled into res
-
-    // compute(stage): multiply the tiles parked in LDS buffer stage mod 2
-    auto compute = [&](int stage) __attribute__((always_inline)) {
+    // One K stage: multiply the tile parked in LDS buffer (stage mod 2), request stage + 3 into
+    // `incoming`, and park `ready` (stage + 1, requested three stages ago) in the other buffer.
+    auto run_stage = [&](int stage, const Staged &ready, Staged &incoming) {
         const int buf = stage & 1;
-        const unsigned char *px = &sX[buf][(wrow0 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
-        const unsigned char *py = &sY[buf][(wcol0 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
-        const float *ps = &sYs[buf][YP ? 0 : 2 * (wcol0 + (lane & 31))];
+        if (YP) {
+            // both operands as pieces: the six piece pairs that matter, smallest contributions first
+            // (hi,lo) (lo,hi) (mid,mid) (hi,mid) (mid,hi) (hi,hi); what is dropped is below 2^-24 of a term
+            fetch(incoming, stage + 3);
+            const unsigned char *pxp = &sX[buf][(wrow0 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
+            const unsigned char *pyp = &sY[buf][(wcol0 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
 #pragma unroll
-        for (int ks = 0; ks < kStageK / 16; ++ks) {
-            if (YP) {
-                bf16x8 fx[3][TX], fy[3];
+            for (int ks = 0; ks < kStageK / 16; ++ks) {
+                bf16x8 fxp[3][TX], fyp[3];
 #pragma unroll
                 for (int p = 0; p < 3; ++p) {
-                    fy[p] = *reinterpret_cast<const bf16x8 *>(py + p * kYPlane + ks * 32);
+                    fyp[p] = *reinterpret_cast<const bf16x8 *>(pyp + p * kYPlane + ks * 32);
 #pragma unroll
                     for (int tx = 0; tx < TX; ++tx)
-                        fx[p][tx] = *reinterpret_cast<const bf16x8 *>(px + p * kPieceBytes + tx * 32 * kRowBytes + ks * 32);
+                        fxp[p][tx] = *reinterpret_cast<const bf16x8 *>(pxp + p * kPieceBytes + tx * 32 * kRowBytes + ks * 32);
                 }
-                // the six piece pairs that matter, smallest contributions first:
-                // (hi,lo) (lo,hi) (mid,mid) (hi,mid) (mid,hi) (hi,hi); what is dropped is below 2^-24 of a term
                 constexpr int kPairs[6][2] = {{0, 2}, {2, 0}, {1, 1}, {0, 1}, {1, 0}, {0, 0}};
 #pragma unroll
                 for (int q = 0; q < 6; ++q)
 #pragma unroll
                     for (int tx = 0; tx < TX; ++tx)
-                        res[tx][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[kPairs[q][0]][tx], fy[kPairs[q][1]], res[tx][0], 0, 0, 0);
-            } else {
-                bf16x8 fy[TY];
-#pragma unroll
-                for (int ty = 0; ty < TY; ++ty)
-                    fy[ty] = *reinterpret_cast<const bf16x8 *>(py + ty * 32 * kRowBytes + ks * 32);
-#pragma unroll
-                for (int p = 0; p < 3; ++p) {
-                    bf16x8 fx[TX];
-#pragma unroll
-                    for (int tx = 0; tx < TX; ++tx)
-                        fx[tx] = *reinterpret_cast<const bf16x8 *>(px + p * kPieceBytes + tx * 32 * kRowBytes + ks * 32);
-#pragma unroll
-                    for (int tx = 0; tx < TX; ++tx)
-#pragma unroll
-                        for (int ty = 0; ty < TY; ++ty)
-                            acc[tx][ty] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[tx], fy[ty], acc[tx][ty], 0, 0, 0);
-                }
-                if (Y16) {
-                    float sc16[TY];
-#pragma unroll
-                    for (int ty = 0; ty < TY; ++ty) sc16[ty] = ps[64 * ty + ks];
-                    apply_scale(sc16);
-                }
+                        res[tx][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fxp[kPairs[q][0]][tx], fyp[kPairs[q][1]], res[tx][0], 0, 0, 0);
             }
+            park(ready, buf ^ 1);
+            __syncthreads();
+            return;
         }
-        if (!YP && !Y16) {
-            // the segment's scale is taken now, while this buffer is certain to hold this stage
+        // The scales are requested before the prefetch: loads return in order, so waiting for the
+        // scales at the end of the stage then leaves the prefetch in flight.
+        float sc16[2][TY];
+        bool seg_last = false;
+        if (Y16) {
 #pragma unroll
-            for (int ty = 0; ty < TY; ++ty) sc_seg[ty] = ps[64 * ty];
-            pending = ((stage + 1) & (a.stages_per_yseg - 1)) == 0;   // stages per Y segment is a power of two
+            for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                for (int ty = 0; ty < TY; ++ty) sc16[ks][ty] = srow[ty][stage * 2 + ks];
+        } else {
+            // stages per Y segment is a power of two.  The scale is re-read every stage rather than
+            // at segment starts only: a load under a condition hides the number of outstanding loads
+            // from the compiler, which then waits for all of them, prefetches included.
+            seg_last = ((stage + 1) & (a.stages_per_yseg - 1)) == 0;
+#pragma unroll
+            for (int ty = 0; ty < TY; ++ty) sc_seg[ty] = srow[ty][stage >> a.log2_stages_per_yseg];
         }
-    };
-
-    // memory(stage): scale a finished segment, request stage + 3 into `incoming`, park `ready`
-    // (stage + 1, requested three stages ago) in the other buffer.  Global loads are requested
-    // here only, so they complete in the order in which park() needs them.
-    auto memory = [&](int stage, const Staged &ready, Staged &incoming) __attribute__((always_inline)) {
         fetch(incoming, stage + 3);
-        if (pending) {
-            apply_scale(sc_seg);
-            pending = false;
+        const unsigned char *px = &sX[buf][(wrow0 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
+        const unsigned char *py = &sY[buf][(wcol0 + (lane & 31)) * kRowBytes + (lane >> 5) * 16];
+#pragma unroll
+        for (int ks = 0; ks < kStageK / 16; ++ks) {
+            bf16x8 fy[TY];
+#pragma unroll
+            for (int ty = 0; ty < TY; ++ty)
+                fy[ty] = *reinterpret_cast<const bf16x8 *>(py + ty * 32 * kRowBytes + ks * 32);
+#pragma unroll
+            for (int p = 0; p < 3; ++p) {
+                bf16x8 fx[TX];
+#pragma unroll
+                for (int tx = 0; tx < TX; ++tx)
+                    fx[tx] = *reinterpret_cast<const bf16x8 *>(px + p * kPieceBytes + tx * 32 * kRowBytes + ks * 32);
+#pragma unroll
+                for (int tx = 0; tx < TX; ++tx)
+#pragma unroll
+                    for (int ty = 0; ty < TY; ++ty)
+                        acc[tx][ty] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[tx], fy[ty], acc[tx][ty], 0, 0, 0);
+            }
+            if (Y16) apply_scale(sc16[ks]);
         }
-        park(ready, (stage & 1) ^ 1);   // past the last stage this parks data that nobody reads
+        // The next stage is parked before the (conditional) segment epilogue so that the splitting
+        // and sign-expansion arithmetic sits in the same scheduling region as the MFMAs.
+        park(ready, buf ^ 1);   // past the last stage this parks data that nobody reads
+        if (!Y16 && seg_last) apply_scale(sc_seg);
+        __syncthreads();
     };
 
     Staged s0, s1, s2;
@@ -456,49 +457,17 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
     fetch(s0, 1);
     fetch(s1, 2);
     __syncthreads();
-    if (!PP) {
-        auto run_stage = [&](int stage, const Staged &ready, Staged &incoming) __attribute__((always_inline)) {
-            compute(stage);
-            memory(stage, ready, incoming);
-            __syncthreads();
-        };
-        for (int stage = 0; stage < nstages; stage += 3) {
-            run_stage(stage, s0, s2);
-            if (stage + 1 < nstages) run_stage(stage + 1, s1, s0);
-            if (stage + 2 < nstages) run_stage(stage + 2, s2, s1);
-        }
-    } else if (wave < 4) {
-        auto run_stage = [&](int stage, const Staged &ready, Staged &incoming) __attribute__((always_inline)) {
-            compute(stage);
-            __syncthreads();
-            memory(stage, ready, incoming);
-            __syncthreads();
-        };
-        for (int stage = 0; stage < nstages; stage += 3) {
-            run_stage(stage, s0, s2);
-            if (stage + 1 < nstages) run_stage(stage + 1, s1, s0);
-            if (stage + 2 < nstages) run_stage(stage + 2, s2, s1);
-        }
-    } else {
-        auto run_stage = [&](int stage, const Staged &ready, Staged &incoming) __attribute__((always_inline)) {
-            memory(stage, ready, incoming);
-            __syncthreads();
-            compute(stage);
-            __syncthreads();
-        };
-        for (int stage = 0; stage < nstages; stage += 3) {
-            run_stage(stage, s0, s2);
-            if (stage + 1 < nstages) run_stage(stage + 1, s1, s0);
-            if (stage + 2 < nstages) run_stage(stage + 2, s2, s1);
-        }
+    for (int stage = 0; stage < nstages; stage += 3) {
+        run_stage(stage, s0, s2);
+        if (stage + 1 < nstages) run_stage(stage + 1, s1, s0);
+        if (stage + 2 < nstages) run_stage(stage + 2, s2, s1);
     }
-    if (pending) apply_scale(sc_seg);
 
     if (XMODE == kXConv) {
         // Output is B x Y x OH x OW: positions are contiguous, filters are OH*OW apart.  The
         // accumulator tiles hold filters across lanes, so each 32 x 32 tile is turned through LDS
         // (row stride 33 words) and written with positions across lanes.
-        // (every wave has passed the loop's last barrier: nobody reads the operand tiles any more)
+        __syncthreads();   // every wave has finished reading the operand tiles
         float *turn = reinterpret_cast<float *>(&sX[0][0]) + wave * (32 * 33);
 #pragma unroll
         for (int tx = 0; tx < TX; ++tx) {
@@ -532,8 +501,8 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
     for (int tx = 0; tx < TX; ++tx)
 #pragma unroll
         for (int ty = 0; ty < TY; ++ty) {
+            if (!col_ok[ty]) continue;
             const int col = y0 + wcol0 + ty * 32 + (lane & 31);
-            if (col >= a.Y) continue;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = x0 + wrow0 + tx * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
@@ -876,44 +845,38 @@ __global__ __launch_bounds__(kThreadsS) void conv_patch_kernel(const ConvPatchAr
     }
 }
 
-#ifndef HBMM_SPLIT_PP
-#define HBMM_SPLIT_PP 1
-#endif
-constexpr bool kPingPong = HBMM_SPLIT_PP != 0;
-
-template <int XMODE, int YMODE>
-hipError_t launch_mode_y(const SplitArgs &a, unsigned grid, hipStream_t s)
+template <int XMODE>
+hipError_t launch_mode(const SplitArgs &a, int beta_y, unsigned grid, hipStream_t s)
 {
     const dim3 g(grid), b(kThreadsS);
-    if (YMODE >= kYPieces1) {
-        mfma_split_gemm_kernel<XMODE, YMODE, 0, kPingPong><<<g, b, 0, s>>>(a);
+    if (beta_y < 16) {
+        // a Y segment shorter than an MFMA step: Y as pieces
+        if (beta_y == 2)
+            mfma_split_gemm_kernel<XMODE, kYPieces4, 0><<<g, b, 0, s>>>(a);
+        else if (beta_y == 4)
+            mfma_split_gemm_kernel<XMODE, kYPieces2, 0><<<g, b, 0, s>>>(a);
+        else
+            mfma_split_gemm_kernel<XMODE, kYPieces1, 0><<<g, b, 0, s>>>(a);
         return hipGetLastError();
     }
-    // signs: the sub-tile shape follows the number of Y rows
-    constexpr int YS = YMODE >= kYPieces1 ? kYSign : YMODE;   // (keeps the dead branch from instantiating NTY forms of the piece modes)
-    if (a.Y <= 64)
-        mfma_split_gemm_kernel<XMODE, YS, 1, kPingPong><<<g, b, 0, s>>>(a);
-    else if (a.Y <= 128)
-        mfma_split_gemm_kernel<XMODE, YS, 2, kPingPong><<<g, b, 0, s>>>(a);
-    else if (a.Y <= 192)
-        mfma_split_gemm_kernel<XMODE, YS, 3, kPingPong><<<g, b, 0, s>>>(a);
+    const int nty = a.Y <= 64 ? 1 : a.Y <= 128 ? 2 : a.Y <= 192 ? 3 : 0;
+#define HBMM_SPLIT_LAUNCH(YM)                                                                        \
+    do {                                                                                             \
+        if (nty == 1)                                                                                \
+            mfma_split_gemm_kernel<XMODE, YM, 1><<<g, b, 0, s>>>(a);                                 \
+        else if (nty == 2)                                                                           \
+            mfma_split_gemm_kernel<XMODE, YM, 2><<<g, b, 0, s>>>(a);                                 \
+        else if (nty == 3)                                                                           \
+            mfma_split_gemm_kernel<XMODE, YM, 3><<<g, b, 0, s>>>(a);                                 \
+        else                                                                                         \
+            mfma_split_gemm_kernel<XMODE, YM, 0><<<g, b, 0, s>>>(a);                                 \
+    } while (0)
+    if (beta_y == 16)
+        HBMM_SPLIT_LAUNCH(kYSign16);
     else
-        mfma_split_gemm_kernel<XMODE, YS, 0, kPingPong><<<g, b, 0, s>>>(a);
+        HBMM_SPLIT_LAUNCH(kYSign);
+#undef HBMM_SPLIT_LAUNCH
     return hipGetLastError();
-}
-
-// beta_y: 2 / 4 / 8 (and any longer segment that has to be rebuilt) -> pieces; 16 -> a segment per MFMA
-// step; >= 32 -> signs with the scale applied when the segment ends.
-template <int XMODE>
-hipError_t launch_mode(const SplitArgs &a, int beta_y, bool y_pieces, unsigned grid, hipStream_t s)
-{
-    if (y_pieces) {
-        if (beta_y == 2) return launch_mode_y<XMODE, kYPieces4>(a, grid, s);
-        if (beta_y == 4) return launch_mode_y<XMODE, kYPieces2>(a, grid, s);
-        return launch_mode_y<XMODE, kYPieces1>(a, grid, s);
-    }
-    if (beta_y == 16) return launch_mode_y<XMODE, kYSign16>(a, grid, s);
-    return launch_mode_y<XMODE, kYSign>(a, grid, s);
 }
 
 int ilog2s(int v)
@@ -933,7 +896,6 @@ hipError_t launch_mfma_split_gemm(const SplitGemmOperand &x, const SplitGemmOper
     if (y.beta < 2 || y.bits == nullptr || K % kStageK != 0) return hipErrorNotSupported;
     if (x.beta == 1 && (x.raw == nullptr || x.ld_raw % 4 != 0)) return hipErrorNotSupported;
     if (x.beta != 1 && x.bits == nullptr) return hipErrorNotSupported;
-    const bool y_pieces = y.beta < 16;
     SplitArgs a{};
     a.x_raw = x.raw; a.ldx_raw = x.ld_raw;
     a.x_bits = x.bits; a.x_scales = x.scales; a.ldw_x = (int32_t)x.ldw; a.lds_x = (int32_t)x.lds;
@@ -943,17 +905,18 @@ hipError_t launch_mfma_split_gemm(const SplitGemmOperand &x, const SplitGemmOper
     a.log2_beta_x = ilog2s(x.beta);
     a.log2_beta_y = ilog2s(y.beta);
     a.stages_per_yseg = y.beta >= 32 ? y.beta / kStageK : 1;
-    const int by = y_pieces ? 128 : kBY;
+    a.log2_stages_per_yseg = ilog2s(a.stages_per_yseg);
+    const int by = y.beta < 16 ? 128 : kBY;
     const int64_t tiles_x = (x.rows + kBX - 1) / kBX, tiles_y = (y.rows + by - 1) / by;
     const int64_t total = tiles_x * tiles_y;
     const int64_t per_xcd = (total + kNumXcdS - 1) / kNumXcdS;
     if (per_xcd * kNumXcdS > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     a.tiles_y = (int32_t)tiles_y; a.tiles_total = (int32_t)total; a.slots_per_xcd = (int32_t)per_xcd;
     const unsigned grid = (unsigned)(per_xcd * kNumXcdS);
-    if (x.beta == 1) return launch_mode<kXRaw>(a, y.beta, y_pieces, grid, s);
-    if (x.beta == 2) return launch_mode<kXScale4>(a, y.beta, y_pieces, grid, s);
-    if (x.beta == 4) return launch_mode<kXScale2>(a, y.beta, y_pieces, grid, s);
-    return launch_mode<kXScale1>(a, y.beta, y_pieces, grid, s);
+    if (x.beta == 1) return launch_mode<kXRaw>(a, y.beta, grid, s);
+    if (x.beta == 2) return launch_mode<kXScale4>(a, y.beta, grid, s);
+    if (x.beta == 4) return launch_mode<kXScale2>(a, y.beta, grid, s);
+    return launch_mode<kXScale1>(a, y.beta, grid, s);
 }
 
 // The staged-patch kernel when the layer fits it; false = use the gather kernel.
@@ -1039,6 +1002,7 @@ hipError_t launch_mfma_split_conv(const ConvActivations &x, const SplitGemmOpera
     a.X = (int32_t)M; a.Y = (int32_t)y.rows; a.K = (int32_t)K;
     a.log2_beta_y = ilog2s(y.beta);
     a.stages_per_yseg = y.beta >= 32 ? y.beta / kStageK : 1;
+    a.log2_stages_per_yseg = ilog2s(a.stages_per_yseg);
     a.cv_c = (int32_t)g.C; a.cv_h = (int32_t)g.H; a.cv_w = (int32_t)g.W; a.cv_hw = (int32_t)(g.H * g.W);
     a.cv_ow = (int32_t)OW; a.cv_ohw = (int32_t)(OH * OW);
     a.cv_kw = g.KW; a.cv_kk = g.KH * g.KW; a.cv_stride = g.stride; a.cv_pad = g.pad;
@@ -1050,7 +1014,7 @@ hipError_t launch_mfma_split_conv(const ConvActivations &x, const SplitGemmOpera
     const int64_t per_xcd = (total + kNumXcdS - 1) / kNumXcdS;
     if (per_xcd * kNumXcdS > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     a.tiles_y = (int32_t)tiles_y; a.tiles_total = (int32_t)total; a.slots_per_xcd = (int32_t)per_xcd;
-    return launch_mode<kXConv>(a, y.beta, y_pieces, (unsigned)(per_xcd * kNumXcdS), s);
+    return launch_mode<kXConv>(a, y.beta, (unsigned)(per_xcd * kNumXcdS), s);
 }
 
 }  // namespace hbmm
