@@ -120,7 +120,8 @@ def test_conv_workload(hbmm, name, batch):
     import dataclasses
     w = dataclasses.replace(synth.CONV_WORKLOADS[name], batch=batch)
     A, Wf = w.make_a(), w.make_w()
-    ab, asc = hbmm.quantize_pack_tensor(dev(A), w.beta_a)
+    # beta_a = 1: the activations are not binarised and go in as they are
+    ab, asc = (None, dev(A)) if w.beta_a == 1 else hbmm.quantize_pack_tensor(dev(A), w.beta_a)
     wb, ws = hbmm.quantize_pack(dev(Wf.reshape(w.N, -1)), w.beta_w)
     got = hbmm.conv2d(ab, asc, w.beta_a, A.shape, wb, ws, w.beta_w, (w.KH, w.KW), w.stride, w.pad).cpu().numpy()
     print(f"[{name}] gpu done", flush=True)

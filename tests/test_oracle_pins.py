@@ -276,6 +276,25 @@ def test_paths_agree_and_T_bounds():
         assert (T >= np.abs(pop) - 1e-12).all()
 
 
+def test_error_scale_T_of_the_product_is_the_sum_of_absolute_terms():
+    """T, the scale every fp32 parity bar is taken relative to, recomputed with exact rationals for
+    equal, mixed and ragged segment lengths: T[m, n] = sum over the pieces between consecutive
+    segment ends of either operand of |sA * sB * d| (Eq. 7's terms).  An inflated T would loosen
+    every GPU tolerance without any other test noticing."""
+    A, B = synth.normal(63, (3, 19)), synth.uniform_pm1(64, (2, 19))
+    for ba, bw in ((4, 4), (2, 8), (8, 2), (3, 5), (19, 4), (6, 19)):
+        sa, sb = oracle.block_scales(A, ba), oracle.block_scales(B, bw)
+        _, T = oracle.popcount_gemm(oracle.sign_pack(A), sa, ba, oracle.sign_pack(B), sb, bw, 19, want_T=True)
+        cuts = sorted(set(range(0, 19, ba)) | set(range(0, 19, bw)) | {19})
+        for m in range(3):
+            for n in range(2):
+                want = Fraction(0)
+                for k0, k1 in zip(cuts[:-1], cuts[1:]):
+                    d = sum(int(_sgn(A[m, k]) * _sgn(B[n, k])) for k in range(k0, k1))
+                    want += abs(Fraction(float(sa[m, k0 // ba])) * Fraction(float(sb[n, k0 // bw])) * d)
+                assert T[m, n] == pytest.approx(float(want), rel=1e-13), (ba, bw, m, n)
+
+
 def test_positive_scaling_invariance():
     """Scaling an operand by c > 0 (a power of two, so exact) scales C and leaves bits alone."""
     A, B = synth.normal(61, (8, 128)), synth.normal(62, (8, 128))
@@ -358,7 +377,10 @@ def test_backward_brute_force_ragged_and_mask_edges():
         sdot = sum(Fraction(float(g[0, j])) * _sgn(x[0, j]) for j in range(k0, k1))
         want = _sgn(x[0, i]) * sdot / n + (delta * Fraction(float(g[0, i])) if abs(x[0, i]) <= 1 else 0)
         assert got[0, i] == pytest.approx(float(want), abs=1e-14), i
-        assert T[0, i] >= abs(got[0, i]) - 1e-14
+        # the error scale: (1/n) sum_j |g_j| + delta |g_i| [|x_i| <= 1], exactly
+        want_T = sum(abs(Fraction(float(g[0, j]))) for j in range(k0, k1)) / n + (
+            delta * abs(Fraction(float(g[0, i]))) if abs(x[0, i]) <= 1 else 0)
+        assert T[0, i] == pytest.approx(float(want_T), rel=1e-13), i
 
 
 # ----------------------------------------------------------------------------- convolution (Eq. 1-4 on tensors)
@@ -435,15 +457,18 @@ def test_conv_beta_one_is_plain_convolution_and_brute_force():
     B, C, H, W, N, KH, KW, stride, pad = 1, 2, 4, 4, 2, 3, 3, 1, 1
     A = rng.integers(-3, 4, (B, C, H, W)).astype(np.float32)
     Wf = rng.integers(-2, 3, (N, C, KH, KW)).astype(np.float32)
-    got = oracle.hbmm_conv2d(A, Wf, 1, 1, stride, pad)
+    got, T = oracle.hbmm_conv2d(A, Wf, 1, 1, stride, pad, want_T=True)
     for n in range(N):
         for oz in range(H):
             for oy in range(W):
-                acc = Fraction(0)
+                acc, tabs = Fraction(0), Fraction(0)
                 for c in range(C):
                     for dz in range(KH):
                         for dy in range(KW):
                             z, y = oz - pad + dz, oy - pad + dy
                             if 0 <= z < H and 0 <= y < W:
-                                acc += Fraction(float(A[0, c, z, y])) * Fraction(float(Wf[n, c, dz, dy]))
+                                term = Fraction(float(A[0, c, z, y])) * Fraction(float(Wf[n, c, dz, dy]))
+                                acc += term
+                                tabs += abs(term)
                 assert got[0, n, oz, oy] == float(acc)
+                assert T[0, n, oz, oy] == float(tabs)      # the error scale is the sum of the absolute terms, exactly

@@ -194,6 +194,32 @@ def convolution_pads_with_ones(At, Wt, stride, pad, want_T=False):
     return REAL["conv2d_f64"](padded, Wt, stride, 0, want_T)
 
 
+def product_error_scale_doubled(*args, **kw):
+    """An inflated T would silently loosen every fp32 parity bar."""
+    out = REAL["popcount_gemm"](*args, **kw)
+    return (out[0], 2.0 * out[1]) if kw.get("want_T") else out
+
+
+def product_error_scale_without_abs(*args, **kw):
+    out = REAL["popcount_gemm"](*args, **kw)
+    return (out[0], np.abs(out[0])) if kw.get("want_T") else out
+
+
+def backward_error_scale_doubled(x, g, beta, want_T=False):
+    out = REAL["binarize_backward"](x, g, beta, want_T)
+    return (out[0], 2.0 * out[1]) if want_T else out
+
+
+def convolution_error_scale_doubled(At, Wt, stride, pad, want_T=False):
+    out = REAL["conv2d_f64"](At, Wt, stride, pad, want_T)
+    return (out[0], 2.0 * out[1]) if want_T else out
+
+
+def binary_weight_error_scale_doubled(A, b_bits, b_s, beta_w, want_T=False):
+    out = REAL["binary_weight_gemm"](A, b_bits, b_s, beta_w, want_T)
+    return (out[0], 2.0 * out[1]) if want_T else out
+
+
 # mistake -> (oracle function it lives in, pins that must notice)
 CASES = [
     (bits_msb_first, "sign_pack", ["test_pack_matches_paper_example", "test_pack_roundtrip_ragged_and_pad_zero",
@@ -229,6 +255,11 @@ CASES = [
                                                   "test_conv_beta_one_is_plain_convolution_and_brute_force"]),
     (convolution_pads_with_ones, "conv2d_f64", ["test_conv_matches_library_convolution",
                                                 "test_conv_beta_one_is_plain_convolution_and_brute_force"]),
+    (product_error_scale_doubled, "popcount_gemm", ["test_error_scale_T_of_the_product_is_the_sum_of_absolute_terms"]),
+    (product_error_scale_without_abs, "popcount_gemm", ["test_error_scale_T_of_the_product_is_the_sum_of_absolute_terms"]),
+    (backward_error_scale_doubled, "binarize_backward", ["test_backward_brute_force_ragged_and_mask_edges"]),
+    (convolution_error_scale_doubled, "conv2d_f64", ["test_conv_beta_one_is_plain_convolution_and_brute_force"]),
+    (binary_weight_error_scale_doubled, "binary_weight_gemm", ["test_binary_weight_form"]),
 ]
 
 
