@@ -94,6 +94,52 @@ def _dev(t: torch.Tensor, dtype, name: str) -> None:
         raise TypeError(f"{name}: expected a {dtype} device tensor")
 
 
+def _rows_view(t: torch.Tensor, name: str):
+    """(rows, cols, leading dimension) of a 2-D tensor whose rows the library can walk: unit inner
+    stride, rows that do not overlap.  The C ABI sees pointers and sizes only, so what it cannot check
+    -- that the memory behind a pointer has the shape the sizes claim -- is checked here."""
+    if t.dim() != 2:
+        raise ValueError(f"{name}: expected a 2-D tensor, got {t.dim()}-D")
+    rows, cols = t.shape
+    if cols > 1 and t.stride(1) != 1:
+        raise ValueError(f"{name}: the inner stride must be 1")
+    ld = t.stride(0) if rows > 1 else max(cols, 1)
+    if rows > 1 and ld < cols:
+        raise ValueError(f"{name}: rows overlap (stride {ld} < {cols} columns)")
+    return rows, cols, ld
+
+
+def check_out(out: torch.Tensor, shape, name: str = "out") -> int:
+    """A caller-supplied output matrix: exact shape, unit inner stride; returns its leading dimension."""
+    rows, cols, ld = _rows_view(out, name)
+    if (rows, cols) != tuple(shape):
+        raise ValueError(f"{name}: shape {tuple(out.shape)} where {tuple(shape)} is written")
+    return ld
+
+
+def check_gemm_operand(bits, scales, beta: int, K: int, name: str):
+    """One operand of hbmm_gemm as tensors: packed (bits rows x >= packed_ld_words(K) words, scales
+    rows x >= K / beta) or, with beta == 1, unquantised (bits None, scales = the rows x K matrix).
+    Returns (rows, ldw, lds)."""
+    rows, cols, lds = _rows_view(scales, name + "_scales")
+    if beta == 1:
+        if bits is not None:
+            raise ValueError(f"{name}: an unquantised operand (beta = 1) takes bits=None")
+        if cols < K:
+            raise ValueError(f"{name}: {cols} columns for K = {K}")
+        return rows, 0, lds
+    if bits is None:
+        raise ValueError(f"{name}_bits missing (beta = {beta})")
+    brows, bcols, ldw = _rows_view(bits, name + "_bits")
+    if brows != rows:
+        raise ValueError(f"{name}: {brows} rows of bits but {rows} rows of scales")
+    if bcols < packed_ld_words(K):
+        raise ValueError(f"{name}_bits: {bcols} words per row, K = {K} needs {packed_ld_words(K)}")
+    if beta > 1 and cols < num_blocks(K, beta):
+        raise ValueError(f"{name}_scales: {cols} scales per row, K = {K} with beta = {beta} needs {num_blocks(K, beta)}")
+    return rows, ldw, lds
+
+
 def quantize_pack(x: torch.Tensor, beta: int, layout: int = 0, bits: torch.Tensor | None = None,
                   scales: torch.Tensor | None = None):
     """hbmm_quantize_pack.  x: fp32 device matrix; layout 0 = rows x K, layout 1 = K x rows.
@@ -110,9 +156,12 @@ def quantize_pack(x: torch.Tensor, beta: int, layout: int = 0, bits: torch.Tenso
         scales = torch.empty((rows, nb), dtype=torch.float32, device=x.device)
     _dev(bits, torch.int32, "bits")
     _dev(scales, torch.float32, "scales")
-    rc = lib.hbmm_quantize_pack(x.data_ptr(), rows, K, ldx, layout, beta, bits.data_ptr(),
-                                bits.stride(0) if rows > 1 else bits.shape[1], scales.data_ptr(),
-                                scales.stride(0) if rows > 1 else max(scales.shape[1], 1), _stream())
+    brows, bcols, ldw_out = _rows_view(bits, "bits")
+    srows, scols, lds_out = _rows_view(scales, "scales")
+    if brows != rows or srows != rows or bcols < ldw or scols < nb:
+        raise ValueError(f"bits / scales: need {rows} rows of >= {ldw} words and >= {nb} scales")
+    rc = lib.hbmm_quantize_pack(x.data_ptr(), rows, K, ldx, layout, beta, bits.data_ptr(), ldw_out,
+                                scales.data_ptr(), lds_out, _stream())
     _check(rc, "hbmm_quantize_pack")
     return bits, scales
 
@@ -123,24 +172,18 @@ def gemm(a_bits, a_scales, beta_a: int, b_bits, b_scales, beta_w: int, K: int, a
     fp32 matrix (rows x K)."""
     _dev(b_scales, torch.float32, "b_scales")
     _dev(a_scales, torch.float32, "a_scales")
-    M, N = a_scales.shape[0], b_scales.shape[0]
+    for bits, name in ((a_bits, "a_bits"), (b_bits, "b_bits")):
+        if bits is not None:
+            _dev(bits, torch.int32, name)
+    M, ldw_a, lds_a = check_gemm_operand(a_bits, a_scales, beta_a, K, "a")
+    N, ldw_b, lds_b = check_gemm_operand(b_bits, b_scales, beta_w, K, "b")
     if out is None:
         out = torch.empty((M, N), dtype=torch.float32, device=a_scales.device)
     _dev(out, torch.float32, "out")
-
-    def packed(bits, rows, name):
-        if bits is None:
-            return 0, 0
-        _dev(bits, torch.int32, name)
-        return bits.data_ptr(), bits.stride(0) if rows > 1 else bits.shape[1]
-
-    a_ptr, ldw_a = packed(a_bits, M, "a_bits")
-    b_ptr, ldw_b = packed(b_bits, N, "b_bits")
-    rc = lib.hbmm_gemm(a_ptr, a_scales.data_ptr(), ldw_a,
-                       a_scales.stride(0) if M > 1 else max(a_scales.shape[1], 1), beta_a,
-                       b_ptr, b_scales.data_ptr(), ldw_b,
-                       b_scales.stride(0) if N > 1 else max(b_scales.shape[1], 1), beta_w,
-                       M, N, K, out.data_ptr(), out.stride(0) if M > 1 else max(N, 1), algo, _stream())
+    ldc = check_out(out, (M, N))
+    rc = lib.hbmm_gemm(a_bits.data_ptr() if a_bits is not None else 0, a_scales.data_ptr(), ldw_a, lds_a, beta_a,
+                       b_bits.data_ptr() if b_bits is not None else 0, b_scales.data_ptr(), ldw_b, lds_b, beta_w,
+                       M, N, K, out.data_ptr(), ldc, algo, _stream())
     _check(rc, "hbmm_gemm")
     return out
 
@@ -149,13 +192,14 @@ def gemm_int(a_bits, b_bits, K: int, out: torch.Tensor | None = None) -> torch.T
     """hbmm_gemm_int: D[m, n] = K - 2 * hamming(a_row, b_row), int32."""
     _dev(a_bits, torch.int32, "a_bits")
     _dev(b_bits, torch.int32, "b_bits")
-    M, N = a_bits.shape[0], b_bits.shape[0]
+    (M, wa, ldw_a), (N, wb, ldw_b) = _rows_view(a_bits, "a_bits"), _rows_view(b_bits, "b_bits")
+    if min(wa, wb) < packed_ld_words(K):
+        raise ValueError(f"bits: {min(wa, wb)} words per row, K = {K} needs {packed_ld_words(K)}")
     if out is None:
         out = torch.empty((M, N), dtype=torch.int32, device=a_bits.device)
     _dev(out, torch.int32, "out")
-    rc = lib.hbmm_gemm_int(a_bits.data_ptr(), a_bits.stride(0) if M > 1 else a_bits.shape[1],
-                           b_bits.data_ptr(), b_bits.stride(0) if N > 1 else b_bits.shape[1],
-                           M, N, K, out.data_ptr(), out.stride(0) if M > 1 else max(N, 1), _stream())
+    ldd = check_out(out, (M, N))
+    rc = lib.hbmm_gemm_int(a_bits.data_ptr(), ldw_a, b_bits.data_ptr(), ldw_b, M, N, K, out.data_ptr(), ldd, _stream())
     _check(rc, "hbmm_gemm_int")
     return out
 
@@ -166,12 +210,15 @@ def dense_ref_gemm(A: torch.Tensor, B: torch.Tensor, out: torch.Tensor | None = 
         raise TypeError("A and B must both be fp32 or both bf16")
     _dev(A, A.dtype, "A")
     _dev(B, A.dtype, "B")
-    (M, K), N = A.shape, B.shape[0]
+    (M, K, lda), (N, Kb, ldb) = _rows_view(A, "A"), _rows_view(B, "B")
+    if Kb != K:
+        raise ValueError(f"A has K = {K} columns, B has {Kb}")
     if out is None:
         out = torch.empty((M, N), dtype=torch.float32, device=A.device)
-    rc = lib.hbmm_dense_ref_gemm(A.data_ptr(), A.stride(0) if M > 1 else K, B.data_ptr(),
-                                 B.stride(0) if N > 1 else K, 0 if A.dtype == torch.float32 else 1,
-                                 M, N, K, out.data_ptr(), out.stride(0) if M > 1 else max(N, 1), _stream())
+    _dev(out, torch.float32, "out")
+    ldc = check_out(out, (M, N))
+    rc = lib.hbmm_dense_ref_gemm(A.data_ptr(), lda, B.data_ptr(), ldb, 0 if A.dtype == torch.float32 else 1,
+                                 M, N, K, out.data_ptr(), ldc, _stream())
     _check(rc, "hbmm_dense_ref_gemm")
     return out
 
@@ -186,6 +233,7 @@ def binarize_backward(x: torch.Tensor, grad_out: torch.Tensor, beta: int, out: t
     if out is None:
         out = torch.empty((rows, K), dtype=torch.float32, device=x.device)
     _dev(out, torch.float32, "out")
+    check_out(out, (rows, K))
     ld = lambda t: t.stride(0) if rows > 1 else K
     rc = lib.hbmm_binarize_backward(x.data_ptr(), grad_out.data_ptr(), rows, K, ld(x), ld(grad_out), beta,
                                     out.data_ptr(), ld(out), _stream())
@@ -198,13 +246,14 @@ def gemm_fused(A: torch.Tensor, beta_a: int, b_bits, b_scales, beta_w: int, out:
     _dev(A, torch.float32, "A")
     _dev(b_bits, torch.int32, "b_bits")
     _dev(b_scales, torch.float32, "b_scales")
-    (M, K), N = A.shape, b_bits.shape[0]
+    M, K, lda = _rows_view(A, "A")
+    N, ldw_b, lds_b = check_gemm_operand(b_bits, b_scales, beta_w, K, "b")
     if out is None:
         out = torch.empty((M, N), dtype=torch.float32, device=A.device)
-    rc = lib.hbmm_gemm_fused(A.data_ptr(), A.stride(0) if M > 1 else K, beta_a, b_bits.data_ptr(), b_scales.data_ptr(),
-                             b_bits.stride(0) if N > 1 else b_bits.shape[1],
-                             b_scales.stride(0) if N > 1 else max(b_scales.shape[1], 1), beta_w, M, N, K,
-                             out.data_ptr(), out.stride(0) if M > 1 else max(N, 1), _stream())
+    _dev(out, torch.float32, "out")
+    ldc = check_out(out, (M, N))
+    rc = lib.hbmm_gemm_fused(A.data_ptr(), lda, beta_a, b_bits.data_ptr(), b_scales.data_ptr(), ldw_b, lds_b, beta_w,
+                             M, N, K, out.data_ptr(), ldc, _stream())
     _check(rc, "hbmm_gemm_fused")
     return out
 
@@ -242,13 +291,20 @@ def conv2d(a_bits, a_scales, beta_a: int, shape, w_bits, w_scales, beta_w: int, 
     _dev(w_scales, torch.float32, "w_scales")
     B, Cc, H, W = (int(v) for v in shape)
     KH, KW = (int(v) for v in kernel)
-    N = w_bits.shape[0]
+    count = B * Cc * H * W
+    N, ldw_w, lds_w = check_gemm_operand(w_bits, w_scales, beta_w, Cc * KH * KW, "w")
+    if not a_scales.is_contiguous() or (a_bits is not None and not a_bits.is_contiguous()):
+        raise ValueError("the packed activation tensor must be contiguous")
+    if a_scales.numel() < count // max(beta_a, 1) or (a_bits is not None and a_bits.numel() < count // 32):
+        raise ValueError(f"activations: too few words / scales for a tensor of {count} elements")
     OH, OW = (H + 2 * pad - KH) // stride + 1, (W + 2 * pad - KW) // stride + 1
     if out is None:
         out = torch.empty((B, N, OH, OW), dtype=torch.float32, device=a_scales.device)
-    rc = lib.hbmm_conv2d(a_bits.data_ptr() if a_bits is not None else 0, a_scales.data_ptr(), beta_a, w_bits.data_ptr(), w_scales.data_ptr(),
-                         w_bits.stride(0) if N > 1 else w_bits.shape[1],
-                         w_scales.stride(0) if N > 1 else max(w_scales.shape[1], 1), beta_w, B, Cc, H, W, N, KH, KW,
+    _dev(out, torch.float32, "out")
+    if tuple(out.shape) != (B, N, OH, OW) or not out.is_contiguous():
+        raise ValueError(f"out: a contiguous tensor of shape {(B, N, OH, OW)} is written")
+    rc = lib.hbmm_conv2d(a_bits.data_ptr() if a_bits is not None else 0, a_scales.data_ptr(), beta_a, w_bits.data_ptr(),
+                         w_scales.data_ptr(), ldw_w, lds_w, beta_w, B, Cc, H, W, N, KH, KW,
                          stride, pad, out.data_ptr(), algo, _stream())
     _check(rc, "hbmm_conv2d")
     return out

@@ -21,14 +21,41 @@ def words(t: torch.Tensor) -> np.ndarray:
 REL_TOL = 1e-5
 
 
+# Plain relative error |gpu - ref| / |ref|, in two forms.
+#  * over the outputs that are not cancelled by more than 8x (|ref| >= T / 8): the stated bar itself,
+#    1e-5 (what the kernels reach there: 2.5e-6 at worst);
+#  * over every output with |ref| >= 1e-3 max |ref|: these include sums cancelled by a factor of up to
+#    ~2000, so the T bar alone would admit 2e-2; measured worst over the suite: 7.0e-4 (the 25 million
+#    outputs of c5xw4, err / (1e-5 T) = 0.037 there), 1e-4 or less on the other full-size workloads.
+#    The bar is 1e-3.
+# The worst values of a run are kept in WORST_PLAIN_REL and printed at the end of the run; the full-size
+# workload tests print their own.
+SOLID_REL_TOL = 1e-5
+PLAIN_REL_TOL = 1e-3
+WORST_PLAIN_REL = {"value": 0.0, "what": "", "solid": 0.0, "solid_what": ""}
+
+
+def plain_relative_error(got: np.ndarray, ref: np.ndarray) -> float:
+    if not ref.size:
+        return 0.0
+    err = np.abs(got.astype(np.float64) - ref)
+    big = np.abs(ref) >= 1e-3 * np.abs(ref).max()
+    return float((err[big] / np.abs(ref[big])).max()) if big.any() else 0.0
+
+
 def assert_close_to_oracle(got: np.ndarray, ref: np.ndarray, T: np.ndarray, what: str = ""):
     err = np.abs(got.astype(np.float64) - ref)
     bound = REL_TOL * T + 1e-30
     worst = float((err / bound).max()) if err.size else 0.0
     assert worst <= 1.0, f"{what}: max err/(1e-5*T) = {worst:.3f}"
-    # plain relative error where the reference is not cancelled away
-    big = np.abs(ref) >= 1e-3 * np.abs(ref).max() if ref.size else np.zeros_like(ref, bool)
-    if big.any():
-        rel = float((err[big] / np.abs(ref[big])).max())
-        assert rel <= 1e-3, f"{what}: max plain relative error {rel:.2e}"
+    solid = (np.abs(ref) >= T / 8) & (np.abs(ref) > 0)
+    if solid.any():
+        rel_solid = float((err[solid] / np.abs(ref[solid])).max())
+        if rel_solid > WORST_PLAIN_REL["solid"]:
+            WORST_PLAIN_REL.update(solid=rel_solid, solid_what=what)
+        assert rel_solid <= SOLID_REL_TOL, f"{what}: max relative error of the outputs that are not cancelled {rel_solid:.2e}"
+    rel = plain_relative_error(got, ref)
+    if rel > WORST_PLAIN_REL["value"]:
+        WORST_PLAIN_REL.update(value=rel, what=what)
+    assert rel <= PLAIN_REL_TOL, f"{what}: max plain relative error {rel:.2e}"
     return worst

@@ -199,3 +199,90 @@ def test_isa_checker_detects_a_planted_early_use(tmp_path):
     (tmp_path / "bad.s").write_text(bad)
     assert check_isa.check(str(tmp_path / "good.s"), verbose=False) == 0
     assert check_isa.check(str(tmp_path / "bad.s"), verbose=False) == 1
+
+
+def test_binding_checks_what_the_c_abi_cannot_see():
+    """The C ABI gets pointers and sizes; whether the memory behind a pointer has that shape only the
+    binding can tell.  A mismatch must raise before any call is made (on the device it would be an
+    out-of-bounds access, not an error code).  The checkers work on shapes and strides only, so CPU
+    tensors serve."""
+    import torch
+
+    from paper_1905_10759_amd import hbmm
+
+    K, beta = 128, 32
+    bits = torch.zeros((6, 4), dtype=torch.int32)
+    scales = torch.zeros((6, 4), dtype=torch.float32)
+    assert hbmm.check_gemm_operand(bits, scales, beta, K, "a") == (6, 4, 4)
+    wide = torch.zeros((6, 12), dtype=torch.float32)
+    assert hbmm.check_gemm_operand(bits, wide[:, :4], beta, K, "a") == (6, 4, 12)          # a padded leading dimension is fine
+    assert hbmm.check_gemm_operand(None, torch.zeros((6, K)), 1, K, "a") == (6, 0, K)       # unquantised operand
+    with pytest.raises(ValueError):
+        hbmm.check_gemm_operand(bits[:5], scales, beta, K, "a")                             # rows of bits != rows of scales
+    with pytest.raises(ValueError):
+        hbmm.check_gemm_operand(bits, scales, beta, 256, "a")                               # K needs 8 words and 8 scales per row
+    with pytest.raises(ValueError):
+        hbmm.check_gemm_operand(bits, scales[:, :3], beta, K, "a")                          # too few scales
+    with pytest.raises(ValueError):
+        hbmm.check_gemm_operand(bits, wide[:, ::3], beta, K, "a")                           # inner stride 3
+    with pytest.raises(ValueError):
+        hbmm.check_gemm_operand(bits, torch.zeros((6, K)), 1, K, "a")                       # beta = 1 takes no bits
+    with pytest.raises(ValueError):
+        hbmm.check_gemm_operand(None, torch.zeros((6, K - 1)), 1, K, "a")                   # unquantised operand narrower than K
+    with pytest.raises(ValueError):
+        hbmm.check_gemm_operand(None, scales, beta, K, "a")                                 # packed operand without bits
+    with pytest.raises(ValueError):
+        hbmm.check_gemm_operand(bits, torch.zeros((6, 4, 1)), beta, K, "a")                 # not a matrix
+
+    out = torch.zeros((6, 9), dtype=torch.float32)
+    assert hbmm.check_out(out, (6, 9)) == 9
+    assert hbmm.check_out(torch.zeros((6, 20))[:, :9], (6, 9)) == 20
+    with pytest.raises(ValueError):
+        hbmm.check_out(out, (6, 10))                                                        # wrong shape
+    with pytest.raises(ValueError):
+        hbmm.check_out(out.t(), (9, 6))                                                     # transposed view: inner stride 6
+    with pytest.raises(ValueError):
+        hbmm.check_out(torch.zeros(9).expand(6, 9), (6, 9))                                 # rows overlap
+
+
+def test_binding_entry_points_validate_before_the_call(monkeypatch):
+    """gemm / gemm_fused / dense_ref_gemm / conv2d run the checks above on their arguments: with the
+    device-tensor test switched off, mismatched CPU tensors must raise ValueError and never reach
+    the library."""
+    import torch
+
+    from paper_1905_10759_amd import hbmm
+
+    monkeypatch.setattr(hbmm, "_dev", lambda t, dtype, name: None)
+    monkeypatch.setattr(hbmm, "_stream", lambda: 0)
+
+    class Untouchable:
+        def __getattr__(self, name):
+            raise AssertionError(f"library call {name} reached with mismatched arguments")
+
+    monkeypatch.setattr(hbmm, "lib", Untouchable())
+    monkeypatch.setattr(hbmm, "packed_ld_words", lambda K: ((K + 31) // 32 + 3) // 4 * 4)
+    monkeypatch.setattr(hbmm, "num_blocks", lambda K, beta: (K + beta - 1) // beta)
+    bits = torch.zeros((6, 4), dtype=torch.int32)
+    scales = torch.zeros((6, 4), dtype=torch.float32)
+    with pytest.raises(ValueError):
+        hbmm.gemm(bits, scales, 32, bits[:5], scales, 32, 128)
+    with pytest.raises(ValueError):
+        hbmm.gemm(bits, scales, 32, bits, scales, 32, 128, out=torch.zeros((6, 7)))
+    with pytest.raises(ValueError):
+        hbmm.gemm(bits, scales, 32, bits, scales, 32, 512)                                  # K larger than the rows hold
+    with pytest.raises(ValueError):
+        hbmm.gemm_int(bits, bits, 512)
+    with pytest.raises(ValueError):
+        hbmm.dense_ref_gemm(torch.zeros((4, 64)), torch.zeros((5, 32)))                     # K mismatch
+    with pytest.raises(ValueError):
+        hbmm.dense_ref_gemm(torch.zeros((64, 4)).t(), torch.zeros((5, 64)))                 # strided A
+    with pytest.raises(ValueError):
+        hbmm.gemm_fused(torch.zeros((64, 4)).t(), 32, bits, scales, 32)                     # strided A
+    with pytest.raises(ValueError):
+        hbmm.gemm_fused(torch.zeros((9, 128)), 32, bits, scales, 32, out=torch.zeros((9, 5)))
+    act_bits, act_scales = torch.zeros(8, dtype=torch.int32), torch.zeros(64)              # a 1 x 4 x 8 x 8 tensor, beta_a = 4
+    with pytest.raises(ValueError):
+        hbmm.conv2d(act_bits[:7], act_scales, 4, (1, 4, 8, 8), bits, scales, 32, (4, 8), 1, 0)           # too few activation words
+    with pytest.raises(ValueError):
+        hbmm.conv2d(act_bits, act_scales, 4, (1, 4, 8, 8), bits, scales, 32, (4, 8), 1, 0, out=torch.zeros((1, 6, 5, 2)))   # out is 1 x 6 x 5 x 1

@@ -385,6 +385,10 @@ def test_gemm_seeded_random_sweep(M, N, K, beta_a, beta_w, algo, kind_a, kind_b)
     A, B = make[kind_a](4000 + M, (M, K)), make[kind_b](5000 + N, (N, K))
     At, Bt = oracle.materialize(A, beta_a), oracle.materialize(B, beta_w)
     ref, T = oracle.dense_f64_gemm(At, Bt), oracle.dense_f64_gemm(np.abs(At), np.abs(Bt))
+    if beta_a >= 32 and beta_w >= 32:
+        # the XNOR + popcount kernel (and its matrix-core twins) add one term per segment: its error scale
+        # is the sum of the absolute segment terms, about sqrt(segment length) tighter than |A~| . |B~|^T
+        _, T = oracle.hbmm_popcount(A, B, beta_a, beta_w, want_T=True)
 
     def operand(x, beta):
         if beta == 1:

@@ -11,7 +11,7 @@ import torch
 import oracle
 from paper_1905_10759_amd import synth
 
-from gpu_common import assert_close_to_oracle, dev, words
+from gpu_common import assert_close_to_oracle, dev, plain_relative_error, words
 
 pytestmark = pytest.mark.gpu
 
@@ -57,7 +57,7 @@ def test_workload_full_size(hbmm, name):
     ref, T = oracle.popcount_gemm(ra, sa, w.beta_a, rb, sb, w.beta_w, w.K, want_T=True)
     got = hbmm.gemm(a_bits, dev(sa), w.beta_a, b_bits, dev(sb), w.beta_w, w.K).cpu().numpy()
     worst = assert_close_to_oracle(got, ref, T, name)
-    print(f"[{name}] gemm ok, worst err/(1e-5 T) = {worst:.3f}", flush=True)
+    print(f"[{name}] gemm ok, worst err/(1e-5 T) = {worst:.3f}, worst plain relative error = {plain_relative_error(got, ref):.2e}", flush=True)
 
     # --- the matrix-core variants reach the same segment sums and round in the same places
     same = torch.from_numpy(got).cuda()
@@ -88,7 +88,7 @@ def test_workload_paper_setting_beta16(hbmm):
     got = hbmm.gemm(a_bits, dev(sa), 16, b_bits, dev(sb), 16, w.K).cpu().numpy()
     ref, T = oracle.popcount_gemm(ra, sa, 16, rb, sb, 16, w.K, want_T=True)
     worst = assert_close_to_oracle(got, ref, T, "sq4k16")
-    print(f"[sq4k16] ok, worst err/(1e-5 T) = {worst:.3f}", flush=True)
+    print(f"[sq4k16] ok, worst err/(1e-5 T) = {worst:.3f}, worst plain relative error = {plain_relative_error(got, ref):.2e}", flush=True)
     rows = np.unique(np.linspace(0, w.M - 1, 16).astype(np.int64))
     dense = oracle.dense_f64_gemm(oracle.materialize(A[rows], 16, sa[rows]), oracle.materialize(B, 16, sb))
     assert_close_to_oracle(got[rows], dense, T[rows], "sq4k16 (dense f64, sampled rows)")
@@ -106,7 +106,7 @@ def test_workload_binary_weight_full_size(hbmm, name):
     print(f"[{name}] gpu done", flush=True)
     ref, T = oracle.binary_weight_gemm(A, rb, sb, w.beta_w, want_T=True)
     worst = assert_close_to_oracle(got, ref, T, name)
-    print(f"[{name}] ok, worst err/(1e-5 T) = {worst:.3f}", flush=True)
+    print(f"[{name}] ok, worst err/(1e-5 T) = {worst:.3f}, worst plain relative error = {plain_relative_error(got, ref):.2e}", flush=True)
     rows = np.unique(np.linspace(0, w.M - 1, 16).astype(np.int64))
     dense = oracle.dense_f64_gemm(oracle.materialize(A[rows], 1), oracle.materialize(B, w.beta_w, sb))
     assert_close_to_oracle(got[rows], dense, T[rows], name + " (dense f64, sampled rows)")
@@ -129,4 +129,4 @@ def test_conv_workload(hbmm, name, batch):
     # summation order, (log2 beta + 1) * 2^-24 relative at most, far inside the bound
     ref, T = oracle.hbmm_conv2d(A, Wf, w.beta_a, w.beta_w, w.stride, w.pad, want_T=True)
     worst = assert_close_to_oracle(got, ref, T, name)
-    print(f"[{name}] ok, worst err/(1e-5 T) = {worst:.3f}", flush=True)
+    print(f"[{name}] ok, worst err/(1e-5 T) = {worst:.3f}, worst plain relative error = {plain_relative_error(got, ref):.2e}", flush=True)
