@@ -45,16 +45,39 @@ def parse():
     return ap.parse_args()
 
 
-def profiled_traffic(kernel_file: str):
-    """HBM bytes per launch measured with rocprofv3 counters for the headline workload (a committed
-    summary under profiles/; bench.py cannot collect counters itself).  None if absent."""
+def kernel_source_digest(*files: str) -> str:
+    """sha256 over the kernel sources a profile summary belongs to (csrc/ file names)."""
+    import hashlib
+    h = hashlib.sha256()
+    for f in files:
+        h.update((ROOT / "paper_1905_10759_amd" / "csrc" / f).read_bytes())
+    return h.hexdigest()[:16]
+
+
+def profiled_traffic(kernel_file: str, *sources: str) -> dict:
+    """HBM bytes per launch measured with rocprofv3 counters for the headline workload.  bench.py cannot
+    collect counters itself: the figure comes from the committed summary under profiles/ (two --pmc runs
+    of this bench, FETCH_SIZE and WRITE_SIZE, scaled by what a plain copy of known size reads).  The
+    summary records a digest of the kernel sources it was taken from; if they have changed since, the
+    figure is stale and reported as null."""
+    info = {"traffic": None, "traffic_source": f"profiles/{kernel_file} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this "
+                                               "bench, calibrated with a 256 MiB device copy; not measured in this run)"}
     try:
-        for line in (ROOT / "profiles" / kernel_file).read_text().splitlines():
-            if line.startswith("TRAFFIC_BYTES_PER_LAUNCH="):
-                return float(line.split("=", 1)[1])
+        text = (ROOT / "profiles" / kernel_file).read_text()
     except OSError:
-        pass
-    return None
+        info["traffic_source"] += "; summary missing"
+        return info
+    recorded = value = None
+    for line in text.splitlines():
+        if line.startswith("TRAFFIC_BYTES_PER_LAUNCH="):
+            value = float(line.split("=", 1)[1])
+        if line.startswith("KERNEL_SOURCES_SHA256="):
+            recorded = line.split("=", 1)[1].strip()
+    if recorded is not None and sources and recorded != kernel_source_digest(*sources):
+        info["traffic_source"] += "; kernel sources changed since the summary was taken: figure withheld"
+        return info
+    info["traffic"] = value
+    return info
 
 
 def pack_bytes(rows: int, K: int, beta: int) -> float:
@@ -72,6 +95,42 @@ def time_loop(fn, steps, warmup, torch):
         ev[i + 1].record()
     torch.cuda.synchronize()
     return [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
+
+
+def back_to_back_ms(calls, reps, torch, warm=3):
+    """Average time of one call when `calls` (a list of closures, walked round robin) are queued back to
+    back between ONE pair of events: kernel time, not launch or event latency."""
+    for i in range(warm * len(calls)):
+        calls[i % len(calls)]()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(reps):
+        calls[i % len(calls)]()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+VALU_EPILOGUE_LANE_OPS = VALU_LANE_OPS      # lane-ops / s of plain vector instructions (one per lane per cycle)
+
+
+def split_kernel_roofline(M, N, K, beta_a, beta_w, ms):
+    """Roofline of the matrix-core path (an unquantised operand or a segment shorter than a word): bf16 MFMA
+    flops actually issued -- 3 piece products per element pair, 6 when both operands are rebuilt -- against
+    the dense bf16 peak; for beta = 16 also the vector-ALU bound of its epilogue (one FMA and one clear per
+    output per 16-element segment)."""
+    pieces = 6 if max(beta_a, beta_w) < 16 or (min(beta_a, beta_w) == 1 and max(beta_a, beta_w) < 16) else 3
+    flops = pieces * 2.0 * M * N * K
+    r = {"bound": "mfma", "kernel": "mfma_split_gemm_kernel", "piece_products": pieces,
+         "achieved": flops / (ms * 1e-3) / 1e12, "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+         "frac": flops / (ms * 1e-3) / 1e12 / BF16_PEAK_TFLOPS}
+    g = max(beta_a, beta_w) if min(beta_a, beta_w) < 16 else min(beta_a, beta_w)   # the sign side's segment
+    if pieces == 3 and g == 16:
+        lane_ops = 2.0 * M * N * (K / 16)
+        r["epilogue_alu_bound_ms"] = lane_ops / VALU_EPILOGUE_LANE_OPS * 1e3
+        r["frac_of_epilogue_alu_bound"] = r["epilogue_alu_bound_ms"] / ms
+    return r
 
 
 def cpu_baseline(w, A, B):
@@ -94,6 +153,9 @@ def cpu_baseline(w, A, B):
         "value": 2.0 * rows_i * w.N * w.K / t_int / 1e9,
         "unit": "GOPS",
         "cores": threads,
+        "nproc": os.cpu_count(),
+        "physical_cores": _physical_cores(),
+        "omp_num_threads_env": os.environ.get("OMP_NUM_THREADS"),
         "kind": "oracle",
         "sample": f"integer path (scales + sign-pack of both operands + Eq.7 popcount product), all {rows_i} rows of A "
                   f"x all {w.N} rows of B: {t_int:.2f} s; dense f64 path (materialise + naive product) on the first "
@@ -101,6 +163,20 @@ def cpu_baseline(w, A, B):
         "dense_f64_gops": 2.0 * rows_d * w.N * w.K / t_dense / 1e9,
         "cpu_model": _cpu_model(),
     }
+
+
+def _physical_cores():
+    """Distinct (physical id, core id) pairs of /proc/cpuinfo; None if the file does not say."""
+    try:
+        cores, phys = set(), None
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("physical id"):
+                phys = line.split(":", 1)[1].strip()
+            elif line.startswith("core id"):
+                cores.add((phys, line.split(":", 1)[1].strip()))
+        return len(cores) or None
+    except OSError:
+        return None
 
 
 def _cpu_model() -> str:
@@ -221,18 +297,18 @@ def main():
             "peak": POPCOUNT_PEAK_TOPS,
             "unit": "TOP/s",
             "frac": ops / (t_gemm * 1e-3) / 1e12 / POPCOUNT_PEAK_TOPS,
-            "traffic": profiled_traffic("popcount_gemm_kernel_sq8k.txt") if w.name == "sq8k" else None,
-            "traffic_unit": "bytes per launch (FETCH_SIZE + WRITE_SIZE, calibrated; algorithmic 287.3e6)",
+            "traffic": None,
+            "traffic_unit": "HBM bytes per launch (FETCH_SIZE + WRITE_SIZE counters, calibrated)",
+            # packed bits and scales of both operands in, fp32 C out
+            "algorithmic_bytes": (w.M + w.N) * (w.K / 8.0) + 4.0 * (w.M * (w.K // w.beta_a) + w.N * (w.K // w.beta_w)) + 4.0 * w.M * w.N,
         }
+        if w.name == "sq8k":
+            out["roofline"].update(profiled_traffic("popcount_gemm_kernel_sq8k.txt", "gemm_popcount.hip", "tile_map.h"))
     else:
         # beta = 1 or a segment shorter than 32 runs on the matrix cores: the dense side is split into
-        # three bf16 pieces, so the kernel issues 3 x 2MNK bf16 flops per launch.
-        mfma_flops = 3.0 * ops
-        out["roofline"] = {
-            "kernel": "mfma_split_gemm_kernel (hbmm_gemm, beta 1 or < 32 on one side)", "bound": "mfma",
-            "achieved": mfma_flops / (t_gemm * 1e-3) / 1e12, "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": mfma_flops / (t_gemm * 1e-3) / 1e12 / BF16_PEAK_TFLOPS, "traffic": None,
-        }
+        # three bf16 pieces, so the kernel issues 3 x 2MNK bf16 flops per launch (6 when both sides are rebuilt).
+        out["roofline"] = split_kernel_roofline(w.M, w.N, w.K, w.beta_a, w.beta_w, t_gemm)
+        out["roofline"]["traffic"] = None
     if binary_act and w.b_layout == 0:
         # Pack timed on its own: launches queued back to back (A, B, A, B, ...: 2 x 268 MB of source at
         # the headline size, more than the 256 MB last-level cache) between one pair of events, so the
@@ -251,9 +327,11 @@ def main():
         out["roofline_pack"] = {
             "kernel": "pack_rows_kernel (hbmm_quantize_pack)", "bound": "hbm", "achieved": gbs,
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
-            "traffic": profiled_traffic("pack_rows_kernel_sq8k.txt") if w.name == "sq8k" else None,
+            "traffic": None, "algorithmic_bytes": 0.5 * (pack_bytes(w.M, w.K, w.beta_a) + pack_bytes(w.N, w.K, w.beta_w)),
             "ms_per_launch": t_pack, "launches": n_pack,
         }
+        if w.name == "sq8k":
+            out["roofline_pack"].update(profiled_traffic("pack_rows_kernel_sq8k.txt", "pack.hip", "wave_ops.h"))
         # context for that fraction: what a plain device-to-device copy of the same sources reaches on this
         # device (library copy kernel; bytes read + bytes written per second)
         dst = torch.empty_like(A)
@@ -297,9 +375,10 @@ def main():
                 "speedup_vs_headline_step": ms_per_step / ms4,
                 "roofline": {"kernel": "mfma_fp4_gemm_kernel (hbmm_gemm algo 2)", "bound": "mfma",
                              "achieved": ops / (g4 * 1e-3) / 1e12, "peak": FP4_PEAK_TFLOPS, "unit": "TFLOP/s",
-                             "frac": ops / (g4 * 1e-3) / 1e12 / FP4_PEAK_TFLOPS,
-                             "traffic": profiled_traffic("mfma_fp4_gemm_kernel_sq8k.txt") if w.name == "sq8k" else None},
+                             "frac": ops / (g4 * 1e-3) / 1e12 / FP4_PEAK_TFLOPS, "traffic": None},
             }
+            if w.name == "sq8k":
+                out["step_with_fp4_mfma_variant"]["roofline"].update(profiled_traffic("mfma_fp4_gemm_kernel_sq8k.txt", "gemm_mfma_fp4.hip"))
         except Exception as e:   # a comparison figure must never take the headline line down
             out["step_with_fp4_mfma_variant"] = {"error": f"{type(e).__name__}: {e}"}
 
@@ -379,10 +458,22 @@ def extras(w, A, B, a_bits, a_s, b_bits, b_s, C, torch, hbmm, synth, args):
         entry = {}
         if ww.beta_a != 1:
             ab, as_ = hbmm.quantize_pack(dA, ww.beta_a)
-            tp = time_loop(lambda: hbmm.quantize_pack(dA, ww.beta_a, 0, ab, as_), 30, 20, torch)
+            # pack(A) on its own: launches queued back to back over enough copies of the source (at least
+            # 512 MB together, at most 16) that it cannot stay in the 256 MB last-level cache
+            ncopy = max(1, min(16, -(-512 * 2**20 // (dA.numel() * 4))))
+            srcs = [dA] + [dA.clone() for _ in range(ncopy - 1)]
+            t_pack_a = back_to_back_ms([(lambda x=x: hbmm.quantize_pack(x, ww.beta_a, 0, ab, as_)) for x in srcs], 60, torch)
+            from_hbm = ncopy * dA.numel() * 4 >= 512 * 2**20
+            entry["pack_a_ms"] = t_pack_a
+            gbs_a = pack_bytes(ww.M, ww.K, ww.beta_a) / (t_pack_a * 1e-3) / 1e9
+            if from_hbm:
+                entry["pack_a_GBs"] = gbs_a
+                entry["pack_a_frac_of_hbm_peak"] = gbs_a / HBM_PEAK_GBS
+            else:   # too small to be pushed out of the cache with 16 copies: not an HBM figure
+                entry["pack_a_GBs_cache_resident"] = gbs_a
+            entry["pack_a_sources_rotated"] = ncopy
+            del srcs
             tg = time_loop(lambda: hbmm.gemm(ab, as_, ww.beta_a, bb, bs, ww.beta_w, ww.K), 30, 20, torch)
-            entry["pack_a_ms"] = min(tp)
-            entry["pack_a_GBs"] = pack_bytes(ww.M, ww.K, ww.beta_a) / (min(tp) * 1e-3) / 1e9
             # the fastest kernel for these segment lengths (hbmm_gemm algo -1: fp4 / fp8 matrix-core variants)
             tf = time_loop(lambda: hbmm.gemm(ab, as_, ww.beta_a, bb, bs, ww.beta_w, ww.K, hbmm.ALGO_FASTEST), 30, 20, torch)
             entry["gemm_fastest_algo_ms"] = min(tf)
@@ -393,6 +484,10 @@ def extras(w, A, B, a_bits, a_s, b_bits, b_s, C, torch, hbmm, synth, args):
         entry["gemm_gops"] = 2.0 * ww.M * ww.N * ww.K / (min(tg) * 1e-3) / 1e9
         if min(ww.beta_a, ww.beta_w) >= 32:   # the XNOR + popcount kernel
             entry["gemm_frac_of_popcount_peak"] = entry["gemm_gops"] / (POPCOUNT_PEAK_TOPS * 1e3)
+            entry["roofline"] = {"bound": "alu", "kernel": "popcount_gemm_kernel", "achieved": entry["gemm_gops"] / 1e3,
+                                 "peak": POPCOUNT_PEAK_TOPS, "unit": "TOP/s", "frac": entry["gemm_frac_of_popcount_peak"]}
+        else:
+            entry["roofline"] = split_kernel_roofline(ww.M, ww.N, ww.K, ww.beta_a, ww.beta_w, entry["gemm_ms"])
         # the full-precision comparison on the same shape: the library's bf16 GEMM and this
         # repository's own dense kernel (operands in the same rows x K form)
         try:
@@ -480,14 +575,27 @@ def extras(w, A, B, a_bits, a_s, b_bits, b_s, C, torch, hbmm, synth, args):
             dA = torch.from_numpy(cw.make_a()).cuda()
             dW = torch.from_numpy(cw.make_w().reshape(cw.N, -1)).cuda()
             wb, ws = hbmm.quantize_pack(dW, cw.beta_w)
-            ab, asc = hbmm.quantize_pack_tensor(dA, cw.beta_a)
+            entry = {"beta_a": cw.beta_a, "beta_w": cw.beta_w}
+            if cw.beta_a == 1:      # binary-weight layer: the activations go in as they are
+                ab, asc = None, dA
+            else:
+                ab, asc = hbmm.quantize_pack_tensor(dA, cw.beta_a)
+                # queued back to back between one pair of events (a single launch of the small layers is
+                # shorter than the events' own resolution)
+                tq = back_to_back_ms([lambda: hbmm.quantize_pack_tensor(dA, cw.beta_a, ab, asc)], 40, torch)
+                qbytes = dA.numel() * (4.0 + 1.0 / 8.0 + 4.0 / cw.beta_a)
+                entry["quantize_ms"] = tq
+                entry["quantize_GBs_cache_resident" if dA.numel() * 4 < 512 * 2**20 else "quantize_GBs"] = qbytes / (tq * 1e-3) / 1e9
             out = hbmm.conv2d(ab, asc, cw.beta_a, dA.shape, wb, ws, cw.beta_w, (cw.KH, cw.KW), cw.stride, cw.pad)
-            tq = time_loop(lambda: hbmm.quantize_pack_tensor(dA, cw.beta_a), 10, 2, torch)
-            tc = time_loop(lambda: hbmm.conv2d(ab, asc, cw.beta_a, dA.shape, wb, ws, cw.beta_w, (cw.KH, cw.KW),
-                                               cw.stride, cw.pad, out), 10, 2, torch)
-            convs[name] = {"quantize_ms": min(tq), "conv_ms": min(tc),
-                           "conv_effective_gflops": 2.0 * cw.macs / (min(tc) * 1e-3) / 1e9,
-                           "beta_a": cw.beta_a, "beta_w": cw.beta_w}
+            tc = back_to_back_ms([lambda: hbmm.conv2d(ab, asc, cw.beta_a, dA.shape, wb, ws, cw.beta_w, (cw.KH, cw.KW),
+                                                      cw.stride, cw.pad, out)], 20, torch)
+            pieces = 6 if cw.beta_w < 16 else 3
+            entry.update({"conv_ms": tc, "conv_effective_gflops": 2.0 * cw.macs / (tc * 1e-3) / 1e9,
+                          "roofline": {"bound": "mfma", "kernel": "conv_patch_kernel / mfma_split_gemm_kernel (conv mode)",
+                                       "piece_products": pieces,
+                                       "achieved": pieces * 2.0 * cw.macs / (tc * 1e-3) / 1e12, "peak": BF16_PEAK_TFLOPS,
+                                       "unit": "TFLOP/s", "frac": pieces * 2.0 * cw.macs / (tc * 1e-3) / 1e12 / BF16_PEAK_TFLOPS}})
+            convs[name] = entry
             del dA, dW, out
         except Exception as e:
             convs[name] = {"error": str(e)}

@@ -123,8 +123,9 @@ int hbmm_binarize_backward(const float *x, const float *grad_out, int64_t rows, 
  *                     3: (both beta >= 16, the shorter one 16 or 32, K a multiple of 128) the same
  *                        d[m, n, g] from 8-bit-float +-1 matrix-core products, 16 elements of K per step;
  *                        same epilogue (bit-identical to 0 when both beta >= 32).
- *                    -1: the fastest of these for the given segment lengths (2 when both beta >= 64,
- *                        3 when both are 16 or 32 and K is a multiple of 128, else 0).
+ *                    -1: the fastest of these for the given segment lengths and output size (2 when both
+ *                        beta >= 64, 3 when both are 16 or 32 and K is a multiple of 128, else 0; and 0
+ *                        when both beta >= 32 and the output has fewer than 32 tiles of 128 x 128).
  *
  * M == 0 or N == 0 is a valid no-op; K == 0 writes zeros.
  */

@@ -176,6 +176,9 @@ int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int6
         const int gmax = beta_a < beta_w ? beta_w : beta_a;
         // (a short segment against a long one is as fast on the bf16 kernel: its epilogue is rare there)
         algo = g >= 64 ? 2 : (g >= 16 && gmax <= 32 && K % 128 == 0) ? 3 : 0;
+        // The matrix-core variants work on 128 x 128 tiles at least; on a grid of a few tiles the popcount
+        // kernel, which has a 64-row form for small grids, is as fast or faster (64 x 64 x 512: 11 against 18 us).
+        if (algo >= 2 && beta_a >= 32 && beta_w >= 32 && ((M + 127) / 128) * ((N + 127) / 128) < 32) algo = 0;
     }
     const bool word_a = supported_beta(beta_a), word_w = supported_beta(beta_w);   // 32 .. 256
     if (!(beta_a == 1 || supported_pack_beta(beta_a)) || !(beta_w == 1 || supported_pack_beta(beta_w)))

@@ -33,7 +33,34 @@ def test_bench_prints_one_consistent_json_line():
     assert rf["achieved"] == pytest.approx(2.0 * M * N * K / (d["kernel_ms"]["gemm"] * 1e-3) / 1e12, rel=1e-6)
     assert 0.3 < rf["frac"] < 1.2                      # a healthy device lands near 0.85
     assert rf["traffic"] is None or rf["traffic"] > 0
+    assert "profiles/" in rf["traffic_source"] and rf["algorithmic_bytes"] > 0     # where the counter figure comes from
+    assert rf["traffic"] is None or rf["traffic"] >= 0.9 * rf["algorithmic_bytes"]
     rp = d["roofline_pack"]
     assert rp["bound"] == "hbm" and rp["peak"] == 8000.0 and rp["frac"] == pytest.approx(rp["achieved"] / 8000.0, rel=1e-9)
     cb = d["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["cores"] >= 1 and cb["value"] > 0 and cb["unit"] == d["unit"] and cb["sample"]
+    assert cb["nproc"] >= 1 and "physical_cores" in cb and "cpu_model" in cb
+
+
+def test_bench_comparison_rows_carry_a_bound_and_a_fraction():
+    """Every row next to the headline -- the other workloads, the convolution layers, the backward --
+    states which roofline bounds it and the fraction it reaches; pack figures say whether they are HBM
+    figures or cache-resident ones."""
+    r = subprocess.run([sys.executable, str(ROOT / "bench.py"), "--steps", "3", "--warmup", "1", "--no-cpu-baseline"],
+                       capture_output=True, text=True, timeout=900)
+    assert r.returncode == 0, r.stderr[-2000:]
+    d = json.loads([ln for ln in r.stdout.splitlines() if ln.strip()][-1])
+    cmp_ = d["comparisons"]
+    assert "error" not in cmp_, cmp_
+    for name, e in cmp_["other_workloads"].items():
+        rf = e["roofline"]
+        assert rf["bound"] in ("alu", "mfma") and 0 < rf["frac"] < 1.5, name
+        assert rf["frac"] == pytest.approx(rf["achieved"] / rf["peak"], rel=1e-9), name
+        if "pack_a_ms" in e:
+            assert ("pack_a_GBs" in e) != ("pack_a_GBs_cache_resident" in e), name
+    assert cmp_["other_workloads"]["c5xw4"]["roofline"]["piece_products"] == 6
+    assert "frac_of_epilogue_alu_bound" in cmp_["other_workloads"]["sq4k16"]["roofline"]
+    for name, e in cmp_["conv2d"].items():
+        assert "error" not in e, (name, e)
+        assert e["roofline"]["bound"] == "mfma" and 0 < e["roofline"]["frac"] < 1.0, name
+    assert 0 < cmp_["binarize_backward"]["frac_of_hbm_peak"] < 1.2
