@@ -8,6 +8,7 @@ order the paper's definitions give (scale -> sign -> Hadamard product -> matrix 
 from __future__ import annotations
 
 import ctypes as C
+import os
 
 import numpy as np
 
@@ -26,7 +27,9 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        # HBMM_ORACLE_LIB: another build of the same source (the sanitizer test points it at an
+        # instrumented one)
+        path = os.environ.get("HBMM_ORACLE_LIB") or _build.build(force=False)
         lib = C.CDLL(str(path))
         i64, p = C.c_int64, C.c_void_p
         lib.oracle_num_threads.restype = C.c_int

@@ -1,0 +1,21 @@
+// Stand-ins for the kernel launchers of libhbmm, for the host-only sanitizer build of the C-ABI layer
+// (csrc/api.hip): every launcher counts the call and reports success, so that the argument checking
+// and dispatch code of api.hip runs under AddressSanitizer / UBSan on a machine without a GPU.
+// Test infrastructure only: nothing in the product links this file.
+#include "../../paper_1905_10759_amd/csrc/kernels.h"
+
+static int g_launches = 0;
+extern "C" int hbmm_stub_launches(void) { return g_launches; }
+
+namespace hbmm {
+hipError_t launch_pack_rows(const float *, int64_t, int64_t, int64_t, int, uint32_t *, int64_t, float *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_pack_cols(const float *, int64_t, int64_t, int64_t, int, uint32_t *, int64_t, float *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_binarize_backward(const float *, const float *, int64_t, int64_t, int64_t, int64_t, int, float *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_popcount_gemm(const PopcountGemmArgs &, int, int, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_mfma_split_gemm(const SplitGemmOperand &, const SplitGemmOperand &, int64_t, float *, int64_t, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_mfma_split_conv(const ConvActivations &, const SplitGemmOperand &, const ConvGeometry &, float *, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_mfma_i8_gemm(const uint32_t *, const float *, int64_t, int64_t, int, const uint32_t *, const float *, int64_t, int64_t, int, int64_t, int64_t, int64_t, float *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_mfma_fp4_gemm(const uint32_t *, const float *, int64_t, int64_t, int, const uint32_t *, const float *, int64_t, int64_t, int, int64_t, int64_t, int64_t, float *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_mfma_fp8_gemm(const uint32_t *, const float *, int64_t, int64_t, int, const uint32_t *, const float *, int64_t, int64_t, int, int64_t, int64_t, int64_t, float *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_dense_ref(const void *, int64_t, const void *, int64_t, int, int64_t, int64_t, int64_t, float *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
+}  // namespace hbmm

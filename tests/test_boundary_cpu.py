@@ -90,7 +90,6 @@ def test_validation_rejects_before_launch(lib):
     assert call(ba=48) == -2                      # not a power of two
     assert call(bw=512) == -2
     assert call(ba=1, a=None, bw=1, b=None, ldsa=64, ldsb=64) == -2   # two unquantised operands: a plain dense product
-    assert call(ba=1, a=None, bw=1, b=None, ldsa=64, ldsb=64) == -2   # two unquantised operands: dense product
     assert call(ba=16, ldsa=4, algo=1) == -2      # the int8 comparison variant needs word-sized segments
     assert call(K=48, ba=16, bw=16, ldsa=3, ldsb=3) == -2   # K must be a multiple of 32
     assert call(ba=16, ldsa=3) == -1              # lds_a < K / beta_a
