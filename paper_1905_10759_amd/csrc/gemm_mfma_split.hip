@@ -562,7 +562,9 @@ __global__ __launch_bounds__(kThreadsS) void conv_patch_kernel(const ConvPatchAr
 
     const int slot_id = (blockIdx.x % kNumXcdS) * a.slots_per_xcd + blockIdx.x / kNumXcdS;
     if (slot_id >= a.tiles_total) return;
-    const int tile_x = slot_id / a.tiles_y, y0 = (slot_id % a.tiles_y) * kBY;
+    // (a tile covers 256 filters, or 64 NTY of them: the latter also with several tiles along the filters,
+    // which the launcher uses to fill the chip when there are few position tiles)
+    const int tile_x = slot_id / a.tiles_y, y0 = (slot_id % a.tiles_y) * (NTY == 0 ? kBY : 64 * NTY);
     const int img = tile_x / a.tiles_per_image, oz0 = (tile_x % a.tiles_per_image) * a.R;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -935,7 +937,15 @@ static bool try_launch_conv_patch(const ConvActivations &x, const SplitGemmOpera
     if (ipt > 8) return false;
     const int NS = (2 * kStageK - 1) / KK + 3, PS = (P + 7) / 8 * 8;
     if (NS * PS > kPatchPlane) return false;
-    const int64_t tiles_x = g.B * tiles_per_image, tiles_y = (y.rows + kBY - 1) / kBY;
+    // Filters per tile: 256, or all of them when there are at most 192; narrower tiles (128, then 64
+    // filters: every position tile is then staged by several workgroups) as long as the grid does not
+    // give every compute unit a workgroup.
+    int nty = y.rows <= 64 ? 1 : y.rows <= 128 ? 2 : y.rows <= 192 ? 3 : 0;
+    const int64_t tiles_x = g.B * tiles_per_image;
+    auto tiles_along_y = [&](int n) { return (y.rows + (n == 0 ? kBY : 64 * n) - 1) / (n == 0 ? kBY : 64 * n); };
+    if (nty == 0 && tiles_x * tiles_along_y(0) < 256) nty = 2;
+    if (nty == 2 && y.rows > 64 && tiles_x * tiles_along_y(2) < 256) nty = 1;
+    const int64_t tiles_y = tiles_along_y(nty);
     const int64_t total = tiles_x * tiles_y, per_xcd = (total + kNumXcdS - 1) / kNumXcdS;
     if (per_xcd * kNumXcdS > 0x7fffffffLL) return false;
     ConvPatchArgs a{};
@@ -957,7 +967,6 @@ static bool try_launch_conv_patch(const ConvActivations &x, const SplitGemmOpera
     a.last_elem = (uint32_t)(g.B * g.C * g.H * g.W - 1);
     a.q32 = kStageK / KK; a.r32 = kStageK % KK; a.magic_kw = 65536 / g.KW + 1;
     const dim3 grid((unsigned)(per_xcd * kNumXcdS)), block(kThreadsS);
-    const int nty = y.rows <= 64 ? 1 : y.rows <= 128 ? 2 : y.rows <= 192 ? 3 : 0;
 #define HBMM_PATCH_LAUNCH(I)                                                \
     do {                                                                    \
         if (nty == 1)                                                       \

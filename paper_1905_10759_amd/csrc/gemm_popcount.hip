@@ -71,7 +71,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // 1 (64 rows) is used for small problems, which then spread over twice as many workgroups; 4 (256
 // rows) for a K of at most two chunks on a large grid.  The fused form uses 2 and 1 the same way.
 template <int G, bool INTEGER, bool FUSED, int TP>
-__global__ __launch_bounds__(kThreads, TP == 2 ? 3 : 2) void popcount_gemm_kernel(const PopcountGemmArgs a)
+__global__ __launch_bounds__(kThreads, TP == 2 ? (G >= 128 && !FUSED ? 4 : 3) : 2) void popcount_gemm_kernel(const PopcountGemmArgs a)
 {
     constexpr int kTP = TP;
     constexpr int kTileP = 64 * TP;                             // P rows per workgroup
