@@ -61,13 +61,16 @@ int64_t hbmm_packed_ld_words(int64_t K);
  *                         layout 1: K x rows, element (r, k) at x[k*ldx + r]   (ldx >= rows);
  *                         this is a right-hand operand written the usual K x N way; the result
  *                         is identical to packing its transpose.
- *   beta    segment length; supported: the powers of two 2 .. 256, with K a multiple of beta and of 32.
+ *   beta    segment length, 2 .. 256.  The paper's settings -- a power of two that divides K, K a
+ *           multiple of 32 -- take the tuned kernels.  Any other beta in that range and any K >= 1 is
+ *           accepted too: the last segment is then the shorter remainder and its scale is the mean of
+ *           |x| over its own length (Eq. 1 applied to the elements that exist); bits at k >= K are 0.
  *   bits    out, rows x ldw (ldw >= hbmm_packed_ld_words(K), multiple of 4).
  *   scales  out, rows x lds (lds >= hbmm_num_blocks(K, beta)).
  *
  * rows == 0 or K == 0 is a valid no-op.  The fp32 scale is a pairwise fp32 sum for layout 0
  * (relative error <= (log2(beta) + 1) * 2^-24) and a double-precision sequential sum rounded
- * once for layout 1.
+ * once for layout 1 and for the general kernel.
  */
 int hbmm_quantize_pack(const float *x, int64_t rows, int64_t K, int64_t ldx, int32_t layout,
                        int32_t beta, uint32_t *bits, int64_t ldw, float *scales, int64_t lds,
@@ -100,7 +103,8 @@ int hbmm_binarize_backward(const float *x, const float *grad_out, int64_t rows, 
  *
  *   a_bits, a_scales  packed A (M rows), from hbmm_quantize_pack with beta_a.
  *   b_bits, b_scales  packed B (N rows), from hbmm_quantize_pack with beta_w.
- *   beta_a, beta_w    each a power of two in 2 .. 256, or 1; K a multiple of both and of 32.
+ *   beta_a, beta_w    each in 1 .. 256.  The paper's settings -- powers of two (or 1) with K a multiple
+ *                     of both and of 32 -- are described first; the general case is at the end.
  *                     beta == 1 means that operand is not binarised (the paper's beta = 1; beta_a = 1
  *                     is its HBWN): its bits pointer must be NULL, its scales pointer is the raw fp32
  *                     operand (rows x K, leading dimension lds, a multiple of 4), and e.g. for
@@ -113,6 +117,13 @@ int hbmm_binarize_backward(const float *x, const float *grad_out, int64_t rows, 
  *                     covers the paper's binary-weight networks, beta_a = 1 with beta_w = 4 or 8, and
  *                     its HadaNets with beta_a = beta_w = 4).  Not supported: beta = 1 for both (that
  *                     is hbmm_dense_ref_gemm).
+ *                     General case (a segment length that is not a power of two, a K that beta does not
+ *                     divide, K not a multiple of 32; K < 2^24; algo 0 or -1): the operands are as
+ *                     hbmm_quantize_pack writes them for that beta and K (scales per row:
+ *                     hbmm_num_blocks(K, beta), the last segment shorter); both are rebuilt as fp32
+ *                     values on the matrix-core kernel, C[m, n] = sum_k A~[m, k] * B~[n, k] with
+ *                     X~[r, k] = sX[r, k div beta] * Sign(X)[r, k].  An unquantised operand needs no
+ *                     particular leading dimension here.
  *   C                 out, M x N fp32, leading dimension ldc >= N.
  *   algo              0: the method's kernel as described above.
  *                     1: (both beta >= 32 only) the same d[m, n, g] from int8 +-1 matrix-core (MFMA)

@@ -17,6 +17,9 @@ int log2_exact(int v)
 
 bool supported_beta(int beta) { return beta == 32 || beta == 64 || beta == 128 || beta == 256; }
 bool supported_pack_beta(int beta) { return beta >= 2 && beta <= 256 && (beta & (beta - 1)) == 0; }
+// What the general (untuned) kernels take: any segment length up to 256, 1 = unquantised
+bool any_beta(int beta) { return beta >= 1 && beta <= 256; }
+constexpr int64_t kMaxAnyK = ((int64_t)1 << 24) - 1;   // their k div beta is a 32-bit multiply-high
 
 int from_hip(hipError_t e)
 {
@@ -77,17 +80,20 @@ int hbmm_quantize_pack(const float *x, int64_t rows, int64_t K, int64_t ldx, int
 {
     if (rows < 0 || K < 0 || rows > kMaxDim || K > kMaxPackK) return HBMM_EINVAL;
     if (layout != 0 && layout != 1) return HBMM_EINVAL;
-    if (layout == 1 && K > kMaxPackColsK) return HBMM_EINVAL;
     if (beta < 1) return HBMM_EINVAL;
-    if (!supported_pack_beta(beta)) return HBMM_EUNSUPPORTED;
-    if (K % beta != 0 || K % 32 != 0) return HBMM_EUNSUPPORTED;
+    if (beta == 1 || !any_beta(beta)) return HBMM_EUNSUPPORTED;
+    // the tuned kernels take the paper's settings (power-of-two segments that divide K, whole words);
+    // everything else goes to the general kernel
+    const bool tuned = supported_pack_beta(beta) && K % beta == 0 && K % 32 == 0;
+    if (tuned && layout == 1 && K > kMaxPackColsK) return HBMM_EINVAL;
     if (rows == 0 || K == 0) return HBMM_OK;
     if (!x || !bits || !scales) return HBMM_EINVAL;
     if (!aligned16(x) || !aligned16(bits) || !aligned16(scales)) return HBMM_EINVAL;
     if (ldx < (layout == 0 ? K : rows)) return HBMM_EINVAL;
     if (ldw < hbmm::packed_words(K) || ldw % 4 != 0) return HBMM_EINVAL;
-    if (lds < K / beta) return HBMM_EINVAL;
+    if (lds < (K + beta - 1) / beta) return HBMM_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!tuned) return from_hip(hbmm::launch_pack_any(x, rows, K, ldx, layout, beta, bits, ldw, scales, lds, s));
     if (layout == 0) return from_hip(hbmm::launch_pack_rows(x, rows, K, ldx, beta, bits, ldw, scales, lds, s));
     return from_hip(hbmm::launch_pack_cols(x, rows, K, ldx, beta, bits, ldw, scales, lds, s));
 }
@@ -141,7 +147,7 @@ static int check_operand(const GemmOperand &o, int64_t K)
         if (o.bits != nullptr) return HBMM_EINVAL;     // raw operand travels through `scales`
         return o.lds < K ? HBMM_EINVAL : HBMM_OK;
     }
-    if (o.lds < K / o.beta) return HBMM_EINVAL;
+    if (o.lds < (K + o.beta - 1) / o.beta) return HBMM_EINVAL;
     return check_packed(o.bits, o.rows, K, o.ldw);
 }
 
@@ -181,9 +187,13 @@ int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int6
         if (algo >= 2 && beta_a >= 32 && beta_w >= 32 && ((M + 127) / 128) * ((N + 127) / 128) < 32) algo = 0;
     }
     const bool word_a = supported_beta(beta_a), word_w = supported_beta(beta_w);   // 32 .. 256
-    if (!(beta_a == 1 || supported_pack_beta(beta_a)) || !(beta_w == 1 || supported_pack_beta(beta_w)))
-        return HBMM_EUNSUPPORTED;
-    if (K % beta_w != 0 || K % beta_a != 0 || K % 32 != 0) return HBMM_EUNSUPPORTED;
+    if (!any_beta(beta_a) || !any_beta(beta_w)) return HBMM_EUNSUPPORTED;
+    // The paper's settings: power-of-two segments that divide K (and whole 32-bit words).  Anything else
+    // -- other segment lengths, a shorter last segment, K not a multiple of 32 -- is the general path below.
+    const bool tuned = (beta_a == 1 || supported_pack_beta(beta_a)) && (beta_w == 1 || supported_pack_beta(beta_w)) &&
+                       K % beta_w == 0 && K % beta_a == 0 && K % 32 == 0 &&
+                       (beta_a != 1 || lds_a % 4 == 0) && (beta_w != 1 || lds_b % 4 == 0);   // 16-byte row loads
+    if (!tuned && (algo > 0 || K > kMaxAnyK)) return HBMM_EUNSUPPORTED;
     if ((algo == 1 || algo == 2) && !(word_a && word_w)) return HBMM_EUNSUPPORTED;
     if (algo == 2 && (beta_a < 64 || beta_w < 64)) return HBMM_EUNSUPPORTED;   // one fp4 MFMA step is 64 bits of K
     if (algo == 3) {
@@ -202,6 +212,12 @@ int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int6
     const GemmOperand ob{b_bits, b_scales, ldw_b, lds_b, N, beta_w};
     if (int rc = check_operand(ob, K)) return rc;
     if (int rc = check_operand(oa, K)) return rc;
+
+    if (!tuned) {
+        // both sides rebuilt as fp32 values element by element; an unquantised operand is the "x" side
+        if (beta_w != 1) return from_hip(hbmm::launch_mfma_split_any(to_split(oa), to_split(ob), K, C, ldc, 1, s));
+        return from_hip(hbmm::launch_mfma_split_any(to_split(ob), to_split(oa), K, C, 1, ldc, s));
+    }
 
     if (algo == 3)
         return from_hip(hbmm::launch_mfma_fp8_gemm(a_bits, a_scales, ldw_a, lds_a, beta_a, b_bits, b_scales,

@@ -53,6 +53,7 @@ constexpr int kXScale1 = 1;   // packed, beta_x >= 8: one scale covers a thread'
 constexpr int kXScale2 = 2;   // packed, beta_x = 4: two scales per 8 elements
 constexpr int kXScale4 = 3;   // packed, beta_x = 2: four scales per 8 elements
 constexpr int kXConv = 4;     // packed activation tensor read through a convolution window (see below)
+constexpr int kXAny = 5;      // any beta_x (1 included), any K: a scale looked up per element (see kYAny)
 
 // Sign masks for `n` (<= 8) pairs of elements: complemented bit 2i of `inv` -> bit 15 of dword i,
 // complemented bit 2i+1 -> bit 31 (the sign positions of a pair of bf16 values).
@@ -125,6 +126,10 @@ struct SplitArgs {
     int32_t cv_magic_kk, cv_magic_kw;   // 65536 / d + 1: (t * magic) >> 16 == t / d for t < 64, d <= 32
     int32_t cv_q32, cv_r32;             // 32 div KK, 32 mod KK: how (c, tap) moves from stage to stage
     uint32_t cv_sign;                   // 0x80000000; 0 when the tensor is unquantised (see launch_mfma_split_conv)
+    // kXAny / kYAny
+    uint32_t any_magic_x, any_magic_y;  // ceil(2^32 / beta)
+    uint32_t any_sign_x;                // 0x80000000; 0 when X is the raw operand
+    int32_t any_x_raw;                  // X is raw: x_scales is the operand itself, x_bits is never used
 };
 
 // Y modes: how the other side is given
@@ -133,6 +138,11 @@ constexpr int kYSign16 = 1;   // packed, beta_y = 16: the same with a segment pe
 constexpr int kYPieces1 = 2;  // packed, beta_y = 8: a segment is shorter than an MFMA step, so Y is rebuilt as fp32
 constexpr int kYPieces2 = 3;  // packed, beta_y = 4   values and split into pieces like X; the six largest of the
 constexpr int kYPieces4 = 4;  // packed, beta_y = 2   nine piece products are added and there is no epilogue
+// Segment lengths that are not powers of two, and K that is not a multiple of 32 or of beta: both sides
+// are rebuilt as fp32 values element by element (scale index k div beta by a multiply-high with
+// ceil(2^32 / beta), exact for k < 2^24), elements at k >= K are parked as zero, and the last segment
+// is simply the shorter one whose scale the pack kernel averaged over its own length.
+constexpr int kYAny = 5;
 
 // NTY: 0 for the general case; 1, 2 or 3 when Y keeps its signs and has at most 64, 128 or 192 rows
 // (one tile), see below.  With Y as pieces the tile is 128 x 128 (the Y tile is three planes in LDS).
@@ -159,7 +169,7 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
     constexpr int TX = NTY == 0 ? 2 : 1, TY = YP ? 1 : NTY == 0 ? 2 : NTY;
     const int wrow0 = NTY == 0 ? (wave >> 2) * 64 : (wave & 3) * 32;
     const int wcol0 = YP ? (wave & 3) * 32 : NTY == 0 ? (wave & 3) * 64 : (wave >> 2) * (32 * NTY);
-    const int nstages = a.K / kStageK;
+    const int nstages = (a.K + kStageK - 1) / kStageK;   // only the kXAny / kYAny pair sees a ragged K
 
     constexpr int kScalesPerThread = XMODE == kXScale4 ? 4 : XMODE == kXScale2 ? 2 : 1;
     constexpr int kYScalesPerThread = YMODE == kYPieces4 ? 4 : YMODE == kYPieces2 ? 2 : 1;
@@ -171,6 +181,8 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
         float ys[kYScalesPerThread];                       // pieces: the scales of this thread's 8 elements of Y
         uint32_t cw[XMODE == kXConv ? 8 : 1];              // conv: the word holding each element's bit
         float cs[XMODE == kXConv ? 8 : 1];                 // conv: each element's scale
+        float gx[XMODE == kXAny ? 8 : 1];                  // any beta: each element's scale (or raw value)
+        float gy[YMODE == kYAny ? 8 : 1];
     };
 
     // ---- sources (clamped, so every load below is unconditional)
@@ -254,6 +266,13 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
                 st.cs[i] = a.x_scales[e >> a.log2_beta_x];
             }
             conv_advance(fc0, fr0);
+        } else if constexpr (XMODE == kXAny) {
+            st.xb = xb_src[sg];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t k = (uint32_t)min(sg * kStageK + poct * 8 + i, a.K - 1);
+                st.gx[i] = xs_src[a.any_x_raw ? k : __umulhi(k, a.any_magic_x)];
+            }
         } else {
             st.xb = xb_src[sg];
             const int sidx = (sg * kStageK + poct * 8) >> a.log2_beta_x;
@@ -261,14 +280,42 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
             for (int j = 0; j < kScalesPerThread; ++j) st.xs[j] = xs_src[sidx + j];
         }
         st.yb = yb_src[sg];
-        if (YP) {
+        if constexpr (YMODE == kYAny) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t k = (uint32_t)min(sg * kStageK + yoct * 8 + i, a.K - 1);
+                st.gy[i] = ys_src[__umulhi(k, a.any_magic_y)];
+            }
+        } else if (YP) {
             const int yidx = (sg * kStageK + yoct * 8) >> a.log2_beta_y;
 #pragma unroll
             for (int j = 0; j < kYScalesPerThread; ++j) st.ys[j] = ys_src[yidx + j];
         }
     };
 
+    // any-beta modes: 8 elements starting at k0, values +-scale (bit = 1: positive) or 0 past K
+    auto any_pieces = [&](uint32_t byte, const float (&sc)[8], int k0, uint32_t sign, u32x4 &dh, u32x4 &dm, u32x4 &dl)
+                          __attribute__((always_inline)) {
+        uint32_t h[8], m[8], l[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t keep = k0 + i < a.K ? 0xffffffffu : 0u;
+            const uint32_t minus = (~(byte >> i) << 31) & sign;
+            const uint32_t value = (__builtin_bit_cast(uint32_t, sc[i]) ^ minus) & keep;
+            split3(__builtin_bit_cast(float, value), h[i], m[i], l[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            dh[i] = pair16(h[2 * i], h[2 * i + 1]);
+            dm[i] = pair16(m[2 * i], m[2 * i + 1]);
+            dl[i] = pair16(l[2 * i], l[2 * i + 1]);
+        }
+    };
+    int park_k0 = 0;   // first k of the stage that the next call of park() handles (any-beta modes)
+
     auto park = [&](const Staged &st, int buf) {
+        const int pk0 = park_k0;
+        park_k0 += kStageK;
         if (XMODE == kXRaw) {
 #pragma unroll
             for (int r = 0; r < 2; ++r) {
@@ -308,6 +355,14 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
             *reinterpret_cast<u32x4 *>(dst) = dh;
             *reinterpret_cast<u32x4 *>(dst + kPieceBytes) = dm;
             *reinterpret_cast<u32x4 *>(dst + 2 * kPieceBytes) = dl;
+        } else if constexpr (XMODE == kXAny) {
+            // a raw operand carries its own sign: the mask is then 0 and the bits are ignored
+            u32x4 dh, dm, dl;
+            any_pieces(st.xb >> (8 * poct), st.gx, pk0 + 8 * poct, a.any_sign_x, dh, dm, dl);
+            unsigned char *dst = &sX[buf][prow * kRowBytes + poct * 16];
+            *reinterpret_cast<u32x4 *>(dst) = dh;
+            *reinterpret_cast<u32x4 *>(dst + kPieceBytes) = dm;
+            *reinterpret_cast<u32x4 *>(dst + 2 * kPieceBytes) = dl;
         } else {
             u32x4 dh, dm, dl;
             packed_pieces<kScalesPerThread>(st.xb >> (8 * poct), st.xs, dh, dm, dl);
@@ -318,7 +373,10 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
         }
         if (YP) {
             u32x4 dh, dm, dl;
-            packed_pieces<kYScalesPerThread>(st.yb >> (8 * yoct), st.ys, dh, dm, dl);
+            if constexpr (YMODE == kYAny)
+                any_pieces(st.yb >> (8 * yoct), st.gy, pk0 + 8 * yoct, 0x80000000u, dh, dm, dl);
+            else
+                packed_pieces<kYScalesPerThread>(st.yb >> (8 * yoct), st.ys, dh, dm, dl);
             unsigned char *dst = &sY[buf][yrow_t * kRowBytes + yoct * 16];
             *reinterpret_cast<u32x4 *>(dst) = dh;
             *reinterpret_cast<u32x4 *>(dst + kYPlane) = dm;
@@ -919,6 +977,36 @@ hipError_t launch_mfma_split_gemm(const SplitGemmOperand &x, const SplitGemmOper
     if (x.beta == 2) return launch_mode<kXScale4>(a, y.beta, grid, s);
     if (x.beta == 4) return launch_mode<kXScale2>(a, y.beta, grid, s);
     return launch_mode<kXScale1>(a, y.beta, grid, s);
+}
+
+hipError_t launch_mfma_split_any(const SplitGemmOperand &x, const SplitGemmOperand &y, int64_t K, float *out,
+                                 int64_t ld_out_x, int64_t ld_out_y, hipStream_t s)
+{
+    if (y.beta < 2 || y.beta > 256 || y.bits == nullptr || y.scales == nullptr) return hipErrorNotSupported;
+    if (x.beta < 1 || x.beta > 256 || K < 1 || K >= (1 << 24)) return hipErrorNotSupported;
+    if (x.beta == 1 ? x.raw == nullptr : (x.bits == nullptr || x.scales == nullptr)) return hipErrorNotSupported;
+    const bool raw = x.beta == 1;
+    if ((raw ? x.ld_raw : x.ldw) > 0x7fffffffLL || x.lds > 0x7fffffffLL) return hipErrorNotSupported;
+    SplitArgs a{};
+    // raw X: the "scales" are the values; the word loaded as bits is any in-bounds word of the row
+    a.x_bits = raw ? reinterpret_cast<const uint32_t *>(x.raw) : x.bits;
+    a.x_scales = raw ? x.raw : x.scales;
+    a.ldw_x = (int32_t)(raw ? x.ld_raw : x.ldw);
+    a.lds_x = (int32_t)(raw ? x.ld_raw : x.lds);
+    a.any_x_raw = raw ? 1 : 0;
+    a.any_sign_x = raw ? 0u : 0x80000000u;
+    a.any_magic_x = raw ? 0u : (uint32_t)(((1ull << 32) + x.beta - 1) / x.beta);
+    a.any_magic_y = (uint32_t)(((1ull << 32) + y.beta - 1) / y.beta);
+    a.y_bits = y.bits; a.y_scales = y.scales; a.ldw_y = (int32_t)y.ldw; a.lds_y = (int32_t)y.lds;
+    a.out = out; a.ld_out_x = ld_out_x; a.ld_out_y = ld_out_y;
+    a.X = (int32_t)x.rows; a.Y = (int32_t)y.rows; a.K = (int32_t)K;
+    const int64_t tiles_x = (x.rows + kBX - 1) / kBX, tiles_y = (y.rows + 127) / 128;
+    const int64_t total = tiles_x * tiles_y;
+    const int64_t per_xcd = (total + kNumXcdS - 1) / kNumXcdS;
+    if (per_xcd * kNumXcdS > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    a.tiles_y = (int32_t)tiles_y; a.tiles_total = (int32_t)total; a.slots_per_xcd = (int32_t)per_xcd;
+    mfma_split_gemm_kernel<kXAny, kYAny, 0><<<dim3((unsigned)(per_xcd * kNumXcdS)), dim3(kThreadsS), 0, s>>>(a);
+    return hipGetLastError();
 }
 
 // The staged-patch kernel when the layer fits it; false = use the gather kernel.

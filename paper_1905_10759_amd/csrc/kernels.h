@@ -17,6 +17,10 @@ hipError_t launch_pack_rows(const float *x, int64_t rows, int64_t K, int64_t ldx
 hipError_t launch_pack_cols(const float *x, int64_t rows, int64_t K, int64_t ldx, int beta,
                             uint32_t *bits, int64_t ldw, float *scales, int64_t lds, hipStream_t s);
 
+// Any beta in 2..256 and any K >= 1 (the last segment may be shorter); layout 0: x is rows x K, 1: K x rows.
+hipError_t launch_pack_any(const float *x, int64_t rows, int64_t K, int64_t ldx, int layout, int beta,
+                           uint32_t *bits, int64_t ldw, float *scales, int64_t lds, hipStream_t s);
+
 // ---- backward.hip -----------------------------------------------------------------------------
 hipError_t launch_binarize_backward(const float *x, const float *g, int64_t rows, int64_t K, int64_t ldx,
                                     int64_t ldg, int beta, float *gx, int64_t ldgx, hipStream_t s);
@@ -69,6 +73,11 @@ struct SplitGemmOperand {
 // K must be a multiple of 32.
 hipError_t launch_mfma_split_gemm(const SplitGemmOperand &x, const SplitGemmOperand &y, int64_t K, float *out,
                                   int64_t ld_out_x, int64_t ld_out_y, hipStream_t s);
+// The same product for any beta in 1..256 on either side (y: >= 2) and any 1 <= K < 2^24, including
+// segment lengths that are not powers of two and a shorter last segment: both sides are rebuilt as fp32
+// values element by element.
+hipError_t launch_mfma_split_any(const SplitGemmOperand &x, const SplitGemmOperand &y, int64_t K, float *out,
+                                 int64_t ld_out_x, int64_t ld_out_y, hipStream_t s);
 // Convolution layer on the same kernel: the dense side is an activation tensor B x C x H x W packed
 // flat with segments of `beta` along W (beta divides W), read through the KH x KW window of each
 // output position; the other side holds the filters packed as rows of C*KH*KW (beta >= 2).

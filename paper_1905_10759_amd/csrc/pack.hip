@@ -152,6 +152,36 @@ __global__ __launch_bounds__(256) void pack_cols_kernel(
         for (int w = K >> 5; w < words_valid; ++w) bits[r * ldw + w] = 0u;
 }
 
+// Any segment length in 2..256 and any K, either layout: element (r, k) is x[r * sr + k * sk].
+// One thread per output word (its 32 signs) and one per scale (a sequential double-precision sum of
+// the segment's |x|, divided by the segment's own length -- the last one may be shorter).  This is
+// the path for settings outside the paper's table (its segment lengths are powers of two dividing
+// K); it reads every element twice and is not tuned.
+__global__ __launch_bounds__(256) void pack_any_kernel(
+    const float *__restrict__ x, int64_t rows, int K, int64_t sr, int64_t sk, int beta, uint32_t *__restrict__ bits,
+    int64_t ldw, float *__restrict__ scales, int64_t lds, int words_valid, int nseg)
+{
+    const int per_row = words_valid + nseg;
+    const int64_t total = rows * per_row;
+    for (int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x; id < total; id += (int64_t)gridDim.x * 256) {
+        const int64_t r = id / per_row;
+        const int item = (int)(id - r * per_row);
+        const float *xr = x + r * sr;
+        if (item < words_valid) {
+            uint32_t w = 0;
+            const int k0 = item * 32, n = min(32, K - k0);   // n <= 0: a padding word
+            for (int b = 0; b < n; ++b) w |= (xr[(int64_t)(k0 + b) * sk] >= 0.f ? 1u : 0u) << b;
+            bits[r * ldw + item] = w;
+        } else {
+            const int j = item - words_valid;
+            const int k0 = j * beta, n = min(beta, K - k0);
+            double acc = 0.0;
+            for (int b = 0; b < n; ++b) acc += fabs((double)xr[(int64_t)(k0 + b) * sk]);
+            scales[r * lds + j] = (float)(acc / (double)n);
+        }
+    }
+}
+
 template <int BETA>
 hipError_t pack_rows_beta(const float *x, int64_t rows, int64_t K, int64_t ldx, uint32_t *bits,
                           int64_t ldw, float *scales, int64_t lds, hipStream_t s)
@@ -214,6 +244,18 @@ hipError_t launch_pack_cols(const float *x, int64_t rows, int64_t K, int64_t ldx
     case 256: return pack_cols_beta<256>(x, rows, K, ldx, bits, ldw, scales, lds, s);
     }
     return hipErrorInvalidValue;
+}
+
+hipError_t launch_pack_any(const float *x, int64_t rows, int64_t K, int64_t ldx, int layout, int beta,
+                           uint32_t *bits, int64_t ldw, float *scales, int64_t lds, hipStream_t s)
+{
+    const int wv = (int)packed_words(K), nseg = (int)((K + beta - 1) / beta);
+    const int64_t total = rows * (wv + nseg);
+    const int64_t blocks = (total + 255) / 256;
+    const unsigned grid = (unsigned)(blocks < 256 * 64 ? blocks : 256 * 64);
+    pack_any_kernel<<<dim3(grid), dim3(256), 0, s>>>(x, rows, (int)K, layout == 0 ? ldx : 1, layout == 0 ? 1 : ldx, beta,
+                                                     bits, ldw, scales, lds, wv, nseg);
+    return hipGetLastError();
 }
 
 }  // namespace hbmm

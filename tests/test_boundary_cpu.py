@@ -64,8 +64,10 @@ def test_validation_rejects_before_launch(lib):
     qp.argtypes = [p, i64, i64, i64, i32, i32, p, i64, p, i64, p]
     fake = 0x1000  # 16-byte aligned, never dereferenced: every call below fails validation first
     assert qp(None, 4, 64, 64, 0, 32, fake, 4, fake, 2, None) == -1          # null x
-    assert qp(fake, 4, 64, 64, 0, 48, fake, 4, fake, 2, None) == -2          # beta not supported
-    assert qp(fake, 4, 96, 96, 0, 64, fake, 4, fake, 2, None) == -2          # K not a multiple of beta
+    assert qp(fake, 4, 64, 64, 0, 512, fake, 4, fake, 2, None) == -2         # beta above 256
+    assert qp(fake, 4, 64, 64, 0, 1, fake, 4, fake, 64, None) == -2          # beta = 1: nothing to pack
+    assert qp(fake, 4, 96, 96, 0, 64, fake, 4, fake, 1, None) == -1          # lds < ceil(K / beta) (last segment shorter)
+    assert qp(fake, 4, 100, 100, 0, 7, fake, 4, fake, 14, None) == -1        # the same with a segment length of 7
     assert qp(fake, 4, 64, 32, 0, 32, fake, 4, fake, 2, None) == -1          # ldx < K
     assert qp(fake, 4, 64, 64, 0, 32, fake, 2, fake, 2, None) == -1          # ldw too small
     assert qp(fake, 4, 64, 64, 0, 32, fake, 6, fake, 2, None) == -1          # ldw not a multiple of 4
@@ -87,14 +89,18 @@ def test_validation_rejects_before_launch(lib):
 
     assert call(C=None) == -1
     assert call(ldc=4) == -1
-    assert call(ba=48) == -2                      # not a power of two
+    assert call(ba=48, algo=1) == -2              # not a power of two: the general kernel only (algo 0 or -1)
+    assert call(ba=300) == -2
+    assert call(ba=48, K=1 << 24, ldsa=1 << 20, ldsb=1 << 20, ldwa=1 << 20, ldwb=1 << 20) == -2   # general kernel: K < 2^24
+    assert call(ba=48, ldsa=1) == -1              # lds_a < ceil(K / beta_a)
     assert call(bw=512) == -2
     assert call(ba=1, a=None, bw=1, b=None, ldsa=64, ldsb=64) == -2   # two unquantised operands: a plain dense product
     assert call(ba=16, ldsa=4, algo=1) == -2      # the int8 comparison variant needs word-sized segments
-    assert call(K=48, ba=16, bw=16, ldsa=3, ldsb=3) == -2   # K must be a multiple of 32
+    assert call(K=48, ba=16, bw=16, ldsa=3, ldsb=3, algo=3) == -2   # K not a multiple of 32: general kernel only
     assert call(ba=16, ldsa=3) == -1              # lds_a < K / beta_a
     assert call(algo=5) == -2
-    assert call(K=96, ba=64, bw=32) == -2
+    assert call(K=96, ba=64, bw=32) == -1         # lds_b < ceil(K / beta_w)
+    assert call(K=96, ba=64, bw=32, ldsb=3, algo=2) == -2   # a shorter last segment: general kernel only
     assert call(a=None) == -1
     assert call(ba=1, a=fake, ldsa=64) == -1      # beta_a = 1 takes raw A through a_scales, a_bits must be NULL
     assert call(ba=1, a=None, ldsa=8) == -1       # lds_a is then the leading dimension of A (>= K)

@@ -400,6 +400,110 @@ def test_gemm_seeded_random_sweep(M, N, K, beta_a, beta_w, algo, kind_a, kind_b)
     assert_close_to_oracle(got.cpu().numpy(), ref, T, f"sweep {M}x{N}x{K} b=({beta_a},{beta_w}) algo {algo}")
 
 
+# ------------------------------------------------------------------------------ general beta and K
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("rows,K,beta", [(3, 19, 5), (7, 19, 3), (1, 1, 2), (33, 100, 7), (130, 1000, 48), (5, 257, 256),
+                                          (9, 96, 6), (40, 333, 32), (17, 64, 3), (2, 4100, 255), (65, 31, 16)])
+def test_pack_any_beta_and_ragged_k(rows, K, beta, layout):
+    """Segment lengths that are not powers of two, K that beta does not divide (the last segment is the
+    shorter remainder, averaged over its own length) and K that does not fill its last 32-bit word.
+    Double-precision sequential sums rounded once: the scales are the oracle's bit for bit."""
+    x = synth.normal(7000 + rows + K + beta, (rows, K))
+    x[0, :min(K, 4)] = [0.0, -0.0, 1e-38, -1e-38][:min(K, 4)]
+    src = dev(x) if layout == 0 else dev(np.ascontiguousarray(x.T))
+    nb = -(-K // beta)
+    scales = torch.full((rows, nb + 2), -7.0, dtype=torch.float32, device="cuda")
+    bits, _ = hbmm.quantize_pack(src, beta, layout, None, scales[:, :nb])
+    assert np.array_equal(words(bits), oracle.sign_pack(x))
+    got = scales.cpu().numpy()
+    assert np.array_equal(got[:, :nb], oracle.block_scales(x, beta))
+    assert (got[:, nb:] == -7.0).all()
+
+
+@pytest.mark.parametrize("M,N,K,beta_a,beta_w", [
+    (4, 3, 19, 3, 5), (4, 3, 19, 5, 3), (130, 260, 19, 3, 5), (200, 300, 1000, 7, 6), (257, 129, 96, 3, 16),
+    (64, 64, 1280, 5, 1), (70, 90, 333, 1, 7), (33, 40, 100, 32, 48), (129, 131, 4607, 255, 9), (50, 60, 31, 2, 4),
+    (1, 1, 1, 2, 2), (150, 140, 1056, 12, 12), (90, 200, 2000, 64, 100), (300, 10, 65, 1, 64), (10, 300, 70, 64, 1)])
+def test_gemm_any_beta_and_ragged_k(M, N, K, beta_a, beta_w):
+    """General segment lengths and K against the dense double-precision definition: operands packed by the
+    oracle, so this checks the product alone (the pack kernel has its own test above)."""
+    split_case(synth.normal(7100 + M + K, (M, K)), synth.normal(7101 + N + K, (N, K), std=0.05), beta_a, beta_w)
+
+
+def _random_any_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < n:
+        beta_a, beta_w = int(rng.integers(1, 257)), int(rng.integers(1, 257))
+        if rng.integers(0, 3) == 0:
+            beta_a = int(rng.integers(1, 17))
+        if rng.integers(0, 3) == 0:
+            beta_w = int(rng.integers(1, 17))
+        if beta_a == 1 and beta_w == 1:
+            continue
+        cases.append((int(rng.integers(1, 300)), int(rng.integers(1, 300)), int(rng.integers(1, 1500)), beta_a, beta_w,
+                      int(rng.integers(0, 3)), int(rng.integers(0, 3))))
+    return cases
+
+
+@pytest.mark.parametrize("M,N,K,beta_a,beta_w,kind_a,kind_b", _random_any_cases(40, 20260104))
+def test_gemm_any_beta_seeded_random_sweep(M, N, K, beta_a, beta_w, kind_a, kind_b):
+    """Any segment lengths in 1..256 and any K, packed on the GPU and multiplied there (algo -1), against the
+    dense double-precision definition."""
+    make = [synth.normal, synth.relu_normal, synth.uniform_pm1]
+    A, B = make[kind_a](7300 + M, (M, K)), make[kind_b](7400 + N, (N, K))
+    At, Bt = oracle.materialize(A, beta_a), oracle.materialize(B, beta_w)
+    ref, T = oracle.dense_f64_gemm(At, Bt), oracle.dense_f64_gemm(np.abs(At), np.abs(Bt))
+
+    def operand(x, beta):
+        if beta == 1:
+            return None, dev(x)
+        bits, scales = hbmm.quantize_pack(dev(x), beta)
+        assert np.array_equal(words(bits), oracle.sign_pack(x))
+        # tuned kernels: pairwise fp32 sums; general kernel: the oracle's own rounding
+        ref_s = oracle.block_scales(x, beta)
+        assert np.all(np.abs(scales.cpu().numpy() - ref_s) <= scale_tol(beta) * ref_s + 1e-30)
+        return bits, scales
+
+    (ab, as_), (bb, bs) = operand(A, beta_a), operand(B, beta_w)
+    got = hbmm.gemm(ab, as_, beta_a, bb, bs, beta_w, K, algo=-1)
+    assert_close_to_oracle(got.cpu().numpy(), ref, T, f"any-beta sweep {M}x{N}x{K} b=({beta_a},{beta_w})")
+
+
+def test_gemm_any_beta_end_to_end_and_strided():
+    """Pack on the GPU, multiply on the GPU; the unquantised operand with a leading dimension that is not
+    a multiple of 4 and an output with a padded leading dimension."""
+    M, N, K = 77, 130, 203
+    A, B = synth.relu_normal(7200, (M, K)), synth.normal(7201, (N, K), std=0.05)
+    At, Bt = oracle.materialize(A, 1), oracle.materialize(B, 7)
+    ref, T = oracle.dense_f64_gemm(At, Bt), oracle.dense_f64_gemm(np.abs(At), np.abs(Bt))
+    wide = torch.zeros((M, K + 3), dtype=torch.float32, device="cuda")
+    wide[:, :K] = dev(A)
+    bb, bs = hbmm.quantize_pack(dev(B), 7)
+    out = torch.full((M, N + 5), -3.0, dtype=torch.float32, device="cuda")
+    hbmm.gemm(None, wide[:, :K], 1, bb, bs, 7, K, out=out[:, :N])
+    got = out.cpu().numpy()
+    assert_close_to_oracle(got[:, :N], ref, T, "any-beta end to end")
+    assert (got[:, N:] == -3.0).all()
+    # and both sides packed on the GPU with different odd segment lengths
+    ab, as_ = hbmm.quantize_pack(dev(A), 11)
+    At = oracle.materialize(A, 11)
+    ref, T = oracle.dense_f64_gemm(At, Bt), oracle.dense_f64_gemm(np.abs(At), np.abs(Bt))
+    assert_close_to_oracle(hbmm.gemm(ab, as_, 11, bb, bs, 7, K).cpu().numpy(), ref, T, "any-beta (11, 7)")
+
+
+def test_gemm_any_beta_limits():
+    x = torch.zeros((4, 96), dtype=torch.float32, device="cuda")
+    bits, scales = hbmm.quantize_pack(x, 6)
+    for algo in (1, 2, 3):
+        with pytest.raises(hbmm.HbmmError) as ei:
+            hbmm.gemm(bits, scales, 6, bits, scales, 6, 96, algo=algo)
+        assert ei.value.code == hbmm.EUNSUPPORTED
+    with pytest.raises(hbmm.HbmmError) as ei:
+        hbmm.quantize_pack(x, 257)
+    assert ei.value.code == hbmm.EUNSUPPORTED
+
+
 def test_gemm_two_unquantised_operands_are_reported_unsupported():
     x = torch.zeros((4, 64), dtype=torch.float32, device="cuda")
     with pytest.raises(hbmm.HbmmError) as ei:
@@ -419,7 +523,7 @@ def test_gemm_empty_and_zero_k():
 def test_unsupported_is_reported_not_faked():
     x = torch.zeros((4, 96), dtype=torch.float32, device="cuda")
     with pytest.raises(hbmm.HbmmError) as ei:
-        hbmm.quantize_pack(x, 48)
+        hbmm.quantize_pack(x, 512)
     assert ei.value.code == hbmm.EUNSUPPORTED
 
 

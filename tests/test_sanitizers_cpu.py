@@ -80,7 +80,13 @@ cv = lib.hbmm_conv2d
 cv.argtypes = [p, p, i32, p, p, i64, i64, i32, i64, i64, i64, i64, i64, i32, i32, i32, i32, p, i32, p]
 for (ba, bw) in [(4, 32), (1, 4), (4, 4), (2, 8), (8, 16)]:
     assert cv(None if ba == 1 else fake, fake, ba, fake, fake, 12, 144, bw, 2, 32, 8, 8, 40, 3, 3, 1, 1, fake, 0, None) == 0
-assert lib.hbmm_stub_launches() - n0 == 14 + 16 + 5
+# the general kernels: other segment lengths, a shorter last segment, K that does not fill a word
+for (ba, bw, K) in [(3, 5, 19), (7, 1, 100), (1, 6, 96), (48, 64, 200), (32, 32, 40)]:
+    rc = g(None if ba == 1 else fake, fake, 8, 256, ba, None if bw == 1 else fake, fake, 8, 256, bw, 30, 20, K, fake, 20, -1, None)
+    assert rc == 0, (ba, bw, K, rc)
+assert qp(fake, 7, 100, 100, 0, 7, fake, 4, fake, 15, None) == 0
+assert qp(fake, 7, 19, 8, 1, 5, fake, 4, fake, 4, None) == 0
+assert lib.hbmm_stub_launches() - n0 == 14 + 16 + 5 + 5 + 2
 print("api under sanitizers: ok")
 """
 
