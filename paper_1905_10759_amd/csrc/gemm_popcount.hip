@@ -33,10 +33,10 @@
 namespace hbmm {
 namespace {
 
-constexpr int kTQ = 16;                // Q rows per wave
+constexpr int kTQMax = 16;             // Q rows per wave: 16, or fewer when that balances the grid (see the launcher)
 constexpr int kWaves = 4;
 constexpr int kThreads = 64 * kWaves;  // 256
-constexpr int kTileQ = kTQ * kWaves;   // 64 Q rows per workgroup
+constexpr int kSlotsQ = kTQMax * kWaves;   // Q scale slots per segment in LDS (wave w owns slots 16 w .. 16 w + 15)
 constexpr int kCK = 16;                // 32-bit words of K per chunk (512 bits)
 constexpr int kStep = 2;               // words per inner step (one 8-byte LDS read, one s_load_dwordx2)
 constexpr int kBitsStride = kCK + 2;   // LDS row stride in words: 2 * odd => conflict-free b64 reads
@@ -70,10 +70,16 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // 1 row per lane is slower again (the scalar loads of Q are then shared by too little arithmetic).
 // 1 (64 rows) is used for small problems, which then spread over twice as many workgroups; 4 (256
 // rows) for a K of at most two chunks on a large grid.  The fused form uses 2 and 1 the same way.
-template <int G, bool INTEGER, bool FUSED, int TP>
+//
+// TQ = Q rows per wave (a workgroup owns 4 TQ rows of Q).  16 unless the launcher finds that a smaller
+// tile spreads the work more evenly over the compute units.
+template <int G, bool INTEGER, bool FUSED, int TP, int TQ>
 __global__ __launch_bounds__(kThreads, TP == 2 ? (G >= 128 && !FUSED ? 4 : 3) : 2) void popcount_gemm_kernel(const PopcountGemmArgs a)
 {
+    static_assert(TQ == kTQMax || (TQ >= 12 && TQ <= 14), "wait_q() below is written out for 12, 13, 14 and 16 rows");
     constexpr int kTP = TP;
+    constexpr int kTQ = TQ;
+    constexpr int kTileQ = kTQ * kWaves;                        // Q rows per workgroup
     constexpr int kTileP = 64 * TP;                             // P rows per workgroup
     constexpr int kRowsPerWave = kTileP / kWaves;                // rows of P a wave binarises in the fused form
     constexpr int kWordsPerGran = G / 32;                       // 1, 2, 4, 8
@@ -89,7 +95,7 @@ __global__ __launch_bounds__(kThreads, TP == 2 ? (G >= 128 && !FUSED ? 4 : 3) : 
     __shared__ __attribute__((aligned(16))) uint32_t s_bits[2][kTileP * kBitsStride];
     constexpr int kScaleStrideP = kGranPerChunk + 1;   // odd => conflict-free b32 reads
     __shared__ __attribute__((aligned(16))) float s_ps[INTEGER ? 1 : 2][INTEGER ? 1 : kTileP * kScaleStrideP];
-    __shared__ __attribute__((aligned(16))) float s_qs[INTEGER ? 1 : 2][INTEGER ? 1 : kGranPerChunk * kTileQ];
+    __shared__ __attribute__((aligned(16))) float s_qs[INTEGER ? 1 : 2][INTEGER ? 1 : kGranPerChunk * kSlotsQ];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -111,7 +117,7 @@ __global__ __launch_bounds__(kThreads, TP == 2 ? (G >= 128 && !FUSED ? 4 : 3) : 
     // ---- staging registers for the next chunk
     constexpr int kBitPieces = kTileP * (kCK / 4) / kThreads;             // 2 x 16 bytes per thread
     constexpr int kPsPerThread = (kTileP * kGranPerChunk + kThreads - 1) / kThreads;   // <= 8
-    constexpr int kQsPerThread = (kTileQ * kGranPerChunk + kThreads - 1) / kThreads;  // <= 4
+    constexpr int kQsPerThread = (kSlotsQ * kGranPerChunk + kThreads - 1) / kThreads;  // <= 4
     uint4 st_bits[kBitPieces];
     float st_ps[INTEGER ? 1 : kPsPerThread];
     float st_qs[INTEGER ? 1 : kQsPerThread];
@@ -153,11 +159,12 @@ __global__ __launch_bounds__(kThreads, TP == 2 ? (G >= 128 && !FUSED ? 4 : 3) : 
 #pragma unroll
             for (int r = 0; r < kQsPerThread; ++r) {
                 const int id = tid + r * kThreads;
-                const int row = q0_wg + id / kGranPerChunk;
+                const int slot = id / kGranPerChunk;          // wave (slot / 16) and its row (slot % 16)
+                const int row = q0_wg + (slot >> 4) * kTQ + (slot & 15);
                 const int e = id % kGranPerChunk;
                 const int blk = chunk * nsq + e;
                 st_qs[r] = 0.f;
-                if (id < kTileQ * kGranPerChunk && e < nsq && row < a.Q && blk < nblk_q)
+                if (id < kSlotsQ * kGranPerChunk && (slot & 15) < kTQ && e < nsq && row < a.Q && blk < nblk_q)
                     st_qs[r] = a.q_scales[(int64_t)row * a.lds_q + blk];
             }
         }
@@ -188,8 +195,8 @@ __global__ __launch_bounds__(kThreads, TP == 2 ? (G >= 128 && !FUSED ? 4 : 3) : 
 #pragma unroll
             for (int r = 0; r < kQsPerThread; ++r) {
                 const int id = tid + r * kThreads;
-                if (id < kTileQ * kGranPerChunk)
-                    s_qs[buf][(id % kGranPerChunk) * kTileQ + id / kGranPerChunk] = st_qs[r];
+                if (id < kSlotsQ * kGranPerChunk)
+                    s_qs[buf][(id % kGranPerChunk) * kSlotsQ + id / kGranPerChunk] = st_qs[r];
             }
         }
     };
@@ -337,14 +344,14 @@ __global__ __launch_bounds__(kThreads, TP == 2 ? (G >= 128 && !FUSED ? 4 : 3) : 
         for (int i = 0; i < kTP; ++i)
             sp[i] = s_ps[buf][(lane + 64 * i) * kScaleStrideP + (g_local >> a.shift_p)];
         const float4 *sq4 =
-            reinterpret_cast<const float4 *>(&s_qs[buf][(g_local >> a.shift_q) * kTileQ + wave * kTQ]);
+            reinterpret_cast<const float4 *>(&s_qs[buf][(g_local >> a.shift_q) * kSlotsQ + wave * kTQMax]);
 #pragma unroll
-        for (int v = 0; v < kTQ / 4; ++v) {
+        for (int v = 0; v < (kTQ + 3) / 4; ++v) {
             const float4 t = sq4[v];
-            sq[4 * v + 0] = t.x;
-            sq[4 * v + 1] = t.y;
-            sq[4 * v + 2] = t.z;
-            sq[4 * v + 3] = t.w;
+            const float tv[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (4 * v + j < kTQ) sq[4 * v + j] = tv[j];
         }
     };
     // Epilogue of one segment: res += (hamming - G/2) * (-2 sP * sQ)  (-2 (hamming - G/2) = d).  The
@@ -376,11 +383,17 @@ __global__ __launch_bounds__(kThreads, TP == 2 ? (G >= 128 && !FUSED ? 4 : 3) : 
             asm volatile("s_load_dwordx2 %0, %1, %2" : "=s"(qw[q]) : "s"(base), "s"(qoff[q]));
     };
     auto wait_q = [&](u32x2 (&qw)[kTQ]) {
-        static_assert(kTQ == 16, "operand list below is written out for 16 rows");
-        asm volatile("s_waitcnt lgkmcnt(0)"
-                     : "+s"(qw[0]), "+s"(qw[1]), "+s"(qw[2]), "+s"(qw[3]), "+s"(qw[4]), "+s"(qw[5]), "+s"(qw[6]),
-                       "+s"(qw[7]), "+s"(qw[8]), "+s"(qw[9]), "+s"(qw[10]), "+s"(qw[11]), "+s"(qw[12]),
-                       "+s"(qw[13]), "+s"(qw[14]), "+s"(qw[15]));
+#define HBMM_QW12 "+s"(qw[0]), "+s"(qw[1]), "+s"(qw[2]), "+s"(qw[3]), "+s"(qw[4]), "+s"(qw[5]), "+s"(qw[6]), \
+                  "+s"(qw[7]), "+s"(qw[8]), "+s"(qw[9]), "+s"(qw[10]), "+s"(qw[11])
+        if constexpr (kTQ == 16)
+            asm volatile("s_waitcnt lgkmcnt(0)" : HBMM_QW12, "+s"(qw[12]), "+s"(qw[13]), "+s"(qw[14]), "+s"(qw[15]));
+        else if constexpr (kTQ == 14)
+            asm volatile("s_waitcnt lgkmcnt(0)" : HBMM_QW12, "+s"(qw[12]), "+s"(qw[13]));
+        else if constexpr (kTQ == 13)
+            asm volatile("s_waitcnt lgkmcnt(0)" : HBMM_QW12, "+s"(qw[12]));
+        else
+            asm volatile("s_waitcnt lgkmcnt(0)" : HBMM_QW12);
+#undef HBMM_QW12
     };
     auto load_p = [&](u32x2 (&pw)[kTP], int buf, int s) {
         const uint32_t *lbits = &s_bits[buf][lane * kBitsStride + s * kStep];
@@ -390,7 +403,7 @@ __global__ __launch_bounds__(kThreads, TP == 2 ? (G >= 128 && !FUSED ? 4 : 3) : 
     // One word of one half of the Q rows: 32 x (v_xor_b32 + v_bcnt_u32_b32).
     auto reduce_half = [&](const uint32_t (&pwv)[kTP], const uint32_t (&qwv)[kTQ], int half, bool first) {
 #pragma unroll
-        for (int q = half * (kTQ / 2); q < (half + 1) * (kTQ / 2); ++q)
+        for (int q = half ? kTQ / 2 : 0; q < (half ? kTQ : kTQ / 2); ++q)
 #pragma unroll
             for (int i = 0; i < kTP; ++i)
                 acc[i][q] = first ? bcnt_seed(pwv[i] ^ qwv[q], kSeed) : bcnt_acc(pwv[i] ^ qwv[q], acc[i][q]);
@@ -501,7 +514,7 @@ __global__ __launch_bounds__(kThreads, TP == 2 ? (G >= 128 && !FUSED ? 4 : 3) : 
 
     // ---- store.  When Q runs along the rows of the output (ld_out_q == 1: P is the M side), a lane's 16
     // results of one P row are contiguous: four 16-byte stores instead of sixteen 4-byte ones.
-    const bool row_vectors = a.ld_out_q == 1 && (a.ld_out_p & 3) == 0 && q0 + kTQ <= a.Q;
+    const bool row_vectors = kTQ % 4 == 0 && a.ld_out_q == 1 && (a.ld_out_p & 3) == 0 && q0 + kTQ <= a.Q;
 #pragma unroll
     for (int i = 0; i < kTP; ++i) {
         const int p = p0 + lane + 64 * i;
@@ -525,14 +538,14 @@ __global__ __launch_bounds__(kThreads, TP == 2 ? (G >= 128 && !FUSED ? 4 : 3) : 
     }
 }
 
-template <int G, bool INTEGER, bool FUSED = false, int TP = 4>
+template <int G, bool INTEGER, bool FUSED = false, int TP = 4, int TQ = kTQMax>
 hipError_t launch(const PopcountGemmArgs &a, hipStream_t s)
 {
     int64_t nblocks = (int64_t)a.tiles_p * a.tiles_q;
     if (nblocks <= 0) return hipSuccess;
     if (nblocks > 0x7fffff00LL) return hipErrorInvalidConfiguration;
     nblocks = popcount_map_blocks(a.tiles_p, a.tiles_q, a.sup_p);
-    popcount_gemm_kernel<G, INTEGER, FUSED, TP><<<dim3((unsigned)nblocks), dim3(kThreads), 0, s>>>(a);
+    popcount_gemm_kernel<G, INTEGER, FUSED, TP, TQ><<<dim3((unsigned)nblocks), dim3(kThreads), 0, s>>>(a);
     return hipGetLastError();
 }
 
@@ -541,6 +554,7 @@ hipError_t launch(const PopcountGemmArgs &a, hipStream_t s)
 hipError_t launch_popcount_gemm(const PopcountGemmArgs &args, int G, int integer, hipStream_t s)
 {
     PopcountGemmArgs a = args;
+    constexpr int kTileQ = kTQMax * kWaves;
     a.tiles_q = (a.Q + kTileQ - 1) / kTileQ;
     // 128 rows of P per workgroup (three workgroups share a compute unit), or 64 when that grid would
     // leave compute units without a workgroup (small problems are bound by the length of one
@@ -586,12 +600,46 @@ hipError_t launch_popcount_gemm(const PopcountGemmArgs &args, int G, int integer
         }
         return hipErrorInvalidValue;
     }
-    switch (G) {
-    case 32: return launch<32, false, false, 2>(a, s);
-    case 64: return launch<64, false, false, 2>(a, s);
-    case 128: return launch<128, false, false, 2>(a, s);
-    case 256: return launch<256, false, false, 2>(a, s);
+    // Rows of Q per wave.  All workgroups of a launch are about equally long and a compute unit works on
+    // its share of them side by side, so the launch lasts as long as the unit with the most workgroups:
+    // ceil(tiles / 256) workgroups of 4 tq rows.  12544 x 512 with 64-row tiles is 784 tiles -- 3.06 per
+    // unit, so the launch takes as long as 4 per unit would (measured: 16384 rows take the same 92 us as
+    // 12544, 12288 rows take 73) -- while 52-row tiles give 968, still 4 per unit, each 13/16 as long.
+    // A smaller tile is taken only for a modelled gain of 8 % or more: its fixed costs weigh more (so 15
+    // rows are never chosen).  Measured, 16 / 14 / 13 / 12 rows per wave: 12544 x 512 x 4608 at 128-bit
+    // segments 95 / 84 / 81 / 88 us, 50176 x 128 x 1152 at 64-bit segments 38 / 33 / 29 / 33 us,
+    // 9000 x 512 x 2048 at 256-bit segments 33 / 30 / 28 / 27 us; the model picks 13, 13 and 12.
+    int tq = kTQMax;
+    {
+        auto rounds = [&](int t) {
+            const int64_t tiles = (int64_t)a.tiles_p * ((a.Q + kWaves * t - 1) / (kWaves * t));
+            return (double)((tiles + 255) / 256) * t;
+        };
+        double best = rounds(kTQMax) * 0.92;
+        for (int t = 14; t >= 12; --t)
+            if (rounds(t) < best) {
+                best = rounds(t);
+                tq = t;
+            }
     }
+    if (tq != kTQMax) {
+        a.tiles_q = (a.Q + kWaves * tq - 1) / (kWaves * tq);
+        if ((int64_t)a.tiles_p * a.tiles_q <= 2 * kMapXcds * kMapSuperTiles) a.sup_p = 0;
+    }
+#define HBMM_POPCOUNT_TQ(GV)                                                  \
+    switch (tq) {                                                             \
+    case 12: return launch<GV, false, false, 2, 12>(a, s);                    \
+    case 13: return launch<GV, false, false, 2, 13>(a, s);                    \
+    case 14: return launch<GV, false, false, 2, 14>(a, s);                    \
+    default: return launch<GV, false, false, 2>(a, s);                        \
+    }
+    switch (G) {
+    case 32: HBMM_POPCOUNT_TQ(32)
+    case 64: HBMM_POPCOUNT_TQ(64)
+    case 128: HBMM_POPCOUNT_TQ(128)
+    case 256: HBMM_POPCOUNT_TQ(256)
+    }
+#undef HBMM_POPCOUNT_TQ
     return hipErrorInvalidValue;
 }
 

@@ -181,6 +181,15 @@ def test_gemm_equal_beta(beta, M, N, K):
     run_gemm_case(synth.normal(400 + M, (M, K)), synth.uniform_pm1(401 + N, (N, K)), beta, beta)
 
 
+@pytest.mark.parametrize("beta_a,beta_w", [(32, 32), (64, 128), (128, 128), (256, 64)])
+@pytest.mark.parametrize("M,N", [(1000, 2066), (1185, 2599), (1259, 2599), (520, 9001)])
+def test_gemm_grids_between_whole_rounds(beta_a, beta_w, M, N):
+    """Shapes whose 64-row tiling leaves the last round of workgroups nearly empty: the launcher then takes
+    fewer rows of the broadcast operand per wave (12, 13 or 14 instead of 16).  Odd sizes on both sides, so
+    every tile size meets a ragged edge."""
+    run_gemm_case(synth.normal(300 + M, (M, 512)), synth.normal(301 + N, (N, 512)), beta_a, beta_w)
+
+
 @pytest.mark.parametrize("beta_a,beta_w", [(32, 64), (64, 32), (32, 256), (256, 32), (128, 64), (64, 256)])
 def test_gemm_mixed_beta(beta_a, beta_w):
     run_gemm_case(synth.relu_normal(500, (150, 1280)), synth.normal(501, (270, 1280), std=0.04), beta_a, beta_w)
