@@ -198,6 +198,37 @@ int hbmm_conv2d(const uint32_t *a_bits, const float *a_scales, int32_t beta_a, c
                 float *out, int32_t algo, void *stream);
 
 /*
+ * The same layer with the filters prepared ahead of time -- they do not change between calls -- which is
+ * the fast form: hbmm_conv_prepare_filters turns the packed filters into the three bf16 pieces of every
+ * weight (delta_w * Sign(w), Eq. 1-2), laid out in the order the matrix cores consume them, and
+ * hbmm_conv2d_prepared multiplies them with the activations (Eq. 3-4) read through the window of each
+ * output position.  Both sides are fp32 values split exactly into three pieces; the six largest of the
+ * nine piece products are added in fp32 (what is dropped is below 2^-24 of a term).  The sum runs
+ * over (channel group of 32, tap, channel), a fixed order: results are the same from call to call.
+ *
+ *   hbmm_conv_filter_pieces_bytes   size of `pieces` for N filters of C x KH x KW (0 for an invalid shape):
+ *                                   6 bytes per weight, N rounded up to 32 and C to 32.
+ *   hbmm_conv_prepare_filters       w_bits / w_scales as for hbmm_conv2d, with any beta_w in 2 .. 256
+ *                                   (a shorter last segment included: lds_w >= hbmm_num_blocks(C*KH*KW, beta_w)),
+ *                                   or beta_w = 1: filters not binarised, w_bits NULL and w_scales the
+ *                                   fp32 N x (C*KH*KW) matrix with leading dimension lds_w.
+ *                                   pieces: out, device, 16-byte aligned, hbmm_conv_filter_pieces_bytes(...) bytes.
+ *                                   C*KH*KW < 2^24; KH, KW <= 32.
+ *   hbmm_conv2d_prepared            a_bits / a_scales / beta_a / out and the geometry as for hbmm_conv2d;
+ *                                   pieces from hbmm_conv_prepare_filters for the same N, C, KH, KW.
+ *                                   The layer must fit the kernel: OW <= 128 and
+ *                                   ((OW - 1) * stride + KW) * KH <= 512 (the input patch of one output
+ *                                   row in on-chip memory); otherwise HBMM_EUNSUPPORTED (use hbmm_conv2d).
+ *                                   No restriction on C*KH*KW being a multiple of 32 or of beta_w.
+ */
+int64_t hbmm_conv_filter_pieces_bytes(int64_t N, int64_t C, int32_t KH, int32_t KW);
+int hbmm_conv_prepare_filters(const uint32_t *w_bits, const float *w_scales, int64_t ldw_w, int64_t lds_w,
+                              int32_t beta_w, int64_t N, int64_t C, int32_t KH, int32_t KW, void *pieces, void *stream);
+int hbmm_conv2d_prepared(const uint32_t *a_bits, const float *a_scales, int32_t beta_a, const void *pieces, int64_t B,
+                         int64_t C, int64_t H, int64_t W, int64_t N, int32_t KH, int32_t KW, int32_t stride,
+                         int32_t pad, float *out, void *stream);
+
+/*
  * Fused form for the activation operand: the same C as
  *     hbmm_quantize_pack(A, layout 0, beta_a)  followed by  hbmm_gemm(..., algo 0)
  * (bit for bit: same scale arithmetic, same contraction, same epilogue order), but A is binarised

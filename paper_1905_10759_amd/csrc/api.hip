@@ -362,6 +362,67 @@ int hbmm_conv2d(const uint32_t *a_bits, const float *a_scales, int32_t beta_a, c
     return from_hip(hbmm::launch_mfma_split_conv(x, y, g, out, static_cast<hipStream_t>(stream)));
 }
 
+// Shape checks shared by the two entry points of the prepared-filter convolution.
+static int check_conv_filter_shape(int64_t N, int64_t C, int32_t KH, int32_t KW)
+{
+    if (N < 0 || C < 0 || KH < 1 || KW < 1 || N > kMaxDim || C > kMaxDim || KH > 32 || KW > 32) return HBMM_EINVAL;
+    if ((double)C * KH * KW > (double)kMaxAnyK) return HBMM_EUNSUPPORTED;   // k div beta is a 32-bit multiply-high
+    return HBMM_OK;
+}
+
+int64_t hbmm_conv_filter_pieces_bytes(int64_t N, int64_t C, int32_t KH, int32_t KW)
+{
+    if (check_conv_filter_shape(N, C, KH, KW) != HBMM_OK) return 0;
+    return hbmm::conv_filter_pieces_bytes(N, C, KH, KW);
+}
+
+int hbmm_conv_prepare_filters(const uint32_t *w_bits, const float *w_scales, int64_t ldw_w, int64_t lds_w,
+                              int32_t beta_w, int64_t N, int64_t C, int32_t KH, int32_t KW, void *pieces, void *stream)
+{
+    if (int rc = check_conv_filter_shape(N, C, KH, KW)) return rc;
+    if (beta_w < 1) return HBMM_EINVAL;
+    if (!any_beta(beta_w)) return HBMM_EUNSUPPORTED;
+    if (N == 0 || C == 0) return HBMM_OK;
+    const int64_t K = C * KH * KW;
+    if (!pieces || !aligned16(pieces)) return HBMM_EINVAL;
+    if (!w_scales || !aligned16(w_scales)) return HBMM_EINVAL;
+    if (beta_w == 1) {
+        if (w_bits != nullptr || lds_w < K) return HBMM_EINVAL;   // unquantised filters travel through w_scales
+    } else {
+        if (lds_w < (K + beta_w - 1) / beta_w) return HBMM_EINVAL;
+        if (int rc = check_packed(w_bits, N, K, ldw_w)) return rc;
+    }
+    return from_hip(hbmm::launch_conv_prepare_filters(w_bits, w_scales, ldw_w, lds_w, beta_w, N, C, KH, KW, pieces,
+                                                      static_cast<hipStream_t>(stream)));
+}
+
+int hbmm_conv2d_prepared(const uint32_t *a_bits, const float *a_scales, int32_t beta_a, const void *pieces, int64_t B,
+                         int64_t C, int64_t H, int64_t W, int64_t N, int32_t KH, int32_t KW, int32_t stride,
+                         int32_t pad, float *out, void *stream)
+{
+    if (B < 0 || H < 0 || W < 0 || stride < 1 || pad < 0 || B > kMaxDim || H > kMaxDim || W > kMaxDim) return HBMM_EINVAL;
+    if (int rc = check_conv_filter_shape(N, C, KH, KW)) return rc;
+    if (pad > 32 || stride > 32) return HBMM_EINVAL;
+    if (beta_a < 1) return HBMM_EINVAL;
+    if (!(beta_a == 1 || supported_pack_beta(beta_a))) return HBMM_EUNSUPPORTED;
+    if (H + 2 * pad < KH || W + 2 * pad < KW) return HBMM_EINVAL;
+    const int64_t OH = (H + 2 * pad - KH) / stride + 1, OW = (W + 2 * pad - KW) / stride + 1;
+    if ((double)B * (double)C * (double)H * (double)W > 2147483647.0) return HBMM_EUNSUPPORTED;
+    if ((double)B * (double)OH * (double)OW * (double)(N > 0 ? N : 1) > 9.0e18) return HBMM_EUNSUPPORTED;
+    if ((double)B * (double)OH * (double)OW > 2147483647.0) return HBMM_EUNSUPPORTED;
+    if (B == 0 || N == 0) return HBMM_OK;
+    if (C == 0 || H == 0 || W == 0) return HBMM_EINVAL;
+    if (W % beta_a != 0) return HBMM_EUNSUPPORTED;
+    hbmm::ConvGeometry g{B, C, H, W, KH, KW, stride, pad, 0};
+    if (!hbmm::conv_direct_fits(g)) return HBMM_EUNSUPPORTED;
+    if (!out || !aligned16(out)) return HBMM_EINVAL;
+    if (!pieces || !aligned16(pieces)) return HBMM_EINVAL;
+    if (!a_scales || !aligned16(a_scales)) return HBMM_EINVAL;
+    if (beta_a == 1 ? a_bits != nullptr : (!a_bits || !aligned16(a_bits))) return HBMM_EINVAL;
+    hbmm::ConvActivations x{a_bits, a_scales, beta_a};
+    return from_hip(hbmm::launch_conv_direct(x, pieces, N, g, out, static_cast<hipStream_t>(stream)));
+}
+
 int hbmm_gemm_int(const uint32_t *a_bits, int64_t ldw_a, const uint32_t *b_bits, int64_t ldw_b,
                   int64_t M, int64_t N, int64_t K, int32_t *D, int64_t ldd, void *stream)
 {

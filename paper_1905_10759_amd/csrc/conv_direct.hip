@@ -1,0 +1,456 @@
+// Convolution layer of a Hadamard-binarised network (HadaNets section 3.2: activations binarised along
+// the width with beta_a, filters along their flattened C*KH*KW with beta_w) on the matrix cores, with
+// filters prepared ahead of time and the activation fragments read straight from a patch in LDS.
+//
+//   out[b, n, oz, oy] = sum_{c, dz, dy} A~[b, c, oz*stride - pad + dz, oy*stride - pad + dy] * W~[n, c, dz, dy]
+//
+// with A~ = scale * sign of the activation (0 outside the input) and W~ = scale * sign of the filter
+// weight.  Both are fp32 numbers; each is split exactly into three bf16 pieces and the six largest of the
+// nine piece products are added on v_mfma_f32_32x32x16_bf16 (what is dropped is below 2^-24 of a term).
+// Because both sides are plain numbers here, the sum over k may run in any order, and the order chosen
+// is (channel group of 32, filter tap, channel inside the group).  One K stage is then one tap of one
+// channel group: 32 channels at a fixed offset (dz, dy) from every output position.
+//
+// Filters.  They do not change between calls, so their pieces are produced once by
+// conv_prepare_filters_kernel, in the order in which a wave consumes them: for a block of 32 filters, a
+// channel group, a tap, an MFMA step of 16 channels and a piece, 64 x 16 bytes = the B operand of one
+// MFMA (lane l: filter l mod 32, channels 8 (l div 32) .. + 7).  In the layer kernel a wave loads these
+// operands straight from memory into registers, one stage ahead, with 1 KB contiguous per instruction;
+// filters never pass through LDS and cost no arithmetic per workgroup.
+//
+// Activations.  A workgroup owns R whole output rows of one image (R * OW <= 128 positions) and a tile
+// of 64 or 128 filters.  For the current channel group it keeps the input patch those rows need --
+// ((R - 1) stride + KH) rows x ((OW - 1) stride + KW) columns, zero outside the image -- in LDS as
+// three planes of bf16 pieces, 32 channels contiguous per pixel (pixel stride 80 bytes: the 16-byte
+// fragment reads of neighbouring positions fall on distinct banks).  The A operand of position m,
+// tap (dz, dy), channels 8j .. 8j+7 is one 16-byte LDS read at
+//     pixel(m) + dz * PW + dy,   pixel(m) = (orow * stride) * PW + oy * stride,
+// so every activation is fetched, rebuilt and split once per workgroup and channel group and read KH*KW
+// times by the multiply itself: no operand tile is assembled, and the only barrier is the one per
+// channel group that hands over the next patch (fetched after the first tap of a group, written after
+// its last one -- into the other buffer when two fit, else between two barriers).
+#include "bf16_pieces.h"
+#include "kernels.h"
+
+namespace hbmm {
+namespace {
+
+constexpr int kGroup = 32;                  // channels per group = K elements per stage
+constexpr int kPixBytes = 80;               // 32 bf16 + 16 bytes of padding
+constexpr int kNumXcdD = 8;
+constexpr int kThreadsD = 512;
+constexpr int kPatchArea = 160 * 1024 - 512;   // LDS of a workgroup, all of it patch (and, after the multiply, output turn areas)
+constexpr int kOperandBytes = 1024;         // one MFMA B operand: 64 lanes x 16 bytes
+constexpr int kStageBytes = 2 * 3 * kOperandBytes;   // filters of one stage for one block of 32: 2 steps x 3 pieces
+
+// ------------------------------------------------------------------------------------------------
+// Filter preparation: one thread per (block of 32 filters, group, tap, step, lane) writes the three
+// pieces of its 8 values.  Filters past N and channels past C are written as zeros.
+struct PrepareArgs {
+    const uint32_t *w_bits;      // unused with beta = 1
+    const float *w_scales;       // beta = 1: the filters themselves, N x K
+    unsigned char *pieces;
+    int64_t ldw, lds;
+    int32_t N, C, KK;
+    int32_t groups;
+    uint32_t magic;              // ceil(2^32 / beta): k div beta = umulhi(k, magic) for k < 2^24
+    int32_t raw;                 // beta = 1
+    int64_t total;               // threads that have work
+};
+
+__global__ __launch_bounds__(256) void conv_prepare_filters_kernel(const PrepareArgs a)
+{
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= a.total) return;
+    const int lane = (int)(id & 63);
+    int64_t r = id >> 6;
+    const int ks = (int)(r & 1);
+    r >>= 1;
+    const int t = (int)(r % a.KK);
+    r /= a.KK;
+    const int g = (int)(r % a.groups);
+    const int cb = (int)(r / a.groups);
+    const int n = cb * 32 + (lane & 31);
+    const int c0 = g * kGroup + ks * 16 + (lane >> 5) * 8;
+    const int64_t nrow = n < a.N ? n : a.N - 1;
+    uint32_t h[8], m[8], l[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int c = c0 + i;
+        const bool live = n < a.N && c < a.C;
+        const uint32_t k = (uint32_t)(live ? c * a.KK + t : 0);
+        float v;
+        if (a.raw) {
+            v = a.w_scales[nrow * a.lds + k];
+        } else {
+            const float s = a.w_scales[nrow * a.lds + __umulhi(k, a.magic)];
+            const uint32_t word = a.w_bits[nrow * a.ldw + (k >> 5)];
+            v = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, s) ^ (~(word >> (k & 31)) << 31));
+        }
+        split3(live ? v : 0.f, h[i], m[i], l[i]);
+    }
+    u32x4 dh, dm, dl;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        dh[i] = pair16(h[2 * i], h[2 * i + 1]);
+        dm[i] = pair16(m[2 * i], m[2 * i + 1]);
+        dl[i] = pair16(l[2 * i], l[2 * i + 1]);
+    }
+    unsigned char *dst = a.pieces + ((((int64_t)cb * a.groups + g) * a.KK + t) * 2 + ks) * (3 * kOperandBytes) + lane * 16;
+    *reinterpret_cast<u32x4 *>(dst) = dh;
+    *reinterpret_cast<u32x4 *>(dst + kOperandBytes) = dm;
+    *reinterpret_cast<u32x4 *>(dst + 2 * kOperandBytes) = dl;
+}
+
+// ------------------------------------------------------------------------------------------------
+struct ConvDirectArgs {
+    const uint32_t *x_bits;
+    const float *x_scales;
+    const unsigned char *pieces;
+    float *out;
+    int32_t Y, yblocks;          // filters, and blocks of 32 of them in `pieces`
+    int32_t log2_beta_x;
+    int32_t C, H, W, HW, OH, OW, OHW, KW, KK, stride, pad;
+    int32_t R, tiles_per_image, tiles_y, tiles_total, slots_per_xcd;
+    int32_t PW, P;               // patch width and pixels
+    int32_t plane;               // bytes of one piece plane of the patch: P * 80
+    int32_t patch_bufs;          // 2: group g lives in buffer g & 1; 1: one buffer, refilled between two barriers
+    int32_t groups;              // ceil(C / 32)
+    uint32_t sign;               // 0x80000000; 0 when the tensor is unquantised (then x_scales holds the values)
+};
+
+// XI: (pixel, 8-channel octet) items a thread stages per channel group; XI * 512 >= 4 * P.
+// Eight waves on a tile of 128 positions; every wave owns 64 positions x 32 filters.
+// NTY = 2 (128 filters): 2 x 4 wave tiles, each wave takes both MFMA steps of a stage;
+// NTY = 1 (64 filters): 2 x 2 wave tiles, waves 0-3 take the first step of every stage and waves 4-7 the
+//      second; the two halves are added through LDS at the end.
+template <int XI, int NTY>
+__global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirectArgs a)
+{
+    constexpr int NT = 64 * NTY;
+    constexpr int TX = 2;
+    constexpr int WV = kThreadsD / 64;
+    constexpr int KS = NTY == 1 ? 1 : 2;     // MFMA steps a wave takes per stage
+    constexpr int kWavesY = NTY == 1 ? 2 : 4;   // waves side by side along the filters
+    __shared__ __attribute__((aligned(16))) unsigned char sPatch[kPatchArea];
+
+    const int slot_id = (blockIdx.x % kNumXcdD) * a.slots_per_xcd + blockIdx.x / kNumXcdD;
+    if (slot_id >= a.tiles_total) return;
+    const int tile_x = slot_id / a.tiles_y, y0 = (slot_id % a.tiles_y) * NT;
+    const int img = tile_x / a.tiles_per_image, oz0 = (tile_x % a.tiles_per_image) * a.R;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // wave -> (filter block, position half, MFMA step): the fastest index runs along the filters
+    const int wcol0 = (wave % kWavesY) * 32;
+    const int wrow0 = ((wave / kWavesY) & 1) * 64;
+    const int ks0 = NTY == 1 ? wave / (WV / 2) : 0;       // first MFMA step of a stage this wave takes
+    const int npos = a.R * a.OW;                            // positions of a full tile (<= 128)
+
+    // ---- role 1: patch staging.  Item i = tid + 512 j is (octet i div P, pixel i mod P).
+    uint32_t pe0[XI], pkeep[XI];
+    int pdst[XI];        // byte offset of the item inside a plane; -1: the item does not exist
+    int poct[XI];
+#pragma unroll
+    for (int j = 0; j < XI; ++j) {
+        const int item = tid + j * kThreadsD;
+        const int oct = item / a.P, pix = item - oct * a.P;
+        const int prow = pix / a.PW, pcol = pix - prow * a.PW;
+        const int z = oz0 * a.stride - a.pad + prow, y = pcol - a.pad;
+        const bool inside = oct < 4 && z >= 0 && z < a.H && y >= 0 && y < a.W;
+        poct[j] = min(oct, 3);
+        pdst[j] = oct < 4 ? pix * kPixBytes + oct * 16 : -1;
+        pkeep[j] = inside ? 0xffffffffu : 0u;
+        pe0[j] = inside ? (uint32_t)((img * a.C * a.H + z) * a.W + y) : 0u;
+    }
+    const char *xb_bytes = reinterpret_cast<const char *>(a.x_bits);
+    const char *xs_bytes = reinterpret_cast<const char *>(a.x_scales);
+    struct PatchRegs {
+        uint32_t w[XI][8];
+        float s[XI][8];
+    };
+    // channel c of item j: element pe0 + c * HW; a channel past C (last group only) or a pixel outside the
+    // image reads element 0 and is written as zero
+    auto fetch_patch = [&](PatchRegs &r, int g) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < XI; ++j)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int c = g * kGroup + poct[j] * 8 + i;
+                const uint32_t e = c < a.C ? (pe0[j] + (uint32_t)(c * a.HW)) & pkeep[j] : 0u;
+                // (byte pointers with 32-bit offsets: one address register per load instead of two)
+                r.w[j][i] = *reinterpret_cast<const uint32_t *>(xb_bytes + ((e >> 5) << 2));
+                r.s[j][i] = *reinterpret_cast<const float *>(xs_bytes + ((e >> a.log2_beta_x) << 2));
+            }
+    };
+    auto park_patch = [&](const PatchRegs &r, int g, unsigned char *buf) __attribute__((always_inline)) {
+        // (the element indices are recomputed rather than kept in registers since fetch_patch)
+        asm volatile("" : "+s"(g));
+#pragma unroll
+        for (int j = 0; j < XI; ++j) {
+            uint32_t h[8], m[8], l[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int c = g * kGroup + poct[j] * 8 + i;
+                const uint32_t keep = c < a.C ? pkeep[j] : 0u;
+                const uint32_t e = (pe0[j] + (uint32_t)(c * a.HW)) & keep;
+                const uint32_t minus = (~(r.w[j][i] >> (e & 31)) << 31) & a.sign;
+                const uint32_t value = (__builtin_bit_cast(uint32_t, r.s[j][i]) ^ minus) & keep;
+                split3(__builtin_bit_cast(float, value), h[i], m[i], l[i]);
+            }
+            if (pdst[j] >= 0) {
+                u32x4 dh, dm, dl;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    dh[i] = pair16(h[2 * i], h[2 * i + 1]);
+                    dm[i] = pair16(m[2 * i], m[2 * i + 1]);
+                    dl[i] = pair16(l[2 * i], l[2 * i + 1]);
+                }
+                unsigned char *dst = buf + pdst[j];
+                *reinterpret_cast<u32x4 *>(dst) = dh;
+                *reinterpret_cast<u32x4 *>(dst + a.plane) = dm;
+                *reinterpret_cast<u32x4 *>(dst + 2 * a.plane) = dl;
+            }
+        }
+    };
+
+    // ---- role 2: multiply.  Lane l feeds position row (l mod 32) and channels 8 (l div 32) .. + 7 of a step.
+    int xoff[TX];   // byte offset of the lane's position (window corner) and channel octet inside a plane
+#pragma unroll
+    for (int tx = 0; tx < TX; ++tx) {
+        const int ml = min(wrow0 + tx * 32 + (lane & 31), npos - 1);
+        const int orow = ml / a.OW, oy = ml - orow * a.OW;
+        xoff[tx] = ((orow * a.stride) * a.PW + oy * a.stride) * kPixBytes + (lane >> 5) * 16 + ks0 * 32;
+    }
+    // filter operands of this wave's block of 32 filters: stage s at s * kStageBytes (a block past the last
+    // one re-reads the last: its columns are never stored)
+    const unsigned char *ysrc = a.pieces + (int64_t)min((y0 + wcol0) >> 5, a.yblocks - 1) * a.groups * a.KK * kStageBytes +
+                                ks0 * (3 * kOperandBytes) + lane * 16;
+    const int nstages = a.groups * a.KK;
+    struct FilterRegs {
+        bf16x8 f[KS][3];
+    };
+    auto fetch_filter = [&](FilterRegs &r, int stage) __attribute__((always_inline)) {
+        const unsigned char *src = ysrc + (int64_t)min(stage, nstages - 1) * kStageBytes;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int p = 0; p < 3; ++p)
+                r.f[ks][p] = *reinterpret_cast<const bf16x8 *>(src + (ks * 3 + p) * kOperandBytes);
+    };
+
+    f32x16 res[TX];
+#pragma unroll
+    for (int tx = 0; tx < TX; ++tx)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) res[tx][v] = 0.f;
+
+    const int patch_stride = a.patch_bufs == 2 ? 3 * a.plane : 0;
+    PatchRegs xr;
+    FilterRegs ya, yb, yc;
+    fetch_patch(xr, 0);
+    fetch_filter(ya, 0);
+    fetch_filter(yb, 1);
+    park_patch(xr, 0, sPatch);
+    __syncthreads();
+
+    int g = 0, t = 0, dz = 0, dy = 0, stage = 0;
+    // One stage: request the filter operands of the stage after next into `next`, multiply with `cur`.
+    // (Two stages ahead: a stage of a 64-filter tile is only 12 MFMAs per wave, shorter than a trip to L2.)
+    auto run_stage = [&](const FilterRegs &cur, FilterRegs &next) __attribute__((always_inline)) {
+        const bool more = g + 1 < a.groups;
+        fetch_filter(next, stage + 2);
+        // (without this fence the scheduler sinks the loads below the multiplies to save registers, and the
+        // next stage then waits out their whole latency)
+        __builtin_amdgcn_sched_barrier(0);
+        const unsigned char *px = sPatch + (g & 1) * patch_stride + (dz * a.PW + dy) * kPixBytes;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            bf16x8 fx[3][TX];
+#pragma unroll
+            for (int p = 0; p < 3; ++p)
+#pragma unroll
+                for (int tx = 0; tx < TX; ++tx)
+                    fx[p][tx] = *reinterpret_cast<const bf16x8 *>(px + p * a.plane + xoff[tx] + ks * 32);
+#pragma unroll
+            for (int q = 0; q < 6; ++q)
+#pragma unroll
+                for (int tx = 0; tx < TX; ++tx)
+                    res[tx] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[kPiecePairs[q][0]][tx], cur.f[ks][kPiecePairs[q][1]],
+                                                                      res[tx], 0, 0, 0);
+        }
+        // the next group's activations: requested once the first tap's multiplies are queued, so that the
+        // loads are the youngest in flight and nothing before the last tap waits for them
+        if (t == 0 && more) fetch_patch(xr, g + 1);
+        ++stage;
+        if (++dy == a.KW) {
+            dy = 0;
+            ++dz;
+        }
+        if (++t == a.KK) {
+            if (more) {
+                if (a.patch_bufs == 1) __syncthreads();   // every wave has read the last tap of this group
+                park_patch(xr, g + 1, sPatch + ((g + 1) & 1) * patch_stride);
+                __syncthreads();
+            }
+            t = dz = dy = 0;
+            ++g;
+        }
+    };
+    while (stage < nstages) {
+        run_stage(ya, yc);
+        if (stage < nstages) run_stage(yb, ya);
+        if (stage < nstages) run_stage(yc, yb);
+    }
+
+    // ---- store: out is B x Y x OH x OW; each 32 x 32 accumulator tile is turned through LDS so that lanes
+    // run along positions.  (Every wave must have left the multiply loop before the patch area is reused.)
+    __syncthreads();
+    if (NTY == 1) {
+        // add the two halves of K: the second half of the waves hands its accumulators to the first
+        float *half = reinterpret_cast<float *>(sPatch) + WV * (32 * 33) + (wave % (WV / 2)) * (TX * 16 * 64);
+        if (wave >= WV / 2) {
+#pragma unroll
+            for (int tx = 0; tx < TX; ++tx)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) half[(tx * 16 + v) * 64 + lane] = res[tx][v];
+        }
+        __syncthreads();
+        if (wave >= WV / 2) return;
+#pragma unroll
+        for (int tx = 0; tx < TX; ++tx)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) res[tx][v] += half[(tx * 16 + v) * 64 + lane];
+    }
+    float *turn = reinterpret_cast<float *>(sPatch) + wave * (32 * 33);
+#pragma unroll
+    for (int tx = 0; tx < TX; ++tx) {
+        const int ml = wrow0 + tx * 32 + (lane & 31);
+        const int mc = min(ml, npos - 1);
+        const int orow = mc / a.OW, oy = mc - orow * a.OW;
+        const bool pos_ok = ml < npos && oz0 + orow < a.OH;
+        float *dst = a.out + ((int64_t)img * a.Y * a.OH + (oz0 + orow)) * a.OW + oy;
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            turn[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * 33 + (lane & 31)] = res[tx][v];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        // (all reads first: under the store's condition each would be waited for on its own)
+        float val[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) val[j] = turn[(lane & 31) * 33 + 2 * j + (lane >> 5)];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int col = y0 + wcol0 + 2 * j + (lane >> 5);
+            if (pos_ok && col < a.Y) dst[(int64_t)col * a.OHW] = val[j];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+}
+
+int ilog2d(int v)
+{
+    int s = 0;
+    while ((1 << s) < v) ++s;
+    return s;
+}
+
+// Rows of output per workgroup: as many as fill 128 positions, fewer if the patch would not fit the LDS or
+// would take more than 4 staging items per thread; 0 if not even one row fits.
+int rows_per_tile(const ConvGeometry &g, int64_t OH, int64_t OW)
+{
+    if (OW > 128) return 0;
+    const int PW = (int)(OW - 1) * g.stride + g.KW;
+    int R = (int)(128 / OW < OH ? 128 / OW : OH);
+    auto pixels = [&](int r) { return ((r - 1) * g.stride + g.KH) * PW; };
+    while (R >= 1 && (pixels(R) > kThreadsD || 3 * pixels(R) * kPixBytes > kPatchArea)) --R;
+    return R;
+}
+
+}  // namespace
+
+int64_t conv_filter_pieces_bytes(int64_t N, int64_t C, int KH, int KW)
+{
+    return ((N + 31) / 32) * ((C + kGroup - 1) / kGroup) * KH * KW * (int64_t)kStageBytes;
+}
+
+hipError_t launch_conv_prepare_filters(const uint32_t *w_bits, const float *w_scales, int64_t ldw, int64_t lds, int beta,
+                                       int64_t N, int64_t C, int KH, int KW, void *pieces, hipStream_t s)
+{
+    PrepareArgs a{};
+    a.w_bits = w_bits; a.w_scales = w_scales; a.pieces = static_cast<unsigned char *>(pieces);
+    a.ldw = ldw; a.lds = lds;
+    a.N = (int32_t)N; a.C = (int32_t)C; a.KK = KH * KW;
+    a.groups = (int32_t)((C + kGroup - 1) / kGroup);
+    a.raw = beta == 1 ? 1 : 0;
+    a.magic = beta == 1 ? 0u : (uint32_t)(((1ull << 32) + beta - 1) / beta);
+    a.total = ((N + 31) / 32) * a.groups * a.KK * 2 * 64;
+    const int64_t blocks = (a.total + 255) / 256;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    conv_prepare_filters_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(a);
+    return hipGetLastError();
+}
+
+bool conv_direct_fits(const ConvGeometry &g)
+{
+    const int64_t OH = (g.H + 2 * g.pad - g.KH) / g.stride + 1, OW = (g.W + 2 * g.pad - g.KW) / g.stride + 1;
+    return rows_per_tile(g, OH, OW) >= 1;
+}
+
+hipError_t launch_conv_direct(const ConvActivations &x, const void *pieces, int64_t N, const ConvGeometry &g, float *out,
+                              hipStream_t s)
+{
+    const int64_t OH = (g.H + 2 * g.pad - g.KH) / g.stride + 1, OW = (g.W + 2 * g.pad - g.KW) / g.stride + 1;
+    const int KK = g.KH * g.KW;
+    const int nty = N <= 64 ? 1 : 2;
+    const int PW = (int)(OW - 1) * g.stride + g.KW;
+    const int64_t tiles_y = (N + 64 * nty - 1) / (64 * nty);
+    int R = rows_per_tile(g, OH, OW);
+    if (R < 1) return hipErrorNotSupported;
+    const int tiles_per_image = (int)((OH + R - 1) / R);
+    R = (int)((OH + tiles_per_image - 1) / tiles_per_image);   // even rows per tile
+    const int threads = kThreadsD;
+    const int P = ((R - 1) * g.stride + g.KH) * PW;
+    const int bufs = 2 * 3 * P * kPixBytes <= kPatchArea ? 2 : 1;
+    const int64_t tiles_x = g.B * tiles_per_image;
+    const int64_t total = tiles_x * tiles_y, per_xcd = (total + kNumXcdD - 1) / kNumXcdD;
+    if (per_xcd * kNumXcdD > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    ConvDirectArgs a{};
+    // beta = 1: `scales` is the unquantised tensor.  It then plays both parts: read as the "scale" of
+    // element e (segment length 1) it is the value itself, sign included, and the sign taken from the
+    // bit word is switched off; the word loads still happen and are pointed at the same memory.
+    a.x_bits = x.beta == 1 ? reinterpret_cast<const uint32_t *>(x.scales) : x.bits;
+    a.x_scales = x.scales; a.log2_beta_x = ilog2d(x.beta); a.sign = x.beta == 1 ? 0u : 0x80000000u;
+    a.pieces = static_cast<const unsigned char *>(pieces);
+    a.out = out; a.Y = (int32_t)N; a.yblocks = (int32_t)((N + 31) / 32);
+    a.C = (int32_t)g.C; a.H = (int32_t)g.H; a.W = (int32_t)g.W; a.HW = (int32_t)(g.H * g.W);
+    a.OH = (int32_t)OH; a.OW = (int32_t)OW; a.OHW = (int32_t)(OH * OW);
+    a.KW = g.KW; a.KK = KK; a.stride = g.stride; a.pad = g.pad;
+    a.R = R; a.tiles_per_image = tiles_per_image; a.tiles_y = (int32_t)tiles_y; a.tiles_total = (int32_t)total;
+    a.slots_per_xcd = (int32_t)per_xcd;
+    a.PW = PW; a.P = P; a.plane = P * kPixBytes; a.patch_bufs = bufs;
+    a.groups = (int32_t)((g.C + kGroup - 1) / kGroup);
+    const int xi = (4 * P + threads - 1) / threads;
+    const dim3 grid((unsigned)(per_xcd * kNumXcdD)), block(threads);
+#define HBMM_DIRECT_LAUNCH(I)                                        \
+    do {                                                             \
+        if (nty == 1)                                                \
+            conv_direct_kernel<I, 1><<<grid, block, 0, s>>>(a);      \
+        else                                                         \
+            conv_direct_kernel<I, 2><<<grid, block, 0, s>>>(a);      \
+    } while (0)
+    if (xi <= 1)
+        HBMM_DIRECT_LAUNCH(1);
+    else if (xi == 2)
+        HBMM_DIRECT_LAUNCH(2);
+    else if (xi == 3)
+        HBMM_DIRECT_LAUNCH(3);
+    else
+        HBMM_DIRECT_LAUNCH(4);
+#undef HBMM_DIRECT_LAUNCH
+    return hipGetLastError();
+}
+
+}  // namespace hbmm

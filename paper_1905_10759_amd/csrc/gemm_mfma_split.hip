@@ -31,14 +31,11 @@
 // are outstanding) and run three stages ahead through three rotating register sets: a stage is
 // only ~16 KB per workgroup and HBM latency is several stages long.  Tiles that share X rows get
 // consecutive slots on one XCD so that the repeat reads of X come from that XCD's L2.
+#include "bf16_pieces.h"
 #include "kernels.h"
 
 namespace hbmm {
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBX = 128, kBY = 256;
 constexpr int kThreadsS = 512;
@@ -63,18 +60,6 @@ __device__ __forceinline__ void sign_masks(uint32_t inv, uint32_t (&m)[PAIRS])
 #pragma unroll
     for (int i = 0; i < PAIRS; ++i) m[i] = ((inv << (15 - 2 * i)) | (inv << (30 - 2 * i))) & 0x80008000u;
 }
-
-// Exact split of an fp32 value into three bf16 patterns (each returned in the HIGH half of a word).
-__device__ __forceinline__ void split3(float v, uint32_t &hi, uint32_t &mid, uint32_t &lo)
-{
-    hi = __builtin_bit_cast(uint32_t, v) & 0xffff0000u;
-    const float r1 = v - __builtin_bit_cast(float, hi);
-    mid = __builtin_bit_cast(uint32_t, r1) & 0xffff0000u;
-    const float r2 = r1 - __builtin_bit_cast(float, mid);
-    lo = __builtin_bit_cast(uint32_t, r2) & 0xffff0000u;
-}
-// Two high-half patterns -> one dword holding element a in the low half and element b in the high half.
-__device__ __forceinline__ uint32_t pair16(uint32_t a_hi, uint32_t b_hi) { return (a_hi >> 16) | b_hi; }
 
 // The three bf16 piece rows of 8 consecutive elements of a packed operand: `byte` holds their sign
 // bits (1 = +), `sc` the SPT scales that cover them (8 / SPT elements each).  Only the scales are
@@ -451,12 +436,11 @@ __global__ __launch_bounds__(kThreadsS) void mfma_split_gemm_kernel(const SplitA
                     for (int tx = 0; tx < TX; ++tx)
                         fxp[p][tx] = *reinterpret_cast<const bf16x8 *>(pxp + p * kPieceBytes + tx * 32 * kRowBytes + ks * 32);
                 }
-                constexpr int kPairs[6][2] = {{0, 2}, {2, 0}, {1, 1}, {0, 1}, {1, 0}, {0, 0}};
 #pragma unroll
                 for (int q = 0; q < 6; ++q)
 #pragma unroll
                     for (int tx = 0; tx < TX; ++tx)
-                        res[tx][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fxp[kPairs[q][0]][tx], fyp[kPairs[q][1]], res[tx][0], 0, 0, 0);
+                        res[tx][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fxp[kPiecePairs[q][0]][tx], fyp[kPiecePairs[q][1]], res[tx][0], 0, 0, 0);
             }
             park(ready, buf ^ 1);
             __syncthreads();

@@ -180,6 +180,44 @@ def test_validation_of_the_fused_tensor_and_convolution_entry_points(lib):
     assert conv(H=1, pad=0) == -1            # window larger than the padded input
     assert conv(B=0) == 0 and conv(N=0) == 0
 
+    # the prepared-filter form
+    nb = lib.hbmm_conv_filter_pieces_bytes
+    nb.restype, nb.argtypes = i64, [i64, i64, i32, i32]
+    assert nb(128, 128, 3, 3) == 128 * 128 * 9 * 6
+    assert nb(40, 20, 3, 3) == 64 * 32 * 9 * 6          # filters rounded up to 32, channels to 32
+    assert nb(8, 8, 0, 3) == 0 and nb(-1, 8, 3, 3) == 0 and nb(8, 8, 40, 3) == 0
+    pf = lib.hbmm_conv_prepare_filters
+    pf.argtypes = [p, p, i64, i64, i32, i64, i64, i32, i32, p, p]
+    assert pf(fake, fake, 12, 9, 32, 8, 32, 3, 3, None, None) == -1        # no output buffer
+    assert pf(fake, fake, 12, 8, 32, 8, 32, 3, 3, fake, None) == -1        # lds_w < ceil(K / beta_w)
+    assert pf(fake, fake, 12, 57, 5, 8, 32, 3, 3, fake, None) == -1        # beta_w = 5: 58 scales per filter
+    assert pf(fake, fake, 8, 9, 32, 8, 32, 3, 3, fake, None) == -1         # ldw_w too small
+    assert pf(fake, fake, 12, 288, 1, 8, 32, 3, 3, fake, None) == -1       # beta_w = 1 takes the filters through w_scales
+    assert pf(None, fake, 12, 100, 1, 8, 32, 3, 3, fake, None) == -1       # ... with a leading dimension >= K
+    assert pf(fake, fake, 12, 9, 300, 8, 32, 3, 3, fake, None) == -2       # beta_w above 256
+    assert pf(fake, fake, 12, 9, 32, 8, 1 << 22, 3, 3, fake, None) == -2   # C*KH*KW beyond 2^24
+    assert pf(None, None, 12, 9, 32, 0, 32, 3, 3, None, None) == 0
+    cp = lib.hbmm_conv2d_prepared
+    cp.argtypes = [p, p, i32, p, i64, i64, i64, i64, i64, i32, i32, i32, i32, p, p]
+    okp = dict(ab=fake, asc=fake, ba=4, pieces=fake, B=1, C=32, H=8, W=8, N=8, KH=3, KW=3, stride=1, pad=1, out=fake)
+
+    def convp(**kw):
+        a = {**okp, **kw}
+        return cp(a["ab"], a["asc"], a["ba"], a["pieces"], a["B"], a["C"], a["H"], a["W"], a["N"], a["KH"], a["KW"],
+                  a["stride"], a["pad"], a["out"], None)
+
+    assert convp(ba=16) == -2                # beta_a does not divide the width
+    assert convp(ba=3) == -2                 # beta_a not a power of two
+    assert convp(W=200, pad=1) == -2         # an output row of 200 positions does not fit a tile
+    assert convp(W=128, KH=5, KW=5, pad=2) == -2   # the patch of one output row: 132 x 5 pixels
+    assert convp(pieces=None) == -1
+    assert convp(out=None) == -1
+    assert convp(ab=None) == -1
+    assert convp(ba=1) == -1                 # unquantised activations travel through a_scales, a_bits must be NULL
+    assert convp(stride=0) == -1
+    assert convp(H=1, pad=0) == -1
+    assert convp(B=0) == 0 and convp(N=0) == 0
+
 
 def test_compiled_gemm_keeps_inflight_scalar_registers_untouched():
     """The popcount GEMM waits for its asm-issued scalar loads by hand; the compiled ISA must not touch

@@ -780,9 +780,8 @@ def test_conv2d(case, algo):
     out = hbmm.conv2d(ab, asc, beta_a, A.shape, wb, ws, beta_w, (KH, KW), stride, pad, algo=algo)
     assert tuple(out.shape) == ref.shape
     assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d {case} algo {algo}")
-    if algo == 0:
-        # both kernels add the same exact products in the same order
-        assert torch.equal(out, hbmm.conv2d(ab, asc, beta_a, A.shape, wb, ws, beta_w, (KH, KW), stride, pad, algo=1))
+    # no atomics, no order that depends on timing: a second call gives the same bits
+    assert torch.equal(out, hbmm.conv2d(ab, asc, beta_a, A.shape, wb, ws, beta_w, (KH, KW), stride, pad, algo=algo))
 
 
 def _random_conv_cases(n, seed):
@@ -815,6 +814,132 @@ def test_conv2d_seeded_random_sweep(case):
     out = hbmm.conv2d(ab, asc, beta_a, A.shape, wb, ws, beta_w, (KH, KW), stride, pad)
     assert tuple(out.shape) == ref.shape
     assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d sweep {case}")
+
+
+# ------------------------------------------------------------------ convolution with prepared filters
+def _decode_filter_pieces(pieces: np.ndarray, N, C, KH, KW) -> np.ndarray:
+    """The prepared form back to numbers: for each block of 32 filters, channel group of 32, tap, step of
+    16 channels and piece, 64 lanes x 8 bf16 (lane l: filter l mod 32, channels 8 (l div 32) .. + 7).
+    Returns hi + mid + lo as float64, shape (N rounded up to 32, C rounded up to 32, KH, KW)."""
+    nb, G, KK = -(-N // 32), -(-C // 32), KH * KW
+    raw = pieces.view(np.uint16).reshape(nb, G, KK, 2, 3, 64, 8)
+    val = (raw.astype(np.uint32) << 16).view(np.float32).astype(np.float64).sum(axis=4)   # nb, G, KK, ks, lane, 8
+    val = val.reshape(nb, G, KK, 2, 2, 32, 8)                    # lane = half * 32 + filter
+    out = val.transpose(0, 5, 1, 3, 4, 6, 2)                     # nb, filter, G, ks, half, i, tap
+    return out.reshape(nb * 32, G * 32, KH, KW)
+
+
+@pytest.mark.parametrize("N,C,KH,KW,beta_w", [(40, 32, 3, 3, 32), (130, 64, 1, 1, 64), (7, 20, 3, 3, 4), (33, 48, 2, 3, 7),
+                                              (64, 96, 3, 3, 1), (5, 3, 5, 5, 25), (96, 128, 3, 3, 128)])
+def test_conv_prepare_filters_is_exact(N, C, KH, KW, beta_w):
+    """The three pieces of every weight add up to delta_w * Sign(w) exactly (Eq. 1-2 on the flattened filter),
+    each piece is a bf16 number, and the padding (filters past N, channels past C) is zero."""
+    Wf = synth.normal(8100 + N + C, (N, C, KH, KW)).astype(np.float32)
+    K = C * KH * KW
+    if beta_w == 1:
+        pieces = hbmm.conv_prepare_filters(None, dev(Wf.reshape(N, K)), 1, C, (KH, KW))
+        want = Wf.astype(np.float64)
+    else:
+        # (words and scales from the oracle, so that the values are the oracle's bit for bit)
+        flat = Wf.reshape(N, K)
+        wb, ws = dev(oracle.sign_pack(flat).view(np.int32)), dev(oracle.block_scales(flat, beta_w))
+        pieces = hbmm.conv_prepare_filters(wb, ws, beta_w, C, (KH, KW))
+        want = oracle.materialize_filters(Wf, beta_w)
+    assert pieces.numel() == hbmm.conv_filter_pieces_bytes(N, C, KH, KW) == -(-N // 32) * 32 * -(-C // 32) * 32 * KH * KW * 6
+    got = _decode_filter_pieces(pieces.cpu().numpy(), N, C, KH, KW)
+    assert np.array_equal(got[:N, :C], want)
+    assert not got[N:].any() and not got[:, C:].any()
+
+
+PREPARED_CONV_CASES = CONV_CASES + [
+    # B, C, H, W, N, KH, KW, stride, pad, beta_a, beta_w
+    (2, 20, 8, 8, 40, 3, 3, 1, 1, 4, 5),        # channels not a multiple of 32, K = 180 not a multiple of 32, beta_w = 5
+    (1, 48, 8, 12, 70, 3, 3, 1, 1, 2, 7),       # one and a half channel groups; the last filter segment is shorter
+    (3, 64, 28, 28, 64, 3, 3, 1, 1, 4, 64),     # 4 output rows per tile, 7 tiles per image, two staging items per thread
+    (2, 32, 14, 14, 96, 3, 3, 1, 1, 2, 128),    # 9 rows per tile (126 positions), second tile of 5 rows
+    (1, 3, 16, 16, 16, 5, 5, 1, 2, 4, 25),      # a first-layer shape: 3 channels, 5 x 5 window
+    (2, 64, 56, 56, 64, 3, 3, 2, 1, 8, 64),     # stride 2: the patch of two output rows is 5 x 57 pixels
+    (1, 32, 8, 120, 8, 3, 3, 1, 1, 8, 32),      # one output row of 120 positions: 366 pixels, three staging items
+    (1, 160, 6, 8, 200, 1, 1, 1, 0, 4, 160),    # five channel groups, two filter tiles of 128 (the second ragged)
+]
+
+
+@pytest.mark.parametrize("case", PREPARED_CONV_CASES, ids=lambda c: "x".join(str(v) for v in c))
+def test_conv2d_prepared(case):
+    B, C, H, W, N, KH, KW, stride, pad, beta_a, beta_w = case
+    A, Wf = _conv_inputs(8200 + B + C + N, B, C, H, W, N, KH, KW)
+    A[0, 0, 0, :2] = [0.0, -0.0]
+    ab, asc = hbmm.quantize_pack_tensor(dev(A), beta_a)
+    wb, ws = hbmm.quantize_pack(dev(Wf.reshape(N, -1)), beta_w)
+    pieces = hbmm.conv_prepare_filters(wb, ws, beta_w, C, (KH, KW))
+    OW = (W + 2 * pad - KW) // stride + 1
+    if OW > 128 or ((OW - 1) * stride + KW) * KH > 512:
+        with pytest.raises(hbmm.HbmmError) as ei:
+            hbmm.conv2d_prepared(ab, asc, beta_a, A.shape, pieces, N, (KH, KW), stride, pad)
+        assert ei.value.code == hbmm.EUNSUPPORTED
+        return
+    ref, T = oracle.hbmm_conv2d(A, Wf, beta_a, beta_w, stride, pad, want_T=True)
+    out = hbmm.conv2d_prepared(ab, asc, beta_a, A.shape, pieces, N, (KH, KW), stride, pad)
+    assert tuple(out.shape) == ref.shape
+    assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d_prepared {case}")
+    # a fixed summation order: a second call gives the same bits
+    assert torch.equal(out, hbmm.conv2d_prepared(ab, asc, beta_a, A.shape, pieces, N, (KH, KW), stride, pad))
+
+
+@pytest.mark.parametrize("case", [(2, 32, 8, 8, 40, 3, 3, 1, 1, 32), (1, 64, 12, 12, 70, 1, 1, 1, 0, 64),
+                                  (2, 32, 9, 16, 24, 3, 3, 2, 1, 4), (1, 64, 12, 12, 140, 3, 3, 1, 1, 8),
+                                  (2, 24, 10, 10, 30, 3, 3, 1, 1, 1)], ids=str)
+def test_conv2d_prepared_unquantised_operands(case):
+    """beta_a = 1: activations stay fp32 (the paper's binary-weight layers, Tables 2-3); the last case also
+    leaves the filters unquantised (beta_w = 1), i.e. a plain fp32 convolution through the same kernel."""
+    B, C, H, W, N, KH, KW, stride, pad, beta_w = case
+    A = synth.normal(8300 + C + N, (B, C, H, W))
+    A[0, 0, 0, :3] = [0.0, -0.0, 1e-30]
+    Wf = synth.normal(8301 + C, (N, C, KH, KW)).astype(np.float32)
+    ref, T = oracle.hbmm_conv2d(A, Wf, 1, beta_w, stride, pad, want_T=True)
+    if beta_w == 1:
+        pieces = hbmm.conv_prepare_filters(None, dev(Wf.reshape(N, -1)), 1, C, (KH, KW))
+    else:
+        wb, ws = hbmm.quantize_pack(dev(Wf.reshape(N, -1)), beta_w)
+        pieces = hbmm.conv_prepare_filters(wb, ws, beta_w, C, (KH, KW))
+    out = hbmm.conv2d_prepared(None, dev(A), 1, A.shape, pieces, N, (KH, KW), stride, pad)
+    assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d_prepared unquantised {case}")
+
+
+def _random_prepared_conv_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < n:
+        C = int(rng.integers(1, 100))
+        KH, KW = (int(v) for v in rng.integers(1, 4, size=2))
+        beta_w = int(rng.integers(1, 65))
+        beta_a = int(rng.choice([1, 2, 4, 8]))
+        W = max(beta_a, 4) * int(rng.integers(1, 9))
+        H = int(rng.integers(3, 20))
+        stride, pad = int(rng.integers(1, 3)), int(rng.integers(0, 3))
+        B = int(rng.integers(1, 4))
+        if H + 2 * pad < KH or W + 2 * pad < KW or (beta_a != 1 and (B * C * H * W) % 128):
+            continue
+        cases.append((B, C, H, W, int(rng.integers(1, 150)), KH, KW, stride, pad, beta_a, beta_w))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_prepared_conv_cases(32, 20260105), ids=lambda c: "x".join(str(v) for v in c))
+def test_conv2d_prepared_seeded_random_sweep(case):
+    """Layer geometries, channel counts and segment lengths (any beta_w in 1..64, beta_a in {1, 2, 4, 8})
+    drawn from a fixed seed."""
+    B, C, H, W, N, KH, KW, stride, pad, beta_a, beta_w = case
+    A, Wf = _conv_inputs(8400 + H + W + N, B, C, H, W, N, KH, KW)
+    ref, T = oracle.hbmm_conv2d(A, Wf, beta_a, beta_w, stride, pad, want_T=True)
+    ab, asc = (None, dev(A)) if beta_a == 1 else hbmm.quantize_pack_tensor(dev(A), beta_a)
+    if beta_w == 1:
+        pieces = hbmm.conv_prepare_filters(None, dev(Wf.reshape(N, -1)), 1, C, (KH, KW))
+    else:
+        wb, ws = hbmm.quantize_pack(dev(Wf.reshape(N, -1)), beta_w)
+        pieces = hbmm.conv_prepare_filters(wb, ws, beta_w, C, (KH, KW))
+    out = hbmm.conv2d_prepared(ab, asc, beta_a, A.shape, pieces, N, (KH, KW), stride, pad)
+    assert tuple(out.shape) == ref.shape
+    assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d_prepared sweep {case}")
 
 
 def test_conv2d_equals_gemm_on_im2col():
