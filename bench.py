@@ -595,11 +595,33 @@ def extras(w, A, B, a_bits, a_s, b_bits, b_s, C, torch, hbmm, synth, args):
                                        "piece_products": pieces,
                                        "achieved": pieces * 2.0 * cw.macs / (tc * 1e-3) / 1e12, "peak": BF16_PEAK_TFLOPS,
                                        "unit": "TFLOP/s", "frac": pieces * 2.0 * cw.macs / (tc * 1e-3) / 1e12 / BF16_PEAK_TFLOPS}})
+            # the same layer with the filters prepared ahead of time (once per set of weights, outside the timed
+            # region like the packing of the filters itself); six piece products per element pair
+            try:
+                prepared = hbmm.conv_prepare_filters(wb, ws, cw.beta_w, cw.C, (cw.KH, cw.KW))
+                tprep = back_to_back_ms([lambda: hbmm.conv_prepare_filters(wb, ws, cw.beta_w, cw.C, (cw.KH, cw.KW), prepared)], 20, torch)
+                hbmm.conv2d_prepared(ab, asc, cw.beta_a, dA.shape, prepared, cw.N, (cw.KH, cw.KW), cw.stride, cw.pad, out)
+                tp = back_to_back_ms([lambda: hbmm.conv2d_prepared(ab, asc, cw.beta_a, dA.shape, prepared, cw.N, (cw.KH, cw.KW),
+                                                                   cw.stride, cw.pad, out)], 20, torch)
+                entry.update({"conv_prepared_ms": tp, "prepare_filters_ms": tprep,
+                              "roofline_prepared": {"bound": "mfma", "kernel": "conv_direct_kernel", "piece_products": 6,
+                                                    "achieved": 6 * 2.0 * cw.macs / (tp * 1e-3) / 1e12, "peak": BF16_PEAK_TFLOPS,
+                                                    "unit": "TFLOP/s", "frac": 6 * 2.0 * cw.macs / (tp * 1e-3) / 1e12 / BF16_PEAK_TFLOPS}})
+                del prepared
+            except Exception as e:
+                entry["conv_prepared_error"] = str(e)
             convs[name] = entry
             del dA, dW, out
         except Exception as e:
             convs[name] = {"error": str(e)}
     res["conv2d"] = convs
+    # what the matrix cores sustain on this device with nothing else in the loop (pseudo-random register operands,
+    # one workgroup of eight waves per compute unit): the ceiling that the fractions of the bf16 peak above can reach
+    try:
+        hbmm.probe_mfma_rate(500, 256)
+        res["mfma_bf16_sustained_TFLOPs"] = min(hbmm.probe_mfma_rate(4000, 256) for _ in range(3))
+    except Exception as e:
+        res["mfma_bf16_sustained_TFLOPs"] = {"error": str(e)}
     try:
         M, K, N, beta = 3136 * 64, 576, 64, 64
         dA = torch.from_numpy(synth.relu_normal(8001, (M, K))).cuda()

@@ -262,6 +262,16 @@ int hbmm_gemm_int(const uint32_t *a_bits, int64_t ldw_a, const uint32_t *b_bits,
 int hbmm_dense_ref_gemm(const void *A, int64_t lda, const void *B, int64_t ldb, int32_t dtype,
                         int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, void *stream);
 
+/*
+ * Diagnostic, not part of the method: runs `blocks` workgroups of eight waves, each wave steps * 24
+ * matrix-core instructions of the kind the fp32-as-three-bf16-pieces kernels use (32 x 32 x 16, bf16, 32768
+ * flops each) on pseudo-random register operands with nothing else in the loop, so that a caller who times
+ * the call learns the rate the machine sustains under that load (with every compute unit busy the clock,
+ * and so the rate, is below the published peak).  sink: device, blocks * 512 floats, written with values of
+ * no meaning.  steps <= 2^24, blocks <= 65536.
+ */
+int hbmm_probe_mfma_rate(int32_t steps, int32_t blocks, float *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

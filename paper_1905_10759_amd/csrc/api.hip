@@ -423,6 +423,14 @@ int hbmm_conv2d_prepared(const uint32_t *a_bits, const float *a_scales, int32_t 
     return from_hip(hbmm::launch_conv_direct(x, pieces, N, g, out, static_cast<hipStream_t>(stream)));
 }
 
+int hbmm_probe_mfma_rate(int32_t steps, int32_t blocks, float *sink, void *stream)
+{
+    if (steps < 0 || blocks < 0 || steps > (1 << 24) || blocks > (1 << 16)) return HBMM_EINVAL;
+    if (steps == 0 || blocks == 0) return HBMM_OK;
+    if (!sink || !aligned16(sink)) return HBMM_EINVAL;
+    return from_hip(hbmm::launch_probe_mfma(steps, blocks, sink, static_cast<hipStream_t>(stream)));
+}
+
 int hbmm_gemm_int(const uint32_t *a_bits, int64_t ldw_a, const uint32_t *b_bits, int64_t ldw_b,
                   int64_t M, int64_t N, int64_t K, int32_t *D, int64_t ldd, void *stream)
 {

@@ -130,6 +130,10 @@ hipError_t launch_mfma_fp8_gemm(const uint32_t *a_bits, const float *a_scales, i
                                 const float *b_scales, int64_t ldw_b, int64_t lds_b, int beta_w,
                                 int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, hipStream_t s);
 
+// ---- probe.hip ---------------------------------------------------------------------------------
+// `blocks` workgroups of eight waves, each wave steps * 24 MFMAs (32 x 32 x 16, bf16); sink: blocks * 512 floats.
+hipError_t launch_probe_mfma(int steps, int blocks, float *sink, hipStream_t s);
+
 // ---- dense_ref.hip ----------------------------------------------------------------------------
 hipError_t launch_dense_ref(const void *A, int64_t lda, const void *B, int64_t ldb, int dtype,
                             int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, hipStream_t s);

@@ -22,7 +22,7 @@ EXPORTS = (
     "hbmm_strerror", "hbmm_num_blocks", "hbmm_packed_ld_words", "hbmm_quantize_pack", "hbmm_gemm",
     "hbmm_gemm_int", "hbmm_dense_ref_gemm", "hbmm_binarize_backward", "hbmm_gemm_fused",
     "hbmm_quantize_pack_tensor", "hbmm_conv2d", "hbmm_binarize_backward_tensor",
-    "hbmm_conv_filter_pieces_bytes", "hbmm_conv_prepare_filters", "hbmm_conv2d_prepared",
+    "hbmm_conv_filter_pieces_bytes", "hbmm_conv_prepare_filters", "hbmm_conv2d_prepared", "hbmm_probe_mfma_rate",
 )
 
 
@@ -65,6 +65,8 @@ def _load() -> C.CDLL:
     lib.hbmm_conv_prepare_filters.argtypes = [p, p, i64, i64, i32, i64, i64, i32, i32, p, p]
     lib.hbmm_conv2d_prepared.restype = C.c_int
     lib.hbmm_conv2d_prepared.argtypes = [p, p, i32, p, i64, i64, i64, i64, i64, i32, i32, i32, i32, p, p]
+    lib.hbmm_probe_mfma_rate.restype = C.c_int
+    lib.hbmm_probe_mfma_rate.argtypes = [i32, i32, p, p]
     lib.hbmm_binarize_backward.restype = C.c_int
     lib.hbmm_binarize_backward.argtypes = [p, p, i64, i64, i64, i64, i32, p, i64, p]
     lib.hbmm_dense_ref_gemm.restype = C.c_int
@@ -371,6 +373,20 @@ def conv2d_prepared(a_bits, a_scales, beta_a: int, shape, pieces: torch.Tensor, 
                                   pieces.data_ptr(), B, Cc, H, W, N, KH, KW, stride, pad, out.data_ptr(), _stream())
     _check(rc, "hbmm_conv2d_prepared")
     return out
+
+
+def probe_mfma_rate(steps: int = 2000, blocks: int = 256) -> float:
+    """hbmm_probe_mfma_rate, timed: the bf16 matrix-core rate (TFLOP/s) this device sustains on random register
+    operands with `blocks` workgroups of eight waves (256 = one per compute unit).  A diagnostic."""
+    sink = torch.empty((blocks * 512,), dtype=torch.float32, device="cuda")
+    _check(lib.hbmm_probe_mfma_rate(steps, blocks, sink.data_ptr(), _stream()), "hbmm_probe_mfma_rate")
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    _check(lib.hbmm_probe_mfma_rate(steps, blocks, sink.data_ptr(), _stream()), "hbmm_probe_mfma_rate")
+    e1.record()
+    torch.cuda.synchronize()
+    return steps * 24.0 * 8 * blocks * 32768.0 / (e0.elapsed_time(e1) * 1e-3) / 1e12
 
 
 def binarize_backward_tensor(x: torch.Tensor, grad_out: torch.Tensor, beta: int) -> torch.Tensor:

@@ -28,5 +28,6 @@ hipError_t launch_conv_direct(const ConvActivations &, const void *, int64_t, co
 hipError_t launch_mfma_i8_gemm(const uint32_t *, const float *, int64_t, int64_t, int, const uint32_t *, const float *, int64_t, int64_t, int, int64_t, int64_t, int64_t, float *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_mfma_fp4_gemm(const uint32_t *, const float *, int64_t, int64_t, int, const uint32_t *, const float *, int64_t, int64_t, int, int64_t, int64_t, int64_t, float *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_mfma_fp8_gemm(const uint32_t *, const float *, int64_t, int64_t, int, const uint32_t *, const float *, int64_t, int64_t, int, int64_t, int64_t, int64_t, float *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_probe_mfma(int, int, float *, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_dense_ref(const void *, int64_t, const void *, int64_t, int, int64_t, int64_t, int64_t, float *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
 }  // namespace hbmm
