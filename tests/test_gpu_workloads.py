@@ -130,3 +130,9 @@ def test_conv_workload(hbmm, name, batch):
     ref, T = oracle.hbmm_conv2d(A, Wf, w.beta_a, w.beta_w, w.stride, w.pad, want_T=True)
     worst = assert_close_to_oracle(got, ref, T, name)
     print(f"[{name}] ok, worst err/(1e-5 T) = {worst:.3f}, worst plain relative error = {plain_relative_error(got, ref):.2e}", flush=True)
+    # the same layer with the filters prepared ahead of time
+    prepared = hbmm.conv_prepare_filters(wb, ws, w.beta_w, w.C, (w.KH, w.KW))
+    got_p = hbmm.conv2d_prepared(ab, asc, w.beta_a, A.shape, prepared, w.N, (w.KH, w.KW), w.stride, w.pad).cpu().numpy()
+    worst_p = assert_close_to_oracle(got_p, ref, T, name + " (prepared filters)")
+    print(f"[{name}] prepared filters ok, worst err/(1e-5 T) = {worst_p:.3f}, worst plain relative error = "
+          f"{plain_relative_error(got_p, ref):.2e}", flush=True)
