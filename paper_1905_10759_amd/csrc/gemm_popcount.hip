@@ -76,7 +76,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 template <int G, bool INTEGER, bool FUSED, int TP, int TQ>
 __global__ __launch_bounds__(kThreads, TP == 2 ? (G >= 128 && !FUSED ? 4 : 3) : 2) void popcount_gemm_kernel(const PopcountGemmArgs a)
 {
-    static_assert(TQ == kTQMax || (TQ >= 12 && TQ <= 14), "wait_q() below is written out for 12, 13, 14 and 16 rows");
+    static_assert(TQ == 1 || TQ == 2 || TQ == 4 || (TQ >= 12 && TQ <= 14) || TQ == kTQMax,
+                  "wait_q() below is written out for 1, 2, 4, 12, 13, 14 and 16 rows");
     constexpr int kTP = TP;
     constexpr int kTQ = TQ;
     constexpr int kTileQ = kTQ * kWaves;                        // Q rows per workgroup
@@ -383,17 +384,26 @@ __global__ __launch_bounds__(kThreads, TP == 2 ? (G >= 128 && !FUSED ? 4 : 3) : 
             asm volatile("s_load_dwordx2 %0, %1, %2" : "=s"(qw[q]) : "s"(base), "s"(qoff[q]));
     };
     auto wait_q = [&](u32x2 (&qw)[kTQ]) {
-#define HBMM_QW12 "+s"(qw[0]), "+s"(qw[1]), "+s"(qw[2]), "+s"(qw[3]), "+s"(qw[4]), "+s"(qw[5]), "+s"(qw[6]), \
-                  "+s"(qw[7]), "+s"(qw[8]), "+s"(qw[9]), "+s"(qw[10]), "+s"(qw[11])
+#define HBMM_QW2 "+s"(qw[0]), "+s"(qw[1])
+#define HBMM_QW4 HBMM_QW2, "+s"(qw[2]), "+s"(qw[3])
+#define HBMM_QW12 HBMM_QW4, "+s"(qw[4]), "+s"(qw[5]), "+s"(qw[6]), "+s"(qw[7]), "+s"(qw[8]), "+s"(qw[9]), "+s"(qw[10]), "+s"(qw[11])
         if constexpr (kTQ == 16)
             asm volatile("s_waitcnt lgkmcnt(0)" : HBMM_QW12, "+s"(qw[12]), "+s"(qw[13]), "+s"(qw[14]), "+s"(qw[15]));
         else if constexpr (kTQ == 14)
             asm volatile("s_waitcnt lgkmcnt(0)" : HBMM_QW12, "+s"(qw[12]), "+s"(qw[13]));
         else if constexpr (kTQ == 13)
             asm volatile("s_waitcnt lgkmcnt(0)" : HBMM_QW12, "+s"(qw[12]));
-        else
+        else if constexpr (kTQ == 12)
             asm volatile("s_waitcnt lgkmcnt(0)" : HBMM_QW12);
+        else if constexpr (kTQ == 4)
+            asm volatile("s_waitcnt lgkmcnt(0)" : HBMM_QW4);
+        else if constexpr (kTQ == 2)
+            asm volatile("s_waitcnt lgkmcnt(0)" : HBMM_QW2);
+        else
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(qw[0]));
 #undef HBMM_QW12
+#undef HBMM_QW4
+#undef HBMM_QW2
     };
     auto load_p = [&](u32x2 (&pw)[kTP], int buf, int s) {
         const uint32_t *lbits = &s_bits[buf][lane * kBitsStride + s * kStep];
@@ -584,12 +594,32 @@ hipError_t launch_popcount_gemm(const PopcountGemmArgs &args, int G, int integer
         return hipErrorInvalidValue;
     }
     if (narrow) {
+        // A grid this small is bound by the length of one workgroup's work, not by throughput: take the
+        // fewest rows of Q per wave (1, 2, 4 or 16) that still give every workgroup a compute unit of its
+        // own.  Kernel durations, 16 rows -> chosen: 64 x 64 x 512 at 32-bit segments 7.5 -> 4.8 us (1 row,
+        // 16 workgroups); 3136 x 64 x 576 at 64 bits 8.4 -> 5.5 us (4 rows, 196 workgroups); 70 x 50 x 992
+        // 15.1 -> 6.2 us; 1000 x 100 x 2048 at 256 bits 12.6 -> 6.0 us.  What remains is launch and latency.
+        int tqn = kTQMax;
+        for (int t : {1, 2, 4})
+            if ((int64_t)a.tiles_p * ((a.Q + kWaves * t - 1) / (kWaves * t)) <= 256) {
+                tqn = t;
+                break;
+            }
+        if (tqn != kTQMax) a.tiles_q = (a.Q + kWaves * tqn - 1) / (kWaves * tqn);
+#define HBMM_POPCOUNT_NARROW(GV)                                              \
+    switch (tqn) {                                                            \
+    case 1: return launch<GV, false, false, 1, 1>(a, s);                      \
+    case 2: return launch<GV, false, false, 1, 2>(a, s);                      \
+    case 4: return launch<GV, false, false, 1, 4>(a, s);                      \
+    default: return launch<GV, false, false, 1>(a, s);                        \
+    }
         switch (G) {
-        case 32: return launch<32, false, false, 1>(a, s);
-        case 64: return launch<64, false, false, 1>(a, s);
-        case 128: return launch<128, false, false, 1>(a, s);
-        case 256: return launch<256, false, false, 1>(a, s);
+        case 32: HBMM_POPCOUNT_NARROW(32)
+        case 64: HBMM_POPCOUNT_NARROW(64)
+        case 128: HBMM_POPCOUNT_NARROW(128)
+        case 256: HBMM_POPCOUNT_NARROW(256)
         }
+#undef HBMM_POPCOUNT_NARROW
         return hipErrorInvalidValue;
     }
     if (wide) {
