@@ -217,7 +217,7 @@ int hbmm_conv2d(const uint32_t *a_bits, const float *a_scales, int32_t beta_a, c
  *   hbmm_conv2d_prepared            a_bits / a_scales / beta_a / out and the geometry as for hbmm_conv2d;
  *                                   pieces from hbmm_conv_prepare_filters for the same N, C, KH, KW.
  *                                   The layer must fit the kernel: OW <= 128 and
- *                                   ((OW - 1) * stride + KW) * KH <= 512 (the input patch of one output
+ *                                   ((OW - 1) * stride + KW) * KH <= 640 (the input patch of one output
  *                                   row in on-chip memory); otherwise HBMM_EUNSUPPORTED (use hbmm_conv2d).
  *                                   No restriction on C*KH*KW being a multiple of 32 or of beta_w.
  */

@@ -42,6 +42,7 @@ constexpr int kThreadsD = 512;
 constexpr int kPatchArea = 160 * 1024 - 512;   // LDS of a workgroup, all of it patch (and, after the multiply, output turn areas)
 constexpr int kOperandBytes = 1024;         // one MFMA B operand: 64 lanes x 16 bytes
 constexpr int kStageBytes = 2 * 3 * kOperandBytes;   // filters of one stage for one block of 32: 2 steps x 3 pieces
+constexpr int kMaxItems = 5;                // staging items per thread (a stride-2 3 x 3 layer on 56 x 56 needs 513 pixels = 5)
 
 // ------------------------------------------------------------------------------------------------
 // Filter preparation: one thread per (block of 32 filters, group, tap, step, lane) writes the three
@@ -358,14 +359,14 @@ int ilog2d(int v)
 }
 
 // Rows of output per workgroup: as many as fill 128 positions, fewer if the patch would not fit the LDS or
-// would take more than 4 staging items per thread; 0 if not even one row fits.
+// would take more than 5 staging items per thread; 0 if not even one row fits.
 int rows_per_tile(const ConvGeometry &g, int64_t OH, int64_t OW)
 {
     if (OW > 128) return 0;
     const int PW = (int)(OW - 1) * g.stride + g.KW;
     int R = (int)(128 / OW < OH ? 128 / OW : OH);
     auto pixels = [&](int r) { return ((r - 1) * g.stride + g.KH) * PW; };
-    while (R >= 1 && (pixels(R) > kThreadsD || 3 * pixels(R) * kPixBytes > kPatchArea)) --R;
+    while (R >= 1 && (4 * pixels(R) > kMaxItems * kThreadsD || 3 * pixels(R) * kPixBytes > kPatchArea)) --R;
     return R;
 }
 
@@ -447,8 +448,10 @@ hipError_t launch_conv_direct(const ConvActivations &x, const void *pieces, int6
         HBMM_DIRECT_LAUNCH(2);
     else if (xi == 3)
         HBMM_DIRECT_LAUNCH(3);
-    else
+    else if (xi == 4)
         HBMM_DIRECT_LAUNCH(4);
+    else
+        HBMM_DIRECT_LAUNCH(5);
 #undef HBMM_DIRECT_LAUNCH
     return hipGetLastError();
 }

@@ -105,7 +105,7 @@ int64_t conv_filter_pieces_bytes(int64_t N, int64_t C, int KH, int KW);
 hipError_t launch_conv_prepare_filters(const uint32_t *w_bits, const float *w_scales, int64_t ldw, int64_t lds, int beta,
                                        int64_t N, int64_t C, int KH, int KW, void *pieces, hipStream_t s);
 // Whether the layer fits the kernel: output rows of at most 128 positions, and the input patch of one
-// output row within the LDS and the staging registers ((OW - 1) stride + KW) * KH <= 512 pixels).
+// output row within the LDS and the staging registers ((OW - 1) stride + KW) * KH <= 640 pixels).
 bool conv_direct_fits(const ConvGeometry &g);
 hipError_t launch_conv_direct(const ConvActivations &x, const void *pieces, int64_t N, const ConvGeometry &g, float *out,
                               hipStream_t s);

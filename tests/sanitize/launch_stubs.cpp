@@ -20,9 +20,9 @@ int64_t conv_filter_pieces_bytes(int64_t N, int64_t C, int KH, int KW) { return 
 hipError_t launch_conv_prepare_filters(const uint32_t *, const float *, int64_t, int64_t, int, int64_t, int64_t, int, int, void *, hipStream_t) { ++g_launches; return hipSuccess; }
 bool conv_direct_fits(const ConvGeometry &g)
 {
-    // the documented limits: OW <= 128 and ((OW - 1) * stride + KW) * KH <= 512
+    // the documented limits: OW <= 128 and ((OW - 1) * stride + KW) * KH <= 640
     const int64_t OW = (g.W + 2 * g.pad - g.KW) / g.stride + 1;
-    return OW <= 128 && ((OW - 1) * g.stride + g.KW) * g.KH <= 512;
+    return OW <= 128 && ((OW - 1) * g.stride + g.KW) * g.KH <= 640;
 }
 hipError_t launch_conv_direct(const ConvActivations &, const void *, int64_t, const ConvGeometry &, float *, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_mfma_i8_gemm(const uint32_t *, const float *, int64_t, int64_t, int, const uint32_t *, const float *, int64_t, int64_t, int, int64_t, int64_t, int64_t, float *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }

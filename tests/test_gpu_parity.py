@@ -858,7 +858,8 @@ PREPARED_CONV_CASES = CONV_CASES + [
     (3, 64, 28, 28, 64, 3, 3, 1, 1, 4, 64),     # 4 output rows per tile, 7 tiles per image, two staging items per thread
     (2, 32, 14, 14, 96, 3, 3, 1, 1, 2, 128),    # 9 rows per tile (126 positions), second tile of 5 rows
     (1, 3, 16, 16, 16, 5, 5, 1, 2, 4, 25),      # a first-layer shape: 3 channels, 5 x 5 window
-    (2, 64, 56, 56, 64, 3, 3, 2, 1, 8, 64),     # stride 2: the patch of two output rows is 5 x 57 pixels
+    (2, 64, 56, 56, 64, 3, 3, 2, 1, 8, 64),     # stride 2: the patch of four output rows is 9 x 57 = 513 pixels, five staging items
+    (1, 32, 56, 56, 96, 3, 3, 2, 1, 8, 32),     # the same patch with a 128-filter tile
     (1, 32, 8, 120, 8, 3, 3, 1, 1, 8, 32),      # one output row of 120 positions: 366 pixels, three staging items
     (1, 160, 6, 8, 200, 1, 1, 1, 0, 4, 160),    # five channel groups, two filter tiles of 128 (the second ragged)
 ]
@@ -873,7 +874,7 @@ def test_conv2d_prepared(case):
     wb, ws = hbmm.quantize_pack(dev(Wf.reshape(N, -1)), beta_w)
     pieces = hbmm.conv_prepare_filters(wb, ws, beta_w, C, (KH, KW))
     OW = (W + 2 * pad - KW) // stride + 1
-    if OW > 128 or ((OW - 1) * stride + KW) * KH > 512:
+    if OW > 128 or ((OW - 1) * stride + KW) * KH > 640:
         with pytest.raises(hbmm.HbmmError) as ei:
             hbmm.conv2d_prepared(ab, asc, beta_a, A.shape, pieces, N, (KH, KW), stride, pad)
         assert ei.value.code == hbmm.EUNSUPPORTED
