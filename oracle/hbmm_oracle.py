@@ -193,8 +193,8 @@ def materialize_activations(A, beta_a: int) -> np.ndarray:
     delta over segments of beta_a along the width of every row of every channel, times Sign(A)."""
     A = np.ascontiguousarray(A, dtype=np.float32)
     B, C, H, W = A.shape
-    if W % beta_a:
-        raise ValueError("beta_a must divide the input width")
+    # (the paper only asks beta_a <= w_in: when beta_a does not divide the width, the last segment of every
+    # row is the shorter remainder and its delta the mean over its own length, as for any other operand)
     return materialize(A.reshape(B * C * H, W), beta_a).reshape(B, C, H, W)
 
 

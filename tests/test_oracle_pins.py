@@ -433,6 +433,34 @@ def test_conv_activation_segments_run_along_the_width():
     np.testing.assert_array_equal(out[0, 0], 3.0 * At[0, 0])
 
 
+def test_conv_activation_segments_with_a_shorter_last_one():
+    """Widths that beta_a does not divide (7 x 7 feature maps with beta_a = 4 or 2; the paper asks only
+    beta_a <= w_in): every row's last segment is the remainder, averaged over its own length -- means
+    written out by hand here -- and segments never run on into the next row."""
+    A = np.array([1, -2, 3, -4, 5, -6, 7], dtype=np.float32) * np.ones((1, 2, 3, 1), dtype=np.float32)
+    A[0, 1] *= 2.0
+    At = oracle.materialize_activations(A, 4)
+    np.testing.assert_array_equal(At[0, 0, 1], [2.5, -2.5, 2.5, -2.5, 6.0, -6.0, 6.0])      # (1+2+3+4)/4, (5+6+7)/3
+    np.testing.assert_array_equal(At[0, 1, 2], [5.0, -5.0, 5.0, -5.0, 12.0, -12.0, 12.0])
+    At2 = oracle.materialize_activations(A, 2)
+    np.testing.assert_array_equal(np.abs(At2[0, 0, 0]), [1.5, 1.5, 3.5, 3.5, 5.5, 5.5, 7.0])   # the last one alone
+    # through the layer: a 1 x 1 filter with one weight reads the materialised tensor back, and with exact
+    # rationals a 3 x 3 window over it gives the same sums as the oracle
+    Wf = np.zeros((1, 2, 3, 3), dtype=np.float32)
+    Wf[0, :, :, :] = np.arange(1, 19, dtype=np.float32).reshape(2, 3, 3) - 9.0
+    got = oracle.hbmm_conv2d(A, Wf, 4, 1, 1, 1)
+    for oz in range(3):
+        for oy in range(7):
+            acc = Fraction(0)
+            for c in range(2):
+                for dz in range(3):
+                    for dy in range(3):
+                        z, y = oz - 1 + dz, oy - 1 + dy
+                        if 0 <= z < 3 and 0 <= y < 7:
+                            acc += Fraction(float(At[0, c, z, y])) * Fraction(float(Wf[0, c, dz, dy]))
+            assert got[0, 0, oz, oy] == float(acc)
+
+
 def test_conv_filter_segments_run_over_the_flattened_filter():
     """Eq. 1: the filter is reshaped to (filters, C*KH*KW) before it is cut into segments, so a
     segment may cross kernel rows and channels.  With beta_w = C*KH*KW the scale is one per filter."""

@@ -175,6 +175,24 @@ def activation_segments_along_height(A, beta_a):
     return np.ascontiguousarray(At.transpose(0, 1, 3, 2))
 
 
+def activation_segments_run_on_into_the_next_row(A, beta_a):
+    """A width that beta_a does not divide, cut as one flat run of elements instead of row by row."""
+    A = np.ascontiguousarray(A, dtype=np.float32)
+    B, C, H, W = A.shape
+    if W % beta_a == 0 or (B * C * H * W) % beta_a:
+        return REAL["materialize_activations"](A, beta_a)
+    return REAL["materialize"](A.reshape(1, -1), beta_a).reshape(A.shape)
+
+
+def activation_short_segment_divided_by_beta(A, beta_a):
+    A = np.ascontiguousarray(A, dtype=np.float32)
+    At = REAL["materialize_activations"](A, beta_a)
+    r = A.shape[3] % beta_a
+    if r:
+        At[..., -r:] *= r / beta_a
+    return At
+
+
 def filter_segments_restart_per_channel(Wf, beta_w):
     Wf = np.ascontiguousarray(Wf, dtype=np.float32)
     N, C, KH, KW = Wf.shape
@@ -249,6 +267,8 @@ CASES = [
                                                                "test_backward_brute_force_ragged_and_mask_edges"]),
     (activation_segments_along_height, "materialize_activations", ["test_conv_activation_segments_run_along_the_width",
                                                                    "test_conv_matches_library_convolution"]),
+    (activation_segments_run_on_into_the_next_row, "materialize_activations", ["test_conv_activation_segments_with_a_shorter_last_one"]),
+    (activation_short_segment_divided_by_beta, "materialize_activations", ["test_conv_activation_segments_with_a_shorter_last_one"]),
     (filter_segments_restart_per_channel, "materialize_filters", ["test_conv_filter_segments_run_over_the_flattened_filter",
                                                                   "test_conv_matches_library_convolution"]),
     (convolution_flips_the_filter, "conv2d_f64", ["test_conv_matches_library_convolution",
