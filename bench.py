@@ -576,8 +576,13 @@ def extras(w, A, B, a_bits, a_s, b_bits, b_s, C, torch, hbmm, synth, args):
             dW = torch.from_numpy(cw.make_w().reshape(cw.N, -1)).cuda()
             wb, ws = hbmm.quantize_pack(dW, cw.beta_w)
             entry = {"beta_a": cw.beta_a, "beta_w": cw.beta_w}
+            ragged = cw.W % cw.beta_a != 0    # only the prepared-filter form takes a width that beta_a does not divide
             if cw.beta_a == 1:      # binary-weight layer: the activations go in as they are
                 ab, asc = None, dA
+            elif ragged:
+                ab, asc = hbmm.quantize_pack_activations(dA, cw.beta_a)
+                entry["quantize_ms"] = back_to_back_ms([lambda: hbmm.quantize_pack_activations(dA, cw.beta_a, ab, asc)], 40, torch)
+                entry["quantize_kernel"] = "pack_activations_any_kernel (untuned)"
             else:
                 ab, asc = hbmm.quantize_pack_tensor(dA, cw.beta_a)
                 # queued back to back between one pair of events (a single launch of the small layers is
@@ -586,15 +591,18 @@ def extras(w, A, B, a_bits, a_s, b_bits, b_s, C, torch, hbmm, synth, args):
                 qbytes = dA.numel() * (4.0 + 1.0 / 8.0 + 4.0 / cw.beta_a)
                 entry["quantize_ms"] = tq
                 entry["quantize_GBs_cache_resident" if dA.numel() * 4 < 512 * 2**20 else "quantize_GBs"] = qbytes / (tq * 1e-3) / 1e9
-            out = hbmm.conv2d(ab, asc, cw.beta_a, dA.shape, wb, ws, cw.beta_w, (cw.KH, cw.KW), cw.stride, cw.pad)
-            tc = back_to_back_ms([lambda: hbmm.conv2d(ab, asc, cw.beta_a, dA.shape, wb, ws, cw.beta_w, (cw.KH, cw.KW),
-                                                      cw.stride, cw.pad, out)], 20, torch)
-            pieces = 6 if cw.beta_w < 16 else 3
-            entry.update({"conv_ms": tc, "conv_effective_gflops": 2.0 * cw.macs / (tc * 1e-3) / 1e9,
-                          "roofline": {"bound": "mfma", "kernel": "conv_patch_kernel / mfma_split_gemm_kernel (conv mode)",
-                                       "piece_products": pieces,
-                                       "achieved": pieces * 2.0 * cw.macs / (tc * 1e-3) / 1e12, "peak": BF16_PEAK_TFLOPS,
-                                       "unit": "TFLOP/s", "frac": pieces * 2.0 * cw.macs / (tc * 1e-3) / 1e12 / BF16_PEAK_TFLOPS}})
+            oh, ow = (cw.H + 2 * cw.pad - cw.KH) // cw.stride + 1, (cw.W + 2 * cw.pad - cw.KW) // cw.stride + 1
+            out = torch.empty((cw.batch, cw.N, oh, ow), dtype=torch.float32, device="cuda")
+            if not ragged:
+                hbmm.conv2d(ab, asc, cw.beta_a, dA.shape, wb, ws, cw.beta_w, (cw.KH, cw.KW), cw.stride, cw.pad, out)
+                tc = back_to_back_ms([lambda: hbmm.conv2d(ab, asc, cw.beta_a, dA.shape, wb, ws, cw.beta_w, (cw.KH, cw.KW),
+                                                          cw.stride, cw.pad, out)], 20, torch)
+                pieces = 6 if cw.beta_w < 16 else 3
+                entry.update({"conv_ms": tc, "conv_effective_gflops": 2.0 * cw.macs / (tc * 1e-3) / 1e9,
+                              "roofline": {"bound": "mfma", "kernel": "conv_patch_kernel / mfma_split_gemm_kernel (conv mode)",
+                                           "piece_products": pieces,
+                                           "achieved": pieces * 2.0 * cw.macs / (tc * 1e-3) / 1e12, "peak": BF16_PEAK_TFLOPS,
+                                           "unit": "TFLOP/s", "frac": pieces * 2.0 * cw.macs / (tc * 1e-3) / 1e12 / BF16_PEAK_TFLOPS}})
             # the same layer with the filters prepared ahead of time (once per set of weights, outside the timed
             # region like the packing of the filters itself); six piece products per element pair
             try:

@@ -159,6 +159,22 @@ int hbmm_quantize_pack_tensor(const float *x, int64_t count, int32_t beta, uint3
                               void *stream);
 
 /*
+ * Hadamard binarisation of an activation tensor with Eq. 3's segments for any segment length: the tensor is
+ * `rows` rows of W contiguous elements (rows = batch * channels * height, W the width), segments of beta run
+ * along the width and start anew in every row; when beta does not divide W (the paper only asks
+ * beta <= w_in; e.g. 7 x 7 feature maps with beta = 4) the last segment of a row is the shorter remainder and
+ * its scale the mean of |x| over its own length.
+ *   bits    out, ceil(rows * W / 32) words: element e = r * W + y is bit e mod 32 of word e div 32 (rows are not
+ *           padded; bits past the last element are 0).
+ *   scales  out, rows x ceil(W / beta) fp32, contiguous.
+ * beta in 2 .. 256; rows * W below 2^31.  When beta is a power of two that divides W (and rows * W is a multiple
+ * of 128) this is the layout hbmm_quantize_pack_tensor writes, and that kernel is used.  Scales otherwise:
+ * double-precision sums rounded once.
+ */
+int hbmm_quantize_pack_activations(const float *x, int64_t rows, int64_t W, int32_t beta, uint32_t *bits, float *scales,
+                                   void *stream);
+
+/*
  * hbmm_binarize_backward for a whole tensor stored contiguously, segments of beta consecutive elements
  * (the counterpart of hbmm_quantize_pack_tensor: for an activation tensor whose width is a multiple
  * of beta this is the gradient through Eq. 3-4).  count: a multiple of 128 and of beta, below 2^31.
@@ -214,7 +230,11 @@ int hbmm_conv2d(const uint32_t *a_bits, const float *a_scales, int32_t beta_a, c
  *                                   fp32 N x (C*KH*KW) matrix with leading dimension lds_w.
  *                                   pieces: out, device, 16-byte aligned, hbmm_conv_filter_pieces_bytes(...) bytes.
  *                                   C*KH*KW < 2^24; KH, KW <= 32.
- *   hbmm_conv2d_prepared            a_bits / a_scales / beta_a / out and the geometry as for hbmm_conv2d;
+ *   hbmm_conv2d_prepared            a_bits / a_scales / out and the geometry as for hbmm_conv2d, with any beta_a
+ *                                   in 1 .. 256: the activations as written by hbmm_quantize_pack_activations
+ *                                   (flat bits, scales (B*C*H) x ceil(W / beta_a): for a beta_a that divides W
+ *                                   that is also what hbmm_quantize_pack_tensor writes); beta_a = 1: a_bits
+ *                                   NULL, a_scales the fp32 tensor.
  *                                   pieces from hbmm_conv_prepare_filters for the same N, C, KH, KW.
  *                                   The layer must fit the kernel: OW <= 128 and
  *                                   ((OW - 1) * stride + KW) * KH <= 640 (the input patch of one output

@@ -319,6 +319,22 @@ int hbmm_quantize_pack_tensor(const float *x, int64_t count, int32_t beta, uint3
     return hbmm_quantize_pack(x, count / K, K, K, 0, beta, bits, K / 32, scales, K / beta, stream);
 }
 
+int hbmm_quantize_pack_activations(const float *x, int64_t rows, int64_t W, int32_t beta, uint32_t *bits, float *scales,
+                                   void *stream)
+{
+    if (rows < 0 || W < 0 || rows > kMaxDim || W > kMaxDim) return HBMM_EINVAL;
+    if ((double)rows * (double)W > 2147483647.0) return HBMM_EINVAL;
+    if (beta < 1) return HBMM_EINVAL;
+    if (beta == 1 || !any_beta(beta)) return HBMM_EUNSUPPORTED;
+    if (rows == 0 || W == 0) return HBMM_OK;
+    if (!x || !bits || !scales || !aligned16(x) || !aligned16(bits) || !aligned16(scales)) return HBMM_EINVAL;
+    // widths that beta divides, in the tuned kernels' range: the flat view is the same layout
+    const int64_t count = rows * W;
+    if (supported_pack_beta(beta) && W % beta == 0 && count % 128 == 0 && tensor_view_k(count) % beta == 0)
+        return hbmm_quantize_pack_tensor(x, count, beta, bits, scales, stream);
+    return from_hip(hbmm::launch_pack_activations_any(x, rows, W, beta, bits, scales, static_cast<hipStream_t>(stream)));
+}
+
 int hbmm_binarize_backward_tensor(const float *x, const float *grad_out, int64_t count, int32_t beta, float *grad_in,
                                    void *stream)
 {
@@ -404,7 +420,7 @@ int hbmm_conv2d_prepared(const uint32_t *a_bits, const float *a_scales, int32_t 
     if (int rc = check_conv_filter_shape(N, C, KH, KW)) return rc;
     if (pad > 32 || stride > 32) return HBMM_EINVAL;
     if (beta_a < 1) return HBMM_EINVAL;
-    if (!(beta_a == 1 || supported_pack_beta(beta_a))) return HBMM_EUNSUPPORTED;
+    if (!any_beta(beta_a)) return HBMM_EUNSUPPORTED;
     if (H + 2 * pad < KH || W + 2 * pad < KW) return HBMM_EINVAL;
     const int64_t OH = (H + 2 * pad - KH) / stride + 1, OW = (W + 2 * pad - KW) / stride + 1;
     if ((double)B * (double)C * (double)H * (double)W > 2147483647.0) return HBMM_EUNSUPPORTED;
@@ -412,7 +428,6 @@ int hbmm_conv2d_prepared(const uint32_t *a_bits, const float *a_scales, int32_t 
     if ((double)B * (double)OH * (double)OW > 2147483647.0) return HBMM_EUNSUPPORTED;
     if (B == 0 || N == 0) return HBMM_OK;
     if (C == 0 || H == 0 || W == 0) return HBMM_EINVAL;
-    if (W % beta_a != 0) return HBMM_EUNSUPPORTED;
     hbmm::ConvGeometry g{B, C, H, W, KH, KW, stride, pad, 0};
     if (!hbmm::conv_direct_fits(g)) return HBMM_EUNSUPPORTED;
     if (!out || !aligned16(out)) return HBMM_EINVAL;

@@ -110,9 +110,11 @@ struct ConvDirectArgs {
     const unsigned char *pieces;
     float *out;
     int32_t Y, yblocks;          // filters, and blocks of 32 of them in `pieces`
-    int32_t log2_beta_x;
+    int32_t beta_x, nseg, HS;    // activation segment length, segments per row ceil(W / beta_x), H * nseg
     int32_t C, H, W, HW, OH, OW, OHW, KW, KK, stride, pad;
     int32_t R, tiles_per_image, tiles_y, tiles_total, slots_per_xcd;
+    int32_t B, G;                // images, and images per tile (1 unless a whole image is at most 64 positions)
+    int32_t PI, IP;              // patch pixels and tile positions of one image: P = G * PI, positions = G * IP
     int32_t PW, P;               // patch width and pixels
     int32_t plane;               // bytes of one piece plane of the patch: P * 80
     int32_t patch_bufs;          // 2: group g lives in buffer g & 1; 1: one buffer, refilled between two barriers
@@ -138,30 +140,34 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
     const int slot_id = (blockIdx.x % kNumXcdD) * a.slots_per_xcd + blockIdx.x / kNumXcdD;
     if (slot_id >= a.tiles_total) return;
     const int tile_x = slot_id / a.tiles_y, y0 = (slot_id % a.tiles_y) * NT;
-    const int img = tile_x / a.tiles_per_image, oz0 = (tile_x % a.tiles_per_image) * a.R;
+    // (with several images per tile every image is whole: tiles_per_image = 1, oz0 = 0)
+    const int img = (tile_x / a.tiles_per_image) * a.G, oz0 = (tile_x % a.tiles_per_image) * a.R;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // wave -> (filter block, position half, MFMA step): the fastest index runs along the filters
     const int wcol0 = (wave % kWavesY) * 32;
     const int wrow0 = ((wave / kWavesY) & 1) * 64;
     const int ks0 = NTY == 1 ? wave / (WV / 2) : 0;       // first MFMA step of a stage this wave takes
-    const int npos = a.R * a.OW;                            // positions of a full tile (<= 128)
+    const int npos = a.G * a.IP;                            // positions of a full tile (<= 128)
 
     // ---- role 1: patch staging.  Item i = tid + 512 j is (octet i div P, pixel i mod P).
-    uint32_t pe0[XI], pkeep[XI];
+    uint32_t pe0[XI], ps0[XI], pkeep[XI];   // element and scale index of channel 0 at the item's pixel
     int pdst[XI];        // byte offset of the item inside a plane; -1: the item does not exist
     int poct[XI];
 #pragma unroll
     for (int j = 0; j < XI; ++j) {
         const int item = tid + j * kThreadsD;
         const int oct = item / a.P, pix = item - oct * a.P;
-        const int prow = pix / a.PW, pcol = pix - prow * a.PW;
+        const int gi = pix / a.PI, lp = pix - gi * a.PI;     // image of the tile, pixel inside that image's patch
+        const int prow = lp / a.PW, pcol = lp - prow * a.PW;
         const int z = oz0 * a.stride - a.pad + prow, y = pcol - a.pad;
-        const bool inside = oct < 4 && z >= 0 && z < a.H && y >= 0 && y < a.W;
+        const bool inside = oct < 4 && img + gi < a.B && z >= 0 && z < a.H && y >= 0 && y < a.W;
         poct[j] = min(oct, 3);
         pdst[j] = oct < 4 ? pix * kPixBytes + oct * 16 : -1;
         pkeep[j] = inside ? 0xffffffffu : 0u;
-        pe0[j] = inside ? (uint32_t)((img * a.C * a.H + z) * a.W + y) : 0u;
+        pe0[j] = inside ? (uint32_t)(((img + gi) * a.C * a.H + z) * a.W + y) : 0u;
+        // segments run along the width of a row and start anew in every row (the last one may be shorter)
+        ps0[j] = inside ? (uint32_t)(((img + gi) * a.C * a.H + z) * a.nseg + y / a.beta_x) : 0u;
     }
     const char *xb_bytes = reinterpret_cast<const char *>(a.x_bits);
     const char *xs_bytes = reinterpret_cast<const char *>(a.x_scales);
@@ -178,9 +184,10 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
             for (int i = 0; i < 8; ++i) {
                 const int c = g * kGroup + poct[j] * 8 + i;
                 const uint32_t e = c < a.C ? (pe0[j] + (uint32_t)(c * a.HW)) & pkeep[j] : 0u;
+                const uint32_t si = c < a.C ? (ps0[j] + (uint32_t)(c * a.HS)) & pkeep[j] : 0u;
                 // (byte pointers with 32-bit offsets: one address register per load instead of two)
                 r.w[j][i] = *reinterpret_cast<const uint32_t *>(xb_bytes + ((e >> 5) << 2));
-                r.s[j][i] = *reinterpret_cast<const float *>(xs_bytes + ((e >> a.log2_beta_x) << 2));
+                r.s[j][i] = *reinterpret_cast<const float *>(xs_bytes + (si << 2));
             }
     };
     auto park_patch = [&](const PatchRegs &r, int g, unsigned char *buf) __attribute__((always_inline)) {
@@ -219,8 +226,9 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
 #pragma unroll
     for (int tx = 0; tx < TX; ++tx) {
         const int ml = min(wrow0 + tx * 32 + (lane & 31), npos - 1);
-        const int orow = ml / a.OW, oy = ml - orow * a.OW;
-        xoff[tx] = ((orow * a.stride) * a.PW + oy * a.stride) * kPixBytes + (lane >> 5) * 16 + ks0 * 32;
+        const int gi = ml / a.IP, lm = ml - gi * a.IP;
+        const int orow = lm / a.OW, oy = lm - orow * a.OW;
+        xoff[tx] = (gi * a.PI + (orow * a.stride) * a.PW + oy * a.stride) * kPixBytes + (lane >> 5) * 16 + ks0 * 32;
     }
     // filter operands of this wave's block of 32 filters: stage s at s * kStageBytes (a block past the last
     // one re-reads the last: its columns are never stored)
@@ -327,9 +335,10 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
     for (int tx = 0; tx < TX; ++tx) {
         const int ml = wrow0 + tx * 32 + (lane & 31);
         const int mc = min(ml, npos - 1);
-        const int orow = mc / a.OW, oy = mc - orow * a.OW;
-        const bool pos_ok = ml < npos && oz0 + orow < a.OH;
-        float *dst = a.out + ((int64_t)img * a.Y * a.OH + (oz0 + orow)) * a.OW + oy;
+        const int gi = mc / a.IP, lm = mc - gi * a.IP;
+        const int orow = lm / a.OW, oy = lm - orow * a.OW;
+        const bool pos_ok = ml < npos && img + gi < a.B && oz0 + orow < a.OH;
+        float *dst = a.out + ((int64_t)(img + gi) * a.Y * a.OH + (oz0 + orow)) * a.OW + oy;
 #pragma unroll
         for (int v = 0; v < 16; ++v)
             turn[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * 33 + (lane & 31)] = res[tx][v];
@@ -349,13 +358,6 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
-}
-
-int ilog2d(int v)
-{
-    int s = 0;
-    while ((1 << s) < v) ++s;
-    return s;
 }
 
 // Rows of output per workgroup: as many as fill 128 positions, fewer if the patch would not fit the LDS or
@@ -405,17 +407,26 @@ hipError_t launch_conv_direct(const ConvActivations &x, const void *pieces, int6
 {
     const int64_t OH = (g.H + 2 * g.pad - g.KH) / g.stride + 1, OW = (g.W + 2 * g.pad - g.KW) / g.stride + 1;
     const int KK = g.KH * g.KW;
-    const int nty = N <= 64 ? 1 : 2;
     const int PW = (int)(OW - 1) * g.stride + g.KW;
-    const int64_t tiles_y = (N + 64 * nty - 1) / (64 * nty);
     int R = rows_per_tile(g, OH, OW);
     if (R < 1) return hipErrorNotSupported;
     const int tiles_per_image = (int)((OH + R - 1) / R);
     R = (int)((OH + tiles_per_image - 1) / tiles_per_image);   // even rows per tile
     const int threads = kThreadsD;
-    const int P = ((R - 1) * g.stride + g.KH) * PW;
+    const int PI = ((R - 1) * g.stride + g.KH) * PW;
+    // small feature maps (a whole image is at most 64 positions: the 7 x 7 maps of a network's last stage): several
+    // images per tile, each with its own patch, so that the 128 position rows of the tile are not mostly empty
+    int G = 1;
+    if (tiles_per_image == 1)
+        while ((G + 1) * R * OW <= 128 && G + 1 <= g.B && 4 * (G + 1) * PI <= kMaxItems * kThreadsD &&
+               2 * 3 * (G + 1) * PI * kPixBytes <= kPatchArea)
+            ++G;
+    const int P = G * PI;
     const int bufs = 2 * 3 * P * kPixBytes <= kPatchArea ? 2 : 1;
-    const int64_t tiles_x = g.B * tiles_per_image;
+    const int64_t tiles_x = (g.B + G - 1) / G * tiles_per_image;
+    // filters per tile: 128, or 64 when there are no more or when 128 would leave compute units without a workgroup
+    const int nty = N <= 64 || tiles_x * ((N + 127) / 128) < 256 ? 1 : 2;
+    const int64_t tiles_y = (N + 64 * nty - 1) / (64 * nty);
     const int64_t total = tiles_x * tiles_y, per_xcd = (total + kNumXcdD - 1) / kNumXcdD;
     if (per_xcd * kNumXcdD > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     ConvDirectArgs a{};
@@ -423,7 +434,8 @@ hipError_t launch_conv_direct(const ConvActivations &x, const void *pieces, int6
     // element e (segment length 1) it is the value itself, sign included, and the sign taken from the
     // bit word is switched off; the word loads still happen and are pointed at the same memory.
     a.x_bits = x.beta == 1 ? reinterpret_cast<const uint32_t *>(x.scales) : x.bits;
-    a.x_scales = x.scales; a.log2_beta_x = ilog2d(x.beta); a.sign = x.beta == 1 ? 0u : 0x80000000u;
+    a.x_scales = x.scales; a.sign = x.beta == 1 ? 0u : 0x80000000u;
+    a.beta_x = x.beta; a.nseg = (int32_t)((g.W + x.beta - 1) / x.beta); a.HS = (int32_t)(g.H * a.nseg);
     a.pieces = static_cast<const unsigned char *>(pieces);
     a.out = out; a.Y = (int32_t)N; a.yblocks = (int32_t)((N + 31) / 32);
     a.C = (int32_t)g.C; a.H = (int32_t)g.H; a.W = (int32_t)g.W; a.HW = (int32_t)(g.H * g.W);
@@ -431,6 +443,7 @@ hipError_t launch_conv_direct(const ConvActivations &x, const void *pieces, int6
     a.KW = g.KW; a.KK = KK; a.stride = g.stride; a.pad = g.pad;
     a.R = R; a.tiles_per_image = tiles_per_image; a.tiles_y = (int32_t)tiles_y; a.tiles_total = (int32_t)total;
     a.slots_per_xcd = (int32_t)per_xcd;
+    a.B = (int32_t)g.B; a.G = G; a.PI = PI; a.IP = (int32_t)(R * OW);
     a.PW = PW; a.P = P; a.plane = P * kPixBytes; a.patch_bufs = bufs;
     a.groups = (int32_t)((g.C + kGroup - 1) / kGroup);
     const int xi = (4 * P + threads - 1) / threads;

@@ -21,6 +21,11 @@ hipError_t launch_pack_cols(const float *x, int64_t rows, int64_t K, int64_t ldx
 hipError_t launch_pack_any(const float *x, int64_t rows, int64_t K, int64_t ldx, int layout, int beta,
                            uint32_t *bits, int64_t ldw, float *scales, int64_t lds, hipStream_t s);
 
+// An activation tensor as rows x W (rows = batch * channels * height): flat sign bits (ceil(rows * W / 32) words),
+// scales rows x ceil(W / beta) with a shorter last segment per row.  Any beta in 2..256, any W.
+hipError_t launch_pack_activations_any(const float *x, int64_t rows, int64_t W, int beta, uint32_t *bits, float *scales,
+                                       hipStream_t s);
+
 // ---- backward.hip -----------------------------------------------------------------------------
 hipError_t launch_binarize_backward(const float *x, const float *g, int64_t rows, int64_t K, int64_t ldx,
                                     int64_t ldg, int beta, float *gx, int64_t ldgx, hipStream_t s);

@@ -182,6 +182,34 @@ __global__ __launch_bounds__(256) void pack_any_kernel(
     }
 }
 
+// An activation tensor seen as `rows` rows of W contiguous elements (rows = batch * channels * height), for
+// any segment length: the sign bits are packed flat (element e = r * W + y is bit e mod 32 of word e div 32,
+// rows are not padded), the scales are rows x ceil(W / beta), segments starting anew in every row and the
+// last one of a row averaged over its own length.  One thread per output word and one per scale; for
+// widths that beta does not divide (7 x 7 feature maps), not tuned.
+__global__ __launch_bounds__(256) void pack_activations_any_kernel(
+    const float *__restrict__ x, int64_t rows, int W, int beta, uint32_t *__restrict__ bits, float *__restrict__ scales,
+    int64_t nwords, int nseg)
+{
+    const int64_t count = rows * W, nscales = rows * nseg;
+    for (int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x; id < nwords + nscales; id += (int64_t)gridDim.x * 256) {
+        if (id < nwords) {
+            uint32_t w = 0;
+            const int64_t e0 = id * 32;
+            const int n = (int)(count - e0 < 32 ? count - e0 : 32);
+            for (int b = 0; b < n; ++b) w |= (x[e0 + b] >= 0.f ? 1u : 0u) << b;
+            bits[id] = w;
+        } else {
+            const int64_t sid = id - nwords, r = sid / nseg;
+            const int j = (int)(sid - r * nseg);
+            const int y0 = j * beta, n = min(beta, W - y0);
+            double acc = 0.0;
+            for (int b = 0; b < n; ++b) acc += fabs((double)x[r * W + y0 + b]);
+            scales[sid] = (float)(acc / (double)n);
+        }
+    }
+}
+
 template <int BETA>
 hipError_t pack_rows_beta(const float *x, int64_t rows, int64_t K, int64_t ldx, uint32_t *bits,
                           int64_t ldw, float *scales, int64_t lds, hipStream_t s)
@@ -255,6 +283,17 @@ hipError_t launch_pack_any(const float *x, int64_t rows, int64_t K, int64_t ldx,
     const unsigned grid = (unsigned)(blocks < 256 * 64 ? blocks : 256 * 64);
     pack_any_kernel<<<dim3(grid), dim3(256), 0, s>>>(x, rows, (int)K, layout == 0 ? ldx : 1, layout == 0 ? 1 : ldx, beta,
                                                      bits, ldw, scales, lds, wv, nseg);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_activations_any(const float *x, int64_t rows, int64_t W, int beta, uint32_t *bits, float *scales,
+                                       hipStream_t s)
+{
+    const int64_t nwords = (rows * W + 31) / 32;
+    const int nseg = (int)((W + beta - 1) / beta);
+    const int64_t blocks = (nwords + rows * nseg + 255) / 256;
+    const unsigned grid = (unsigned)(blocks < 256 * 64 ? blocks : 256 * 64);
+    pack_activations_any_kernel<<<dim3(grid), dim3(256), 0, s>>>(x, rows, (int)W, beta, bits, scales, nwords, nseg);
     return hipGetLastError();
 }
 

@@ -23,6 +23,7 @@ EXPORTS = (
     "hbmm_gemm_int", "hbmm_dense_ref_gemm", "hbmm_binarize_backward", "hbmm_gemm_fused",
     "hbmm_quantize_pack_tensor", "hbmm_conv2d", "hbmm_binarize_backward_tensor",
     "hbmm_conv_filter_pieces_bytes", "hbmm_conv_prepare_filters", "hbmm_conv2d_prepared", "hbmm_probe_mfma_rate",
+    "hbmm_quantize_pack_activations",
 )
 
 
@@ -65,6 +66,8 @@ def _load() -> C.CDLL:
     lib.hbmm_conv_prepare_filters.argtypes = [p, p, i64, i64, i32, i64, i64, i32, i32, p, p]
     lib.hbmm_conv2d_prepared.restype = C.c_int
     lib.hbmm_conv2d_prepared.argtypes = [p, p, i32, p, i64, i64, i64, i64, i64, i32, i32, i32, i32, p, p]
+    lib.hbmm_quantize_pack_activations.restype = C.c_int
+    lib.hbmm_quantize_pack_activations.argtypes = [p, i64, i64, i32, p, p, p]
     lib.hbmm_probe_mfma_rate.restype = C.c_int
     lib.hbmm_probe_mfma_rate.argtypes = [i32, i32, p, p]
     lib.hbmm_binarize_backward.restype = C.c_int
@@ -319,6 +322,30 @@ def conv2d(a_bits, a_scales, beta_a: int, shape, w_bits, w_scales, beta_w: int, 
     return out
 
 
+def quantize_pack_activations(x: torch.Tensor, beta: int, bits: torch.Tensor | None = None,
+                              scales: torch.Tensor | None = None):
+    """hbmm_quantize_pack_activations: a contiguous fp32 tensor whose last axis is the width W ->
+    (bits int32[ceil(count / 32)], scales fp32[count / W * ceil(W / beta)]); segments of beta along the width, anew in
+    every row, the last one of a row shorter when beta does not divide W."""
+    _dev(x, torch.float32, "x")
+    if not x.is_contiguous() or x.dim() < 1:
+        raise ValueError("x must be a contiguous tensor")
+    count, W = x.numel(), int(x.shape[-1])
+    rows = count // max(W, 1)
+    nseg = -(-W // max(beta, 1))
+    if bits is None:
+        bits = torch.empty(((count + 31) // 32,), dtype=torch.int32, device=x.device)
+    if scales is None:
+        scales = torch.empty((rows * nseg,), dtype=torch.float32, device=x.device)
+    _dev(bits, torch.int32, "bits")
+    _dev(scales, torch.float32, "scales")
+    if bits.numel() < (count + 31) // 32 or scales.numel() < rows * nseg or not bits.is_contiguous() or not scales.is_contiguous():
+        raise ValueError(f"bits / scales: need {(count + 31) // 32} words and {rows * nseg} scales, contiguous")
+    rc = lib.hbmm_quantize_pack_activations(x.data_ptr(), rows, W, beta, bits.data_ptr(), scales.data_ptr(), _stream())
+    _check(rc, "hbmm_quantize_pack_activations")
+    return bits, scales
+
+
 def conv_filter_pieces_bytes(N: int, C: int, KH: int, KW: int) -> int:
     return int(lib.hbmm_conv_filter_pieces_bytes(N, C, KH, KW))
 
@@ -361,8 +388,9 @@ def conv2d_prepared(a_bits, a_scales, beta_a: int, shape, pieces: torch.Tensor, 
         raise ValueError(f"pieces: too few bytes for {N} filters of {(Cc, KH, KW)}")
     if not a_scales.is_contiguous() or (a_bits is not None and not a_bits.is_contiguous()):
         raise ValueError("the packed activation tensor must be contiguous")
-    if a_scales.numel() < count // max(beta_a, 1) or (a_bits is not None and a_bits.numel() < count // 32):
-        raise ValueError(f"activations: too few words / scales for a tensor of {count} elements")
+    nscales = B * Cc * H * -(-W // max(beta_a, 1))
+    if a_scales.numel() < nscales or (a_bits is not None and a_bits.numel() < (count + 31) // 32):
+        raise ValueError(f"activations: too few words / scales for a tensor of {count} elements ({nscales} scales)")
     OH, OW = (H + 2 * pad - KH) // stride + 1, (W + 2 * pad - KW) // stride + 1
     if out is None:
         out = torch.empty((B, N, OH, OW), dtype=torch.float32, device=a_scales.device)

@@ -190,7 +190,8 @@ class ConvWorkload:
         return self.batch * oh * ow * self.N * self.C * self.KH * self.KW
 
 
-# ResNet-18 3x3 layers with the paper's convolution semantics; beta_a must divide the width.
+# ResNet-18 3x3 layers with the paper's convolution semantics.  beta_a divides the width except in conv5x (7 x 7
+# maps, beta_a = 4: segments of 4 + 3 per row), which only the prepared-filter form of the layer takes.
 CONV_WORKLOADS = {
     w.name: w
     for w in (
@@ -202,5 +203,6 @@ CONV_WORKLOADS = {
         # the paper's own settings on conv3_x: HadaNet (beta_w, beta_a) = (4, 4) and the binary-weight (4, 1)
         ConvWorkload("conv3x_hadanet44_b64", 64, 128, 28, 28, 128, 3, 3, 1, 1, 4, 4, 7101, 7102),
         ConvWorkload("conv3x_hbwn41_b64", 64, 128, 28, 28, 128, 3, 3, 1, 1, 1, 4, 7101, 7102),
+        ConvWorkload("conv5x_hadanet44_b64", 64, 512, 7, 7, 512, 3, 3, 1, 1, 4, 4, 7401, 7402),
     )
 }

@@ -197,6 +197,14 @@ def test_validation_of_the_fused_tensor_and_convolution_entry_points(lib):
     assert pf(fake, fake, 12, 9, 300, 8, 32, 3, 3, fake, None) == -2       # beta_w above 256
     assert pf(fake, fake, 12, 9, 32, 8, 1 << 22, 3, 3, fake, None) == -2   # C*KH*KW beyond 2^24
     assert pf(None, None, 12, 9, 32, 0, 32, 3, 3, None, None) == 0
+    qa = lib.hbmm_quantize_pack_activations
+    qa.argtypes = [p, i64, i64, i32, p, p, p]
+    assert qa(fake, 64, 7, 1, fake, fake, None) == -2          # beta = 1: nothing to pack
+    assert qa(fake, 64, 7, 300, fake, fake, None) == -2
+    assert qa(fake, 64, 7, 4, None, fake, None) == -1
+    assert qa(fake + 4, 64, 7, 4, fake, fake, None) == -1      # misaligned
+    assert qa(fake, 1 << 20, 1 << 20, 4, fake, fake, None) == -1   # more than 2^31 elements
+    assert qa(None, 0, 7, 4, None, None, None) == 0
     cp = lib.hbmm_conv2d_prepared
     cp.argtypes = [p, p, i32, p, i64, i64, i64, i64, i64, i32, i32, i32, i32, p, p]
     okp = dict(ab=fake, asc=fake, ba=4, pieces=fake, B=1, C=32, H=8, W=8, N=8, KH=3, KW=3, stride=1, pad=1, out=fake)
@@ -206,8 +214,7 @@ def test_validation_of_the_fused_tensor_and_convolution_entry_points(lib):
         return cp(a["ab"], a["asc"], a["ba"], a["pieces"], a["B"], a["C"], a["H"], a["W"], a["N"], a["KH"], a["KW"],
                   a["stride"], a["pad"], a["out"], None)
 
-    assert convp(ba=16) == -2                # beta_a does not divide the width
-    assert convp(ba=3) == -2                 # beta_a not a power of two
+    assert convp(ba=300) == -2               # beta_a above 256 (any other beta_a goes, also one that does not divide the width)
     assert convp(W=200, pad=1) == -2         # an output row of 200 positions does not fit a tile
     assert convp(W=128, KH=5, KW=5, pad=2) == -2   # the patch of one output row: 132 x 5 pixels
     assert convp(pieces=None) == -1

@@ -62,7 +62,8 @@ def test_bench_comparison_rows_carry_a_bound_and_a_fraction():
     assert "frac_of_epilogue_alu_bound" in cmp_["other_workloads"]["sq4k16"]["roofline"]
     for name, e in cmp_["conv2d"].items():
         assert "error" not in e, (name, e)
-        assert e["roofline"]["bound"] == "mfma" and 0 < e["roofline"]["frac"] < 1.0, name
+        if "conv_ms" in e:      # (a width that beta_a does not divide runs in the prepared-filter form only)
+            assert e["roofline"]["bound"] == "mfma" and 0 < e["roofline"]["frac"] < 1.0, name
         assert "conv_prepared_error" not in e, (name, e)
         assert e["roofline_prepared"]["piece_products"] == 6 and 0 < e["roofline_prepared"]["frac"] < 1.0, name
     # the sustained matrix-core rate lies below the published peak and above half of it

@@ -907,6 +907,55 @@ def test_conv2d_prepared_unquantised_operands(case):
     assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d_prepared unquantised {case}")
 
 
+@pytest.mark.parametrize("shape,beta", [((2, 3, 7, 7), 4), ((2, 3, 7, 7), 2), ((1, 5, 14, 14), 4), ((3, 2, 5, 9), 3), ((1, 1, 1, 1), 2),
+                                        ((2, 4, 8, 8), 4), ((1, 16, 8, 28), 7), ((2, 3, 4, 130), 128), ((1, 2, 3, 300), 256)])
+def test_quantize_pack_activations(shape, beta):
+    """Segments along the width, anew in every row, for any segment length: flat sign bits, and scales that
+    are the oracle's bit for bit where the general kernel runs (double-precision sums rounded once)."""
+    x = synth.normal(8500 + sum(shape) + beta, shape)
+    x.reshape(-1)[:3] = [0.0, -0.0, -1e-30][:min(3, x.size)]
+    bits, scales = hbmm.quantize_pack_activations(dev(x), beta)
+    count, W = x.size, shape[-1]
+    flat = oracle.sign_pack(x.reshape(1, -1))[0, :(count + 31) // 32]
+    assert np.array_equal(words(bits), flat)
+    ref = oracle.block_scales(x.reshape(-1, W), beta).reshape(-1)
+    got = scales.cpu().numpy()
+    assert got.shape == ref.shape
+    assert np.all(np.abs(got - ref) <= scale_tol(beta) * ref)
+    if W % beta:
+        assert np.array_equal(got, ref)
+
+
+RAGGED_WIDTH_CONV_CASES = [
+    # B, C, H, W, N, KH, KW, stride, pad, beta_a, beta_w
+    (2, 32, 7, 7, 40, 3, 3, 1, 1, 4, 4),        # 7 x 7 maps (the last stage of a ResNet) with the paper's beta = 4: segments 4 + 3
+    (3, 48, 7, 7, 70, 3, 3, 1, 1, 2, 8),        # 2 + 2 + 2 + 1
+    (1, 64, 7, 7, 130, 1, 1, 1, 0, 7, 64),      # one segment per row
+    (2, 20, 14, 14, 33, 3, 3, 2, 1, 4, 5),      # 4 + 4 + 4 + 2, stride 2
+    (1, 32, 9, 10, 16, 3, 3, 1, 1, 3, 32),      # 3 + 3 + 3 + 1
+    (2, 16, 5, 13, 12, 2, 3, 1, 1, 16, 6),      # beta_a longer than the width: one short segment per row
+    (5, 32, 7, 7, 40, 3, 3, 1, 1, 4, 4),        # two whole images per tile, the last tile with one
+    (7, 32, 4, 4, 20, 3, 3, 1, 1, 2, 32),       # 16 positions per image: eight images per tile would fit, seven exist
+    (9, 32, 6, 6, 70, 3, 3, 2, 1, 4, 16),       # 3 x 3 outputs per image, stride 2: fourteen images per tile would fit
+    (3, 64, 8, 8, 16, 1, 1, 1, 0, 8, 64),       # 64 positions per image: two images per tile, 1 x 1 window
+]
+
+
+@pytest.mark.parametrize("case", RAGGED_WIDTH_CONV_CASES, ids=lambda c: "x".join(str(v) for v in c))
+def test_conv2d_prepared_width_not_a_multiple_of_beta_a(case):
+    """Eq. 3 on widths that beta_a does not divide: hbmm_quantize_pack_activations + hbmm_conv2d_prepared against
+    the oracle's layer."""
+    B, C, H, W, N, KH, KW, stride, pad, beta_a, beta_w = case
+    A, Wf = _conv_inputs(8600 + B + C + N, B, C, H, W, N, KH, KW)
+    ab, asc = hbmm.quantize_pack_activations(dev(A), beta_a)
+    wb, ws = hbmm.quantize_pack(dev(Wf.reshape(N, -1)), beta_w)
+    pieces = hbmm.conv_prepare_filters(wb, ws, beta_w, C, (KH, KW))
+    ref, T = oracle.hbmm_conv2d(A, Wf, beta_a, beta_w, stride, pad, want_T=True)
+    out = hbmm.conv2d_prepared(ab, asc, beta_a, A.shape, pieces, N, (KH, KW), stride, pad)
+    assert tuple(out.shape) == ref.shape
+    assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d_prepared ragged width {case}")
+
+
 def _random_prepared_conv_cases(n, seed):
     rng = np.random.default_rng(seed)
     cases = []
@@ -914,12 +963,12 @@ def _random_prepared_conv_cases(n, seed):
         C = int(rng.integers(1, 100))
         KH, KW = (int(v) for v in rng.integers(1, 4, size=2))
         beta_w = int(rng.integers(1, 65))
-        beta_a = int(rng.choice([1, 2, 4, 8]))
-        W = max(beta_a, 4) * int(rng.integers(1, 9))
+        beta_a = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 16]))
+        W = int(rng.integers(3, 60))
         H = int(rng.integers(3, 20))
         stride, pad = int(rng.integers(1, 3)), int(rng.integers(0, 3))
         B = int(rng.integers(1, 4))
-        if H + 2 * pad < KH or W + 2 * pad < KW or (beta_a != 1 and (B * C * H * W) % 128):
+        if H + 2 * pad < KH or W + 2 * pad < KW:
             continue
         cases.append((B, C, H, W, int(rng.integers(1, 150)), KH, KW, stride, pad, beta_a, beta_w))
     return cases
@@ -927,12 +976,12 @@ def _random_prepared_conv_cases(n, seed):
 
 @pytest.mark.parametrize("case", _random_prepared_conv_cases(32, 20260105), ids=lambda c: "x".join(str(v) for v in c))
 def test_conv2d_prepared_seeded_random_sweep(case):
-    """Layer geometries, channel counts and segment lengths (any beta_w in 1..64, beta_a in {1, 2, 4, 8})
-    drawn from a fixed seed."""
+    """Layer geometries, channel counts, widths and segment lengths (any beta_w in 1..64, beta_a from 1 to 16,
+    dividing the width or not) drawn from a fixed seed."""
     B, C, H, W, N, KH, KW, stride, pad, beta_a, beta_w = case
     A, Wf = _conv_inputs(8400 + H + W + N, B, C, H, W, N, KH, KW)
     ref, T = oracle.hbmm_conv2d(A, Wf, beta_a, beta_w, stride, pad, want_T=True)
-    ab, asc = (None, dev(A)) if beta_a == 1 else hbmm.quantize_pack_tensor(dev(A), beta_a)
+    ab, asc = (None, dev(A)) if beta_a == 1 else hbmm.quantize_pack_activations(dev(A), beta_a)
     if beta_w == 1:
         pieces = hbmm.conv_prepare_filters(None, dev(Wf.reshape(N, -1)), 1, C, (KH, KW))
     else:

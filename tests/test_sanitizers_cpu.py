@@ -94,7 +94,13 @@ for (ba, bw) in [(4, 32), (1, 4), (4, 5), (2, 1)]:
     K = 20 * 9
     assert pf(None if bw == 1 else fake, fake, 8, K, bw, 40, 20, 3, 3, fake, None) == 0
     assert cp(None if ba == 1 else fake, fake, ba, fake, 2, 20, 8, 8, 40, 3, 3, 1, 1, fake, None) == 0
-assert lib.hbmm_stub_launches() - n0 == 14 + 16 + 5 + 5 + 2 + 8
+qa = lib.hbmm_quantize_pack_activations
+qa.argtypes = [p, i64, i64, i32, p, p, p]
+assert qa(fake, 64 * 7, 7, 4, fake, fake, None) == 0       # ragged width: the general kernel
+assert qa(fake, 64 * 8, 8, 3, fake, fake, None) == 0
+assert qa(fake, 64 * 8, 8, 4, fake, fake, None) == 0       # the tuned kernel through the flat view
+assert cp(fake, fake, 3, fake, 2, 20, 7, 7, 40, 3, 3, 1, 1, fake, None) == 0
+assert lib.hbmm_stub_launches() - n0 == 14 + 16 + 5 + 5 + 2 + 8 + 4
 print("api under sanitizers: ok")
 """
 
