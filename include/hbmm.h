@@ -85,7 +85,9 @@ int hbmm_quantize_pack(const float *x, int64_t rows, int64_t K, int64_t ldx, int
  * x is the full-precision tensor that was binarised (rows x K, segments of beta along K, as in
  * hbmm_quantize_pack layout 0), grad_out the gradient with respect to delta (.) Sign(x), delta the mean
  * of |x| over the segment (recomputed from x).  The upper limit of the sum printed in Eq. 6 is read
- * as exclusive (beta terms).  beta: a power of two in 1 .. 256, K a multiple of beta and of 4.
+ * as exclusive (beta terms).  beta in 1 .. 256; the tuned kernel takes a power of two with K a multiple of beta
+ * and of 4, any other beta or K goes to a general kernel, where a shorter last segment has delta averaged
+ * over its own length n and 1/n in place of 1/beta.
  * grad_in may not alias x or grad_out.  fp32 arithmetic; error <= (log2(beta) + 3) * 2^-24 times
  * ((1/beta) sum_j |grad_out_j| + delta |grad_out_i|).
  */

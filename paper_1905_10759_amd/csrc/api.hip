@@ -103,12 +103,16 @@ int hbmm_binarize_backward(const float *x, const float *grad_out, int64_t rows, 
 {
     if (rows < 0 || K < 0 || rows > kMaxDim || K > kMaxPackK) return HBMM_EINVAL;
     if (beta < 1) return HBMM_EINVAL;
-    if (!(beta == 1 || supported_pack_beta(beta))) return HBMM_EUNSUPPORTED;
-    if (K % beta != 0 || K % 4 != 0) return HBMM_EUNSUPPORTED;
+    if (!any_beta(beta)) return HBMM_EUNSUPPORTED;
+    // the tuned kernel takes the paper's settings; any other segment length or K goes to the general one
+    const bool tuned = (beta == 1 || supported_pack_beta(beta)) && K % beta == 0 && K % 4 == 0;
     if (rows == 0 || K == 0) return HBMM_OK;
     if (!x || !grad_out || !grad_in) return HBMM_EINVAL;
     if (!aligned16(x) || !aligned16(grad_out) || !aligned16(grad_in)) return HBMM_EINVAL;
     if (ldx < K || ldg < K || ldgi < K) return HBMM_EINVAL;
+    if (!tuned)
+        return from_hip(hbmm::launch_binarize_backward_any(x, grad_out, rows, K, ldx, ldg, beta, grad_in, ldgi,
+                                                           static_cast<hipStream_t>(stream)));
     return from_hip(hbmm::launch_binarize_backward(x, grad_out, rows, K, ldx, ldg, beta, grad_in, ldgi,
                                                    static_cast<hipStream_t>(stream)));
 }

@@ -111,7 +111,45 @@ hipError_t launch_beta(const float *x, const float *g, int64_t rows, int64_t K, 
     return hipGetLastError();
 }
 
+// Any segment length in 1..256 and any K (the last segment may be shorter: then delta is the mean over its own
+// length n and its derivative 1/n): one thread per segment, sums in double.  For settings outside the
+// paper's table; it reads x and g twice and is not tuned.
+__global__ __launch_bounds__(256) void binarize_backward_any_kernel(
+    const float *__restrict__ x, const float *__restrict__ g, int64_t rows, int K, int64_t ldx, int64_t ldg, int beta,
+    float *__restrict__ gx, int64_t ldgx, int nseg)
+{
+    const int64_t total = rows * nseg;
+    for (int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x; id < total; id += (int64_t)gridDim.x * 256) {
+        const int64_t r = id / nseg;
+        const int k0 = (int)(id - r * nseg) * beta, n = min(beta, K - k0);
+        const float *xr = x + r * ldx + k0, *gr = g + r * ldg + k0;
+        double sabs = 0.0, sdot = 0.0;
+        for (int i = 0; i < n; ++i) {
+            sabs += fabs((double)xr[i]);
+            sdot += xr[i] >= 0.f ? (double)gr[i] : -(double)gr[i];
+        }
+        const float delta = (float)(sabs / (double)n);
+        const double mean_dot = sdot / (double)n;
+        float *o = gx + r * ldgx + k0;
+        for (int i = 0; i < n; ++i) {
+            const float xv = xr[i];
+            const double ste = fabsf(xv) <= 1.0f ? (double)delta * (double)gr[i] : 0.0;
+            o[i] = (float)((xv >= 0.f ? mean_dot : -mean_dot) + ste);
+        }
+    }
+}
+
 }  // namespace
+
+hipError_t launch_binarize_backward_any(const float *x, const float *g, int64_t rows, int64_t K, int64_t ldx, int64_t ldg,
+                                        int beta, float *gx, int64_t ldgx, hipStream_t s)
+{
+    const int nseg = (int)((K + beta - 1) / beta);
+    const int64_t blocks = (rows * nseg + 255) / 256;
+    const unsigned grid = (unsigned)(blocks < 256 * 64 ? blocks : 256 * 64);
+    binarize_backward_any_kernel<<<dim3(grid), dim3(256), 0, s>>>(x, g, rows, (int)K, ldx, ldg, beta, gx, ldgx, nseg);
+    return hipGetLastError();
+}
 
 hipError_t launch_binarize_backward(const float *x, const float *g, int64_t rows, int64_t K, int64_t ldx,
                                     int64_t ldg, int beta, float *gx, int64_t ldgx, hipStream_t s)

@@ -30,6 +30,10 @@ hipError_t launch_pack_activations_any(const float *x, int64_t rows, int64_t W, 
 hipError_t launch_binarize_backward(const float *x, const float *g, int64_t rows, int64_t K, int64_t ldx,
                                     int64_t ldg, int beta, float *gx, int64_t ldgx, hipStream_t s);
 
+// Any beta in 1..256 and any K >= 1 (a shorter last segment).
+hipError_t launch_binarize_backward_any(const float *x, const float *g, int64_t rows, int64_t K, int64_t ldx, int64_t ldg,
+                                        int beta, float *gx, int64_t ldgx, hipStream_t s);
+
 // ---- gemm_popcount.hip ------------------------------------------------------------------------
 // One operand ("P") is held per lane, the other ("Q") is broadcast through scalar registers.
 // out[p * ld_out_p + q * ld_out_q] receives the result for P-row p and Q-row q, so either of

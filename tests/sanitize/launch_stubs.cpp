@@ -12,6 +12,7 @@ hipError_t launch_pack_rows(const float *, int64_t, int64_t, int64_t, int, uint3
 hipError_t launch_pack_cols(const float *, int64_t, int64_t, int64_t, int, uint32_t *, int64_t, float *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_pack_activations_any(const float *, int64_t, int64_t, int, uint32_t *, float *, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_pack_any(const float *, int64_t, int64_t, int64_t, int, int, uint32_t *, int64_t, float *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_binarize_backward_any(const float *, const float *, int64_t, int64_t, int64_t, int64_t, int, float *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_binarize_backward(const float *, const float *, int64_t, int64_t, int64_t, int64_t, int, float *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_popcount_gemm(const PopcountGemmArgs &, int, int, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_mfma_split_gemm(const SplitGemmOperand &, const SplitGemmOperand &, int64_t, float *, int64_t, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }

@@ -115,8 +115,8 @@ def test_validation_rejects_before_launch(lib):
 
     bw = lib.hbmm_binarize_backward
     bw.argtypes = [p, p, i64, i64, i64, i64, i32, p, i64, p]
-    assert bw(fake, fake, 4, 64, 64, 64, 48, fake, 64, None) == -2     # beta not a power of two
-    assert bw(fake, fake, 4, 64, 64, 64, 128, fake, 64, None) == -2    # K not a multiple of beta
+    assert bw(fake, fake, 4, 64, 64, 64, 300, fake, 64, None) == -2    # beta above 256
+    assert bw(fake, fake, 4, 64, 64, 64, 0, fake, 64, None) == -1
     assert bw(fake, None, 4, 64, 64, 64, 8, fake, 64, None) == -1
     assert bw(fake, fake, 4, 64, 32, 64, 8, fake, 64, None) == -1      # ldx < K
     assert bw(fake, fake, 0, 64, 64, 64, 8, fake, 64, None) == 0

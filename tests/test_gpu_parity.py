@@ -565,6 +565,19 @@ def test_binarize_backward(beta, rows, K):
     assert_close_to_oracle(got, ref, T, f"backward beta={beta}")
 
 
+@pytest.mark.parametrize("rows,K,beta", [(3, 19, 5), (7, 19, 3), (1, 1, 2), (33, 100, 7), (40, 1000, 48), (5, 257, 256),
+                                          (9, 96, 6), (17, 70, 64), (2, 4100, 255), (65, 31, 16), (8, 50, 1)])
+def test_binarize_backward_any_beta_and_ragged_k(rows, K, beta):
+    """Eq. 6 for segment lengths that are not powers of two and a K that beta does not divide: the last segment
+    has delta averaged over its own length n and 1/n in place of 1/beta."""
+    x = synth.normal(8700 + rows + K, (rows, K)) * 1.2
+    x[0, :min(K, 4)] = [1.0, -1.0, 0.0, 1.0000001][:min(K, 4)]
+    g = synth.normal(8701 + rows + beta, (rows, K))
+    got = hbmm.binarize_backward(dev(x), dev(g), beta).cpu().numpy()
+    ref, T = oracle.binarize_backward(x, g, beta, want_T=True)
+    assert_close_to_oracle(got, ref, T, f"backward any beta={beta} K={K}")
+
+
 def test_binarize_backward_ragged_and_strided():
     K, beta = 96, 8
     x, g = synth.normal(1010, (9, K)), synth.normal(1011, (9, K))
