@@ -690,6 +690,62 @@ def test_layer_pipeline_in_a_hip_graph_replays_exactly():
         _ = dX.sum().item()   # unrelated eager work between replays
 
 
+def test_prepared_layer_pipeline_in_a_hip_graph_replays_exactly():
+    """The same with the entry points added for settings outside the paper's table: activations of a 7-wide
+    map packed with a segment length that does not divide the width, the layer with prepared filters, the
+    gradient through the binarisation and a product with segment lengths that are not powers of two --
+    captured once and replayed."""
+    B, C, H, W, N, beta_a, beta_w = 3, 48, 7, 7, 40, 4, 5
+    X0, X1 = synth.relu_normal(1300, (B, C, H, W)), synth.relu_normal(1301, (B, C, H, W))
+    F = synth.normal(1302, (N, C, 3, 3), std=0.1)
+    L = synth.normal(1303, (30, N * H * W), std=0.1)
+    dX = dev(X0)
+    fb, fs = hbmm.quantize_pack(dev(F.reshape(N, -1)), beta_w)
+    prepared = hbmm.conv_prepare_filters(fb, fs, beta_w, C, (3, 3))
+    K2 = N * H * W
+    lb, ls = hbmm.quantize_pack(dev(L), 6)
+    xb, xs = hbmm.quantize_pack_activations(dX, beta_a)
+    Y = torch.empty((B, N, H, W), dtype=torch.float32, device="cuda")
+    yb = torch.empty((B, hbmm.packed_ld_words(K2)), dtype=torch.int32, device="cuda")
+    ys = torch.empty((B, hbmm.num_blocks(K2, 7)), dtype=torch.float32, device="cuda")
+    Z = torch.empty((B, 30), dtype=torch.float32, device="cuda")
+    G = torch.empty((B * C * H, W), dtype=torch.float32, device="cuda")
+
+    def step():
+        hbmm.quantize_pack_activations(dX, beta_a, xb, xs)
+        hbmm.conv2d_prepared(xb, xs, beta_a, dX.shape, prepared, N, (3, 3), 1, 1, out=Y)
+        hbmm.quantize_pack(Y.view(B, K2), 7, 0, yb, ys)
+        hbmm.gemm(yb, ys, 7, lb, ls, 6, K2, out=Z)
+        hbmm.binarize_backward(dX.view(-1, W), dX.view(-1, W), beta_a, out=G)
+
+    def eager(x):
+        dX.copy_(dev(x))
+        step()
+        torch.cuda.synchronize()
+        return Z.clone(), G.clone()
+
+    want0, want1 = eager(X0), eager(X1)
+    assert not torch.equal(want0[0], want1[0])
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        step()
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    for rep in range(4):
+        x, want = (X0, want0) if rep % 2 == 0 else (X1, want1)
+        dX.copy_(dev(x))
+        Z.zero_()
+        G.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            graph.replay()
+        side.synchronize()
+        assert torch.equal(Z, want[0]) and torch.equal(G, want[1]), f"replay {rep} differs from the eager result"
+        _ = dX.sum().item()   # unrelated eager work between replays
+
+
 def test_calls_on_a_side_stream():
     """Kernels go to the stream that is current when the call is made."""
     M, N, K, beta = 130, 70, 512, 128
