@@ -104,6 +104,9 @@ __global__ __launch_bounds__(256) void conv_prepare_filters_kernel(const Prepare
 }
 
 // ------------------------------------------------------------------------------------------------
+// x div d for the small non-negative x of the kernel's set-up (x * d < 2^32): m = ceil(2^32 / d), or 0 for d = 1.
+__device__ __forceinline__ int small_div(int x, uint32_t m) { return m ? (int)__umulhi((uint32_t)x, m) : x; }
+
 struct ConvDirectArgs {
     const uint32_t *x_bits;
     const float *x_scales;
@@ -116,6 +119,7 @@ struct ConvDirectArgs {
     int32_t B, G;                // images, and images per tile (1 unless a whole image is at most 64 positions)
     int32_t PI, IP;              // patch pixels and tile positions of one image: P = G * PI, positions = G * IP
     int32_t PW, P;               // patch width and pixels
+    uint32_t m_P, m_PI, m_PW, m_IP, m_OW, m_beta;   // divisors of the set-up as multipliers, see small_div()
     int32_t plane;               // bytes of one piece plane of the patch: P * 80
     int32_t patch_bufs;          // 2: group g lives in buffer g & 1; 1: one buffer, refilled between two barriers
     int32_t groups;              // ceil(C / 32)
@@ -157,9 +161,9 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
 #pragma unroll
     for (int j = 0; j < XI; ++j) {
         const int item = tid + j * kThreadsD;
-        const int oct = item / a.P, pix = item - oct * a.P;
-        const int gi = pix / a.PI, lp = pix - gi * a.PI;     // image of the tile, pixel inside that image's patch
-        const int prow = lp / a.PW, pcol = lp - prow * a.PW;
+        const int oct = small_div(item, a.m_P), pix = item - oct * a.P;
+        const int gi = small_div(pix, a.m_PI), lp = pix - gi * a.PI;   // image of the tile, pixel inside its patch
+        const int prow = small_div(lp, a.m_PW), pcol = lp - prow * a.PW;
         const int z = oz0 * a.stride - a.pad + prow, y = pcol - a.pad;
         const bool inside = oct < 4 && img + gi < a.B && z >= 0 && z < a.H && y >= 0 && y < a.W;
         poct[j] = min(oct, 3);
@@ -167,7 +171,7 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
         pkeep[j] = inside ? 0xffffffffu : 0u;
         pe0[j] = inside ? (uint32_t)(((img + gi) * a.C * a.H + z) * a.W + y) : 0u;
         // segments run along the width of a row and start anew in every row (the last one may be shorter)
-        ps0[j] = inside ? (uint32_t)(((img + gi) * a.C * a.H + z) * a.nseg + y / a.beta_x) : 0u;
+        ps0[j] = inside ? (uint32_t)(((img + gi) * a.C * a.H + z) * a.nseg + small_div(y, a.m_beta)) : 0u;
     }
     const char *xb_bytes = reinterpret_cast<const char *>(a.x_bits);
     const char *xs_bytes = reinterpret_cast<const char *>(a.x_scales);
@@ -226,8 +230,8 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
 #pragma unroll
     for (int tx = 0; tx < TX; ++tx) {
         const int ml = min(wrow0 + tx * 32 + (lane & 31), npos - 1);
-        const int gi = ml / a.IP, lm = ml - gi * a.IP;
-        const int orow = lm / a.OW, oy = lm - orow * a.OW;
+        const int gi = small_div(ml, a.m_IP), lm = ml - gi * a.IP;
+        const int orow = small_div(lm, a.m_OW), oy = lm - orow * a.OW;
         xoff[tx] = (gi * a.PI + (orow * a.stride) * a.PW + oy * a.stride) * kPixBytes + (lane >> 5) * 16 + ks0 * 32;
     }
     // filter operands of this wave's block of 32 filters: stage s at s * kStageBytes (a block past the last
@@ -335,8 +339,8 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
     for (int tx = 0; tx < TX; ++tx) {
         const int ml = wrow0 + tx * 32 + (lane & 31);
         const int mc = min(ml, npos - 1);
-        const int gi = mc / a.IP, lm = mc - gi * a.IP;
-        const int orow = lm / a.OW, oy = lm - orow * a.OW;
+        const int gi = small_div(mc, a.m_IP), lm = mc - gi * a.IP;
+        const int orow = small_div(lm, a.m_OW), oy = lm - orow * a.OW;
         const bool pos_ok = ml < npos && img + gi < a.B && oz0 + orow < a.OH;
         float *dst = a.out + ((int64_t)(img + gi) * a.Y * a.OH + (oz0 + orow)) * a.OW + oy;
 #pragma unroll
@@ -445,6 +449,9 @@ hipError_t launch_conv_direct(const ConvActivations &x, const void *pieces, int6
     a.slots_per_xcd = (int32_t)per_xcd;
     a.B = (int32_t)g.B; a.G = G; a.PI = PI; a.IP = (int32_t)(R * OW);
     a.PW = PW; a.P = P; a.plane = P * kPixBytes; a.patch_bufs = bufs;
+    auto magic = [](int d) { return d == 1 ? 0u : (uint32_t)(((1ull << 32) + d - 1) / d); };   // 0 stands for d = 1
+    a.m_P = magic(P); a.m_PI = magic(PI); a.m_PW = magic(PW); a.m_IP = magic(a.IP); a.m_OW = magic((int)OW);
+    a.m_beta = magic(x.beta);
     a.groups = (int32_t)((g.C + kGroup - 1) / kGroup);
     const int xi = (4 * P + threads - 1) / threads;
     const dim3 grid((unsigned)(per_xcd * kNumXcdD)), block(threads);
