@@ -26,7 +26,8 @@
  *           bit 0 <=> Sign = -1 (section 4: the row -1 1 1 -1 -1 1 packs to 011001).
  *           Words [0, hbmm_packed_ld_words(K)) of every row are written; bits at k >= K
  *           inside them are 0.  Words past that (if ldw is larger) are not touched.
- *   scales  rows x lds fp32, entry j of a row = mean |x| over k in [j*beta, (j+1)*beta);
+ *   scales  rows x lds fp32, entry j of a row = mean |x| over k in [j*beta, (j+1)*beta) (the last
+ *           segment ends at K and is averaged over its own length when beta does not divide K);
  *           hbmm_num_blocks(K, beta) entries per row are written (section 4.2: the
  *           full-precision side shrinks by the factor beta).
  */
