@@ -336,3 +336,26 @@ def test_binding_entry_points_validate_before_the_call(monkeypatch):
         hbmm.conv2d(act_bits[:7], act_scales, 4, (1, 4, 8, 8), bits, scales, 32, (4, 8), 1, 0)           # too few activation words
     with pytest.raises(ValueError):
         hbmm.conv2d(act_bits, act_scales, 4, (1, 4, 8, 8), bits, scales, 32, (4, 8), 1, 0, out=torch.zeros((1, 6, 5, 2)))   # out is 1 x 6 x 5 x 1
+    # the prepared-filter layer and the activation packing for widths that beta does not divide
+    monkeypatch.setattr(hbmm, "conv_filter_pieces_bytes", lambda N, C, KH, KW: (N + 31) // 32 * ((C + 31) // 32) * KH * KW * 6144)
+    pieces = torch.zeros(6144 * 2 * 9, dtype=torch.uint8)          # 40 filters of 20 x 3 x 3: two blocks of 32, one channel group
+    x7 = torch.zeros((2, 20, 7, 7))
+    a7_bits, a7_scales = torch.zeros((2 * 20 * 49 + 31) // 32, dtype=torch.int32), torch.zeros(2 * 20 * 7 * 2)
+    with pytest.raises(ValueError):
+        hbmm.conv2d_prepared(a7_bits, a7_scales, 4, x7.shape, pieces[:-1], 40, (3, 3), 1, 1)              # prepared filters too short
+    with pytest.raises(ValueError):
+        hbmm.conv2d_prepared(a7_bits, a7_scales[:-1], 4, x7.shape, pieces, 40, (3, 3), 1, 1)              # 2 scales per row of 7: one missing
+    with pytest.raises(ValueError):
+        hbmm.conv2d_prepared(a7_bits[:-1], a7_scales, 4, x7.shape, pieces, 40, (3, 3), 1, 1)              # too few words
+    with pytest.raises(ValueError):
+        hbmm.conv2d_prepared(a7_bits, a7_scales, 4, x7.shape, pieces, 40, (3, 3), 1, 1, out=torch.zeros((2, 40, 7, 6)))
+    with pytest.raises(ValueError):
+        hbmm.conv_prepare_filters(bits, scales, 32, 20, (3, 3))                                          # 180 elements per filter need 8 words, 6 scales
+    with pytest.raises(ValueError):
+        hbmm.conv_prepare_filters(torch.zeros((40, 8), dtype=torch.int32), torch.zeros((40, 6)), 32, 20, (3, 3), pieces[:100])
+    with pytest.raises(ValueError):
+        hbmm.quantize_pack_activations(x7.permute(0, 1, 3, 2), 4)                                         # not contiguous
+    with pytest.raises(ValueError):
+        hbmm.quantize_pack_activations(x7, 4, a7_bits[:-1], a7_scales)
+    with pytest.raises(ValueError):
+        hbmm.quantize_pack_activations(x7, 4, a7_bits, a7_scales[:-1])
