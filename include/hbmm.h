@@ -121,11 +121,13 @@ int hbmm_binarize_backward(const float *x, const float *grad_out, int64_t rows, 
  *                     its HadaNets with beta_a = beta_w = 4).  Not supported: beta = 1 for both (that
  *                     is hbmm_dense_ref_gemm).
  *                     General case (a segment length that is not a power of two, a K that beta does not
- *                     divide, K not a multiple of 32; K < 2^24; algo 0 or -1): the operands are as
+ *                     divide, K not a multiple of 32; algo 0 or -1): the operands are as
  *                     hbmm_quantize_pack writes them for that beta and K (scales per row:
- *                     hbmm_num_blocks(K, beta), the last segment shorter); both are rebuilt as fp32
- *                     values on the matrix-core kernel, C[m, n] = sum_k A~[m, k] * B~[n, k] with
- *                     X~[r, k] = sX[r, k div beta] * Sign(X)[r, k].  An unquantised operand needs no
+ *                     hbmm_num_blocks(K, beta), the last segment shorter, bits at k >= K zero).
+ *                     Both beta powers of two >= 32: still the XNOR + popcount kernel; the last segment
+ *                     of G contributes (K mod G) - 2 * popcount.  Otherwise (K < 2^24) both operands are
+ *                     rebuilt as fp32 values on the matrix-core kernel, C[m, n] = sum_k A~[m, k] * B~[n, k]
+ *                     with X~[r, k] = sX[r, k div beta] * Sign(X)[r, k].  An unquantised operand needs no
  *                     particular leading dimension here.
  *   C                 out, M x N fp32, leading dimension ldc >= N.
  *   algo              0: the method's kernel as described above.

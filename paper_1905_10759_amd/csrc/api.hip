@@ -197,7 +197,11 @@ int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int6
     const bool tuned = (beta_a == 1 || supported_pack_beta(beta_a)) && (beta_w == 1 || supported_pack_beta(beta_w)) &&
                        K % beta_w == 0 && K % beta_a == 0 && K % 32 == 0 &&
                        (beta_a != 1 || lds_a % 4 == 0) && (beta_w != 1 || lds_b % 4 == 0);   // 16-byte row loads
-    if (!tuned && (algo > 0 || K > kMaxAnyK)) return HBMM_EUNSUPPORTED;
+    // (word-sized power-of-two segments with a K that they or 32 do not divide: the popcount kernel itself, whose
+    // tail loop takes the shorter last segment; the matrix-core variants do not)
+    const bool popcount_any_k = word_a && word_w && !tuned;
+    if (popcount_any_k && algo == -1) algo = 0;
+    if (!tuned && (algo > 0 || (K > kMaxAnyK && !popcount_any_k))) return HBMM_EUNSUPPORTED;
     if ((algo == 1 || algo == 2) && !(word_a && word_w)) return HBMM_EUNSUPPORTED;
     if (algo == 2 && (beta_a < 64 || beta_w < 64)) return HBMM_EUNSUPPORTED;   // one fp4 MFMA step is 64 bits of K
     if (algo == 3) {
@@ -217,7 +221,7 @@ int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int6
     if (int rc = check_operand(ob, K)) return rc;
     if (int rc = check_operand(oa, K)) return rc;
 
-    if (!tuned) {
+    if (!tuned && !popcount_any_k) {
         // both sides rebuilt as fp32 values element by element; an unquantised operand is the "x" side
         if (beta_w != 1) return from_hip(hbmm::launch_mfma_split_any(to_split(oa), to_split(ob), K, C, ldc, 1, s));
         return from_hip(hbmm::launch_mfma_split_any(to_split(ob), to_split(oa), K, C, 1, ldc, s));
@@ -266,6 +270,10 @@ int hbmm_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a, int6
     g.out = C;
     g.kwords = (int32_t)hbmm::packed_words(K);
     g.ngran = (int32_t)(K / G);
+    g.tail_bits = (int32_t)(K % G);
+    g.kw_used = (int32_t)((K + 31) / 32);
+    g.nblk_p = (int32_t)((K + (G << g.shift_p) - 1) / (G << g.shift_p));
+    g.nblk_q = (int32_t)((K + (G << g.shift_q) - 1) / (G << g.shift_q));
     g.K = (int32_t)K;
     return from_hip(hbmm::launch_popcount_gemm(g, G, 0, s));
 }
@@ -297,6 +305,10 @@ int hbmm_gemm_fused(const float *A, int64_t lda, int32_t beta_a, const uint32_t 
     g.out = C;
     g.kwords = (int32_t)hbmm::packed_words(K);
     g.ngran = (int32_t)(K / G);
+    g.tail_bits = (int32_t)(K % G);
+    g.kw_used = (int32_t)((K + 31) / 32);
+    g.nblk_p = (int32_t)((K + (G << g.shift_p) - 1) / (G << g.shift_p));
+    g.nblk_q = (int32_t)((K + (G << g.shift_q) - 1) / (G << g.shift_q));
     g.K = (int32_t)K;
     return from_hip(hbmm::launch_popcount_gemm(g, G, 0, s));
 }

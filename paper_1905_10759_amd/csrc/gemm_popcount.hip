@@ -112,8 +112,8 @@ __global__ __launch_bounds__(kThreads, TP == 2 ? (G >= 128 && !FUSED ? 4 : 3) : 
     // scale entries per chunk for each operand: 512 / beta = kGranPerChunk >> shift
     const int nsp = INTEGER ? 0 : (kGranPerChunk >> a.shift_p);
     const int nsq = INTEGER ? 0 : (kGranPerChunk >> a.shift_q);
-    const int nblk_p = INTEGER ? 0 : (a.ngran >> a.shift_p);
-    const int nblk_q = INTEGER ? 0 : (a.ngran >> a.shift_q);
+    const int nblk_p = INTEGER ? 0 : a.nblk_p;
+    const int nblk_q = INTEGER ? 0 : a.nblk_q;
 
     // ---- staging registers for the next chunk
     constexpr int kBitPieces = kTileP * (kCK / 4) / kThreads;             // 2 x 16 bytes per thread
@@ -373,6 +373,20 @@ __global__ __launch_bounds__(kThreads, TP == 2 ? (G >= 128 && !FUSED ? 4 : 3) : 
             for (int q = 0; q < kTQ; ++q) asm volatile("" : "+v"(res[i][q]));
         __builtin_amdgcn_sched_barrier(0);
     };
+    // The shorter last segment of a K that G does not divide: `bits` of it exist, so its inner product is
+    // bits - 2 * hamming (the pad bits of both operands are 0 and xor to 0).  Ragged tail loop only.
+    auto epilogue_tail = [&](const float (&sp)[kTP], const float (&sq)[kTQ], int bits) {
+        // (the hamming count first, exactly; half of an odd `bits` is not a float next to 2^23)
+        const float half = 0.5f * (float)bits;
+#pragma unroll
+        for (int i = 0; i < kTP; ++i) {
+            const float sp2 = -2.0f * sp[i];
+#pragma unroll
+            for (int q = 0; q < kTQ; ++q)
+                res[i][q] = __builtin_fmaf((__builtin_bit_cast(float, acc[i][q]) - 8388608.0f) - half, sp2 * sq[q],
+                                           res[i][q]);
+        }
+    };
     // Scalar loads of Q words, written as asm so that the row offset can ride in the instruction's
     // SGPR-offset field (no address arithmetic per load).  The compiler does not count these loads,
     // so wait_q() must run before their results are read: it waits for every outstanding scalar /
@@ -506,6 +520,12 @@ __global__ __launch_bounds__(kThreads, TP == 2 ? (G >= 128 && !FUSED ? 4 : 3) : 
                 const uint32_t qw1 = *(const_u32_ptr)(qbase + (uint64_t)qoff[q] + (int64_t)(wbase + w) * 4);
 #pragma unroll
                 for (int i = 0; i < kTP; ++i) acc[i][q] += __builtin_popcount(pw1[i] ^ qw1);
+            }
+            if (!INTEGER && a.tail_bits > 0 && wbase + w + 1 == a.kw_used) {
+                // the last word that holds elements: the segment that ends here is shorter than G
+                float sp[kTP], sq[kTQ];
+                load_scales(sp, sq, buf, w / kWordsPerGran);
+                epilogue_tail(sp, sq, a.tail_bits);
             }
             if (!INTEGER && (w + 1) % kWordsPerGran == 0) {
                 const int g_local = w / kWordsPerGran;

@@ -53,7 +53,10 @@ struct PopcountGemmArgs {
     int32_t ldw_p, ldw_q;
     int32_t lds_p, lds_q;
     int32_t kwords;      // words per row that are read: packed_words(K)
-    int32_t ngran;       // K / G   (scaled mode)
+    int32_t ngran;       // K div G: whole segments of the finer operand (scaled mode)
+    int32_t tail_bits;   // K mod G: length of the shorter last segment, 0 if G divides K
+    int32_t kw_used;     // ceil(K / 32): words of a row that hold elements
+    int32_t nblk_p, nblk_q;   // scales per row of each operand: ceil(K / beta)
     int32_t shift_p;     // log2(beta_p / G)
     int32_t shift_q;     // log2(beta_q / G)
     int32_t K;           // bits (integer mode: D = K - 2 * hamming)

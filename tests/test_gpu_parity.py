@@ -439,6 +439,30 @@ def test_gemm_any_beta_and_ragged_k(M, N, K, beta_a, beta_w):
     split_case(synth.normal(7100 + M + K, (M, K)), synth.normal(7101 + N + K, (N, K), std=0.05), beta_a, beta_w)
 
 
+@pytest.mark.parametrize("M,N,K,beta_a,beta_w", [
+    (70, 90, 70, 32, 32), (130, 260, 4100, 64, 64), (200, 150, 1000, 128, 32), (300, 64, 523, 256, 64),
+    (50, 40, 33, 32, 256), (64, 64, 31, 32, 32), (10, 10, 1, 32, 32), (9, 7, 255, 256, 256), (100, 80, 513, 128, 128),
+    (2100, 2100, 1030, 64, 32), (20000, 2000, 600, 64, 64), (1500, 3000, 2047, 32, 32)])
+def test_gemm_word_segments_with_a_shorter_last_one(M, N, K, beta_a, beta_w):
+    """Power-of-two segments of 32 bits or more and a K that they, or a 32-bit word, do not divide: the XNOR +
+    popcount kernel with the last, shorter segment counted over the elements that exist (Eq. 7 with the
+    remainder as its last term).  Against the oracle's own popcount form and its per-segment error scale;
+    grids of one workgroup, of a few (the small-grid forms) and of several rounds (the 128- and 256-row forms)."""
+    A, B = synth.normal(7500 + M + K, (M, K)), synth.normal(7501 + N + K, (N, K), std=0.05)
+    ab, as_, bb, bs = oracle.sign_pack(A), oracle.block_scales(A, beta_a), oracle.sign_pack(B), oracle.block_scales(B, beta_w)
+    ref, T = oracle.popcount_gemm(ab, as_, beta_a, bb, bs, beta_w, K, want_T=True)
+    got = hbmm.gemm(dev(ab.view(np.int32)), dev(as_), beta_a, dev(bb.view(np.int32)), dev(bs), beta_w, K, algo=0)
+    assert_close_to_oracle(got.cpu().numpy(), ref, T, f"ragged K {M}x{N}x{K} b=({beta_a},{beta_w})")
+    if M * N <= 70000:
+        # and the same numbers from the definition on materialised operands
+        dense = oracle.dense_f64_gemm(oracle.materialize(A, beta_a), oracle.materialize(B, beta_w))
+        assert np.allclose(ref, dense, rtol=1e-12, atol=1e-12 * np.abs(dense).max())
+    for algo in (1, 2, 3):
+        with pytest.raises(hbmm.HbmmError) as ei:
+            hbmm.gemm(dev(ab.view(np.int32)), dev(as_), beta_a, dev(bb.view(np.int32)), dev(bs), beta_w, K, algo=algo)
+        assert ei.value.code == hbmm.EUNSUPPORTED
+
+
 def _random_any_cases(n, seed):
     rng = np.random.default_rng(seed)
     cases = []
