@@ -616,6 +616,19 @@ def extras(w, A, B, a_bits, a_s, b_bits, b_s, C, torch, hbmm, synth, args):
                                                     "achieved": 6 * 2.0 * cw.macs / (tp * 1e-3) / 1e12, "peak": BF16_PEAK_TFLOPS,
                                                     "unit": "TFLOP/s", "frac": 6 * 2.0 * cw.macs / (tp * 1e-3) / 1e12 / BF16_PEAK_TFLOPS}})
                 del prepared
+                # the two-piece form of the same layer: operands scaled into fp16's range and written as two fp16
+                # pieces (22 significant bits), three piece products per element pair
+                f16x2 = hbmm.PIECES_F16X2
+                prepared = hbmm.conv_prepare_filters(wb, ws, cw.beta_w, cw.C, (cw.KH, cw.KW), form=f16x2)
+                hbmm.conv2d_prepared(ab, asc, cw.beta_a, dA.shape, prepared, cw.N, (cw.KH, cw.KW), cw.stride, cw.pad, out, form=f16x2)
+                t2 = back_to_back_ms([lambda: hbmm.conv2d_prepared(ab, asc, cw.beta_a, dA.shape, prepared, cw.N, (cw.KH, cw.KW),
+                                                                   cw.stride, cw.pad, out, form=f16x2)], 20, torch)
+                entry.update({"conv_prepared_f16x2_ms": t2,
+                              "roofline_prepared_f16x2": {"bound": "mfma", "kernel": "conv_direct_kernel (two fp16 pieces)",
+                                                          "piece_products": 3,
+                                                          "achieved": 3 * 2.0 * cw.macs / (t2 * 1e-3) / 1e12, "peak": BF16_PEAK_TFLOPS,
+                                                          "unit": "TFLOP/s", "frac": 3 * 2.0 * cw.macs / (t2 * 1e-3) / 1e12 / BF16_PEAK_TFLOPS}})
+                del prepared
             except Exception as e:
                 entry["conv_prepared_error"] = str(e)
             convs[name] = entry

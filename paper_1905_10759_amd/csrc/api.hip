@@ -402,16 +402,18 @@ static int check_conv_filter_shape(int64_t N, int64_t C, int32_t KH, int32_t KW)
     return HBMM_OK;
 }
 
-int64_t hbmm_conv_filter_pieces_bytes(int64_t N, int64_t C, int32_t KH, int32_t KW)
+int64_t hbmm_conv_filter_pieces_bytes(int64_t N, int64_t C, int32_t KH, int32_t KW, int32_t form)
 {
-    if (check_conv_filter_shape(N, C, KH, KW) != HBMM_OK) return 0;
-    return hbmm::conv_filter_pieces_bytes(N, C, KH, KW);
+    if (check_conv_filter_shape(N, C, KH, KW) != HBMM_OK || form < 0 || form > 1) return 0;
+    return hbmm::conv_filter_pieces_bytes(N, C, KH, KW, form);
 }
 
 int hbmm_conv_prepare_filters(const uint32_t *w_bits, const float *w_scales, int64_t ldw_w, int64_t lds_w,
-                              int32_t beta_w, int64_t N, int64_t C, int32_t KH, int32_t KW, void *pieces, void *stream)
+                              int32_t beta_w, int64_t N, int64_t C, int32_t KH, int32_t KW, int32_t form, void *pieces,
+                              void *stream)
 {
     if (int rc = check_conv_filter_shape(N, C, KH, KW)) return rc;
+    if (form < 0 || form > 1) return HBMM_EUNSUPPORTED;
     if (beta_w < 1) return HBMM_EINVAL;
     if (!any_beta(beta_w)) return HBMM_EUNSUPPORTED;
     if (N == 0 || C == 0) return HBMM_OK;
@@ -424,14 +426,15 @@ int hbmm_conv_prepare_filters(const uint32_t *w_bits, const float *w_scales, int
         if (lds_w < (K + beta_w - 1) / beta_w) return HBMM_EINVAL;
         if (int rc = check_packed(w_bits, N, K, ldw_w)) return rc;
     }
-    return from_hip(hbmm::launch_conv_prepare_filters(w_bits, w_scales, ldw_w, lds_w, beta_w, N, C, KH, KW, pieces,
+    return from_hip(hbmm::launch_conv_prepare_filters(w_bits, w_scales, ldw_w, lds_w, beta_w, N, C, KH, KW, form, pieces,
                                                       static_cast<hipStream_t>(stream)));
 }
 
-int hbmm_conv2d_prepared(const uint32_t *a_bits, const float *a_scales, int32_t beta_a, const void *pieces, int64_t B,
-                         int64_t C, int64_t H, int64_t W, int64_t N, int32_t KH, int32_t KW, int32_t stride,
+int hbmm_conv2d_prepared(const uint32_t *a_bits, const float *a_scales, int32_t beta_a, const void *pieces, int32_t form,
+                         int64_t B, int64_t C, int64_t H, int64_t W, int64_t N, int32_t KH, int32_t KW, int32_t stride,
                          int32_t pad, float *out, void *stream)
 {
+    if (form < 0 || form > 1) return HBMM_EUNSUPPORTED;
     if (B < 0 || H < 0 || W < 0 || stride < 1 || pad < 0 || B > kMaxDim || H > kMaxDim || W > kMaxDim) return HBMM_EINVAL;
     if (int rc = check_conv_filter_shape(N, C, KH, KW)) return rc;
     if (pad > 32 || stride > 32) return HBMM_EINVAL;
@@ -451,7 +454,7 @@ int hbmm_conv2d_prepared(const uint32_t *a_bits, const float *a_scales, int32_t 
     if (!a_scales || !aligned16(a_scales)) return HBMM_EINVAL;
     if (beta_a == 1 ? a_bits != nullptr : (!a_bits || !aligned16(a_bits))) return HBMM_EINVAL;
     hbmm::ConvActivations x{a_bits, a_scales, beta_a};
-    return from_hip(hbmm::launch_conv_direct(x, pieces, N, g, out, static_cast<hipStream_t>(stream)));
+    return from_hip(hbmm::launch_conv_direct(x, pieces, N, g, form, out, static_cast<hipStream_t>(stream)));
 }
 
 int hbmm_probe_mfma_rate(int32_t steps, int32_t blocks, float *sink, void *stream)

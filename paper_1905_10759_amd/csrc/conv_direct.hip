@@ -5,8 +5,16 @@
 //   out[b, n, oz, oy] = sum_{c, dz, dy} A~[b, c, oz*stride - pad + dz, oy*stride - pad + dy] * W~[n, c, dz, dy]
 //
 // with A~ = scale * sign of the activation (0 outside the input) and W~ = scale * sign of the filter
-// weight.  Both are fp32 numbers; each is split exactly into three bf16 pieces and the six largest of the
-// nine piece products are added on v_mfma_f32_32x32x16_bf16 (what is dropped is below 2^-24 of a term).
+// weight.  Both are fp32 numbers.  Two forms of the product (FORM):
+//   0  each number is split exactly into three bf16 pieces and the six largest of the nine piece products are
+//      added on v_mfma_f32_32x32x16_bf16 (what is dropped is below 2^-24 of a term);
+//   1  each number is scaled by a power of two into the range of fp16 and split into two fp16 pieces, h =
+//      the number rounded, m = the remainder rounded (22 significant bits together), and hm, mh, hh are added
+//      on v_mfma_f32_32x32x16_f16: half the multiplies, |error| <= 3 * 2^-22 of a term (plus 2^-39 of the
+//      largest activation / weight met so far, where a remainder falls below fp16's smallest subnormal).  The
+//      power of two is per filter for the weights (fixed at preparation) and per workgroup for the
+//      activations: the exponent of the largest magnitude among the channel groups staged so far; when a
+//      later group raises it the accumulators are rescaled (exactly) before that group is multiplied.
 // Because both sides are plain numbers here, the sum over k may run in any order, and the order chosen
 // is (channel group of 32, filter tap, channel inside the group).  One K stage is then one tap of one
 // channel group: 32 channels at a fixed offset (dz, dy) from every output position.
@@ -31,6 +39,7 @@
 // its last one -- into the other buffer when two fit, else between two barriers).
 #include "bf16_pieces.h"
 #include "kernels.h"
+#include "wave_ops.h"
 
 namespace hbmm {
 namespace {
@@ -41,7 +50,29 @@ constexpr int kNumXcdD = 8;
 constexpr int kThreadsD = 512;
 constexpr int kPatchArea = 160 * 1024 - 512;   // LDS of a workgroup, all of it patch (and, after the multiply, output turn areas)
 constexpr int kOperandBytes = 1024;         // one MFMA B operand: 64 lanes x 16 bytes
-constexpr int kStageBytes = 2 * 3 * kOperandBytes;   // filters of one stage for one block of 32: 2 steps x 3 pieces
+// filters of one stage for one block of 32: 2 steps x 3 (bf16) or 2 (fp16) pieces
+constexpr int stage_bytes(int form) { return 2 * (form == 0 ? 3 : 2) * kOperandBytes; }
+constexpr int kTargetExp = 14;              // FORM 1: the largest magnitude is scaled into [2^14, 2^15)
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+// FORM 1 helpers.  e is the biased exponent of the largest magnitude, kept in [14, 254] so that the
+// multiplier 2^(14 - (e - 127)) is a normal float (anything smaller than 2^-113 is treated as 0).
+__device__ __forceinline__ int norm_exponent(uint32_t max_abs_bits)
+{
+    const int e = (int)(max_abs_bits >> 23);
+    return e < 14 ? 14 : (e > 254 ? 254 : e);
+}
+__device__ __forceinline__ float norm_factor(int e) { return __builtin_bit_cast(float, (uint32_t)(268 - e) << 23); }
+// v (already scaled) as two fp16 patterns in the low halves of hi and mid.
+__device__ __forceinline__ void split2_f16(float v, uint32_t &hi, uint32_t &mid)
+{
+    const _Float16 h = (_Float16)v;
+    const _Float16 m = (_Float16)(v - (float)h);
+    hi = __builtin_bit_cast(uint16_t, h);
+    mid = __builtin_bit_cast(uint16_t, m);
+}
+// The three piece pairs (x piece, y piece) of FORM 1, smallest contributions first.
+constexpr int kPiecePairs2[3][2] = {{0, 1}, {1, 0}, {0, 0}};
 constexpr int kMaxItems = 5;                // staging items per thread (a stride-2 3 x 3 layer on 56 x 56 needs 513 pixels = 5)
 
 // ------------------------------------------------------------------------------------------------
@@ -57,10 +88,28 @@ struct PrepareArgs {
     uint32_t magic;              // ceil(2^32 / beta): k div beta = umulhi(k, magic) for k < 2^24
     int32_t raw;                 // beta = 1
     int64_t total;               // threads that have work
+    int32_t *exps;               // FORM 1: biased exponent per filter (32 * blocks entries), inside `pieces`
+    int32_t nscales;             // FORM 1: entries of a row of w_scales that belong to the filter
 };
 
+// FORM 1, first step: one wave per filter finds the exponent of its largest magnitude (of its scales, or of
+// its weights when unquantised).  Filters past N get the smallest exponent (their pieces are zeros).
+__global__ __launch_bounds__(64) void conv_filter_exponents_kernel(const PrepareArgs a)
+{
+    const int n = blockIdx.x, lane = threadIdx.x;
+    uint32_t mx = 0;
+    if (n < a.N)
+        for (int i = lane; i < a.nscales; i += 64)
+            mx = max(mx, __builtin_bit_cast(uint32_t, a.w_scales[(int64_t)n * a.lds + i]) & 0x7fffffffu);
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, d));
+    if (lane == 0) a.exps[n] = norm_exponent(mx);
+}
+
+template <int FORM>
 __global__ __launch_bounds__(256) void conv_prepare_filters_kernel(const PrepareArgs a)
 {
+    constexpr int NP = FORM == 0 ? 3 : 2;
     const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (id >= a.total) return;
     const int lane = (int)(id & 63);
@@ -75,6 +124,8 @@ __global__ __launch_bounds__(256) void conv_prepare_filters_kernel(const Prepare
     const int c0 = g * kGroup + ks * 16 + (lane >> 5) * 8;
     const int64_t nrow = n < a.N ? n : a.N - 1;
     uint32_t h[8], m[8], l[8];
+    float norm = 1.f;
+    if constexpr (FORM == 1) norm = norm_factor(a.exps[n]);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int c = c0 + i;
@@ -88,19 +139,29 @@ __global__ __launch_bounds__(256) void conv_prepare_filters_kernel(const Prepare
             const uint32_t word = a.w_bits[nrow * a.ldw + (k >> 5)];
             v = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, s) ^ (~(word >> (k & 31)) << 31));
         }
-        split3(live ? v : 0.f, h[i], m[i], l[i]);
+        if constexpr (FORM == 0) {
+            split3(live ? v : 0.f, h[i], m[i], l[i]);
+        } else {
+            split2_f16(live ? v * norm : 0.f, h[i], m[i]);
+            l[i] = 0;
+        }
     }
     u32x4 dh, dm, dl;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        dh[i] = pair16(h[2 * i], h[2 * i + 1]);
-        dm[i] = pair16(m[2 * i], m[2 * i + 1]);
-        dl[i] = pair16(l[2 * i], l[2 * i + 1]);
+        if constexpr (FORM == 0) {
+            dh[i] = pair16(h[2 * i], h[2 * i + 1]);
+            dm[i] = pair16(m[2 * i], m[2 * i + 1]);
+            dl[i] = pair16(l[2 * i], l[2 * i + 1]);
+        } else {
+            dh[i] = h[2 * i] | (h[2 * i + 1] << 16);
+            dm[i] = m[2 * i] | (m[2 * i + 1] << 16);
+        }
     }
-    unsigned char *dst = a.pieces + ((((int64_t)cb * a.groups + g) * a.KK + t) * 2 + ks) * (3 * kOperandBytes) + lane * 16;
+    unsigned char *dst = a.pieces + ((((int64_t)cb * a.groups + g) * a.KK + t) * 2 + ks) * (NP * kOperandBytes) + lane * 16;
     *reinterpret_cast<u32x4 *>(dst) = dh;
     *reinterpret_cast<u32x4 *>(dst + kOperandBytes) = dm;
-    *reinterpret_cast<u32x4 *>(dst + 2 * kOperandBytes) = dl;
+    if constexpr (FORM == 0) *reinterpret_cast<u32x4 *>(dst + 2 * kOperandBytes) = dl;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -111,6 +172,7 @@ struct ConvDirectArgs {
     const uint32_t *x_bits;
     const float *x_scales;
     const unsigned char *pieces;
+    const int32_t *exps;         // FORM 1: biased exponent per filter
     float *out;
     int32_t Y, yblocks;          // filters, and blocks of 32 of them in `pieces`
     int32_t beta_x, nseg, HS;    // activation segment length, segments per row ceil(W / beta_x), H * nseg
@@ -131,15 +193,19 @@ struct ConvDirectArgs {
 // NTY = 2 (128 filters): 2 x 4 wave tiles, each wave takes both MFMA steps of a stage;
 // NTY = 1 (64 filters): 2 x 2 wave tiles, waves 0-3 take the first step of every stage and waves 4-7 the
 //      second; the two halves are added through LDS at the end.
-template <int XI, int NTY>
+template <int XI, int NTY, int FORM>
 __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirectArgs a)
 {
+    constexpr int NP = FORM == 0 ? 3 : 2;            // pieces per number
+    constexpr int NQ = FORM == 0 ? 6 : 3;            // piece products per MFMA step
+    constexpr int kStageBytes = stage_bytes(FORM);
     constexpr int NT = 64 * NTY;
     constexpr int TX = 2;
     constexpr int WV = kThreadsD / 64;
     constexpr int KS = NTY == 1 ? 1 : 2;     // MFMA steps a wave takes per stage
     constexpr int kWavesY = NTY == 1 ? 2 : 4;   // waves side by side along the filters
     __shared__ __attribute__((aligned(16))) unsigned char sPatch[kPatchArea];
+    __shared__ uint32_t sMax[WV];                     // FORM 1: largest magnitude staged by each wave
 
     const int slot_id = (blockIdx.x % kNumXcdD) * a.slots_per_xcd + blockIdx.x / kNumXcdD;
     if (slot_id >= a.tiles_total) return;
@@ -194,7 +260,20 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
                 r.s[j][i] = *reinterpret_cast<const float *>(xs_bytes + (si << 2));
             }
     };
-    auto park_patch = [&](const PatchRegs &r, int g, unsigned char *buf) __attribute__((always_inline)) {
+    // FORM 1: the largest magnitude among the values this thread holds of group g (those that will be written)
+    auto patch_max = [&](const PatchRegs &r, int g) __attribute__((always_inline)) {
+        uint32_t mx = 0;
+#pragma unroll
+        for (int j = 0; j < XI; ++j)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int c = g * kGroup + poct[j] * 8 + i;
+                const uint32_t keep = c < a.C ? pkeep[j] : 0u;
+                mx = max(mx, __builtin_bit_cast(uint32_t, r.s[j][i]) & 0x7fffffffu & keep);
+            }
+        return mx;
+    };
+    auto park_patch = [&](const PatchRegs &r, int g, unsigned char *buf, float norm) __attribute__((always_inline)) {
         // (the element indices are recomputed rather than kept in registers since fetch_patch)
         asm volatile("" : "+s"(g));
 #pragma unroll
@@ -207,20 +286,30 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
                 const uint32_t e = (pe0[j] + (uint32_t)(c * a.HW)) & keep;
                 const uint32_t minus = (~(r.w[j][i] >> (e & 31)) << 31) & a.sign;
                 const uint32_t value = (__builtin_bit_cast(uint32_t, r.s[j][i]) ^ minus) & keep;
-                split3(__builtin_bit_cast(float, value), h[i], m[i], l[i]);
+                if constexpr (FORM == 0) {
+                    split3(__builtin_bit_cast(float, value), h[i], m[i], l[i]);
+                } else {
+                    split2_f16(__builtin_bit_cast(float, value) * norm, h[i], m[i]);
+                    l[i] = 0;
+                }
             }
             if (pdst[j] >= 0) {
                 u32x4 dh, dm, dl;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    dh[i] = pair16(h[2 * i], h[2 * i + 1]);
-                    dm[i] = pair16(m[2 * i], m[2 * i + 1]);
-                    dl[i] = pair16(l[2 * i], l[2 * i + 1]);
+                    if constexpr (FORM == 0) {
+                        dh[i] = pair16(h[2 * i], h[2 * i + 1]);
+                        dm[i] = pair16(m[2 * i], m[2 * i + 1]);
+                        dl[i] = pair16(l[2 * i], l[2 * i + 1]);
+                    } else {
+                        dh[i] = h[2 * i] | (h[2 * i + 1] << 16);
+                        dm[i] = m[2 * i] | (m[2 * i + 1] << 16);
+                    }
                 }
                 unsigned char *dst = buf + pdst[j];
                 *reinterpret_cast<u32x4 *>(dst) = dh;
                 *reinterpret_cast<u32x4 *>(dst + a.plane) = dm;
-                *reinterpret_cast<u32x4 *>(dst + 2 * a.plane) = dl;
+                if constexpr (FORM == 0) *reinterpret_cast<u32x4 *>(dst + 2 * a.plane) = dl;
             }
         }
     };
@@ -237,18 +326,18 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
     // filter operands of this wave's block of 32 filters: stage s at s * kStageBytes (a block past the last
     // one re-reads the last: its columns are never stored)
     const unsigned char *ysrc = a.pieces + (int64_t)min((y0 + wcol0) >> 5, a.yblocks - 1) * a.groups * a.KK * kStageBytes +
-                                ks0 * (3 * kOperandBytes) + lane * 16;
+                                ks0 * (NP * kOperandBytes) + lane * 16;
     const int nstages = a.groups * a.KK;
     struct FilterRegs {
-        bf16x8 f[KS][3];
+        u32x4 f[KS][NP];
     };
     auto fetch_filter = [&](FilterRegs &r, int stage) __attribute__((always_inline)) {
         const unsigned char *src = ysrc + (int64_t)min(stage, nstages - 1) * kStageBytes;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-            for (int p = 0; p < 3; ++p)
-                r.f[ks][p] = *reinterpret_cast<const bf16x8 *>(src + (ks * 3 + p) * kOperandBytes);
+            for (int p = 0; p < NP; ++p)
+                r.f[ks][p] = *reinterpret_cast<const u32x4 *>(src + (ks * NP + p) * kOperandBytes);
     };
 
     f32x16 res[TX];
@@ -257,13 +346,51 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
 #pragma unroll
         for (int v = 0; v < 16; ++v) res[tx][v] = 0.f;
 
-    const int patch_stride = a.patch_bufs == 2 ? 3 * a.plane : 0;
+    const int patch_stride = a.patch_bufs == 2 ? NP * a.plane : 0;
     PatchRegs xr;
     FilterRegs ya, yb, yc;
+    // FORM 1: e_run is the exponent that the patches staged so far are scaled by (it only grows)
+    int e_run = 14;
+    float norm = 1.f;
+    // Every wave publishes the largest magnitude it holds of group g; after a barrier all of them agree
+    // on the exponent.  If it grew, what has been accumulated so far is rescaled to the new unit.
+    auto publish_max = [&](int g) __attribute__((always_inline)) {
+        uint32_t mx = patch_max(xr, g);
+        mx = max(mx, dpp_u32<kDppQuadSwap1>(mx));
+        mx = max(mx, dpp_u32<kDppQuadSwap2>(mx));
+        mx = max(mx, dpp_u32<kDppHalfMirror>(mx));
+        mx = max(mx, dpp_u32<kDppRowMirror>(mx));
+        mx = max(mx, (uint32_t)__shfl_xor((int)mx, 16));
+        mx = max(mx, (uint32_t)__shfl_xor((int)mx, 32));
+        if (lane == 0) sMax[wave] = mx;
+    };
+    auto agree_on_exponent = [&]() __attribute__((always_inline)) {
+        uint32_t all = 0;
+#pragma unroll
+        for (int w = 0; w < WV; ++w) all = max(all, sMax[w]);
+        const int e_new = max(e_run, norm_exponent(__builtin_amdgcn_readfirstlane(all)));
+        if (e_new != e_run) {
+#pragma unroll
+            for (int tx = 0; tx < TX; ++tx)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) res[tx][v] = __builtin_amdgcn_ldexpf(res[tx][v], e_run - e_new);
+            e_run = e_new;
+        }
+        norm = norm_factor(e_run);
+    };
     fetch_patch(xr, 0);
     fetch_filter(ya, 0);
     fetch_filter(yb, 1);
-    park_patch(xr, 0, sPatch);
+    // FORM 1: lane l keeps the exponent of filter (l mod 32) of this wave's block for the store (requested here,
+    // where its latency costs nothing)
+    int filter_exp = 0;
+    if constexpr (FORM == 1) filter_exp = a.exps[min(y0 + wcol0 + (lane & 31), a.yblocks * 32 - 1)];
+    if constexpr (FORM == 1) {
+        publish_max(0);
+        __syncthreads();
+        agree_on_exponent();
+    }
+    park_patch(xr, 0, sPatch, norm);
     __syncthreads();
 
     int g = 0, t = 0, dz = 0, dy = 0, stage = 0;
@@ -276,20 +403,31 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
         // next stage then waits out their whole latency)
         __builtin_amdgcn_sched_barrier(0);
         const unsigned char *px = sPatch + (g & 1) * patch_stride + (dz * a.PW + dy) * kPixBytes;
+        // (FORM 1: the next group's largest magnitude is published before the last tap's multiplies, so that the
+        // exchange is over when the barrier after them is reached; a single tap has no earlier place)
+        if constexpr (FORM == 1)
+            if (more && a.KK > 1 && t == a.KK - 1) publish_max(g + 1);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            bf16x8 fx[3][TX];
+            u32x4 fx[NP][TX];
 #pragma unroll
-            for (int p = 0; p < 3; ++p)
-#pragma unroll
-                for (int tx = 0; tx < TX; ++tx)
-                    fx[p][tx] = *reinterpret_cast<const bf16x8 *>(px + p * a.plane + xoff[tx] + ks * 32);
-#pragma unroll
-            for (int q = 0; q < 6; ++q)
+            for (int p = 0; p < NP; ++p)
 #pragma unroll
                 for (int tx = 0; tx < TX; ++tx)
-                    res[tx] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[kPiecePairs[q][0]][tx], cur.f[ks][kPiecePairs[q][1]],
-                                                                      res[tx], 0, 0, 0);
+                    fx[p][tx] = *reinterpret_cast<const u32x4 *>(px + p * a.plane + xoff[tx] + ks * 32);
+#pragma unroll
+            for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                for (int tx = 0; tx < TX; ++tx) {
+                    if constexpr (FORM == 0)
+                        res[tx] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, fx[kPiecePairs[q][0]][tx]),
+                            __builtin_bit_cast(bf16x8, cur.f[ks][kPiecePairs[q][1]]), res[tx], 0, 0, 0);
+                    else
+                        res[tx] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                            __builtin_bit_cast(f16x8, fx[kPiecePairs2[q][0]][tx]),
+                            __builtin_bit_cast(f16x8, cur.f[ks][kPiecePairs2[q][1]]), res[tx], 0, 0, 0);
+                }
         }
         // the next group's activations: requested once the first tap's multiplies are queued, so that the
         // loads are the youngest in flight and nothing before the last tap waits for them
@@ -301,8 +439,14 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
         }
         if (++t == a.KK) {
             if (more) {
-                if (a.patch_bufs == 1) __syncthreads();   // every wave has read the last tap of this group
-                park_patch(xr, g + 1, sPatch + ((g + 1) & 1) * patch_stride);
+                if constexpr (FORM == 1) {
+                    if (a.KK == 1) publish_max(g + 1);
+                    __syncthreads();   // (also the barrier that a single patch buffer needs here)
+                    agree_on_exponent();
+                } else if (a.patch_bufs == 1) {
+                    __syncthreads();   // every wave has read the last tap of this group
+                }
+                park_patch(xr, g + 1, sPatch + ((g + 1) & 1) * patch_stride, norm);
                 __syncthreads();
             }
             t = dz = dy = 0;
@@ -335,6 +479,16 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
             for (int v = 0; v < 16; ++v) res[tx][v] += half[(tx * 16 + v) * 64 + lane];
     }
     float *turn = reinterpret_cast<float *>(sPatch) + wave * (32 * 33);
+    // FORM 1: back to the caller's units: 2^(e_run - 127 - 14) for the activations times the filter's own
+    int unscale[16];
+    if constexpr (FORM == 1) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            // column y0 + wcol0 + 2 j + (lane div 32)
+            const int e0 = __builtin_amdgcn_readlane(filter_exp, 2 * j), e1 = __builtin_amdgcn_readlane(filter_exp, 2 * j + 1);
+            unscale[j] = (lane < 32 ? e0 : e1) + e_run - 2 * (127 + kTargetExp);
+        }
+    }
 #pragma unroll
     for (int tx = 0; tx < TX; ++tx) {
         const int ml = wrow0 + tx * 32 + (lane & 31);
@@ -352,7 +506,10 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
         // (all reads first: under the store's condition each would be waited for on its own)
         float val[16];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) val[j] = turn[(lane & 31) * 33 + 2 * j + (lane >> 5)];
+        for (int j = 0; j < 16; ++j) {
+            val[j] = turn[(lane & 31) * 33 + 2 * j + (lane >> 5)];
+            if constexpr (FORM == 1) val[j] = __builtin_amdgcn_ldexpf(val[j], unscale[j]);
+        }
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const int col = y0 + wcol0 + 2 * j + (lane >> 5);
@@ -366,25 +523,32 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
 
 // Rows of output per workgroup: as many as fill 128 positions, fewer if the patch would not fit the LDS or
 // would take more than 5 staging items per thread; 0 if not even one row fits.
-int rows_per_tile(const ConvGeometry &g, int64_t OH, int64_t OW)
+int rows_per_tile(const ConvGeometry &g, int64_t OH, int64_t OW, int form)
 {
+    const int np = form == 0 ? 3 : 2;
     if (OW > 128) return 0;
     const int PW = (int)(OW - 1) * g.stride + g.KW;
     int R = (int)(128 / OW < OH ? 128 / OW : OH);
     auto pixels = [&](int r) { return ((r - 1) * g.stride + g.KH) * PW; };
-    while (R >= 1 && (4 * pixels(R) > kMaxItems * kThreadsD || 3 * pixels(R) * kPixBytes > kPatchArea)) --R;
+    while (R >= 1 && (4 * pixels(R) > kMaxItems * kThreadsD || np * pixels(R) * kPixBytes > kPatchArea)) --R;
     return R;
 }
 
 }  // namespace
 
-int64_t conv_filter_pieces_bytes(int64_t N, int64_t C, int KH, int KW)
+// Bytes of the pieces proper; FORM 1 appends one exponent (int32) per filter of the 32-filter blocks.
+static int64_t pieces_proper_bytes(int64_t N, int64_t C, int KH, int KW, int form)
 {
-    return ((N + 31) / 32) * ((C + kGroup - 1) / kGroup) * KH * KW * (int64_t)kStageBytes;
+    return ((N + 31) / 32) * ((C + kGroup - 1) / kGroup) * KH * KW * (int64_t)stage_bytes(form);
+}
+
+int64_t conv_filter_pieces_bytes(int64_t N, int64_t C, int KH, int KW, int form)
+{
+    return pieces_proper_bytes(N, C, KH, KW, form) + (form == 0 ? 0 : ((N + 31) / 32) * 32 * (int64_t)sizeof(int32_t));
 }
 
 hipError_t launch_conv_prepare_filters(const uint32_t *w_bits, const float *w_scales, int64_t ldw, int64_t lds, int beta,
-                                       int64_t N, int64_t C, int KH, int KW, void *pieces, hipStream_t s)
+                                       int64_t N, int64_t C, int KH, int KW, int form, void *pieces, hipStream_t s)
 {
     PrepareArgs a{};
     a.w_bits = w_bits; a.w_scales = w_scales; a.pieces = static_cast<unsigned char *>(pieces);
@@ -396,23 +560,33 @@ hipError_t launch_conv_prepare_filters(const uint32_t *w_bits, const float *w_sc
     a.total = ((N + 31) / 32) * a.groups * a.KK * 2 * 64;
     const int64_t blocks = (a.total + 255) / 256;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    conv_prepare_filters_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(a);
+    if (form == 0) {
+        conv_prepare_filters_kernel<0><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(a);
+        return hipGetLastError();
+    }
+    a.exps = reinterpret_cast<int32_t *>(a.pieces + pieces_proper_bytes(N, C, KH, KW, form));
+    const int64_t K = C * KH * KW;
+    a.nscales = (int32_t)(beta == 1 ? K : (K + beta - 1) / beta);
+    conv_filter_exponents_kernel<<<dim3((unsigned)((N + 31) / 32 * 32)), dim3(64), 0, s>>>(a);
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    conv_prepare_filters_kernel<1><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(a);
     return hipGetLastError();
 }
 
 bool conv_direct_fits(const ConvGeometry &g)
 {
     const int64_t OH = (g.H + 2 * g.pad - g.KH) / g.stride + 1, OW = (g.W + 2 * g.pad - g.KW) / g.stride + 1;
-    return rows_per_tile(g, OH, OW) >= 1;
+    return rows_per_tile(g, OH, OW, 0) >= 1;   // (the two-piece form needs less room)
 }
 
-hipError_t launch_conv_direct(const ConvActivations &x, const void *pieces, int64_t N, const ConvGeometry &g, float *out,
-                              hipStream_t s)
+hipError_t launch_conv_direct(const ConvActivations &x, const void *pieces, int64_t N, const ConvGeometry &g, int form,
+                              float *out, hipStream_t s)
 {
+    const int np = form == 0 ? 3 : 2;
     const int64_t OH = (g.H + 2 * g.pad - g.KH) / g.stride + 1, OW = (g.W + 2 * g.pad - g.KW) / g.stride + 1;
     const int KK = g.KH * g.KW;
     const int PW = (int)(OW - 1) * g.stride + g.KW;
-    int R = rows_per_tile(g, OH, OW);
+    int R = rows_per_tile(g, OH, OW, form);
     if (R < 1) return hipErrorNotSupported;
     const int tiles_per_image = (int)((OH + R - 1) / R);
     R = (int)((OH + tiles_per_image - 1) / tiles_per_image);   // even rows per tile
@@ -423,10 +597,10 @@ hipError_t launch_conv_direct(const ConvActivations &x, const void *pieces, int6
     int G = 1;
     if (tiles_per_image == 1)
         while ((G + 1) * R * OW <= 128 && G + 1 <= g.B && 4 * (G + 1) * PI <= kMaxItems * kThreadsD &&
-               2 * 3 * (G + 1) * PI * kPixBytes <= kPatchArea)
+               2 * np * (G + 1) * PI * kPixBytes <= kPatchArea)
             ++G;
     const int P = G * PI;
-    const int bufs = 2 * 3 * P * kPixBytes <= kPatchArea ? 2 : 1;
+    const int bufs = 2 * np * P * kPixBytes <= kPatchArea ? 2 : 1;
     const int64_t tiles_x = (g.B + G - 1) / G * tiles_per_image;
     // filters per tile: 128, or 64 when there are no more or when 128 would leave compute units without a workgroup
     const int nty = N <= 64 || tiles_x * ((N + 127) / 128) < 256 ? 1 : 2;
@@ -441,6 +615,7 @@ hipError_t launch_conv_direct(const ConvActivations &x, const void *pieces, int6
     a.x_scales = x.scales; a.sign = x.beta == 1 ? 0u : 0x80000000u;
     a.beta_x = x.beta; a.nseg = (int32_t)((g.W + x.beta - 1) / x.beta); a.HS = (int32_t)(g.H * a.nseg);
     a.pieces = static_cast<const unsigned char *>(pieces);
+    a.exps = reinterpret_cast<const int32_t *>(a.pieces + pieces_proper_bytes(N, g.C, g.KH, g.KW, form));
     a.out = out; a.Y = (int32_t)N; a.yblocks = (int32_t)((N + 31) / 32);
     a.C = (int32_t)g.C; a.H = (int32_t)g.H; a.W = (int32_t)g.W; a.HW = (int32_t)(g.H * g.W);
     a.OH = (int32_t)OH; a.OW = (int32_t)OW; a.OHW = (int32_t)(OH * OW);
@@ -455,12 +630,19 @@ hipError_t launch_conv_direct(const ConvActivations &x, const void *pieces, int6
     a.groups = (int32_t)((g.C + kGroup - 1) / kGroup);
     const int xi = (4 * P + threads - 1) / threads;
     const dim3 grid((unsigned)(per_xcd * kNumXcdD)), block(threads);
-#define HBMM_DIRECT_LAUNCH(I)                                        \
-    do {                                                             \
-        if (nty == 1)                                                \
-            conv_direct_kernel<I, 1><<<grid, block, 0, s>>>(a);      \
-        else                                                         \
-            conv_direct_kernel<I, 2><<<grid, block, 0, s>>>(a);      \
+#define HBMM_DIRECT_LAUNCH(I)                                           \
+    do {                                                                \
+        if (form == 0) {                                                \
+            if (nty == 1)                                               \
+                conv_direct_kernel<I, 1, 0><<<grid, block, 0, s>>>(a);  \
+            else                                                        \
+                conv_direct_kernel<I, 2, 0><<<grid, block, 0, s>>>(a);  \
+        } else {                                                        \
+            if (nty == 1)                                               \
+                conv_direct_kernel<I, 1, 1><<<grid, block, 0, s>>>(a);  \
+            else                                                        \
+                conv_direct_kernel<I, 2, 1><<<grid, block, 0, s>>>(a);  \
+        }                                                               \
     } while (0)
     if (xi <= 1)
         HBMM_DIRECT_LAUNCH(1);

@@ -108,19 +108,21 @@ hipError_t launch_mfma_split_conv(const ConvActivations &x, const SplitGemmOpera
                                   hipStream_t s);
 
 // ---- conv_direct.hip ---------------------------------------------------------------------------
-// The same layer with the filters prepared once (three bf16 pieces of every weight, in the order the
-// matrix cores consume them) and the activation fragments read straight from a patch in LDS.
+// The same layer with the filters prepared once (the pieces of every weight, in the order the matrix
+// cores consume them) and the activation fragments read straight from a patch in LDS.  form 0: three
+// bf16 pieces per number, six piece products (exact split); form 1: two fp16 pieces of the number scaled
+// by a power of two, three piece products (22 significant bits).
 // Bytes of the prepared form of N filters of C x KH x KW:
-int64_t conv_filter_pieces_bytes(int64_t N, int64_t C, int KH, int KW);
+int64_t conv_filter_pieces_bytes(int64_t N, int64_t C, int KH, int KW, int form);
 // Filters packed as rows of C*KH*KW with any beta in 2..256 (or beta = 1: w_scales is the fp32 filter
 // matrix itself, N x lds) -> pieces.
 hipError_t launch_conv_prepare_filters(const uint32_t *w_bits, const float *w_scales, int64_t ldw, int64_t lds, int beta,
-                                       int64_t N, int64_t C, int KH, int KW, void *pieces, hipStream_t s);
+                                       int64_t N, int64_t C, int KH, int KW, int form, void *pieces, hipStream_t s);
 // Whether the layer fits the kernel: output rows of at most 128 positions, and the input patch of one
 // output row within the LDS and the staging registers ((OW - 1) stride + KW) * KH <= 640 pixels).
 bool conv_direct_fits(const ConvGeometry &g);
-hipError_t launch_conv_direct(const ConvActivations &x, const void *pieces, int64_t N, const ConvGeometry &g, float *out,
-                              hipStream_t s);
+hipError_t launch_conv_direct(const ConvActivations &x, const void *pieces, int64_t N, const ConvGeometry &g, int form,
+                              float *out, hipStream_t s);
 
 // ---- gemm_mfma_i8.hip -------------------------------------------------------------------------
 hipError_t launch_mfma_i8_gemm(const uint32_t *a_bits, const float *a_scales, int64_t ldw_a,

@@ -61,11 +61,11 @@ def _load() -> C.CDLL:
     lib.hbmm_conv2d.restype = C.c_int
     lib.hbmm_conv2d.argtypes = [p, p, i32, p, p, i64, i64, i32, i64, i64, i64, i64, i64, i32, i32, i32, i32, p, i32, p]
     lib.hbmm_conv_filter_pieces_bytes.restype = i64
-    lib.hbmm_conv_filter_pieces_bytes.argtypes = [i64, i64, i32, i32]
+    lib.hbmm_conv_filter_pieces_bytes.argtypes = [i64, i64, i32, i32, i32]
     lib.hbmm_conv_prepare_filters.restype = C.c_int
-    lib.hbmm_conv_prepare_filters.argtypes = [p, p, i64, i64, i32, i64, i64, i32, i32, p, p]
+    lib.hbmm_conv_prepare_filters.argtypes = [p, p, i64, i64, i32, i64, i64, i32, i32, i32, p, p]
     lib.hbmm_conv2d_prepared.restype = C.c_int
-    lib.hbmm_conv2d_prepared.argtypes = [p, p, i32, p, i64, i64, i64, i64, i64, i32, i32, i32, i32, p, p]
+    lib.hbmm_conv2d_prepared.argtypes = [p, p, i32, p, i32, i64, i64, i64, i64, i64, i32, i32, i32, i32, p, p]
     lib.hbmm_quantize_pack_activations.restype = C.c_int
     lib.hbmm_quantize_pack_activations.argtypes = [p, i64, i64, i32, p, p, p]
     lib.hbmm_probe_mfma_rate.restype = C.c_int
@@ -346,20 +346,26 @@ def quantize_pack_activations(x: torch.Tensor, beta: int, bits: torch.Tensor | N
     return bits, scales
 
 
-def conv_filter_pieces_bytes(N: int, C: int, KH: int, KW: int) -> int:
-    return int(lib.hbmm_conv_filter_pieces_bytes(N, C, KH, KW))
+PIECES_BF16X3, PIECES_F16X2 = 0, 1   # `form` of the prepared convolution: exact three-piece split / two fp16 pieces
 
 
-def conv_prepare_filters(w_bits, w_scales, beta_w: int, C: int, kernel, pieces: torch.Tensor | None = None) -> torch.Tensor:
+def conv_filter_pieces_bytes(N: int, C: int, KH: int, KW: int, form: int = PIECES_BF16X3) -> int:
+    return int(lib.hbmm_conv_filter_pieces_bytes(N, C, KH, KW, form))
+
+
+def conv_prepare_filters(w_bits, w_scales, beta_w: int, C: int, kernel, pieces: torch.Tensor | None = None,
+                         form: int = PIECES_BF16X3) -> torch.Tensor:
     """hbmm_conv_prepare_filters: filters (N, C, KH, KW) packed by quantize_pack on the N x (C*KH*KW) matrix
     (or, with beta_w = 1, w_bits=None and w_scales = that fp32 matrix) -> the prepared form, a flat uint8
-    device tensor of conv_filter_pieces_bytes(N, C, KH, KW) bytes."""
+    device tensor of conv_filter_pieces_bytes(N, C, KH, KW, form) bytes."""
     if w_bits is not None:
         _dev(w_bits, torch.int32, "w_bits")
     _dev(w_scales, torch.float32, "w_scales")
     KH, KW = (int(v) for v in kernel)
     N, ldw_w, lds_w = check_gemm_operand(w_bits, w_scales, beta_w, C * KH * KW, "w")
-    nbytes = conv_filter_pieces_bytes(N, C, KH, KW)
+    if form not in (PIECES_BF16X3, PIECES_F16X2):
+        raise ValueError(f"form: {form} is neither PIECES_BF16X3 nor PIECES_F16X2")
+    nbytes = conv_filter_pieces_bytes(N, C, KH, KW, form)
     if nbytes == 0 and N > 0 and C > 0:
         raise ValueError(f"filters: unsupported shape {(N, C, KH, KW)}")
     if pieces is None:
@@ -368,15 +374,15 @@ def conv_prepare_filters(w_bits, w_scales, beta_w: int, C: int, kernel, pieces: 
     if pieces.dim() != 1 or pieces.numel() < nbytes or not pieces.is_contiguous():
         raise ValueError(f"pieces: a flat contiguous tensor of at least {nbytes} bytes is written")
     rc = lib.hbmm_conv_prepare_filters(w_bits.data_ptr() if w_bits is not None else 0, w_scales.data_ptr(), ldw_w, lds_w,
-                                       beta_w, N, C, KH, KW, pieces.data_ptr(), _stream())
+                                       beta_w, N, C, KH, KW, form, pieces.data_ptr(), _stream())
     _check(rc, "hbmm_conv_prepare_filters")
     return pieces
 
 
 def conv2d_prepared(a_bits, a_scales, beta_a: int, shape, pieces: torch.Tensor, N: int, kernel, stride: int = 1,
-                    pad: int = 0, out: torch.Tensor | None = None) -> torch.Tensor:
+                    pad: int = 0, out: torch.Tensor | None = None, form: int = PIECES_BF16X3) -> torch.Tensor:
     """hbmm_conv2d_prepared: activations as for conv2d, filters as written by conv_prepare_filters for the
-    same N, C = shape[1] and kernel = (KH, KW)."""
+    same N, C = shape[1], kernel = (KH, KW) and form."""
     if a_bits is not None:
         _dev(a_bits, torch.int32, "a_bits")
     _dev(a_scales, torch.float32, "a_scales")
@@ -384,7 +390,9 @@ def conv2d_prepared(a_bits, a_scales, beta_a: int, shape, pieces: torch.Tensor, 
     B, Cc, H, W = (int(v) for v in shape)
     KH, KW = (int(v) for v in kernel)
     count = B * Cc * H * W
-    if not pieces.is_contiguous() or pieces.numel() < conv_filter_pieces_bytes(N, Cc, KH, KW):
+    if form not in (PIECES_BF16X3, PIECES_F16X2):
+        raise ValueError(f"form: {form} is neither PIECES_BF16X3 nor PIECES_F16X2")
+    if not pieces.is_contiguous() or pieces.numel() < conv_filter_pieces_bytes(N, Cc, KH, KW, form):
         raise ValueError(f"pieces: too few bytes for {N} filters of {(Cc, KH, KW)}")
     if not a_scales.is_contiguous() or (a_bits is not None and not a_bits.is_contiguous()):
         raise ValueError("the packed activation tensor must be contiguous")
@@ -398,7 +406,7 @@ def conv2d_prepared(a_bits, a_scales, beta_a: int, shape, pieces: torch.Tensor, 
     if tuple(out.shape) != (B, N, OH, OW) or not out.is_contiguous():
         raise ValueError(f"out: a contiguous tensor of shape {(B, N, OH, OW)} is written")
     rc = lib.hbmm_conv2d_prepared(a_bits.data_ptr() if a_bits is not None else 0, a_scales.data_ptr(), beta_a,
-                                  pieces.data_ptr(), B, Cc, H, W, N, KH, KW, stride, pad, out.data_ptr(), _stream())
+                                  pieces.data_ptr(), form, B, Cc, H, W, N, KH, KW, stride, pad, out.data_ptr(), _stream())
     _check(rc, "hbmm_conv2d_prepared")
     return out
 

@@ -18,15 +18,15 @@ hipError_t launch_popcount_gemm(const PopcountGemmArgs &, int, int, hipStream_t)
 hipError_t launch_mfma_split_gemm(const SplitGemmOperand &, const SplitGemmOperand &, int64_t, float *, int64_t, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_mfma_split_any(const SplitGemmOperand &, const SplitGemmOperand &, int64_t, float *, int64_t, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_mfma_split_conv(const ConvActivations &, const SplitGemmOperand &, const ConvGeometry &, float *, hipStream_t) { ++g_launches; return hipSuccess; }
-int64_t conv_filter_pieces_bytes(int64_t N, int64_t C, int KH, int KW) { return ((N + 31) / 32) * ((C + 31) / 32) * KH * KW * 6144; }
-hipError_t launch_conv_prepare_filters(const uint32_t *, const float *, int64_t, int64_t, int, int64_t, int64_t, int, int, void *, hipStream_t) { ++g_launches; return hipSuccess; }
+int64_t conv_filter_pieces_bytes(int64_t N, int64_t C, int KH, int KW, int form) { return ((N + 31) / 32) * ((C + 31) / 32) * KH * KW * (form ? 4096 : 6144) + (form ? (N + 31) / 32 * 128 : 0); }
+hipError_t launch_conv_prepare_filters(const uint32_t *, const float *, int64_t, int64_t, int, int64_t, int64_t, int, int, int, void *, hipStream_t) { ++g_launches; return hipSuccess; }
 bool conv_direct_fits(const ConvGeometry &g)
 {
     // the documented limits: OW <= 128 and ((OW - 1) * stride + KW) * KH <= 640
     const int64_t OW = (g.W + 2 * g.pad - g.KW) / g.stride + 1;
     return OW <= 128 && ((OW - 1) * g.stride + g.KW) * g.KH <= 640;
 }
-hipError_t launch_conv_direct(const ConvActivations &, const void *, int64_t, const ConvGeometry &, float *, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_conv_direct(const ConvActivations &, const void *, int64_t, const ConvGeometry &, int, float *, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_mfma_i8_gemm(const uint32_t *, const float *, int64_t, int64_t, int, const uint32_t *, const float *, int64_t, int64_t, int, int64_t, int64_t, int64_t, float *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_mfma_fp4_gemm(const uint32_t *, const float *, int64_t, int64_t, int, const uint32_t *, const float *, int64_t, int64_t, int, int64_t, int64_t, int64_t, float *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_mfma_fp8_gemm(const uint32_t *, const float *, int64_t, int64_t, int, const uint32_t *, const float *, int64_t, int64_t, int, int64_t, int64_t, int64_t, float *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }

@@ -182,12 +182,19 @@ def test_validation_of_the_fused_tensor_and_convolution_entry_points(lib):
 
     # the prepared-filter form
     nb = lib.hbmm_conv_filter_pieces_bytes
-    nb.restype, nb.argtypes = i64, [i64, i64, i32, i32]
-    assert nb(128, 128, 3, 3) == 128 * 128 * 9 * 6
-    assert nb(40, 20, 3, 3) == 64 * 32 * 9 * 6          # filters rounded up to 32, channels to 32
-    assert nb(8, 8, 0, 3) == 0 and nb(-1, 8, 3, 3) == 0 and nb(8, 8, 40, 3) == 0
-    pf = lib.hbmm_conv_prepare_filters
-    pf.argtypes = [p, p, i64, i64, i32, i64, i64, i32, i32, p, p]
+    nb.restype, nb.argtypes = i64, [i64, i64, i32, i32, i32]
+    assert nb(128, 128, 3, 3, 0) == 128 * 128 * 9 * 6
+    assert nb(40, 20, 3, 3, 0) == 64 * 32 * 9 * 6          # filters rounded up to 32, channels to 32
+    assert nb(40, 20, 3, 3, 1) == 64 * 32 * 9 * 4 + 64 * 4   # two fp16 pieces and one exponent per filter
+    assert nb(8, 8, 0, 3, 0) == 0 and nb(-1, 8, 3, 3, 0) == 0 and nb(8, 8, 40, 3, 0) == 0
+    assert nb(8, 8, 3, 3, 2) == 0 and nb(8, 8, 3, 3, -1) == 0     # no such form
+    pf_raw = lib.hbmm_conv_prepare_filters
+    pf_raw.argtypes = [p, p, i64, i64, i32, i64, i64, i32, i32, i32, p, p]
+    assert pf_raw(fake, fake, 12, 9, 32, 8, 32, 3, 3, 2, fake, None) == -2      # no such form
+    assert pf_raw(fake, fake, 12, 9, 32, 8, 32, 3, 3, 1, None, None) == -1
+
+    def pf(*a):
+        return pf_raw(*a[:9], 0, *a[9:])
     assert pf(fake, fake, 12, 9, 32, 8, 32, 3, 3, None, None) == -1        # no output buffer
     assert pf(fake, fake, 12, 8, 32, 8, 32, 3, 3, fake, None) == -1        # lds_w < ceil(K / beta_w)
     assert pf(fake, fake, 12, 57, 5, 8, 32, 3, 3, fake, None) == -1        # beta_w = 5: 58 scales per filter
@@ -206,14 +213,16 @@ def test_validation_of_the_fused_tensor_and_convolution_entry_points(lib):
     assert qa(fake, 1 << 20, 1 << 20, 4, fake, fake, None) == -1   # more than 2^31 elements
     assert qa(None, 0, 7, 4, None, None, None) == 0
     cp = lib.hbmm_conv2d_prepared
-    cp.argtypes = [p, p, i32, p, i64, i64, i64, i64, i64, i32, i32, i32, i32, p, p]
-    okp = dict(ab=fake, asc=fake, ba=4, pieces=fake, B=1, C=32, H=8, W=8, N=8, KH=3, KW=3, stride=1, pad=1, out=fake)
+    cp.argtypes = [p, p, i32, p, i32, i64, i64, i64, i64, i64, i32, i32, i32, i32, p, p]
+    okp = dict(ab=fake, asc=fake, ba=4, pieces=fake, form=0, B=1, C=32, H=8, W=8, N=8, KH=3, KW=3, stride=1, pad=1, out=fake)
 
     def convp(**kw):
         a = {**okp, **kw}
-        return cp(a["ab"], a["asc"], a["ba"], a["pieces"], a["B"], a["C"], a["H"], a["W"], a["N"], a["KH"], a["KW"],
+        return cp(a["ab"], a["asc"], a["ba"], a["pieces"], a["form"], a["B"], a["C"], a["H"], a["W"], a["N"], a["KH"], a["KW"],
                   a["stride"], a["pad"], a["out"], None)
 
+    assert convp(form=2) == -2 and convp(form=-1) == -2
+    assert convp(form=1, pieces=None) == -1
     assert convp(ba=300) == -2               # beta_a above 256 (any other beta_a goes, also one that does not divide the width)
     assert convp(W=200, pad=1) == -2         # an output row of 200 positions does not fit a tile
     assert convp(W=128, KH=5, KW=5, pad=2) == -2   # the patch of one output row: 132 x 5 pixels
@@ -337,7 +346,7 @@ def test_binding_entry_points_validate_before_the_call(monkeypatch):
     with pytest.raises(ValueError):
         hbmm.conv2d(act_bits, act_scales, 4, (1, 4, 8, 8), bits, scales, 32, (4, 8), 1, 0, out=torch.zeros((1, 6, 5, 2)))   # out is 1 x 6 x 5 x 1
     # the prepared-filter layer and the activation packing for widths that beta does not divide
-    monkeypatch.setattr(hbmm, "conv_filter_pieces_bytes", lambda N, C, KH, KW: (N + 31) // 32 * ((C + 31) // 32) * KH * KW * 6144)
+    monkeypatch.setattr(hbmm, "conv_filter_pieces_bytes", lambda N, C, KH, KW, form=0: (N + 31) // 32 * ((C + 31) // 32) * KH * KW * 6144)
     pieces = torch.zeros(6144 * 2 * 9, dtype=torch.uint8)          # 40 filters of 20 x 3 x 3: two blocks of 32, one channel group
     x7 = torch.zeros((2, 20, 7, 7))
     a7_bits, a7_scales = torch.zeros((2 * 20 * 49 + 31) // 32, dtype=torch.int32), torch.zeros(2 * 20 * 7 * 2)

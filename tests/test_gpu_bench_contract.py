@@ -66,6 +66,8 @@ def test_bench_comparison_rows_carry_a_bound_and_a_fraction():
             assert e["roofline"]["bound"] == "mfma" and 0 < e["roofline"]["frac"] < 1.0, name
         assert "conv_prepared_error" not in e, (name, e)
         assert e["roofline_prepared"]["piece_products"] == 6 and 0 < e["roofline_prepared"]["frac"] < 1.0, name
+        assert e["roofline_prepared_f16x2"]["piece_products"] == 3 and 0 < e["roofline_prepared_f16x2"]["frac"] < 1.0, name
+        assert 0 < e["conv_prepared_f16x2_ms"] < e["conv_prepared_ms"], name
     # the sustained matrix-core rate lies below the published peak and above half of it
     assert 0.4 * 2500 < cmp_["mfma_bf16_sustained_TFLOPs"] < 2500
     assert 0 < cmp_["binarize_backward"]["frac_of_hbm_peak"] < 1.2

@@ -944,6 +944,78 @@ def test_conv_prepare_filters_is_exact(N, C, KH, KW, beta_w):
     assert not got[N:].any() and not got[:, C:].any()
 
 
+def _decode_filter_pieces_f16(pieces: np.ndarray, N, C, KH, KW):
+    """The two-piece form back to numbers: per block of 32 filters, channel group, tap, step and piece, 64 lanes x
+    8 fp16, then one int32 exponent per filter.  Returns (hi + mid scaled back by the filter's power of two, as
+    float64, shape (N rounded up to 32, C rounded up to 32, KH, KW); the pieces themselves; the exponents)."""
+    nb, G, KK = -(-N // 32), -(-C // 32), KH * KW
+    body = nb * G * KK * 2 * 2 * 64 * 16
+    raw = pieces[:body].view(np.float16).reshape(nb, G, KK, 2, 2, 64, 8).astype(np.float64)
+    exps = pieces[body:].view(np.int32)
+    assert exps.size == nb * 32
+    val = raw.sum(axis=4).reshape(nb, G, KK, 2, 2, 32, 8)        # lane = half * 32 + filter
+    out = val.transpose(0, 5, 1, 3, 4, 6, 2).reshape(nb * 32, G * 32, KH, KW)
+    return out * np.ldexp(1.0, exps - 141)[:, None, None, None], raw, exps
+
+
+@pytest.mark.parametrize("N,C,KH,KW,beta_w", [(40, 32, 3, 3, 32), (130, 64, 1, 1, 64), (7, 20, 3, 3, 4), (33, 48, 2, 3, 7),
+                                              (64, 96, 3, 3, 1), (5, 3, 5, 5, 25)])
+def test_conv_prepare_filters_two_fp16_pieces(N, C, KH, KW, beta_w):
+    """The two-piece form: every filter scaled by the power of two that brings its largest magnitude into
+    [2^14, 2^15), the scaled value rounded to fp16 and the remainder rounded to fp16 again: 22 significant
+    bits, i.e. within 2^-22 of delta_w * Sign(w) (Eq. 1-2), or within half of fp16's smallest subnormal of the
+    scaled value."""
+    Wf = synth.normal(8100 + N + C, (N, C, KH, KW)).astype(np.float32)
+    Wf[0] *= np.float32(2.0 ** -60)
+    Wf[N - 1] *= np.float32(2.0 ** 70)
+    Wf[N // 2, 0] *= np.float32(2.0 ** -30)      # a channel far below the filter's largest: subnormal remainders
+    K = C * KH * KW
+    if beta_w == 1:
+        pieces = hbmm.conv_prepare_filters(None, dev(Wf.reshape(N, K)), 1, C, (KH, KW), form=hbmm.PIECES_F16X2)
+        want = Wf.astype(np.float64)
+    else:
+        flat = Wf.reshape(N, K)
+        wb, ws = dev(oracle.sign_pack(flat).view(np.int32)), dev(oracle.block_scales(flat, beta_w))
+        pieces = hbmm.conv_prepare_filters(wb, ws, beta_w, C, (KH, KW), form=hbmm.PIECES_F16X2)
+        want = oracle.materialize_filters(Wf, beta_w)
+    nb = -(-N // 32)
+    assert pieces.numel() == hbmm.conv_filter_pieces_bytes(N, C, KH, KW, hbmm.PIECES_F16X2) \
+        == nb * 32 * -(-C // 32) * 32 * KH * KW * 4 + nb * 32 * 4
+    got, raw, exps = _decode_filter_pieces_f16(pieces.cpu().numpy(), N, C, KH, KW)
+    top = np.abs(want).reshape(N, -1).max(axis=1)
+    assert np.array_equal(exps[:N], np.frexp(top)[1] - 1 + 127)           # the biased exponent of the largest magnitude
+    assert np.all(np.isfinite(raw)) and np.abs(raw).max() < 2.0 ** 15
+    unit = np.ldexp(1.0, exps[:N] - 141)[:, None, None, None]              # one scaled unit in the filter's own units
+    err = np.abs(got[:N, :C] - want)
+    assert np.all(err <= np.maximum(2.0 ** -22 * np.abs(want), 2.0 ** -25 * unit))
+    assert not got[N:].any() and not got[:, C:].any()
+
+
+@pytest.mark.parametrize("beta_a", [1, 4])
+def test_conv2d_two_piece_form_follows_the_largest_magnitude(beta_a):
+    """The two-piece form scales the activations by the exponent of the largest magnitude staged so far.  Channel
+    groups that differ by many orders of magnitude in both directions (the exponent rises in a later group: the
+    partial sums are rescaled; it falls: the later group is written on the coarser grid), whole tensors near
+    the ends of the fp32 range, and an image that is all zeros."""
+    B, C, H, W, N, KH, KW = 3, 128, 10, 12, 40, 3, 3
+    A, Wf = _conv_inputs(8700 + beta_a, B, C, H, W, N, KH, KW)
+    A[0, 32:64] *= 2.0 ** 20      # image 0: the second group is far larger than the first
+    A[0, 96:] *= 2.0 ** -20       #          and the last far smaller
+    A[1] *= 2.0 ** -100           # image 1: tiny throughout ...
+    Wf[:N // 2] *= 2.0 ** 80      #          ... against large filters
+    A[2] = 0.0
+    A, Wf = A.astype(np.float32), Wf.astype(np.float32)
+    for beta_w in (4, 32):
+        ref, T = oracle.hbmm_conv2d(A, Wf, beta_a, beta_w, 1, 1, want_T=True)
+        ab, asc = (None, dev(A)) if beta_a == 1 else hbmm.quantize_pack_activations(dev(A), beta_a)
+        wb, ws = hbmm.quantize_pack(dev(Wf.reshape(N, -1)), beta_w)
+        for form in (hbmm.PIECES_BF16X3, hbmm.PIECES_F16X2):
+            pieces = hbmm.conv_prepare_filters(wb, ws, beta_w, C, (KH, KW), form=form)
+            out = hbmm.conv2d_prepared(ab, asc, beta_a, A.shape, pieces, N, (KH, KW), 1, 1, form=form).cpu().numpy()
+            assert np.all(np.isfinite(out)) and not out[2].any()
+            assert_close_to_oracle(out, ref, T, f"dynamic range beta_a {beta_a} beta_w {beta_w} form {form}")
+
+
 PREPARED_CONV_CASES = CONV_CASES + [
     # B, C, H, W, N, KH, KW, stride, pad, beta_a, beta_w
     (2, 20, 8, 8, 40, 3, 3, 1, 1, 4, 5),        # channels not a multiple of 32, K = 180 not a multiple of 32, beta_w = 5
@@ -958,32 +1030,34 @@ PREPARED_CONV_CASES = CONV_CASES + [
 ]
 
 
+@pytest.mark.parametrize("form", [0, 1], ids=["bf16x3", "f16x2"])
 @pytest.mark.parametrize("case", PREPARED_CONV_CASES, ids=lambda c: "x".join(str(v) for v in c))
-def test_conv2d_prepared(case):
+def test_conv2d_prepared(case, form):
     B, C, H, W, N, KH, KW, stride, pad, beta_a, beta_w = case
     A, Wf = _conv_inputs(8200 + B + C + N, B, C, H, W, N, KH, KW)
     A[0, 0, 0, :2] = [0.0, -0.0]
     ab, asc = hbmm.quantize_pack_tensor(dev(A), beta_a)
     wb, ws = hbmm.quantize_pack(dev(Wf.reshape(N, -1)), beta_w)
-    pieces = hbmm.conv_prepare_filters(wb, ws, beta_w, C, (KH, KW))
+    pieces = hbmm.conv_prepare_filters(wb, ws, beta_w, C, (KH, KW), form=form)
     OW = (W + 2 * pad - KW) // stride + 1
     if OW > 128 or ((OW - 1) * stride + KW) * KH > 640:
         with pytest.raises(hbmm.HbmmError) as ei:
-            hbmm.conv2d_prepared(ab, asc, beta_a, A.shape, pieces, N, (KH, KW), stride, pad)
+            hbmm.conv2d_prepared(ab, asc, beta_a, A.shape, pieces, N, (KH, KW), stride, pad, form=form)
         assert ei.value.code == hbmm.EUNSUPPORTED
         return
     ref, T = oracle.hbmm_conv2d(A, Wf, beta_a, beta_w, stride, pad, want_T=True)
-    out = hbmm.conv2d_prepared(ab, asc, beta_a, A.shape, pieces, N, (KH, KW), stride, pad)
+    out = hbmm.conv2d_prepared(ab, asc, beta_a, A.shape, pieces, N, (KH, KW), stride, pad, form=form)
     assert tuple(out.shape) == ref.shape
-    assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d_prepared {case}")
+    assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d_prepared {case} form {form}")
     # a fixed summation order: a second call gives the same bits
-    assert torch.equal(out, hbmm.conv2d_prepared(ab, asc, beta_a, A.shape, pieces, N, (KH, KW), stride, pad))
+    assert torch.equal(out, hbmm.conv2d_prepared(ab, asc, beta_a, A.shape, pieces, N, (KH, KW), stride, pad, form=form))
 
 
 @pytest.mark.parametrize("case", [(2, 32, 8, 8, 40, 3, 3, 1, 1, 32), (1, 64, 12, 12, 70, 1, 1, 1, 0, 64),
                                   (2, 32, 9, 16, 24, 3, 3, 2, 1, 4), (1, 64, 12, 12, 140, 3, 3, 1, 1, 8),
                                   (2, 24, 10, 10, 30, 3, 3, 1, 1, 1)], ids=str)
-def test_conv2d_prepared_unquantised_operands(case):
+@pytest.mark.parametrize("form", [0, 1], ids=["bf16x3", "f16x2"])
+def test_conv2d_prepared_unquantised_operands(case, form):
     """beta_a = 1: activations stay fp32 (the paper's binary-weight layers, Tables 2-3); the last case also
     leaves the filters unquantised (beta_w = 1), i.e. a plain fp32 convolution through the same kernel."""
     B, C, H, W, N, KH, KW, stride, pad, beta_w = case
@@ -992,12 +1066,12 @@ def test_conv2d_prepared_unquantised_operands(case):
     Wf = synth.normal(8301 + C, (N, C, KH, KW)).astype(np.float32)
     ref, T = oracle.hbmm_conv2d(A, Wf, 1, beta_w, stride, pad, want_T=True)
     if beta_w == 1:
-        pieces = hbmm.conv_prepare_filters(None, dev(Wf.reshape(N, -1)), 1, C, (KH, KW))
+        pieces = hbmm.conv_prepare_filters(None, dev(Wf.reshape(N, -1)), 1, C, (KH, KW), form=form)
     else:
         wb, ws = hbmm.quantize_pack(dev(Wf.reshape(N, -1)), beta_w)
-        pieces = hbmm.conv_prepare_filters(wb, ws, beta_w, C, (KH, KW))
-    out = hbmm.conv2d_prepared(None, dev(A), 1, A.shape, pieces, N, (KH, KW), stride, pad)
-    assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d_prepared unquantised {case}")
+        pieces = hbmm.conv_prepare_filters(wb, ws, beta_w, C, (KH, KW), form=form)
+    out = hbmm.conv2d_prepared(None, dev(A), 1, A.shape, pieces, N, (KH, KW), stride, pad, form=form)
+    assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d_prepared unquantised {case} form {form}")
 
 
 @pytest.mark.parametrize("shape,beta", [((2, 3, 7, 7), 4), ((2, 3, 7, 7), 2), ((1, 5, 14, 14), 4), ((3, 2, 5, 9), 3), ((1, 1, 1, 1), 2),
@@ -1034,19 +1108,20 @@ RAGGED_WIDTH_CONV_CASES = [
 ]
 
 
+@pytest.mark.parametrize("form", [0, 1], ids=["bf16x3", "f16x2"])
 @pytest.mark.parametrize("case", RAGGED_WIDTH_CONV_CASES, ids=lambda c: "x".join(str(v) for v in c))
-def test_conv2d_prepared_width_not_a_multiple_of_beta_a(case):
+def test_conv2d_prepared_width_not_a_multiple_of_beta_a(case, form):
     """Eq. 3 on widths that beta_a does not divide: hbmm_quantize_pack_activations + hbmm_conv2d_prepared against
     the oracle's layer."""
     B, C, H, W, N, KH, KW, stride, pad, beta_a, beta_w = case
     A, Wf = _conv_inputs(8600 + B + C + N, B, C, H, W, N, KH, KW)
     ab, asc = hbmm.quantize_pack_activations(dev(A), beta_a)
     wb, ws = hbmm.quantize_pack(dev(Wf.reshape(N, -1)), beta_w)
-    pieces = hbmm.conv_prepare_filters(wb, ws, beta_w, C, (KH, KW))
+    pieces = hbmm.conv_prepare_filters(wb, ws, beta_w, C, (KH, KW), form=form)
     ref, T = oracle.hbmm_conv2d(A, Wf, beta_a, beta_w, stride, pad, want_T=True)
-    out = hbmm.conv2d_prepared(ab, asc, beta_a, A.shape, pieces, N, (KH, KW), stride, pad)
+    out = hbmm.conv2d_prepared(ab, asc, beta_a, A.shape, pieces, N, (KH, KW), stride, pad, form=form)
     assert tuple(out.shape) == ref.shape
-    assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d_prepared ragged width {case}")
+    assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d_prepared ragged width {case} form {form}")
 
 
 def _random_prepared_conv_cases(n, seed):
@@ -1067,8 +1142,9 @@ def _random_prepared_conv_cases(n, seed):
     return cases
 
 
+@pytest.mark.parametrize("form", [0, 1], ids=["bf16x3", "f16x2"])
 @pytest.mark.parametrize("case", _random_prepared_conv_cases(32, 20260105), ids=lambda c: "x".join(str(v) for v in c))
-def test_conv2d_prepared_seeded_random_sweep(case):
+def test_conv2d_prepared_seeded_random_sweep(case, form):
     """Layer geometries, channel counts, widths and segment lengths (any beta_w in 1..64, beta_a from 1 to 16,
     dividing the width or not) drawn from a fixed seed."""
     B, C, H, W, N, KH, KW, stride, pad, beta_a, beta_w = case
@@ -1076,13 +1152,13 @@ def test_conv2d_prepared_seeded_random_sweep(case):
     ref, T = oracle.hbmm_conv2d(A, Wf, beta_a, beta_w, stride, pad, want_T=True)
     ab, asc = (None, dev(A)) if beta_a == 1 else hbmm.quantize_pack_activations(dev(A), beta_a)
     if beta_w == 1:
-        pieces = hbmm.conv_prepare_filters(None, dev(Wf.reshape(N, -1)), 1, C, (KH, KW))
+        pieces = hbmm.conv_prepare_filters(None, dev(Wf.reshape(N, -1)), 1, C, (KH, KW), form=form)
     else:
         wb, ws = hbmm.quantize_pack(dev(Wf.reshape(N, -1)), beta_w)
-        pieces = hbmm.conv_prepare_filters(wb, ws, beta_w, C, (KH, KW))
-    out = hbmm.conv2d_prepared(ab, asc, beta_a, A.shape, pieces, N, (KH, KW), stride, pad)
+        pieces = hbmm.conv_prepare_filters(wb, ws, beta_w, C, (KH, KW), form=form)
+    out = hbmm.conv2d_prepared(ab, asc, beta_a, A.shape, pieces, N, (KH, KW), stride, pad, form=form)
     assert tuple(out.shape) == ref.shape
-    assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d_prepared sweep {case}")
+    assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d_prepared sweep {case} form {form}")
 
 
 def test_conv2d_equals_gemm_on_im2col():

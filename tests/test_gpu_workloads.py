@@ -138,3 +138,10 @@ def test_conv_workload(hbmm, name, batch):
     worst_p = assert_close_to_oracle(got_p, ref, T, name + " (prepared filters)")
     print(f"[{name}] prepared filters ok, worst err/(1e-5 T) = {worst_p:.3f}, worst plain relative error = "
           f"{plain_relative_error(got_p, ref):.2e}", flush=True)
+    # ... and in the two-piece form (two fp16 pieces per number, 22 significant bits): the same bar
+    prepared = hbmm.conv_prepare_filters(wb, ws, w.beta_w, w.C, (w.KH, w.KW), form=hbmm.PIECES_F16X2)
+    got_2 = hbmm.conv2d_prepared(ab, asc, w.beta_a, A.shape, prepared, w.N, (w.KH, w.KW), w.stride, w.pad,
+                                 form=hbmm.PIECES_F16X2).cpu().numpy()
+    worst_2 = assert_close_to_oracle(got_2, ref, T, name + " (prepared filters, two fp16 pieces)")
+    print(f"[{name}] two fp16 pieces ok, worst err/(1e-5 T) = {worst_2:.3f}, worst plain relative error = "
+          f"{plain_relative_error(got_2, ref):.2e}", flush=True)

@@ -87,20 +87,21 @@ for (ba, bw, K) in [(3, 5, 19), (7, 1, 100), (1, 6, 96), (48, 64, 200), (32, 32,
 assert qp(fake, 7, 100, 100, 0, 7, fake, 4, fake, 15, None) == 0
 assert qp(fake, 7, 19, 8, 1, 5, fake, 4, fake, 4, None) == 0
 pf = lib.hbmm_conv_prepare_filters
-pf.argtypes = [p, p, i64, i64, i32, i64, i64, i32, i32, p, p]
+pf.argtypes = [p, p, i64, i64, i32, i64, i64, i32, i32, i32, p, p]
 cp = lib.hbmm_conv2d_prepared
-cp.argtypes = [p, p, i32, p, i64, i64, i64, i64, i64, i32, i32, i32, i32, p, p]
+cp.argtypes = [p, p, i32, p, i32, i64, i64, i64, i64, i64, i32, i32, i32, i32, p, p]
 for (ba, bw) in [(4, 32), (1, 4), (4, 5), (2, 1)]:
     K = 20 * 9
-    assert pf(None if bw == 1 else fake, fake, 8, K, bw, 40, 20, 3, 3, fake, None) == 0
-    assert cp(None if ba == 1 else fake, fake, ba, fake, 2, 20, 8, 8, 40, 3, 3, 1, 1, fake, None) == 0
+    for form in (0, 1):
+        assert pf(None if bw == 1 else fake, fake, 8, K, bw, 40, 20, 3, 3, form, fake, None) == 0
+        assert cp(None if ba == 1 else fake, fake, ba, fake, form, 2, 20, 8, 8, 40, 3, 3, 1, 1, fake, None) == 0
 qa = lib.hbmm_quantize_pack_activations
 qa.argtypes = [p, i64, i64, i32, p, p, p]
 assert qa(fake, 64 * 7, 7, 4, fake, fake, None) == 0       # ragged width: the general kernel
 assert qa(fake, 64 * 8, 8, 3, fake, fake, None) == 0
 assert qa(fake, 64 * 8, 8, 4, fake, fake, None) == 0       # the tuned kernel through the flat view
-assert cp(fake, fake, 3, fake, 2, 20, 7, 7, 40, 3, 3, 1, 1, fake, None) == 0
-assert lib.hbmm_stub_launches() - n0 == 14 + 16 + 5 + 5 + 2 + 8 + 4
+assert cp(fake, fake, 3, fake, 0, 2, 20, 7, 7, 40, 3, 3, 1, 1, fake, None) == 0
+assert lib.hbmm_stub_launches() - n0 == 14 + 16 + 5 + 5 + 2 + 16 + 4
 print("api under sanitizers: ok")
 """
 
