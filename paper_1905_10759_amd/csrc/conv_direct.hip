@@ -48,7 +48,7 @@ constexpr int kGroup = 32;                  // channels per group = K elements p
 constexpr int kPixBytes = 80;               // 32 bf16 + 16 bytes of padding
 constexpr int kNumXcdD = 8;
 constexpr int kThreadsD = 512;
-constexpr int kPatchArea = 160 * 1024 - 512;   // LDS of a workgroup, all of it patch (and, after the multiply, output turn areas)
+constexpr int kPatchArea = 160 * 1024 - 512;   // LDS of a workgroup, all of it patch (and, after the multiply, the exchange of the two halves of K)
 constexpr int kOperandBytes = 1024;         // one MFMA B operand: 64 lanes x 16 bytes
 // filters of one stage for one block of 32: 2 steps x 3 (bf16) or 2 (fp16) pieces
 constexpr int stage_bytes(int form) { return 2 * (form == 0 ? 3 : 2) * kOperandBytes; }
@@ -419,14 +419,16 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
             for (int q = 0; q < NQ; ++q)
 #pragma unroll
                 for (int tx = 0; tx < TX; ++tx) {
+                    // (filters as the first operand: a lane's 16 results are then 16 filters at one position, and
+                    // the lanes of a half wave run along positions, which is how the output is laid out)
                     if constexpr (FORM == 0)
                         res[tx] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8, fx[kPiecePairs[q][0]][tx]),
-                            __builtin_bit_cast(bf16x8, cur.f[ks][kPiecePairs[q][1]]), res[tx], 0, 0, 0);
+                            __builtin_bit_cast(bf16x8, cur.f[ks][kPiecePairs[q][1]]),
+                            __builtin_bit_cast(bf16x8, fx[kPiecePairs[q][0]][tx]), res[tx], 0, 0, 0);
                     else
                         res[tx] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                            __builtin_bit_cast(f16x8, fx[kPiecePairs2[q][0]][tx]),
-                            __builtin_bit_cast(f16x8, cur.f[ks][kPiecePairs2[q][1]]), res[tx], 0, 0, 0);
+                            __builtin_bit_cast(f16x8, cur.f[ks][kPiecePairs2[q][1]]),
+                            __builtin_bit_cast(f16x8, fx[kPiecePairs2[q][0]][tx]), res[tx], 0, 0, 0);
                 }
         }
         // the next group's activations: requested once the first tap's multiplies are queued, so that the
@@ -459,12 +461,13 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
         if (stage < nstages) run_stage(yc, yb);
     }
 
-    // ---- store: out is B x Y x OH x OW; each 32 x 32 accumulator tile is turned through LDS so that lanes
-    // run along positions.  (Every wave must have left the multiply loop before the patch area is reused.)
-    __syncthreads();
+    // ---- store: out is B x Y x OH x OW.  Lane l of an accumulator tile holds position (l mod 32) and the 16 filters
+    // 8 (v div 4) + 4 (l div 32) + (v mod 4): for each v a half wave writes 32 consecutive positions of one filter.
     if (NTY == 1) {
-        // add the two halves of K: the second half of the waves hands its accumulators to the first
-        float *half = reinterpret_cast<float *>(sPatch) + WV * (32 * 33) + (wave % (WV / 2)) * (TX * 16 * 64);
+        // add the two halves of K: the second half of the waves hands its accumulators to the first through the
+        // patch area (every wave must have left the multiply loop before it is reused)
+        __syncthreads();
+        float *half = reinterpret_cast<float *>(sPatch) + (wave % (WV / 2)) * (TX * 16 * 64);
         if (wave >= WV / 2) {
 #pragma unroll
             for (int tx = 0; tx < TX; ++tx)
@@ -478,15 +481,14 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
 #pragma unroll
             for (int v = 0; v < 16; ++v) res[tx][v] += half[(tx * 16 + v) * 64 + lane];
     }
-    float *turn = reinterpret_cast<float *>(sPatch) + wave * (32 * 33);
     // FORM 1: back to the caller's units: 2^(e_run - 127 - 14) for the activations times the filter's own
     int unscale[16];
     if constexpr (FORM == 1) {
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            // column y0 + wcol0 + 2 j + (lane div 32)
-            const int e0 = __builtin_amdgcn_readlane(filter_exp, 2 * j), e1 = __builtin_amdgcn_readlane(filter_exp, 2 * j + 1);
-            unscale[j] = (lane < 32 ? e0 : e1) + e_run - 2 * (127 + kTargetExp);
+        for (int v = 0; v < 16; ++v) {
+            const int f = 8 * (v >> 2) + (v & 3);
+            const int e0 = __builtin_amdgcn_readlane(filter_exp, f), e1 = __builtin_amdgcn_readlane(filter_exp, f + 4);
+            unscale[v] = (lane < 32 ? e0 : e1) + e_run - 2 * (127 + kTargetExp);
         }
     }
 #pragma unroll
@@ -498,26 +500,12 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
         const bool pos_ok = ml < npos && img + gi < a.B && oz0 + orow < a.OH;
         float *dst = a.out + ((int64_t)(img + gi) * a.Y * a.OH + (oz0 + orow)) * a.OW + oy;
 #pragma unroll
-        for (int v = 0; v < 16; ++v)
-            turn[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * 33 + (lane & 31)] = res[tx][v];
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        // (all reads first: under the store's condition each would be waited for on its own)
-        float val[16];
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            val[j] = turn[(lane & 31) * 33 + 2 * j + (lane >> 5)];
-            if constexpr (FORM == 1) val[j] = __builtin_amdgcn_ldexpf(val[j], unscale[j]);
+        for (int v = 0; v < 16; ++v) {
+            const int col = y0 + wcol0 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            float val = res[tx][v];
+            if constexpr (FORM == 1) val = __builtin_amdgcn_ldexpf(val, unscale[v]);
+            if (pos_ok && col < a.Y) dst[(int64_t)col * a.OHW] = val;
         }
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const int col = y0 + wcol0 + 2 * j + (lane >> 5);
-            if (pos_ok && col < a.Y) dst[(int64_t)col * a.OHW] = val[j];
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
 }
 
