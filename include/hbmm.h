@@ -254,7 +254,10 @@ int hbmm_conv2d(const uint32_t *a_bits, const float *a_scales, int32_t beta_a, c
  *                                   pieces from hbmm_conv_prepare_filters for the same N, C, KH, KW, form.
  *                                   The layer must fit the kernel: OW <= 128 and
  *                                   ((OW - 1) * stride + KW) * KH <= 640 (the input patch of one output
- *                                   row in on-chip memory); otherwise HBMM_EUNSUPPORTED (use hbmm_conv2d).
+ *                                   row in on-chip memory), and the images of one tile within 32-bit byte
+ *                                   offsets (C*H*W below 2^30 / images per tile; a tile holds several images
+ *                                   only when a whole image is at most 64 positions); otherwise
+ *                                   HBMM_EUNSUPPORTED (use hbmm_conv2d).
  *                                   No restriction on C*KH*KW being a multiple of 32 or of beta_w.
  */
 #define HBMM_PIECES_BF16X3 0

@@ -177,6 +177,8 @@ struct ConvDirectArgs {
     int32_t Y, yblocks;          // filters, and blocks of 32 of them in `pieces`
     int32_t beta_x, nseg, HS;    // activation segment length, segments per row ceil(W / beta_x), H * nseg
     int32_t C, H, W, HW, OH, OW, OHW, KW, KK, stride, pad;
+    int32_t CHW, CHS;            // elements and scales of one image: C * H * W, C * H * nseg
+    int64_t bits_bytes, scales_bytes;   // bytes of the activation words and scales: what the buffer loads may touch
     int32_t R, tiles_per_image, tiles_y, tiles_total, slots_per_xcd;
     int32_t B, G;                // images, and images per tile (1 unless a whole image is at most 64 positions)
     int32_t PI, IP;              // patch pixels and tile positions of one image: P = G * PI, positions = G * IP
@@ -188,7 +190,7 @@ struct ConvDirectArgs {
     uint32_t sign;               // 0x80000000; 0 when the tensor is unquantised (then x_scales holds the values)
 };
 
-// XI: (pixel, 8-channel octet) items a thread stages per channel group; XI * 512 >= 4 * P.
+// XI: pixels a lane stages per channel group (for one octet of channels); XI * 128 >= P.
 // Eight waves on a tile of 128 positions; every wave owns 64 positions x 32 filters.
 // NTY = 2 (128 filters): 2 x 4 wave tiles, each wave takes both MFMA steps of a stage;
 // NTY = 1 (64 filters): 2 x 2 wave tiles, waves 0-3 take the first step of every stage and waves 4-7 the
@@ -220,72 +222,90 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
     const int ks0 = NTY == 1 ? wave / (WV / 2) : 0;       // first MFMA step of a stage this wave takes
     const int npos = a.G * a.IP;                            // positions of a full tile (<= 128)
 
-    // ---- role 1: patch staging.  Item i = tid + 512 j is (octet i div P, pixel i mod P).
-    uint32_t pe0[XI], ps0[XI], pkeep[XI];   // element and scale index of channel 0 at the item's pixel
+    // ---- role 1: patch staging.  A wave stages one octet of channels (wave mod 4) for half of the patch's pixels:
+    // item j of a lane is pixel (wave div 4) * 64 + lane + 128 j.  The channel of an element is then the same for
+    // the whole wave, so everything that depends on it is scalar arithmetic, and the loads are buffer loads --
+    // descriptor + 32-bit lane offset (+ a scalar offset for the channel) -- whose range check returns 0 for a
+    // pixel outside the image: such a pixel is given an offset past the end of the buffer and costs no test.
+    const int oct = wave & 3;
+    const int64_t e_base = (int64_t)img * a.CHW;          // first element of the tile's first image
+    const int64_t w_base = e_base >> 5;                   // ... the word that holds its bit
+    const int64_t s_base = (int64_t)img * a.CHS;          // ... its first scale
+    auto records = [](int64_t bytes) { return (int)(uint32_t)(bytes < 0 ? 0 : bytes > 0xffffff00ll ? 0xffffff00ll : bytes); };
+    const __amdgpu_buffer_rsrc_t rsrc_bits = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint32_t *>(a.x_bits) + w_base, 0, records(a.bits_bytes - 4 * w_base), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_scales = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(a.x_scales) + s_base, 0, records(a.scales_bytes - 4 * s_base), 0x00020000);
+    constexpr uint32_t kPastEnd = 0xfffffffcu;            // a byte offset no buffer reaches
+    uint32_t perel[XI];  // element index of channel 0 at the item's pixel, counted from the bit of the tile's first element
+    uint32_t poob[XI];   // 0, or kPastEnd for a pixel outside the image (or-ed into the word's byte offset)
+    uint32_t psoff[XI];  // byte offset of channel 0's scale at the item's pixel (kPastEnd outside the image)
     int pdst[XI];        // byte offset of the item inside a plane; -1: the item does not exist
-    int poct[XI];
 #pragma unroll
     for (int j = 0; j < XI; ++j) {
-        const int item = tid + j * kThreadsD;
-        const int oct = small_div(item, a.m_P), pix = item - oct * a.P;
-        const int gi = small_div(pix, a.m_PI), lp = pix - gi * a.PI;   // image of the tile, pixel inside its patch
+        const int pix = (wave >> 2) * 64 + lane + j * 128;
+        const int pc = min(pix, a.P - 1);
+        const int gi = small_div(pc, a.m_PI), lp = pc - gi * a.PI;   // image of the tile, pixel inside its patch
         const int prow = small_div(lp, a.m_PW), pcol = lp - prow * a.PW;
         const int z = oz0 * a.stride - a.pad + prow, y = pcol - a.pad;
-        const bool inside = oct < 4 && img + gi < a.B && z >= 0 && z < a.H && y >= 0 && y < a.W;
-        poct[j] = min(oct, 3);
-        pdst[j] = oct < 4 ? pix * kPixBytes + oct * 16 : -1;
-        pkeep[j] = inside ? 0xffffffffu : 0u;
-        pe0[j] = inside ? (uint32_t)(((img + gi) * a.C * a.H + z) * a.W + y) : 0u;
+        const bool inside = pix < a.P && img + gi < a.B && z >= 0 && z < a.H && y >= 0 && y < a.W;
+        const int row = gi * a.C * a.H + z;               // row of channel 0, counted from the tile's first image
+        pdst[j] = pix < a.P ? pix * kPixBytes + oct * 16 : -1;
+        poob[j] = inside ? 0u : kPastEnd;
+        perel[j] = inside ? (uint32_t)(row * a.W + y) + (uint32_t)(e_base & 31) : 0u;
         // segments run along the width of a row and start anew in every row (the last one may be shorter)
-        ps0[j] = inside ? (uint32_t)(((img + gi) * a.C * a.H + z) * a.nseg + small_div(y, a.m_beta)) : 0u;
+        psoff[j] = inside ? (uint32_t)(row * a.nseg + small_div(y, a.m_beta)) * 4u : kPastEnd;
     }
-    const char *xb_bytes = reinterpret_cast<const char *>(a.x_bits);
-    const char *xs_bytes = reinterpret_cast<const char *>(a.x_scales);
     struct PatchRegs {
         uint32_t w[XI][8];
         float s[XI][8];
     };
-    // channel c of item j: element pe0 + c * HW; a channel past C (last group only) or a pixel outside the
-    // image reads element 0 and is written as zero
+    // channel c = 32 g + 8 oct + i of item j: element perel + c * HW, scale psoff + 4 c * HS
     auto fetch_patch = [&](PatchRegs &r, int g) __attribute__((always_inline)) {
+        const int c0 = g * kGroup + oct * 8;
+        auto one = [&](int j, int i) __attribute__((always_inline)) {
+            const uint32_t e = perel[j] + (uint32_t)((c0 + i) * a.HW);
+            r.w[j][i] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rsrc_bits, (int)((((e >> 5) << 2)) | poob[j]), 0, 0);
+            r.s[j][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc_scales, (int)psoff[j], (c0 + i) * a.HS * 4, 0));
+        };
+        if (c0 + 8 <= a.C) {
 #pragma unroll
-        for (int j = 0; j < XI; ++j)
+            for (int j = 0; j < XI; ++j)
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int c = g * kGroup + poct[j] * 8 + i;
-                const uint32_t e = c < a.C ? (pe0[j] + (uint32_t)(c * a.HW)) & pkeep[j] : 0u;
-                const uint32_t si = c < a.C ? (ps0[j] + (uint32_t)(c * a.HS)) & pkeep[j] : 0u;
-                // (byte pointers with 32-bit offsets: one address register per load instead of two)
-                r.w[j][i] = *reinterpret_cast<const uint32_t *>(xb_bytes + ((e >> 5) << 2));
-                r.s[j][i] = *reinterpret_cast<const float *>(xs_bytes + (si << 2));
-            }
+                for (int i = 0; i < 8; ++i) one(j, i);
+        } else {
+            // the last group of a channel count that is not a multiple of 8: channels past C are zeros
+#pragma unroll
+            for (int j = 0; j < XI; ++j)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    r.w[j][i] = 0u;
+                    r.s[j][i] = 0.f;
+                    if (c0 + i < a.C) one(j, i);
+                }
+        }
     };
-    // FORM 1: the largest magnitude among the values this thread holds of group g (those that will be written)
-    auto patch_max = [&](const PatchRegs &r, int g) __attribute__((always_inline)) {
+    // FORM 1: the largest magnitude among the values this thread holds (what was not loaded is 0)
+    auto patch_max = [&](const PatchRegs &r) __attribute__((always_inline)) {
         uint32_t mx = 0;
 #pragma unroll
         for (int j = 0; j < XI; ++j)
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int c = g * kGroup + poct[j] * 8 + i;
-                const uint32_t keep = c < a.C ? pkeep[j] : 0u;
-                mx = max(mx, __builtin_bit_cast(uint32_t, r.s[j][i]) & 0x7fffffffu & keep);
-            }
+            for (int i = 0; i < 8; ++i) mx = max(mx, __builtin_bit_cast(uint32_t, r.s[j][i]) & 0x7fffffffu);
         return mx;
     };
     auto park_patch = [&](const PatchRegs &r, int g, unsigned char *buf, float norm) __attribute__((always_inline)) {
-        // (the element indices are recomputed rather than kept in registers since fetch_patch)
-        asm volatile("" : "+s"(g));
+        const int c0 = g * kGroup + oct * 8;
 #pragma unroll
         for (int j = 0; j < XI; ++j) {
             uint32_t h[8], m[8], l[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const int c = g * kGroup + poct[j] * 8 + i;
-                const uint32_t keep = c < a.C ? pkeep[j] : 0u;
-                const uint32_t e = (pe0[j] + (uint32_t)(c * a.HW)) & keep;
-                const uint32_t minus = (~(r.w[j][i] >> (e & 31)) << 31) & a.sign;
-                const uint32_t value = (__builtin_bit_cast(uint32_t, r.s[j][i]) ^ minus) & keep;
+                // value = scale with the sign of the element's bit (1: positive); the bit sits at position e mod 32
+                // of the word, and a shift by (not e) mod 32 = 31 - e mod 32 brings its complement to the sign
+                const uint32_t e = perel[j] + (uint32_t)((c0 + i) * a.HW);
+                const uint32_t minus = (~r.w[j][i] << (~e & 31u)) & a.sign;
+                const uint32_t value = __builtin_bit_cast(uint32_t, r.s[j][i]) ^ minus;
                 if constexpr (FORM == 0) {
                     split3(__builtin_bit_cast(float, value), h[i], m[i], l[i]);
                 } else {
@@ -355,7 +375,7 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
     // Every wave publishes the largest magnitude it holds of group g; after a barrier all of them agree
     // on the exponent.  If it grew, what has been accumulated so far is rescaled to the new unit.
     auto publish_max = [&](int g) __attribute__((always_inline)) {
-        uint32_t mx = patch_max(xr, g);
+        uint32_t mx = patch_max(xr);
         mx = max(mx, dpp_u32<kDppQuadSwap1>(mx));
         mx = max(mx, dpp_u32<kDppQuadSwap2>(mx));
         mx = max(mx, dpp_u32<kDppHalfMirror>(mx));
@@ -602,6 +622,11 @@ hipError_t launch_conv_direct(const ConvActivations &x, const void *pieces, int6
     a.x_bits = x.beta == 1 ? reinterpret_cast<const uint32_t *>(x.scales) : x.bits;
     a.x_scales = x.scales; a.sign = x.beta == 1 ? 0u : 0x80000000u;
     a.beta_x = x.beta; a.nseg = (int32_t)((g.W + x.beta - 1) / x.beta); a.HS = (int32_t)(g.H * a.nseg);
+    // (the buffer loads address the images of one tile with 32-bit byte offsets)
+    if ((double)G * (double)g.C * (double)g.H * (double)g.W * 4.0 > 4.0e9) return hipErrorNotSupported;
+    a.CHW = (int32_t)(g.C * g.H * g.W); a.CHS = (int32_t)(g.C * a.HS);
+    a.bits_bytes = (g.B * g.C * g.H * g.W + 31) / 32 * 4;
+    a.scales_bytes = g.B * g.C * (int64_t)a.HS * 4;
     a.pieces = static_cast<const unsigned char *>(pieces);
     a.exps = reinterpret_cast<const int32_t *>(a.pieces + pieces_proper_bytes(N, g.C, g.KH, g.KW, form));
     a.out = out; a.Y = (int32_t)N; a.yblocks = (int32_t)((N + 31) / 32);
@@ -616,7 +641,7 @@ hipError_t launch_conv_direct(const ConvActivations &x, const void *pieces, int6
     a.m_P = magic(P); a.m_PI = magic(PI); a.m_PW = magic(PW); a.m_IP = magic(a.IP); a.m_OW = magic((int)OW);
     a.m_beta = magic(x.beta);
     a.groups = (int32_t)((g.C + kGroup - 1) / kGroup);
-    const int xi = (4 * P + threads - 1) / threads;
+    const int xi = (P + 127) / 128;
     const dim3 grid((unsigned)(per_xcd * kNumXcdD)), block(threads);
 #define HBMM_DIRECT_LAUNCH(I)                                           \
     do {                                                                \
