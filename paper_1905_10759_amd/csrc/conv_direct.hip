@@ -37,6 +37,8 @@
 // times by the multiply itself: no operand tile is assembled, and the only barrier is the one per
 // channel group that hands over the next patch (fetched after the first tap of a group, written after
 // its last one -- into the other buffer when two fit, else between two barriers).
+#include <type_traits>
+
 #include "bf16_pieces.h"
 #include "kernels.h"
 #include "wave_ops.h"
@@ -294,10 +296,9 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
             for (int i = 0; i < 8; ++i) mx = max(mx, __builtin_bit_cast(uint32_t, r.s[j][i]) & 0x7fffffffu);
         return mx;
     };
-    auto park_patch = [&](const PatchRegs &r, int g, unsigned char *buf, float norm) __attribute__((always_inline)) {
+    auto park_item = [&](const PatchRegs &r, int j, int g, unsigned char *buf, float norm) __attribute__((always_inline)) {
         const int c0 = g * kGroup + oct * 8;
-#pragma unroll
-        for (int j = 0; j < XI; ++j) {
+        {
             uint32_t h[8], m[8], l[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -332,6 +333,10 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
                 if constexpr (FORM == 0) *reinterpret_cast<u32x4 *>(dst + 2 * a.plane) = dl;
             }
         }
+    };
+    auto park_patch = [&](const PatchRegs &r, int g, unsigned char *buf, float norm) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < XI; ++j) park_item(r, j, g, buf, norm);
     };
 
     // ---- role 2: multiply.  Lane l feeds position row (l mod 32) and channels 8 (l div 32) .. + 7 of a step.
@@ -384,11 +389,13 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
         mx = max(mx, (uint32_t)__shfl_xor((int)mx, 32));
         if (lane == 0) sMax[wave] = mx;
     };
-    auto agree_on_exponent = [&]() __attribute__((always_inline)) {
+    auto agreed_exponent = [&]() __attribute__((always_inline)) {
         uint32_t all = 0;
 #pragma unroll
         for (int w = 0; w < WV; ++w) all = max(all, sMax[w]);
-        const int e_new = max(e_run, norm_exponent(__builtin_amdgcn_readfirstlane(all)));
+        return max(e_run, norm_exponent(__builtin_amdgcn_readfirstlane(all)));
+    };
+    auto adopt_exponent = [&](int e_new) __attribute__((always_inline)) {
         if (e_new != e_run) {
 #pragma unroll
             for (int tx = 0; tx < TX; ++tx)
@@ -398,6 +405,7 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
         }
         norm = norm_factor(e_run);
     };
+    auto agree_on_exponent = [&]() __attribute__((always_inline)) { adopt_exponent(agreed_exponent()); };
     fetch_patch(xr, 0);
     fetch_filter(ya, 0);
     fetch_filter(yb, 1);
@@ -413,7 +421,93 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
     park_patch(xr, 0, sPatch, norm);
     __syncthreads();
 
+    // ---- 3 x 3 windows with room for two patches: the nine taps of a channel group written out, so that the staging
+    // of the next group -- the exchange of the maxima (FORM 1) and the splitting of one item per tap -- sits in the
+    // same straight-line code as a tap's multiplies and its vector instructions are issued between them (in the
+    // general loop below it runs after the group's last multiply, with the matrix pipe idle).  Not with four or
+    // five items per lane: holding them across the written-out taps spills registers (measured: slower).
+    constexpr bool kUnrolled3x3 = XI <= 3;
+    bool unrolled = false;
+    if constexpr (kUnrolled3x3) unrolled = a.KK == 9 && a.KW == 3 && a.patch_bufs == 2;
+    if constexpr (kUnrolled3x3) if (unrolled) {
+        auto tap = [&](const FilterRegs &cur, FilterRegs &next, int g_, int k, int stage_, auto &&extra) __attribute__((always_inline)) {
+            fetch_filter(next, stage_ + 2);
+            __builtin_amdgcn_sched_barrier(0);
+            const unsigned char *px = sPatch + (g_ & 1) * patch_stride + ((k / 3) * a.PW + k % 3) * kPixBytes;
+            u32x4 fx[KS][NP][TX];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int p = 0; p < NP; ++p)
+#pragma unroll
+                    for (int tx = 0; tx < TX; ++tx)
+                        fx[ks][p][tx] = *reinterpret_cast<const u32x4 *>(px + p * a.plane + xoff[tx] + ks * 32);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                    for (int tx = 0; tx < TX; ++tx) {
+                        if constexpr (FORM == 0)
+                            res[tx] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                __builtin_bit_cast(bf16x8, cur.f[ks][kPiecePairs[q][1]]),
+                                __builtin_bit_cast(bf16x8, fx[ks][kPiecePairs[q][0]][tx]), res[tx], 0, 0, 0);
+                        else
+                            res[tx] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                                __builtin_bit_cast(f16x8, cur.f[ks][kPiecePairs2[q][1]]),
+                                __builtin_bit_cast(f16x8, fx[ks][kPiecePairs2[q][0]][tx]), res[tx], 0, 0, 0);
+                    }
+            // (after the multiplies in program order and in the same block: the scheduler places these vector
+            // instructions between them, where they are issued while the matrix pipe works)
+            extra();
+        };
+        // taps 9 - XI .. 8 each split one item of the next patch; FORM 1 publishes its maxima with tap 7 - XI and
+        // agrees on the exponent (one barrier) before tap 9 - XI
+        constexpr int kFirstPark = 9 - XI;
+        int e_next = e_run;
+        float norm_next = norm;
+        auto group = [&](auto more_c, int g_) __attribute__((always_inline)) {
+            constexpr bool more = decltype(more_c)::value;
+            const int s0 = g_ * 9;
+            unsigned char *nbuf = sPatch + ((g_ + 1) & 1) * patch_stride;
+            auto staged = [&](auto k_c) __attribute__((always_inline)) {
+                constexpr int k = decltype(k_c)::value;
+                if constexpr (more) {
+                    if constexpr (FORM == 1 && k == kFirstPark - 2) publish_max(g_ + 1);
+                    if constexpr (k >= kFirstPark) park_item(xr, k - kFirstPark, g_ + 1, nbuf, norm_next);
+                }
+            };
+#define HBMM_TAP(K, CUR, NEXT)                                                              \
+    do {                                                                                    \
+        if constexpr (more && FORM == 1 && K == kFirstPark) {                               \
+            __syncthreads();                                                                \
+            e_next = agreed_exponent();                                                     \
+            norm_next = norm_factor(e_next);                                                \
+        }                                                                                   \
+        tap(CUR, NEXT, g_, K, s0 + K, [&]() __attribute__((always_inline)) { staged(std::integral_constant<int, K>{}); }); \
+        if constexpr (more && K == 0) fetch_patch(xr, g_ + 1);                              \
+    } while (0)
+            HBMM_TAP(0, ya, yc);
+            HBMM_TAP(1, yb, ya);
+            HBMM_TAP(2, yc, yb);
+            HBMM_TAP(3, ya, yc);
+            HBMM_TAP(4, yb, ya);
+            HBMM_TAP(5, yc, yb);
+            HBMM_TAP(6, ya, yc);
+            HBMM_TAP(7, yb, ya);
+            HBMM_TAP(8, yc, yb);
+#undef HBMM_TAP
+            if constexpr (more) {
+                __syncthreads();   // the next patch is complete, and every wave has read the last tap of this one
+                if constexpr (FORM == 1) adopt_exponent(e_next);
+            }
+        };
+        for (int g_ = 0; g_ + 1 < a.groups; ++g_) group(std::true_type{}, g_);
+        group(std::false_type{}, a.groups - 1);
+    }
+
     int g = 0, t = 0, dz = 0, dy = 0, stage = 0;
+    if (unrolled) stage = a.groups * a.KK;   // done above
     // One stage: request the filter operands of the stage after next into `next`, multiply with `cur`.
     // (Two stages ahead: a stage of a 64-filter tile is only 12 MFMAs per wave, shorter than a trip to L2.)
     auto run_stage = [&](const FilterRegs &cur, FilterRegs &next) __attribute__((always_inline)) {

@@ -714,7 +714,8 @@ def test_layer_pipeline_in_a_hip_graph_replays_exactly():
         _ = dX.sum().item()   # unrelated eager work between replays
 
 
-def test_prepared_layer_pipeline_in_a_hip_graph_replays_exactly():
+@pytest.mark.parametrize("form", [0, 1], ids=["bf16x3", "f16x2"])
+def test_prepared_layer_pipeline_in_a_hip_graph_replays_exactly(form):
     """The same with the entry points added for settings outside the paper's table: activations of a 7-wide
     map packed with a segment length that does not divide the width, the layer with prepared filters, the
     gradient through the binarisation and a product with segment lengths that are not powers of two --
@@ -725,7 +726,7 @@ def test_prepared_layer_pipeline_in_a_hip_graph_replays_exactly():
     L = synth.normal(1303, (30, N * H * W), std=0.1)
     dX = dev(X0)
     fb, fs = hbmm.quantize_pack(dev(F.reshape(N, -1)), beta_w)
-    prepared = hbmm.conv_prepare_filters(fb, fs, beta_w, C, (3, 3))
+    prepared = hbmm.conv_prepare_filters(fb, fs, beta_w, C, (3, 3), form=form)
     K2 = N * H * W
     lb, ls = hbmm.quantize_pack(dev(L), 6)
     xb, xs = hbmm.quantize_pack_activations(dX, beta_a)
@@ -737,7 +738,7 @@ def test_prepared_layer_pipeline_in_a_hip_graph_replays_exactly():
 
     def step():
         hbmm.quantize_pack_activations(dX, beta_a, xb, xs)
-        hbmm.conv2d_prepared(xb, xs, beta_a, dX.shape, prepared, N, (3, 3), 1, 1, out=Y)
+        hbmm.conv2d_prepared(xb, xs, beta_a, dX.shape, prepared, N, (3, 3), 1, 1, out=Y, form=form)
         hbmm.quantize_pack(Y.view(B, K2), 7, 0, yb, ys)
         hbmm.gemm(yb, ys, 7, lb, ls, 6, K2, out=Z)
         hbmm.binarize_backward(dX.view(-1, W), dX.view(-1, W), beta_a, out=G)
