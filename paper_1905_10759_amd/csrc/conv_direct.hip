@@ -296,43 +296,47 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
             for (int i = 0; i < 8; ++i) mx = max(mx, __builtin_bit_cast(uint32_t, r.s[j][i]) & 0x7fffffffu);
         return mx;
     };
-    auto park_item = [&](const PatchRegs &r, int j, int g, unsigned char *buf, float norm) __attribute__((always_inline)) {
-        const int c0 = g * kGroup + oct * 8;
-        {
-            uint32_t h[8], m[8], l[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                // value = scale with the sign of the element's bit (1: positive); the bit sits at position e mod 32
-                // of the word, and a shift by (not e) mod 32 = 31 - e mod 32 brings its complement to the sign
-                const uint32_t e = perel[j] + (uint32_t)((c0 + i) * a.HW);
-                const uint32_t minus = (~r.w[j][i] << (~e & 31u)) & a.sign;
-                const uint32_t value = __builtin_bit_cast(uint32_t, r.s[j][i]) ^ minus;
-                if constexpr (FORM == 0) {
-                    split3(__builtin_bit_cast(float, value), h[i], m[i], l[i]);
-                } else {
-                    split2_f16(__builtin_bit_cast(float, value) * norm, h[i], m[i]);
-                    l[i] = 0;
-                }
-            }
-            if (pdst[j] >= 0) {
-                u32x4 dh, dm, dl;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    if constexpr (FORM == 0) {
-                        dh[i] = pair16(h[2 * i], h[2 * i + 1]);
-                        dm[i] = pair16(m[2 * i], m[2 * i + 1]);
-                        dl[i] = pair16(l[2 * i], l[2 * i + 1]);
-                    } else {
-                        dh[i] = h[2 * i] | (h[2 * i + 1] << 16);
-                        dm[i] = m[2 * i] | (m[2 * i + 1] << 16);
-                    }
-                }
-                unsigned char *dst = buf + pdst[j];
-                *reinterpret_cast<u32x4 *>(dst) = dh;
-                *reinterpret_cast<u32x4 *>(dst + a.plane) = dm;
-                if constexpr (FORM == 0) *reinterpret_cast<u32x4 *>(dst + 2 * a.plane) = dl;
-            }
+    // One element (channel i of item j) of group g as pieces; then the item's eight elements written to the planes.
+    auto park_elem = [&](const PatchRegs &r, int j, int i, int g, float norm, uint32_t (&h)[8], uint32_t (&m)[8], uint32_t (&l)[8])
+                         __attribute__((always_inline)) {
+        // value = scale with the sign of the element's bit (1: positive); the bit sits at position e mod 32
+        // of the word, and a shift by (not e) mod 32 = 31 - e mod 32 brings its complement to the sign
+        const uint32_t e = perel[j] + (uint32_t)((g * kGroup + oct * 8 + i) * a.HW);
+        const uint32_t minus = (~r.w[j][i] << (~e & 31u)) & a.sign;
+        const uint32_t value = __builtin_bit_cast(uint32_t, r.s[j][i]) ^ minus;
+        if constexpr (FORM == 0) {
+            split3(__builtin_bit_cast(float, value), h[i], m[i], l[i]);
+        } else {
+            split2_f16(__builtin_bit_cast(float, value) * norm, h[i], m[i]);
+            l[i] = 0;
         }
+    };
+    auto park_write = [&](int j, unsigned char *buf, const uint32_t (&h)[8], const uint32_t (&m)[8], const uint32_t (&l)[8])
+                          __attribute__((always_inline)) {
+        if (pdst[j] >= 0) {
+            u32x4 dh, dm, dl;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if constexpr (FORM == 0) {
+                    dh[i] = pair16(h[2 * i], h[2 * i + 1]);
+                    dm[i] = pair16(m[2 * i], m[2 * i + 1]);
+                    dl[i] = pair16(l[2 * i], l[2 * i + 1]);
+                } else {
+                    dh[i] = h[2 * i] | (h[2 * i + 1] << 16);
+                    dm[i] = m[2 * i] | (m[2 * i + 1] << 16);
+                }
+            }
+            unsigned char *dst = buf + pdst[j];
+            *reinterpret_cast<u32x4 *>(dst) = dh;
+            *reinterpret_cast<u32x4 *>(dst + a.plane) = dm;
+            if constexpr (FORM == 0) *reinterpret_cast<u32x4 *>(dst + 2 * a.plane) = dl;
+        }
+    };
+    auto park_item = [&](const PatchRegs &r, int j, int g, unsigned char *buf, float norm) __attribute__((always_inline)) {
+        uint32_t h[8], m[8], l[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) park_elem(r, j, i, g, norm, h, m, l);
+        park_write(j, buf, h, m, l);
     };
     auto park_patch = [&](const PatchRegs &r, int g, unsigned char *buf, float norm) __attribute__((always_inline)) {
 #pragma unroll
@@ -430,7 +434,13 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
     bool unrolled = false;
     if constexpr (kUnrolled3x3) unrolled = a.KK == 9 && a.KW == 3 && a.patch_bufs == 2;
     if constexpr (kUnrolled3x3) if (unrolled) {
-        auto tap = [&](const FilterRegs &cur, FilterRegs &next, int g_, int k, int stage_, auto &&extra) __attribute__((always_inline)) {
+        // `item` >= 0: this tap also splits item `item` of the next group's patch, one element after every eighth of
+        // its multiplies (fenced, so that the order holds): the element's vector instructions are issued while
+        // the matrix pipe works on the MFMAs before them.  `extra` runs after the multiplies.
+        auto tap = [&](const FilterRegs &cur, FilterRegs &next, int g_, int k, int stage_, auto item_c, unsigned char *nbuf,
+                       float item_norm, auto &&extra) __attribute__((always_inline)) {
+            constexpr int item = decltype(item_c)::value;
+            constexpr int NM = KS * NQ * TX;
             fetch_filter(next, stage_ + 2);
             __builtin_amdgcn_sched_barrier(0);
             const unsigned char *px = sPatch + (g_ & 1) * patch_stride + ((k / 3) * a.PW + k % 3) * kPixBytes;
@@ -442,23 +452,32 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
 #pragma unroll
                     for (int tx = 0; tx < TX; ++tx)
                         fx[ks][p][tx] = *reinterpret_cast<const u32x4 *>(px + p * a.plane + xoff[tx] + ks * 32);
+            uint32_t h[8], m[8], l[8];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
+            for (int c = 0; c < 8; ++c) {
 #pragma unroll
-                for (int q = 0; q < NQ; ++q)
-#pragma unroll
-                    for (int tx = 0; tx < TX; ++tx) {
-                        if constexpr (FORM == 0)
-                            res[tx] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                                __builtin_bit_cast(bf16x8, cur.f[ks][kPiecePairs[q][1]]),
-                                __builtin_bit_cast(bf16x8, fx[ks][kPiecePairs[q][0]][tx]), res[tx], 0, 0, 0);
-                        else
-                            res[tx] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                                __builtin_bit_cast(f16x8, cur.f[ks][kPiecePairs2[q][1]]),
-                                __builtin_bit_cast(f16x8, fx[ks][kPiecePairs2[q][0]][tx]), res[tx], 0, 0, 0);
-                    }
-            // (after the multiplies in program order and in the same block: the scheduler places these vector
-            // instructions between them, where they are issued while the matrix pipe works)
+                for (int idx = c * NM / 8; idx < (c + 1) * NM / 8; ++idx) {
+                    const int ks = idx / (NQ * TX), q = (idx / TX) % NQ, tx = idx % TX;
+                    if constexpr (FORM == 0)
+                        res[tx] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, cur.f[ks][kPiecePairs[q][1]]),
+                            __builtin_bit_cast(bf16x8, fx[ks][kPiecePairs[q][0]][tx]), res[tx], 0, 0, 0);
+                    else
+                        res[tx] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                            __builtin_bit_cast(f16x8, cur.f[ks][kPiecePairs2[q][1]]),
+                            __builtin_bit_cast(f16x8, fx[ks][kPiecePairs2[q][0]][tx]), res[tx], 0, 0, 0);
+                }
+                if constexpr (item >= 0) {
+                    park_elem(xr, item, c, g_ + 1, item_norm, h, m, l);
+                    // (pinned: without a use here the optimiser sinks the arithmetic to the write after the last MFMA)
+                    if constexpr (FORM == 0)
+                        asm volatile("" : "+v"(h[c]), "+v"(m[c]), "+v"(l[c]));
+                    else
+                        asm volatile("" : "+v"(h[c]), "+v"(m[c]));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            if constexpr (item >= 0) park_write(item, nbuf, h, m, l);
             extra();
         };
         // taps 9 - XI .. 8 each split one item of the next patch; FORM 1 publishes its maxima with tap 7 - XI and
@@ -474,7 +493,6 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
                 constexpr int k = decltype(k_c)::value;
                 if constexpr (more) {
                     if constexpr (FORM == 1 && k == kFirstPark - 2) publish_max(g_ + 1);
-                    if constexpr (k >= kFirstPark) park_item(xr, k - kFirstPark, g_ + 1, nbuf, norm_next);
                 }
             };
 #define HBMM_TAP(K, CUR, NEXT)                                                              \
@@ -484,7 +502,8 @@ __global__ __launch_bounds__(kThreadsD) void conv_direct_kernel(const ConvDirect
             e_next = agreed_exponent();                                                     \
             norm_next = norm_factor(e_next);                                                \
         }                                                                                   \
-        tap(CUR, NEXT, g_, K, s0 + K, [&]() __attribute__((always_inline)) { staged(std::integral_constant<int, K>{}); }); \
+        tap(CUR, NEXT, g_, K, s0 + K, std::integral_constant<int, (more && K >= kFirstPark) ? K - kFirstPark : -1>{}, nbuf, \
+            norm_next, [&]() __attribute__((always_inline)) { staged(std::integral_constant<int, K>{}); });               \
         if constexpr (more && K == 0) fetch_patch(xr, g_ + 1);                              \
     } while (0)
             HBMM_TAP(0, ya, yc);
