@@ -23,20 +23,26 @@
 // conv_prepare_filters_kernel, in the order in which a wave consumes them: for a block of 32 filters, a
 // channel group, a tap, an MFMA step of 16 channels and a piece, 64 x 16 bytes = the B operand of one
 // MFMA (lane l: filter l mod 32, channels 8 (l div 32) .. + 7).  In the layer kernel a wave loads these
-// operands straight from memory into registers, one stage ahead, with 1 KB contiguous per instruction;
-// filters never pass through LDS and cost no arithmetic per workgroup.
+// operands straight from memory into registers, two stages ahead, with 1 KB contiguous per instruction;
+// filters never pass through LDS and cost no arithmetic per workgroup.  They are the MFMA's first operand
+// and the activations its second: a lane's 16 results are then 16 filters at one position and a half wave
+// holds 32 consecutive positions, which is how the B x N x OH x OW output is laid out -- it is stored
+// straight from the accumulators.
 //
 // Activations.  A workgroup owns R whole output rows of one image (R * OW <= 128 positions) and a tile
 // of 64 or 128 filters.  For the current channel group it keeps the input patch those rows need --
 // ((R - 1) stride + KH) rows x ((OW - 1) stride + KW) columns, zero outside the image -- in LDS as
-// three planes of bf16 pieces, 32 channels contiguous per pixel (pixel stride 80 bytes: the 16-byte
-// fragment reads of neighbouring positions fall on distinct banks).  The A operand of position m,
+// three planes of bf16 pieces (two of fp16 in FORM 1), 32 channels contiguous per pixel (pixel stride 80
+// bytes: the 16-byte fragment reads of neighbouring positions fall on distinct banks).  The A operand of position m,
 // tap (dz, dy), channels 8j .. 8j+7 is one 16-byte LDS read at
 //     pixel(m) + dz * PW + dy,   pixel(m) = (orow * stride) * PW + oy * stride,
 // so every activation is fetched, rebuilt and split once per workgroup and channel group and read KH*KW
 // times by the multiply itself: no operand tile is assembled, and the only barrier is the one per
 // channel group that hands over the next patch (fetched after the first tap of a group, written after
-// its last one -- into the other buffer when two fit, else between two barriers).
+// its last one -- into the other buffer when two fit, else between two barriers; FORM 1 has one more per
+// group, for the exchange of the largest magnitude).  For 3 x 3 windows the nine taps of a group are
+// written out and the next patch is split and written item by item between the multiplies of the last
+// taps, so that the vector instructions are issued while the matrix pipe works.
 #include <type_traits>
 
 #include "bf16_pieces.h"
