@@ -1125,6 +1125,35 @@ def test_conv2d_prepared_width_not_a_multiple_of_beta_a(case, form):
     assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d_prepared ragged width {case} form {form}")
 
 
+MANY_TILE_CONV_CASES = [
+    # B, C, H, W, N, KH, KW, stride, pad, beta_a, beta_w: 3 x 3 layers with more tiles than the chip has compute units
+    (40, 32, 56, 56, 64, 3, 3, 1, 1, 4, 32),     # 560 tiles of 64 filters, one channel group
+    (9, 40, 56, 56, 130, 3, 3, 1, 1, 8, 5),      # 126 position tiles x 3 filter tiles; the second channel group partial
+    (3, 64, 112, 112, 128, 3, 3, 1, 1, 4, 64),   # one output row per tile, three pixels per lane, 128-filter tiles
+    (41, 96, 28, 28, 64, 3, 3, 1, 1, 1, 4),      # unquantised activations, three channel groups, 287 tiles
+]
+
+
+@pytest.mark.parametrize("form", [0, 1], ids=["bf16x3", "f16x2"])
+@pytest.mark.parametrize("case", MANY_TILE_CONV_CASES, ids=lambda c: "x".join(str(v) for v in c))
+def test_conv2d_prepared_many_tiles(case, form):
+    """Layers of several hundred tiles (several rounds of workgroups, all XCD slots in use), with the images scaled
+    differently and one half image of zeros, so that neighbouring tiles of the two-piece form work in different
+    units."""
+    B, C, H, W, N, KH, KW, stride, pad, beta_a, beta_w = case
+    A, Wf = _conv_inputs(8800 + B + C + N, B, C, H, W, N, KH, KW)
+    A *= (2.0 ** (np.arange(B) % 5 * 3 - 6)).astype(np.float32)[:, None, None, None]
+    if B > 2:
+        A[2, :, : H // 2] = 0.0          # tiles that are all zeros between ordinary ones
+    ref, T = oracle.hbmm_conv2d(A, Wf, beta_a, beta_w, stride, pad, want_T=True)
+    ab, asc = (None, dev(A)) if beta_a == 1 else hbmm.quantize_pack_activations(dev(A), beta_a)
+    wb, ws = hbmm.quantize_pack(dev(Wf.reshape(N, -1)), beta_w)
+    pieces = hbmm.conv_prepare_filters(wb, ws, beta_w, C, (KH, KW), form=form)
+    out = hbmm.conv2d_prepared(ab, asc, beta_a, A.shape, pieces, N, (KH, KW), stride, pad, form=form)
+    assert_close_to_oracle(out.cpu().numpy(), ref, T, f"conv2d_prepared many tiles {case} form {form}")
+    assert torch.equal(out, hbmm.conv2d_prepared(ab, asc, beta_a, A.shape, pieces, N, (KH, KW), stride, pad, form=form))
+
+
 def _random_prepared_conv_cases(n, seed):
     rng = np.random.default_rng(seed)
     cases = []
